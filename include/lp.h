@@ -1,0 +1,193 @@
+/*
+ * lp.h - C ABI of the MI355X (gfx950) link-prediction training-step library.
+ *
+ * One worker's training step of distributed GNN link prediction (the body of
+ * the per-worker loop in the paper's Algorithm 1, "Distributed Model
+ * Training"): K GraphSAGE-mean layers over the worker's visible graph
+ * (Eq. 1), per-source uniform negative sampling (Sec. II-B), dot-product edge
+ * scores (Eq. 2), binary cross-entropy averaged over the batch (Sec. IV-B,
+ * last paragraph), and the gradient of that loss with respect to every model
+ * weight.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Every pointer marked "device" is HIP device memory of the current device,
+ *    allocated and owned by the caller.  The library never allocates, frees or
+ *    keeps device memory: outputs and scratch space ("ws") come from the
+ *    caller, and the size of the scratch space is given by the matching
+ *    *_workspace_bytes() function, which is pure host arithmetic.
+ *  - Matrices are row-major and node-major: row v of a [N, F] matrix is the
+ *    vector of node v.  Feature, activation and weight pointers must be
+ *    16-byte aligned and every layer width must be a multiple of 4.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued on it and, except for lp_build_csr, the call returns
+ *    without waiting.
+ *  - Return value: LP_OK or a negative LP_ERR_* code.  Arguments are checked on
+ *    the host before anything is launched; a call that returns an error other
+ *    than LP_ERR_HIP has launched nothing.  No exception crosses this ABI.
+ *  - Node ids, row pointers and column indices are int32; the number of
+ *    directed entries (nnz) must stay below 2^31.
+ */
+#ifndef LP_H_
+#define LP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LP_MAX_LAYERS 8
+
+enum {
+    LP_OK = 0,
+    LP_ERR_INVALID_ARG = -1,  /* null pointer, negative size, misaligned matrix, bad layer count */
+    LP_ERR_OUT_OF_RANGE = -2, /* node id outside [0, n_nodes), or sizes beyond int32 indexing */
+    LP_ERR_WORKSPACE = -3,    /* ws is NULL or smaller than *_workspace_bytes() */
+    LP_ERR_UNSUPPORTED = -4,  /* dtype other than LP_F32, or a width that is not a multiple of 4 */
+    LP_ERR_HIP = -5           /* the HIP runtime reported an error (no device, failed launch) */
+};
+
+enum { LP_F32 = 0 };
+
+/* flags of lp_build_csr */
+#define LP_SYMMETRIZE 1u /* every input pair (r, c) also counts as (c, r) */
+
+/* Visible graph of one worker in canonical CSR form, plus its transpose.
+ * Row v lists N(v), the nodes v aggregates from (Eq. 1), ascending and without
+ * repeats.  Row u of the transposed CSR lists the nodes v with u in N(v). */
+typedef struct lp_csr {
+    int32_t n_nodes;
+    int32_t reserved_;
+    int64_t nnz;               /* entries of colidx and of t_colidx */
+    const int32_t *rowptr;     /* device [n_nodes + 1] */
+    const int32_t *colidx;     /* device [nnz] */
+    const int32_t *t_rowptr;   /* device [n_nodes + 1] */
+    const int32_t *t_colidx;   /* device [nnz] */
+    const float *inv_deg;      /* device [n_nodes]: 1/|N(v)|, 0 when N(v) is empty */
+    const int32_t *row_order;  /* device [n_nodes] or NULL: rows by decreasing |N(v)| (launch order hint) */
+    const int32_t *t_row_order;/* device [n_nodes] or NULL: same for the transposed CSR */
+} lp_csr;
+
+/* K-layer GraphSAGE-mean model.  Layer k = 1..K maps width dims[k-1] to dims[k]:
+ *   z_v = h_v W_self[k-1] + mean_{u in N(v)} h_u W_neigh[k-1] + bias[k-1]
+ *   h'_v = max(z_v, 0) for k < K and z_v for k = K. */
+typedef struct lp_model {
+    int32_t n_layers;                     /* K, 1..LP_MAX_LAYERS */
+    int32_t dtype;                        /* LP_F32 */
+    int32_t dims[LP_MAX_LAYERS + 1];      /* F_0 .. F_K */
+    int32_t reserved_;
+    const void *W_self[LP_MAX_LAYERS];    /* device [F_{k-1}, F_k] */
+    const void *W_neigh[LP_MAX_LAYERS];   /* device [F_{k-1}, F_k] */
+    const void *bias[LP_MAX_LAYERS];      /* device [F_k] */
+} lp_model;
+
+/* Activations written by lp_sage_forward and read by lp_backward. */
+typedef struct lp_acts {
+    void *A[LP_MAX_LAYERS]; /* A[k-1]: device [n_nodes, F_{k-1}], neighbourhood mean of layer k's input */
+    void *H[LP_MAX_LAYERS]; /* H[k-1]: device [n_nodes, F_k], output of layer k; H[K-1] are the embeddings */
+} lp_acts;
+
+/* Gradients written (overwritten, not accumulated) by lp_backward; always fp32. */
+typedef struct lp_grads {
+    float *dW_self[LP_MAX_LAYERS];  /* device [F_{k-1}, F_k] */
+    float *dW_neigh[LP_MAX_LAYERS]; /* device [F_{k-1}, F_k] */
+    float *dbias[LP_MAX_LAYERS];    /* device [F_k] */
+    float *dX;                      /* device [n_nodes, F_0] or NULL to skip the input gradient */
+} lp_grads;
+
+/* Text for a status code (static storage, never NULL). */
+const char *lp_strerror(int status);
+
+/* ---------------------------------------------------------------------------
+ * lp_build_csr - canonical CSR of the visible edge set (Sec. II-A: the graph
+ * is a node set with a set of node pairs; Sec. IV-A: undirected, unweighted,
+ * degree d_v = number of neighbours).  Done once per graph, not per step.
+ *
+ * rows/cols: device [n_in], the pair (rows[i], cols[i]) puts cols[i] into
+ * N(rows[i]).  Repeated pairs collapse; a pair with rows[i] == cols[i] is kept
+ * as an ordinary entry.  With LP_SYMMETRIZE each pair also counts reversed.
+ * Outputs (device): rowptr, t_rowptr [n_nodes+1]; colidx, t_colidx with room
+ * for n_in entries (2*n_in with LP_SYMMETRIZE); inv_deg [n_nodes]; row_order
+ * and t_row_order [n_nodes] (both may be NULL).  *nnz_out (HOST pointer)
+ * receives the number of entries.  There is exactly one correct output.
+ *
+ * This call waits for the stream before it returns (it reads nnz back).
+ * Errors: LP_ERR_OUT_OF_RANGE if an id lies outside [0, n_nodes) - detected
+ * on the device without any out-of-bounds access; outputs are then undefined.
+ */
+size_t lp_build_csr_workspace_bytes(int32_t n_nodes, int64_t n_in, uint32_t flags);
+int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, const int32_t *cols, uint32_t flags,
+                 int32_t *rowptr, int32_t *colidx, int32_t *t_rowptr, int32_t *t_colidx, float *inv_deg,
+                 int32_t *row_order, int32_t *t_row_order, int64_t *nnz_out, void *ws, size_t ws_bytes,
+                 void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_sage_forward - the K aggregation layers of Eq. (1) for every visible
+ * node (Algorithm 1, the loop "for k = 1 to K compute h_v^(k)"), with h^(0) = x.
+ * X: device [n_nodes, F_0].  Fills saved->A[k-1] and saved->H[k-1] for
+ * k = 1..K; the embeddings are saved->H[K-1].  A node without neighbours
+ * aggregates the zero vector.
+ */
+size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes);
+int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_sample_neg - per-source uniform negative sampling (Sec. II-B; Algorithm 1,
+ * "Generate negative samples"): sample q = i*k_neg + j keeps the source
+ * u = pos_src[i] and receives a destination drawn uniformly from [0, n_space)
+ * that is neither u nor a member of N(u).
+ *
+ * Random stream: attempt t of sample q uses 32-bit word (t mod 4) of
+ * Philox4x32-10 with counter (q, t div 4, step_lo, step_hi) and key
+ * (seed_lo, seed_hi); the candidate is floor(word * n_space / 2^32).  The
+ * first valid candidate of attempts 0..15 is taken; after sixteen rejections
+ * the nodes following the last candidate (mod n_space) are tried in order.  If
+ * no node is valid, the last candidate is written and *n_failed incremented.
+ * The result is a pure function of (graph, pos_src, k_neg, n_space, seed, step).
+ *
+ * pos_src: device [n_pos].  neg_dst: device [n_pos*k_neg].  neg_src: device
+ * [n_pos*k_neg] or NULL; receives the kept source of each sample.  n_failed:
+ * device int32 or NULL; the caller zeroes it.  n_pos*k_neg must be < 2^31.
+ * Sources must lie in [0, g->n_nodes); a source outside is treated as having
+ * no neighbours.
+ */
+int lp_sample_neg(const lp_csr *g, int64_t n_pos, const int32_t *pos_src, int32_t k_neg, int32_t n_space,
+                  uint64_t seed, uint64_t step, int32_t *neg_dst, int32_t *neg_src, int32_t *n_failed,
+                  void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_score_loss - edge scores, loss and its derivative (Eq. 2 with the dot
+ * product; Algorithm 1, the per-edge loop and "Compute L^i"):
+ *   s_e = <H[e_src[e]], H[e_dst[e]]>,  y_e = 1 for e < n_pos_edges else 0,
+ *   l_e = -[y ln sigma(s) + (1-y) ln(1-sigma(s))],  loss = (1/B) sum_e l_e,
+ *   dscore_e = (sigma(s_e) - y_e) / B.
+ * HK: device [n_nodes, F].  e_src, e_dst: device [B], ids in [0, n_nodes)
+ * (an edge with an id outside is scored 0 and gets dscore 0, and still counts
+ * in B).  scores: device [B].  loss: device float.  dscore: device [B] or NULL.
+ * The loss is summed in a fixed order, so repeated calls give the same bits.
+ */
+size_t lp_score_loss_workspace_bytes(int64_t B);
+int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                  const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_backward - gradient of the batch loss with respect to all weights
+ * (Algorithm 1, "Compute the gradient"): scatters dscore through the dot
+ * product into dL/dH^K, then walks the layers K..1 through the ReLU, the two
+ * linear maps and the adjoint of the mean aggregation (transposed CSR).
+ * X and `saved` are the input and result of the lp_sage_forward call for the
+ * same graph and model; e_src/e_dst/dscore as in lp_score_loss.
+ */
+size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes);
+int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                const int32_t *e_src, const int32_t *e_dst, const float *dscore, lp_grads *out, void *ws,
+                size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_H_ */

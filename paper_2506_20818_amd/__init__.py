@@ -1,0 +1,22 @@
+"""MI355X-native training step for GNN link prediction (one worker of the data-parallel method).
+
+Thin Python binding over the C ABI declared in include/lp.h.  The binding only marshals arguments; every step
+runs in the HIP kernels of liblp_mi355x.so.  There is no CPU fallback: importing `binding` without the built
+library raises.
+"""
+from .binding import (  # noqa: F401
+    LP_SYMMETRIZE,
+    Acts,
+    Csr,
+    Grads,
+    LpError,
+    Model,
+    lib_path,
+    load_library,
+    lp_backward,
+    lp_build_csr,
+    lp_sage_forward,
+    lp_sample_neg,
+    lp_score_loss,
+    lp_strerror,
+)

@@ -1,0 +1,280 @@
+"""ctypes binding of include/lp.h.  Argument marshalling only.
+
+torch is used for device memory and the current HIP stream; no tensor arithmetic happens here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional
+
+import torch
+
+LP_MAX_LAYERS = 8
+LP_SYMMETRIZE = 1
+LP_F32 = 0
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class LpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, lp_strerror(status), status))
+
+
+class _CsrStruct(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("reserved_", C.c_int32), ("nnz", C.c_int64),
+                ("rowptr", C.c_void_p), ("colidx", C.c_void_p), ("t_rowptr", C.c_void_p), ("t_colidx", C.c_void_p),
+                ("inv_deg", C.c_void_p), ("row_order", C.c_void_p), ("t_row_order", C.c_void_p)]
+
+
+class _ModelStruct(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("dtype", C.c_int32), ("dims", C.c_int32 * (LP_MAX_LAYERS + 1)),
+                ("reserved_", C.c_int32),
+                ("W_self", C.c_void_p * LP_MAX_LAYERS), ("W_neigh", C.c_void_p * LP_MAX_LAYERS),
+                ("bias", C.c_void_p * LP_MAX_LAYERS)]
+
+
+class _ActsStruct(C.Structure):
+    _fields_ = [("A", C.c_void_p * LP_MAX_LAYERS), ("H", C.c_void_p * LP_MAX_LAYERS)]
+
+
+class _GradsStruct(C.Structure):
+    _fields_ = [("dW_self", C.c_void_p * LP_MAX_LAYERS), ("dW_neigh", C.c_void_p * LP_MAX_LAYERS),
+                ("dbias", C.c_void_p * LP_MAX_LAYERS), ("dX", C.c_void_p)]
+
+
+EXPORTS = {
+    "lp_strerror": (C.c_char_p, [C.c_int]),
+    "lp_build_csr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_uint32]),
+    "lp_build_csr": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
+                               C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_sage_forward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
+    "lp_sage_forward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
+                                  C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_sample_neg": (C.c_int, [C.POINTER(_CsrStruct), C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
+                                C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "lp_score_loss_workspace_bytes": (C.c_size_t, [C.c_int64]),
+    "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
+    "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
+                              C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
+                              C.c_size_t, C.c_void_p]),
+}
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "liblp_mi355x.so")
+
+
+def load_library():
+    """Load liblp_mi355x.so.  There is no fallback: a missing library is an error."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError("%s is not built; run `python -m paper_2506_20818_amd.build`" % path)
+        lib = C.CDLL(path)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = lib
+    return _LIB
+
+
+def lp_strerror(status: int) -> str:
+    return load_library().lp_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LpError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _need(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous device tensor of %s" % (name, dtype))
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+class Csr:
+    """Device CSR of the visible graph, its transpose, inverse degrees and degree-ordered row lists."""
+
+    def __init__(self, n_nodes, nnz, rowptr, colidx, t_rowptr, t_colidx, inv_deg, row_order, t_row_order):
+        self.n_nodes, self.nnz = int(n_nodes), int(nnz)
+        self.rowptr, self.colidx, self.t_rowptr, self.t_colidx = rowptr, colidx, t_rowptr, t_colidx
+        self.inv_deg, self.row_order, self.t_row_order = inv_deg, row_order, t_row_order
+        s = _CsrStruct()
+        s.n_nodes, s.nnz = self.n_nodes, self.nnz
+        s.rowptr, s.colidx = rowptr.data_ptr(), colidx.data_ptr()
+        s.t_rowptr, s.t_colidx = t_rowptr.data_ptr(), t_colidx.data_ptr()
+        s.inv_deg = inv_deg.data_ptr()
+        s.row_order = row_order.data_ptr() if row_order is not None else None
+        s.t_row_order = t_row_order.data_ptr() if t_row_order is not None else None
+        self.c = s
+
+
+class Model:
+    """Weights of the K layers: W_self[k], W_neigh[k] of shape [F_{k-1}, F_k] and bias[k] of shape [F_k]."""
+
+    def __init__(self, W_self: List[torch.Tensor], W_neigh: List[torch.Tensor], bias: List[torch.Tensor]):
+        K = len(W_self)
+        if not (1 <= K <= LP_MAX_LAYERS and len(W_neigh) == K and len(bias) == K):
+            raise ValueError("bad layer count")
+        self.W_self, self.W_neigh, self.bias = list(W_self), list(W_neigh), list(bias)
+        self.dims = [int(W_self[0].shape[0])] + [int(w.shape[1]) for w in W_self]
+        s = _ModelStruct()
+        s.n_layers, s.dtype = K, LP_F32
+        for k in range(K + 1):
+            s.dims[k] = self.dims[k]
+        for k in range(K):
+            for t, nm in ((W_self[k], "W_self"), (W_neigh[k], "W_neigh")):
+                _need(t, torch.float32, nm)
+                if tuple(t.shape) != (self.dims[k], self.dims[k + 1]):
+                    raise ValueError("%s[%d] has the wrong shape" % (nm, k))
+            _need(bias[k], torch.float32, "bias")
+            s.W_self[k], s.W_neigh[k], s.bias[k] = W_self[k].data_ptr(), W_neigh[k].data_ptr(), bias[k].data_ptr()
+        self.c = s
+
+
+class Acts:
+    """Saved activations: A[k-1] = mean-aggregated input of layer k, H[k-1] = output of layer k."""
+
+    def __init__(self, n_nodes: int, dims: List[int], device):
+        K = len(dims) - 1
+        self.A = [torch.empty((n_nodes, dims[k]), dtype=torch.float32, device=device) for k in range(K)]
+        self.H = [torch.empty((n_nodes, dims[k + 1]), dtype=torch.float32, device=device) for k in range(K)]
+        s = _ActsStruct()
+        for k in range(K):
+            s.A[k], s.H[k] = self.A[k].data_ptr(), self.H[k].data_ptr()
+        self.c = s
+
+
+class Grads:
+    def __init__(self, n_nodes: int, dims: List[int], device, want_dX: bool = False):
+        K = len(dims) - 1
+        mk = lambda *shape: torch.empty(shape, dtype=torch.float32, device=device)
+        self.dW_self = [mk(dims[k], dims[k + 1]) for k in range(K)]
+        self.dW_neigh = [mk(dims[k], dims[k + 1]) for k in range(K)]
+        self.dbias = [mk(dims[k + 1]) for k in range(K)]
+        self.dX = mk(n_nodes, dims[0]) if want_dX else None
+        s = _GradsStruct()
+        for k in range(K):
+            s.dW_self[k], s.dW_neigh[k], s.dbias[k] = (self.dW_self[k].data_ptr(), self.dW_neigh[k].data_ptr(),
+                                                       self.dbias[k].data_ptr())
+        s.dX = self.dX.data_ptr() if want_dX else None
+        self.c = s
+
+
+# ----------------------------------------------------------------------------------------------------------
+def lp_build_csr(n_nodes: int, rows: torch.Tensor, cols: torch.Tensor, symmetrize: bool,
+                 with_row_order: bool = True) -> Csr:
+    lib = load_library()
+    _need(rows, torch.int32, "rows")
+    _need(cols, torch.int32, "cols")
+    dev = rows.device
+    n_in = int(rows.numel())
+    flags = LP_SYMMETRIZE if symmetrize else 0
+    cap = max(1, n_in * (2 if symmetrize else 1))
+    i32 = lambda n: torch.empty(n, dtype=torch.int32, device=dev)
+    rowptr, t_rowptr = i32(n_nodes + 1), i32(n_nodes + 1)
+    colidx, t_colidx = i32(cap), i32(cap)
+    inv_deg = torch.empty(n_nodes, dtype=torch.float32, device=dev)
+    row_order = i32(n_nodes) if with_row_order else None
+    t_row_order = i32(n_nodes) if with_row_order else None
+    ws_bytes = lib.lp_build_csr_workspace_bytes(n_nodes, n_in, flags)
+    ws = _ws(ws_bytes, dev)
+    nnz = C.c_int64(0)
+    _check(lib.lp_build_csr(n_nodes, n_in, _ptr(rows), _ptr(cols), flags, _ptr(rowptr), _ptr(colidx), _ptr(t_rowptr),
+                            _ptr(t_colidx), _ptr(inv_deg), _ptr(row_order), _ptr(t_row_order), C.byref(nnz), _ptr(ws),
+                            ws.numel(), _stream()), "lp_build_csr")
+    n = int(nnz.value)
+    return Csr(n_nodes, n, rowptr, colidx[:n], t_rowptr, t_colidx[:n], inv_deg, row_order, t_row_order)
+
+
+def lp_sage_forward(g: Csr, m: Model, X: torch.Tensor, acts: Optional[Acts] = None, ws: Optional[torch.Tensor] = None) -> Acts:
+    lib = load_library()
+    _need(X, torch.float32, "X")
+    if tuple(X.shape) != (g.n_nodes, m.dims[0]):
+        raise ValueError("X has the wrong shape")
+    if acts is None:
+        acts = Acts(g.n_nodes, m.dims, X.device)
+    if ws is None:
+        ws = _ws(lib.lp_sage_forward_workspace_bytes(C.byref(m.c), g.n_nodes), X.device)
+    _check(lib.lp_sage_forward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), _ptr(ws), ws.numel(), _stream()),
+           "lp_sage_forward")
+    return acts
+
+
+def lp_sample_neg(g: Csr, pos_src: torch.Tensor, k_neg: int, n_space: int, seed: int, step: int,
+                  neg_dst: Optional[torch.Tensor] = None, neg_src: Optional[torch.Tensor] = None,
+                  n_failed: Optional[torch.Tensor] = None):
+    lib = load_library()
+    _need(pos_src, torch.int32, "pos_src")
+    n_pos = int(pos_src.numel())
+    if neg_dst is None:
+        neg_dst = torch.empty(n_pos * k_neg, dtype=torch.int32, device=pos_src.device)
+    _check(lib.lp_sample_neg(C.byref(g.c), n_pos, _ptr(pos_src), k_neg, n_space, seed, step, _ptr(neg_dst), _ptr(neg_src),
+                             _ptr(n_failed), _stream()), "lp_sample_neg")
+    return neg_dst
+
+
+def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_pos_edges: int,
+                  scores: Optional[torch.Tensor] = None, loss: Optional[torch.Tensor] = None,
+                  dscore: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    lib = load_library()
+    _need(HK, torch.float32, "HK")
+    _need(e_src, torch.int32, "e_src")
+    _need(e_dst, torch.int32, "e_dst")
+    B = int(e_src.numel())
+    dev = HK.device
+    if scores is None:
+        scores = torch.empty(B, dtype=torch.float32, device=dev)
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+    if dscore is None:
+        dscore = torch.empty(B, dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = _ws(lib.lp_score_loss_workspace_bytes(B), dev)
+    _check(lib.lp_score_loss(_ptr(HK), HK.shape[0], HK.shape[1], LP_F32, B, n_pos_edges, _ptr(e_src), _ptr(e_dst),
+                             _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(ws), ws.numel(), _stream()), "lp_score_loss")
+    return scores, loss, dscore
+
+
+def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tensor, e_dst: torch.Tensor,
+                dscore: torch.Tensor, grads: Optional[Grads] = None, ws: Optional[torch.Tensor] = None,
+                want_dX: bool = False) -> Grads:
+    lib = load_library()
+    _need(X, torch.float32, "X")
+    _need(dscore, torch.float32, "dscore")
+    if grads is None:
+        grads = Grads(g.n_nodes, m.dims, X.device, want_dX)
+    if ws is None:
+        ws = _ws(lib.lp_backward_workspace_bytes(C.byref(m.c), g.n_nodes), X.device)
+    _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
+                           _ptr(e_dst), _ptr(dscore), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward")
+    return grads
+
+
+def backward_workspace_bytes(m: Model, n_nodes: int) -> int:
+    return int(load_library().lp_backward_workspace_bytes(C.byref(m.c), n_nodes))
+
+
+def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
+    return int(load_library().lp_sage_forward_workspace_bytes(C.byref(m.c), n_nodes))

@@ -1,0 +1,370 @@
+// Dense products of the layer update (the UPDATE of Eq. 1 of the paper as two linear maps plus bias) and of its
+// backward pass, on the fp32 matrix cores of gfx950 (v_mfma_f32_32x32x2_f32, wavefront of 64 lanes).
+//
+// NT kernel (forward transform, input-gradient transform): both operands have the reduction index contiguous.
+//   Workgroup: 256 threads = 2x2 wavefronts, tile 128 x BN (BN = 128 or 64), K step 32.
+//   LDS: A tile [128][32+4] and B tile [BN][32+4] floats.  The +4 padding makes the 16-byte operand reads
+//   conflict free: eight consecutive rows start in eight different groups of four banks.
+//   One MFMA consumes k = {h, h'} for lane halves h = 0/1.  Since a sum over k may be taken in any order, lane
+//   half h reads the four consecutive k values 4h..4h+3 of each group of eight with a single 16-byte LDS load
+//   and feeds them to four successive MFMAs; A and B use the same assignment, so every k meets its partner.
+// TN kernel (weight gradients): the reduction index (nodes) is the slow index of both operands; tiles are
+//   copied to LDS as they are and read 4 bytes per lane (consecutive lanes, consecutive banks).  The node range
+//   is split over the grid; partial tiles are written out and summed in a fixed order by a second kernel.
+#include "lp_internal.h"
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int BM = 128;
+constexpr int BK = 32;
+constexpr int LDS_LD = BK + 4;
+
+__device__ inline v16f mfma32(float a, float b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+
+// ------------------------------------------------------------------------------------------------ NT
+struct NtTile {  // which K-part and offset a K-tile index refers to
+    int s, k0;
+};
+
+template <int NB>  // 32-column blocks per wavefront: BN = 64 * NB
+__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(GemmNtArgs g) {
+    constexpr int BN = 64 * NB;
+    constexpr int WN = 32 * NB;                 // columns per wavefront
+    constexpr int A_LOADS = BM * BK / 4 / kThreads;  // float4 per thread: 4
+    constexpr int B_LOADS = BN * BK / 4 / kThreads;  // 4 or 2
+    __shared__ float As[BM * LDS_LD];
+    __shared__ float Bs[BN * LDS_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int tiles0 = (g.K[0] + BK - 1) / BK, tiles1 = (g.K[1] + BK - 1) / BK;
+    const int n_tiles = tiles0 + tiles1;
+
+    v16f acc[2][NB];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+
+    float4 ra[A_LOADS], rbv[B_LOADS];
+    auto fetch = [&](int t) {
+        const int s = t < tiles0 ? 0 : 1;
+        const int k0 = (s ? t - tiles0 : t) * BK;
+        const float *__restrict__ A = s ? g.A[1] : g.A[0];  // explicit selects keep the argument block in SGPRs
+        const int K = s ? g.K[1] : g.K[0];
+        const int lda = s ? g.lda[1] : g.lda[0];
+        const int ldb = s ? g.ldb[1] : g.ldb[0];
+        const float *__restrict__ Bt0 = s ? g.Bt[1][0] : g.Bt[0][0];
+        const float *__restrict__ Bt1 = s ? g.Bt[1][1] : g.Bt[0][1];
+#pragma unroll
+        for (int p = 0; p < A_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            const int row = idx >> 3, k = k0 + ((idx & 7) << 2);
+            const int64_t m = m0 + row;
+            ra[p] = (m < g.M && k < K) ? *reinterpret_cast<const float4 *>(A + m * lda + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int p = 0; p < B_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            const int row = idx >> 3, k = k0 + ((idx & 7) << 2);
+            const int n = n0 + row;
+            const float *__restrict__ brow = n < g.n_split ? Bt0 + (int64_t)n * ldb : Bt1 + (int64_t)(n - g.n_split) * ldb;
+            rbv[p] = (n < g.N && k < K) ? *reinterpret_cast<const float4 *>(brow + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < A_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            *reinterpret_cast<float4 *>(&As[(idx >> 3) * LDS_LD + ((idx & 7) << 2)]) = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            *reinterpret_cast<float4 *>(&Bs[(idx >> 3) * LDS_LD + ((idx & 7) << 2)]) = rbv[p];
+        }
+    };
+
+    if (n_tiles > 0) fetch(0);
+    for (int t = 0; t < n_tiles; ++t) {
+        __syncthreads();  // previous tile fully consumed
+        stash();
+        __syncthreads();
+        if (t + 1 < n_tiles) fetch(t + 1);  // global loads overlap the MFMAs below
+#pragma unroll
+        for (int kk = 0; kk < BK / 8; ++kk) {
+            float4 a[2], b[NB];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+                a[rb] = *reinterpret_cast<const float4 *>(&As[(wm * 64 + rb * 32 + i32) * LDS_LD + kk * 8 + 4 * h]);
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb)
+                b[cb] = *reinterpret_cast<const float4 *>(&Bs[(wn * WN + cb * 32 + i32) * LDS_LD + kk * 8 + 4 * h]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb) {
+                    acc[rb][cb] = mfma32(a[rb].x, b[cb].x, acc[rb][cb]);
+                    acc[rb][cb] = mfma32(a[rb].y, b[cb].y, acc[rb][cb]);
+                    acc[rb][cb] = mfma32(a[rb].z, b[cb].z, acc[rb][cb]);
+                    acc[rb][cb] = mfma32(a[rb].w, b[cb].w, acc[rb][cb]);
+                }
+        }
+    }
+
+    // epilogue: accumulator register r of lane (j = lane % 32, h = lane / 32) is row 8*(r/4) + 4*h + r%4, column j
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+        const int n = n0 + wn * WN + cb * 32 + i32;
+        if (n >= g.N) continue;
+        const float bias = g.bias ? g.bias[n] : 0.f;
+        const bool second = n >= g.n_split;
+        float *__restrict__ C = second ? g.C[1] : g.C[0];
+        const int ldc = second ? g.ldc[1] : g.ldc[0];
+        const int nc = second ? n - g.n_split : n;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m >= g.M) continue;
+                float y = acc[rb][cb][r] + bias;
+                if (g.relu) y = fmaxf(y, 0.f);
+                if (second && g.rowscale) y *= g.rowscale[m];
+                C[m * ldc + nc] = y;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ TN
+constexpr int TN_LD = 128 + 4;
+
+template <int MB, int NBk>  // 32-row / 32-column blocks per wavefront: tile (64*MB) x (64*NBk)
+__global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chunk) {
+    constexpr int TM = 64 * MB, TNn = 64 * NBk;
+    __shared__ float As[BK * TN_LD];
+    __shared__ float Bs[BK * TN_LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int tiles_n = (g.Nw + TNn - 1) / TNn;
+    const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TNn;
+    const int64_t kbeg = (int64_t)blockIdx.y * chunk;
+    const int64_t kend = kbeg + chunk < g.Kn ? kbeg + chunk : g.Kn;
+
+    v16f acc[MB][NBk];
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NBk; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+
+    constexpr int A_LOADS = BK * TM / 4 / kThreads;   // 4 or 2
+    constexpr int B_LOADS = BK * TNn / 4 / kThreads;
+    float4 ra[A_LOADS], rbv[B_LOADS];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int p = 0; p < A_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            const int kr = idx / (TM / 4), c = (idx % (TM / 4)) << 2;
+            const int64_t k = k0 + kr;
+            ra[p] = (k < kend && m0 + c < g.Mw) ? *reinterpret_cast<const float4 *>(g.At + k * g.lda + m0 + c)
+                                                : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int p = 0; p < B_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            const int kr = idx / (TNn / 4), c = (idx % (TNn / 4)) << 2;
+            const int64_t k = k0 + kr;
+            rbv[p] = (k < kend && n0 + c < g.Nw) ? *reinterpret_cast<const float4 *>(g.B + k * g.ldb + n0 + c)
+                                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < A_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            *reinterpret_cast<float4 *>(&As[(idx / (TM / 4)) * TN_LD + ((idx % (TM / 4)) << 2)]) = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_LOADS; ++p) {
+            const int idx = p * kThreads + tid;
+            *reinterpret_cast<float4 *>(&Bs[(idx / (TNn / 4)) * TN_LD + ((idx % (TNn / 4)) << 2)]) = rbv[p];
+        }
+    };
+
+    if (kbeg < kend) fetch(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (k0 + BK < kend) fetch(k0 + BK);
+#pragma unroll
+        for (int kp = 0; kp < BK / 2; ++kp) {
+            float a[MB], b[NBk];
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb) a[rb] = As[(kp * 2 + h) * TN_LD + wm * 32 * MB + rb * 32 + i32];
+#pragma unroll
+            for (int cb = 0; cb < NBk; ++cb) b[cb] = Bs[(kp * 2 + h) * TN_LD + wn * 32 * NBk + cb * 32 + i32];
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NBk; ++cb) acc[rb][cb] = mfma32(a[rb], b[cb], acc[rb][cb]);
+        }
+    }
+    float *__restrict__ P = g.partials + (int64_t)blockIdx.y * g.Mw * g.Nw;
+#pragma unroll
+    for (int cb = 0; cb < NBk; ++cb) {
+        const int n = n0 + wn * 32 * NBk + cb * 32 + i32;
+        if (n >= g.Nw) continue;
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 32 * MB + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < g.Mw) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
+            }
+    }
+}
+
+__global__ void sum_partials_kernel(const float *__restrict__ partials, int n_parts, int64_t n, float *__restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int p = 0; p < n_parts; ++p) s += partials[(int64_t)p * n + i];
+    out[i] = s;
+}
+
+struct TnPlan {
+    int tm, tn, tiles, splits, chunk;
+};
+
+TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
+    TnPlan p;
+    p.tm = Mw > 64 ? 128 : 64;
+    p.tn = Nw > 64 ? 128 : 64;
+    p.tiles = (int)(lp_ceil_div(Mw, p.tm) * lp_ceil_div(Nw, p.tn));
+    int64_t want = lp_ceil_div(1024, p.tiles);          // about four workgroups per compute unit
+    int64_t max_by_len = lp_ceil_div(Kn, 8 * BK);       // at least 256 nodes per workgroup
+    int64_t s = want < max_by_len ? want : max_by_len;
+    if (s < 1) s = 1;
+    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), BK) * BK);
+    p.splits = (int)lp_ceil_div(Kn, p.chunk);
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------ small helpers
+__global__ void transpose_kernel(const float *__restrict__ in, int rows, int cols, float *__restrict__ out) {
+    __shared__ float tile[32][33];
+    const int c = blockIdx.x * 32 + threadIdx.x, r0 = blockIdx.y * 32;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (r0 + i < rows && c < cols) tile[i][threadIdx.x] = in[(int64_t)(r0 + i) * cols + c];
+    __syncthreads();
+    const int orow0 = blockIdx.x * 32, ocol = r0 + threadIdx.x;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (orow0 + i < cols && ocol < rows) out[(int64_t)(orow0 + i) * rows + ocol] = tile[threadIdx.x][i];
+}
+
+constexpr int kColsumRows = 1024;
+
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ in, int32_t M, int32_t N,
+                                                                  float *__restrict__ partials) {
+    const int64_t r0 = (int64_t)blockIdx.x * kColsumRows;
+    const int64_t r1 = r0 + kColsumRows < M ? r0 + kColsumRows : M;
+    for (int c = threadIdx.x; c < N; c += kThreads) {
+        float s = 0.f;
+        for (int64_t r = r0; r < r1; ++r) s += in[r * N + c];
+        partials[(int64_t)blockIdx.x * N + c] = s;
+    }
+}
+
+__global__ void zero_kernel(float4 *__restrict__ p4, int64_t n4, float *__restrict__ tail, int n_tail) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n_tail) tail[i] = 0.f;
+}
+
+}  // namespace
+
+int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
+    if (a.M <= 0 || a.N <= 0) return LP_OK;
+    for (int s = 0; s < 2; ++s) {
+        if (a.K[s] <= 0) continue;
+        if ((a.K[s] & 3) || (a.lda[s] & 3) || (a.ldb[s] & 3)) return LP_ERR_UNSUPPORTED;
+        if (!a.A[s] || !a.Bt[s][0] || !lp_aligned16(a.A[s]) || !lp_aligned16(a.Bt[s][0])) return LP_ERR_INVALID_ARG;
+        if (a.n_split < a.N && (!a.Bt[s][1] || !lp_aligned16(a.Bt[s][1]))) return LP_ERR_INVALID_ARG;
+    }
+    if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
+    const unsigned gx = (unsigned)lp_ceil_div(a.M, BM);
+    if (a.N > 64) {
+        hipLaunchKernelGGL((gemm_nt_kernel<2>), dim3(gx, (unsigned)lp_ceil_div(a.N, 128)), dim3(kThreads), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((gemm_nt_kernel<1>), dim3(gx, 1), dim3(kThreads), 0, st, a);
+    }
+    return lp_after_launch();
+}
+
+size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw) {
+    if (Kn <= 0 || Mw <= 0 || Nw <= 0) return 0;
+    const TnPlan p = plan_tn(Kn, Mw, Nw);
+    return lp_align_up(sizeof(float) * (size_t)p.splits * Mw * Nw);
+}
+
+int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
+    if (a.Mw <= 0 || a.Nw <= 0) return LP_OK;
+    if ((a.Mw & 3) || (a.Nw & 3) || (a.lda & 3) || (a.ldb & 3)) return LP_ERR_UNSUPPORTED;
+    if (!a.C || !a.partials) return LP_ERR_INVALID_ARG;
+    if (a.Kn <= 0) return lp_launch_zero(a.C, (int64_t)a.Mw * a.Nw, st);
+    if (!a.At || !a.B || !lp_aligned16(a.At) || !lp_aligned16(a.B)) return LP_ERR_INVALID_ARG;
+    const TnPlan p = plan_tn(a.Kn, a.Mw, a.Nw);
+    const dim3 grid(p.tiles, p.splits);
+    if (p.tm == 128 && p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    else if (p.tm == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<1, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    else hipLaunchKernelGGL((gemm_tn_kernel<1, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    const int64_t n = (int64_t)a.Mw * a.Nw;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)lp_ceil_div(n, 256)), dim3(256), 0, st, a.partials, p.splits, n, a.C);
+    return lp_after_launch();
+}
+
+int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t st) {
+    if (rows <= 0 || cols <= 0) return LP_OK;
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)lp_ceil_div(cols, 32), (unsigned)lp_ceil_div(rows, 32)), dim3(32, 8), 0,
+                       st, in, rows, cols, out);
+    return lp_after_launch();
+}
+
+size_t lp_colsum_partials_bytes(int32_t M, int32_t N) {
+    return lp_align_up(sizeof(float) * (size_t)lp_ceil_div(M > 0 ? M : 1, kColsumRows) * (size_t)(N > 0 ? N : 1));
+}
+
+int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *partials, hipStream_t st) {
+    if (N <= 0) return LP_OK;
+    if (M <= 0) return lp_launch_zero(out, N, st);
+    const int nb = (int)lp_ceil_div(M, kColsumRows);
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(nb), dim3(kThreads), 0, st, in, M, N, partials);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)lp_ceil_div(N, 256)), dim3(256), 0, st, partials, nb, (int64_t)N, out);
+    return lp_after_launch();
+}
+
+int lp_launch_zero(float *p, int64_t n, hipStream_t st) {
+    if (n <= 0) return LP_OK;
+    const int head = (int)((16 - (reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) / 4;  // floats before 16-byte alignment
+    const int64_t h = head < n ? head : n;
+    const int64_t n4 = (n - h) / 4;
+    const int n_tail = (int)(n - h - 4 * n4);
+    if (h) hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(64), 0, st, nullptr, 0, p, (int)h);
+    if (n4 || n_tail)
+        hipLaunchKernelGGL(zero_kernel, dim3((unsigned)lp_ceil_div(n4 > 0 ? n4 : 1, 256)), dim3(256), 0, st,
+                           reinterpret_cast<float4 *>(p + h), n4, p + h + 4 * n4, n_tail);
+    return lp_after_launch();
+}

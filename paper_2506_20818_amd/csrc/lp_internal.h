@@ -1,0 +1,90 @@
+// Internal declarations shared by the HIP translation units of the library.
+// Nothing here is part of the public ABI (that is include/lp.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lp.h"
+
+#define LP_TRY(expr)                         \
+    do {                                     \
+        int lp_status_ = (expr);             \
+        if (lp_status_ != LP_OK) return lp_status_; \
+    } while (0)
+
+#define LP_HIP_TRY(expr)                              \
+    do {                                              \
+        if ((expr) != hipSuccess) return LP_ERR_HIP;  \
+    } while (0)
+
+static inline int lp_after_launch() { return hipGetLastError() == hipSuccess ? LP_OK : LP_ERR_HIP; }
+
+static inline int64_t lp_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t lp_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+static inline bool lp_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---------------------------------------------------------------- sparse aggregation (spmm_mean.hip)
+// out[v, :] = rowscale(v) * sum_{u in row v of (rowptr, colidx)} in[u, :]  (+ addend[v, :])  (* [gate[v, :] > 0])
+//   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1
+// All matrices are [n_rows, F] fp32 with contiguous rows; F % 4 == 0.
+struct SpmmArgs {
+    int32_t n_rows = 0;
+    int32_t F = 0;
+    const int32_t *rowptr = nullptr;
+    const int32_t *colidx = nullptr;
+    const int32_t *row_order = nullptr;  // optional processing order
+    const float *inv_deg = nullptr;      // optional per-output-row scale
+    const float *in = nullptr;
+    const float *addend = nullptr;       // optional [n_rows, F]
+    const float *gate = nullptr;         // optional [n_rows, F]: output is zeroed where gate <= 0
+    float *out = nullptr;
+};
+int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
+
+// ---------------------------------------------------------------- dense products (gemm_mfma.hip)
+// C[M, N] = sum_{s<2} A[s][M, K[s]] * Bt[s][.]^T, operands with the reduction index contiguous ("NT"):
+//   A[s] is [M, K[s]] row-major (leading dimension lda[s]);
+//   the B operand of K-part s is given transposed: column n of the product reads row n of
+//   Bt[s][0] when n < n_split, else row (n - n_split) of Bt[s][1]; rows have K[s] contiguous floats (ldb[s]).
+// Epilogue: + bias[n] (optional), max(.,0) (optional); columns n >= n_split are multiplied by
+// rowscale[m] (optional) and go to C[1] (leading dimension ldc[1]) at column n - n_split, the others to C[0].
+struct GemmNtArgs {
+    int32_t M = 0, N = 0;
+    int32_t n_split = 0;                 // == N when the output is not split
+    const float *A[2] = {nullptr, nullptr};
+    int32_t lda[2] = {0, 0};
+    int32_t K[2] = {0, 0};
+    const float *Bt[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+    int32_t ldb[2] = {0, 0};
+    const float *bias = nullptr;
+    bool relu = false;
+    const float *rowscale = nullptr;
+    float *C[2] = {nullptr, nullptr};
+    int32_t ldc[2] = {0, 0};
+};
+int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t stream);
+
+// dW[Mw, Nw] = At[Kn, Mw]^T * B[Kn, Nw], the reduction index (nodes) is the slow one on both operands ("TN").
+// Also accumulates nothing else; partial sums of the row chunks go to `partials` and are then added up in a
+// fixed order, so the result does not depend on scheduling.
+struct GemmTnArgs {
+    int32_t Kn = 0;                      // reduction length (number of nodes)
+    int32_t Mw = 0, Nw = 0;              // output shape
+    const float *At = nullptr;           // [Kn, Mw], leading dimension lda
+    int32_t lda = 0;
+    const float *B = nullptr;            // [Kn, Nw], leading dimension ldb
+    int32_t ldb = 0;
+    float *C = nullptr;                  // [Mw, Nw] contiguous
+    float *partials = nullptr;           // workspace, lp_gemm_tn_partials_bytes()
+};
+size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw);
+int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t stream);
+
+// out[c, r] = in[r, c] for a small [rows, cols] matrix (weights).
+int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t stream);
+// out[n] = sum_m in[m, n], fixed summation order; partials: lp_colsum_partials_bytes()
+size_t lp_colsum_partials_bytes(int32_t M, int32_t N);
+int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *partials, hipStream_t stream);
+// fill n floats with zero (kernel, so that callers may capture it)
+int lp_launch_zero(float *p, int64_t n, hipStream_t stream);

@@ -1,0 +1,253 @@
+// lp_sage_forward and lp_backward: the K GraphSAGE-mean layers (Eq. 1 of the paper with the mean aggregator and
+// two linear maps per layer) over every visible node, and the reverse walk through them (Algorithm 1, "Compute
+// the gradient").  Host-side orchestration only; the work is done by the kernels in spmm_mean.hip and
+// gemm_mfma.hip plus the edge-gradient scatter below.
+#include "lp_internal.h"
+
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
+
+namespace {
+
+int check_model(const lp_model *m) {
+    if (!m || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
+    if (m->dtype != LP_F32) return LP_ERR_UNSUPPORTED;
+    for (int k = 0; k <= m->n_layers; ++k) {
+        if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
+        if ((m->dims[k] & 3) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;
+    }
+    for (int k = 0; k < m->n_layers; ++k) {
+        if (!m->W_self[k] || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
+        if (!lp_aligned16(m->W_self[k]) || !lp_aligned16(m->W_neigh[k])) return LP_ERR_INVALID_ARG;
+    }
+    return LP_OK;
+}
+
+int check_graph(const lp_csr *g, bool need_transpose) {
+    if (!g || g->n_nodes <= 0 || g->nnz < 0 || !g->rowptr || !g->inv_deg) return LP_ERR_INVALID_ARG;
+    if (g->nnz >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
+    if (g->nnz > 0 && !g->colidx) return LP_ERR_INVALID_ARG;
+    if (need_transpose && (!g->t_rowptr || (g->nnz > 0 && !g->t_colidx))) return LP_ERR_INVALID_ARG;
+    return LP_OK;
+}
+
+int check_acts(const lp_model *m, const lp_acts *a) {
+    if (!a) return LP_ERR_INVALID_ARG;
+    for (int k = 0; k < m->n_layers; ++k)
+        if (!a->A[k] || !a->H[k] || !lp_aligned16(a->A[k]) || !lp_aligned16(a->H[k])) return LP_ERR_INVALID_ARG;
+    return LP_OK;
+}
+
+size_t transposed_weight_floats(const lp_model *m) {
+    size_t n = 0;
+    for (int k = 0; k < m->n_layers; ++k) n += 2 * lp_align_up((size_t)m->dims[k] * m->dims[k + 1], 64);
+    return n;
+}
+
+int max_dim(const lp_model *m) {
+    int d = 0;
+    for (int k = 0; k <= m->n_layers; ++k) d = m->dims[k] > d ? m->dims[k] : d;
+    return d;
+}
+
+// dL/dH^K: every scored edge (u, v) with weight g = dL/ds adds g*h_v to row u and g*h_u to row v.
+// A group of G lanes owns an edge; rows are updated with hardware fp32 atomic adds.
+template <int G>
+__global__ __launch_bounds__(256) void edge_grad_scatter_kernel(const float *__restrict__ H, int32_t n_nodes, int32_t F, int64_t B,
+                                                                const int32_t *__restrict__ e_src,
+                                                                const int32_t *__restrict__ e_dst,
+                                                                const float *__restrict__ dscore, float *__restrict__ Gout) {
+    const int sub = threadIdx.x % G;
+    const int64_t e = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+    if (e >= B) return;
+    const int32_t u = e_src[e], v = e_dst[e];
+    if (u < 0 || u >= n_nodes || v < 0 || v >= n_nodes) return;
+    const float g = dscore[e];
+    const int F4 = F >> 2;
+    const float4 *hu = reinterpret_cast<const float4 *>(H + (int64_t)u * F);
+    const float4 *hv = reinterpret_cast<const float4 *>(H + (int64_t)v * F);
+    float *gu = Gout + (int64_t)u * F, *gv = Gout + (int64_t)v * F;
+    for (int j = sub; j < F4; j += G) {
+        const float4 a = hu[j], b = hv[j];
+        unsafeAtomicAdd(gu + 4 * j + 0, g * b.x);
+        unsafeAtomicAdd(gu + 4 * j + 1, g * b.y);
+        unsafeAtomicAdd(gu + 4 * j + 2, g * b.z);
+        unsafeAtomicAdd(gu + 4 * j + 3, g * b.w);
+        unsafeAtomicAdd(gv + 4 * j + 0, g * a.x);
+        unsafeAtomicAdd(gv + 4 * j + 1, g * a.y);
+        unsafeAtomicAdd(gv + 4 * j + 2, g * a.z);
+        unsafeAtomicAdd(gv + 4 * j + 3, g * a.w);
+    }
+}
+
+int launch_edge_scatter(const float *H, int32_t n_nodes, int32_t F, int64_t B, const int32_t *e_src, const int32_t *e_dst,
+                        const float *dscore, float *Gout, hipStream_t st) {
+    if (B <= 0) return LP_OK;
+    int G = 8;
+    while (G < 64 && G * 4 < F) G <<= 1;
+    const unsigned grid = (unsigned)lp_ceil_div(B, 256 / G);
+#define LP_CASE(g)                                                                                                           \
+    case g:                                                                                                                  \
+        hipLaunchKernelGGL((edge_grad_scatter_kernel<g>), dim3(grid), dim3(256), 0, st, H, n_nodes, F, B, e_src, e_dst,      \
+                           dscore, Gout);                                                                                    \
+        break;
+    switch (G) {
+        LP_CASE(8)
+        LP_CASE(16)
+        LP_CASE(32)
+        default:
+            hipLaunchKernelGGL((edge_grad_scatter_kernel<64>), dim3(grid), dim3(256), 0, st, H, n_nodes, F, B, e_src, e_dst,
+                               dscore, Gout);
+    }
+#undef LP_CASE
+    return lp_after_launch();
+}
+
+struct BackwardWs {
+    float *buf[3];
+    float *tn_partials;
+    float *colsum_partials;
+    size_t bytes;
+};
+
+BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes) {
+    char *p = static_cast<char *>(ws);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += lp_align_up(bytes); return reinterpret_cast<float *>(q); };
+    BackwardWs w;
+    const size_t big = sizeof(float) * (size_t)n_nodes * (size_t)max_dim(m);
+    for (int i = 0; i < 3; ++i) w.buf[i] = take(big);
+    size_t tn = 0, cs = 0;
+    for (int k = 0; k < m->n_layers; ++k) {
+        size_t t = lp_gemm_tn_partials_bytes(n_nodes, m->dims[k], m->dims[k + 1]);
+        tn = t > tn ? t : tn;
+        size_t c = lp_colsum_partials_bytes(n_nodes, m->dims[k + 1]);
+        cs = c > cs ? c : cs;
+    }
+    w.tn_partials = take(tn);
+    w.colsum_partials = take(cs);
+    w.bytes = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
+    (void)n_nodes;
+    if (check_model(m) != LP_OK) return 0;
+    return lp_align_up(sizeof(float) * transposed_weight_floats(m));
+}
+
+extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws, size_t ws_bytes,
+                               void *stream) {
+    LP_TRY(check_model(m));
+    LP_TRY(check_graph(g, false));
+    LP_TRY(check_acts(m, saved));
+    if (!X || !lp_aligned16(X)) return LP_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < lp_sage_forward_workspace_bytes(m, g->n_nodes)) return LP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *wt = static_cast<float *>(ws);
+    const int K = m->n_layers;
+    const float *Hprev = static_cast<const float *>(X);
+    for (int k = 1; k <= K; ++k) {
+        const int Fi = m->dims[k - 1], Fo = m->dims[k];
+        float *A = static_cast<float *>(saved->A[k - 1]);
+        float *H = static_cast<float *>(saved->H[k - 1]);
+        SpmmArgs sp;
+        sp.n_rows = g->n_nodes;
+        sp.F = Fi;
+        sp.rowptr = g->rowptr;
+        sp.colidx = g->colidx;
+        sp.row_order = g->row_order;
+        sp.inv_deg = g->inv_deg;
+        sp.in = Hprev;
+        sp.out = A;
+        LP_TRY(lp_launch_spmm(sp, st));
+        // the NT product wants the reduction index contiguous: W^T is [Fo, Fi]
+        float *WsT = wt, *WnT = wt + lp_align_up((size_t)Fi * Fo, 64);
+        wt += 2 * lp_align_up((size_t)Fi * Fo, 64);
+        LP_TRY(lp_launch_transpose(static_cast<const float *>(m->W_self[k - 1]), Fi, Fo, WsT, st));
+        LP_TRY(lp_launch_transpose(static_cast<const float *>(m->W_neigh[k - 1]), Fi, Fo, WnT, st));
+        GemmNtArgs ge;
+        ge.M = g->n_nodes;
+        ge.N = Fo;
+        ge.n_split = Fo;
+        ge.A[0] = Hprev; ge.A[1] = A;
+        ge.lda[0] = ge.lda[1] = Fi;
+        ge.K[0] = ge.K[1] = Fi;
+        ge.Bt[0][0] = WsT; ge.Bt[1][0] = WnT;
+        ge.ldb[0] = ge.ldb[1] = Fi;
+        ge.bias = static_cast<const float *>(m->bias[k - 1]);
+        ge.relu = k < K;
+        ge.C[0] = H;
+        ge.ldc[0] = Fo;
+        LP_TRY(lp_launch_gemm_nt(ge, st));
+        Hprev = H;
+    }
+    return LP_OK;
+}
+
+extern "C" size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
+    if (check_model(m) != LP_OK || n_nodes <= 0) return 0;
+    return carve_backward(nullptr, m, n_nodes).bytes;
+}
+
+extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                           const int32_t *e_src, const int32_t *e_dst, const float *dscore, lp_grads *out, void *ws,
+                           size_t ws_bytes, void *stream) {
+    LP_TRY(check_model(m));
+    LP_TRY(check_graph(g, true));
+    LP_TRY(check_acts(m, saved));
+    if (!X || !lp_aligned16(X) || !out || B < 0) return LP_ERR_INVALID_ARG;
+    if (B > 0 && (!e_src || !e_dst || !dscore)) return LP_ERR_INVALID_ARG;
+    if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
+    const int K = m->n_layers;
+    for (int k = 0; k < K; ++k)
+        if (!out->dW_self[k] || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
+    if (out->dX && !lp_aligned16(out->dX)) return LP_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < lp_backward_workspace_bytes(m, g->n_nodes)) return LP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BackwardWs w = carve_backward(ws, m, g->n_nodes);
+    const int32_t N = g->n_nodes;
+
+    float *dZ = w.buf[0], *Q = w.buf[1], *R = w.buf[2];
+    const float *HK = static_cast<const float *>(saved->H[K - 1]);
+    LP_TRY(lp_launch_zero(dZ, (int64_t)N * m->dims[K], st));
+    LP_TRY(launch_edge_scatter(HK, N, m->dims[K], B, e_src, e_dst, dscore, dZ, st));
+
+    for (int k = K; k >= 1; --k) {
+        const int Fi = m->dims[k - 1], Fo = m->dims[k];
+        const float *Hin = k > 1 ? static_cast<const float *>(saved->H[k - 2]) : static_cast<const float *>(X);
+        const float *Ak = static_cast<const float *>(saved->A[k - 1]);
+        LP_TRY(lp_launch_colsum(dZ, N, Fo, out->dbias[k - 1], w.colsum_partials, st));
+        GemmTnArgs tn;
+        tn.Kn = N; tn.Mw = Fi; tn.Nw = Fo;
+        tn.B = dZ; tn.ldb = Fo;
+        tn.partials = w.tn_partials;
+        tn.At = Hin; tn.lda = Fi; tn.C = out->dW_self[k - 1];
+        LP_TRY(lp_launch_gemm_tn(tn, st));
+        tn.At = Ak; tn.C = out->dW_neigh[k - 1];
+        LP_TRY(lp_launch_gemm_tn(tn, st));
+        if (k == 1 && !out->dX) break;
+        // [dZ W_self^T | diag(inv_deg) dZ W_neigh^T] -> Q, R
+        GemmNtArgs ge;
+        ge.M = N; ge.N = 2 * Fi; ge.n_split = Fi;
+        ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
+        ge.Bt[0][0] = static_cast<const float *>(m->W_self[k - 1]);
+        ge.Bt[0][1] = static_cast<const float *>(m->W_neigh[k - 1]);
+        ge.ldb[0] = Fo;
+        ge.rowscale = g->inv_deg;
+        ge.C[0] = Q; ge.C[1] = R;
+        ge.ldc[0] = ge.ldc[1] = Fi;
+        LP_TRY(lp_launch_gemm_nt(ge, st));
+        // G^{k-1} = (Q + sum over the transposed CSR of R) gated by relu'(z^{k-1}) = [h^{k-1} > 0]
+        SpmmArgs sp;
+        sp.n_rows = N; sp.F = Fi;
+        sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
+        sp.in = R; sp.addend = Q;
+        sp.gate = k > 1 ? Hin : nullptr;
+        sp.out = k > 1 ? Q : out->dX;
+        LP_TRY(lp_launch_spmm(sp, st));
+        float *t = dZ; dZ = Q; Q = t;
+    }
+    return LP_OK;
+}

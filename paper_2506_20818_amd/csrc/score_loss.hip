@@ -1,0 +1,129 @@
+// lp_score_loss: dot-product edge scores (Eq. 2 of the paper), binary cross-entropy with labels 1/0 and the
+// batch mean (Algorithm 1, per-edge loop and "Compute L^i"; Sec. IV-B last paragraph), plus dL/ds.
+//
+// A group of G = F/4 lanes (power of two, at most a wavefront) owns one edge: each lane loads 16 bytes of both
+// endpoint rows, and the products are summed across the group with xor-shuffles (a segmented reduction inside
+// the wavefront).  The loss is reduced block by block and then by one block, always in the same order.
+#include "lp_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxLossBlocks = 2048;
+
+template <int G>
+__device__ inline float group_sum(float v) {
+#pragma unroll
+    for (int d = G >> 1; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+template <int G>
+__global__ __launch_bounds__(kThreads) void score_loss_kernel(const float *__restrict__ H, int32_t n_nodes, int32_t F,
+                                                              int64_t B, int64_t n_pos, const int32_t *__restrict__ e_src,
+                                                              const int32_t *__restrict__ e_dst, float *__restrict__ scores,
+                                                              float *__restrict__ dscore, float *__restrict__ partial) {
+    __shared__ float red[kThreads / 64];
+    const int sub = threadIdx.x % G;
+    const int64_t groups_per_block = kThreads / G;
+    const int64_t gid = (int64_t)blockIdx.x * groups_per_block + threadIdx.x / G;
+    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    const float invB = 1.0f / (float)B;
+    const int F4 = F >> 2;
+    float acc = 0.0f;
+    for (int64_t e = gid; e < B; e += n_groups) {
+        const int32_t u = e_src[e], v = e_dst[e];
+        const bool ok = u >= 0 && u < n_nodes && v >= 0 && v < n_nodes;
+        float s = 0.0f;
+        if (ok) {
+            const float4 *hu = reinterpret_cast<const float4 *>(H + (int64_t)u * F);
+            const float4 *hv = reinterpret_cast<const float4 *>(H + (int64_t)v * F);
+            for (int j = sub; j < F4; j += G) {
+                const float4 a = hu[j], b = hv[j];
+                s += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+            }
+        }
+        s = group_sum<G>(s);
+        if (sub == 0) {
+            const float y = e < n_pos ? 1.0f : 0.0f;
+            const float ex = expf(-fabsf(s));
+            const float ell = fmaxf(s, 0.0f) - y * s + log1pf(ex);
+            const float sig = s >= 0.0f ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
+            scores[e] = s;
+            if (dscore) dscore[e] = ok ? (sig - y) * invB : 0.0f;
+            if (ok) acc += ell;
+        }
+    }
+    // block sum in a fixed order
+    acc = group_sum<64>(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(kThreads) void loss_finish_kernel(const float *__restrict__ partial, int n, int64_t B,
+                                                               float *__restrict__ loss) {
+    __shared__ double red[kThreads];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += kThreads) s += (double)partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int d = kThreads / 2; d >= 1; d >>= 1) {
+        if (threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = B > 0 ? (float)(red[0] / (double)B) : 0.0f;
+}
+
+int loss_blocks(int64_t B, int G) {
+    const int64_t groups_per_block = kThreads / G;
+    int64_t nb = lp_ceil_div(B, groups_per_block * 4);  // about four edges per group
+    if (nb < 1) nb = 1;
+    if (nb > kMaxLossBlocks) nb = kMaxLossBlocks;
+    return (int)nb;
+}
+
+int group_lanes(int F) {
+    int g = 8;
+    while (g < 64 && g * 4 < F) g <<= 1;
+    return g;
+}
+
+}  // namespace
+
+extern "C" size_t lp_score_loss_workspace_bytes(int64_t B) {
+    (void)B;
+    return sizeof(float) * kMaxLossBlocks;
+}
+
+extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                             const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, void *ws,
+                             size_t ws_bytes, void *stream) {
+    if (!HK || n_nodes <= 0 || F <= 0 || B < 0 || n_pos_edges < 0 || n_pos_edges > B || !loss) return LP_ERR_INVALID_ARG;
+    if (B > 0 && (!e_src || !e_dst || !scores)) return LP_ERR_INVALID_ARG;
+    if (dtype != LP_F32 || (F & 3)) return LP_ERR_UNSUPPORTED;
+    if (!lp_aligned16(HK)) return LP_ERR_INVALID_ARG;
+    if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
+    if (!ws || ws_bytes < lp_score_loss_workspace_bytes(B)) return LP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *partial = static_cast<float *>(ws);
+    const float *H = static_cast<const float *>(HK);
+    const int G = group_lanes(F);
+    const int nb = loss_blocks(B, G);
+#define LP_SCORE_CASE(g)                                                                                              \
+    case g:                                                                                                           \
+        hipLaunchKernelGGL((score_loss_kernel<g>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos_edges,    \
+                           e_src, e_dst, scores, dscore, partial);                                                    \
+        break;
+    switch (G) {
+        LP_SCORE_CASE(8)
+        LP_SCORE_CASE(16)
+        LP_SCORE_CASE(32)
+        default:
+            hipLaunchKernelGGL((score_loss_kernel<64>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos_edges,
+                               e_src, e_dst, scores, dscore, partial);
+    }
+#undef LP_SCORE_CASE
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, B, loss);
+    return lp_after_launch();
+}

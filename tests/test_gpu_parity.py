@@ -1,0 +1,299 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: CSR arrays and sampled negatives bit-exact; activations, scores and loss within 1e-4 relative;
+gradients within 1e-3 relative (per tensor, max-norm and 2-norm), all in fp32 on the GPU vs fp64 in the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2506_20818_amd as lp
+from lp_workloads import make_workload
+from oracle import lp_oracle as O
+from gpu_util import DEV, HipStep, assert_close, dev_f32, dev_i32, host, make_model
+
+TOL_ACT = 1e-4
+TOL_GRAD = 1e-3
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def random_pairs(rng, n, e):
+    return rng.integers(0, n, e).astype(np.int32), rng.integers(0, n, e).astype(np.int32)
+
+
+def check_csr(g, ref):
+    assert g.nnz == ref.nnz
+    for name in ("rowptr", "colidx", "t_rowptr", "t_colidx"):
+        assert np.array_equal(host(getattr(g, name)), getattr(ref, name)), name
+    assert np.array_equal(host(g.inv_deg).view(np.uint32), ref.inv_deg.view(np.uint32)), "inv_deg bits"
+    for order, rp in ((g.row_order, ref.rowptr), (g.t_row_order, ref.t_rowptr)):
+        o = host(order)
+        assert np.array_equal(np.sort(o), np.arange(ref.n_nodes)), "row order is not a permutation"
+        deg = np.diff(rp)[o].astype(np.int64)
+        cls = np.where(deg > 0, np.floor(np.log2(np.maximum(deg, 1))), -1)
+        assert np.all(np.diff(cls) <= 0), "rows are not listed by decreasing size class"
+
+
+# ------------------------------------------------------------------------------------------------ lp_build_csr
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("sym", [False, True])
+def test_build_csr_small_random(seed, sym):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 3000))
+    e = int(rng.integers(0, 9000))
+    say("build_csr random seed=%d sym=%s n=%d e=%d" % (seed, sym, n, e))
+    r, c = random_pairs(rng, n, e)                 # duplicates and self-loops included
+    check_csr(lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym), O.build_csr(n, r, c, sym))
+
+
+def test_build_csr_edge_cases():
+    say("build_csr empty / single node / hub / out of range")
+    z = np.zeros(0, np.int32)
+    check_csr(lp.lp_build_csr(7, dev_i32(z), dev_i32(z), True), O.build_csr(7, z, z, True))
+    one = np.zeros(3, np.int32)
+    check_csr(lp.lp_build_csr(1, dev_i32(one), dev_i32(one), False), O.build_csr(1, one, one, False))
+    n = 70000                                      # one hub row longer than a sort tile, 17-bit ids
+    r = np.zeros(n - 1, np.int32)
+    c = np.arange(1, n, dtype=np.int32)
+    check_csr(lp.lp_build_csr(n, dev_i32(r), dev_i32(c), False), O.build_csr(n, r, c, False))
+    check_csr(lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True), O.build_csr(n, r, c, True))
+    with pytest.raises(lp.LpError) as ei:
+        lp.lp_build_csr(5, dev_i32([0, 5]), dev_i32([1, 1]), False)
+    assert ei.value.status == -2
+    with pytest.raises(lp.LpError):
+        lp.lp_build_csr(5, dev_i32([0, 1]), dev_i32([1, -1]), True)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_build_csr_workloads(name):
+    wl = make_workload(name, with_features=False)
+    say("build_csr %s n=%d e=%d" % (name, wl.n_nodes, wl.src.size))
+    check_csr(lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True),
+              O.build_csr(wl.n_nodes, wl.src, wl.dst, True))
+
+
+# ------------------------------------------------------------------------------------------------ lp_sample_neg
+def run_sampler(ref, g, pos, k_neg, n_space, seed, step):
+    nf = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ns = torch.empty(pos.size * k_neg, dtype=torch.int32, device=DEV)
+    got = lp.lp_sample_neg(g, dev_i32(pos), k_neg, n_space, seed, step, neg_src=ns, n_failed=nf)
+    exp, exp_failed = O.sample_neg(ref, pos, k_neg, n_space, seed, step)
+    assert np.array_equal(host(got), exp)
+    assert np.array_equal(host(ns), np.repeat(pos, k_neg))
+    assert int(host(nf)[0]) == exp_failed
+    return exp
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_sample_neg_bit_exact_dense_small_graphs(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(3, 60))
+    r, c = random_pairs(rng, n, int(rng.integers(0, n * n // 2 + 1)))      # dense: retries and probing happen
+    say("sample_neg dense seed=%d n=%d" % (seed, n))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    pos = rng.integers(0, n, 3000).astype(np.int32)
+    n_space = n if seed % 2 else n + 9
+    run_sampler(ref, g, pos, int(rng.integers(1, 5)), n_space, int(rng.integers(0, 2 ** 63)), int(rng.integers(0, 2 ** 40)))
+
+
+def test_sample_neg_degenerate_rows():
+    say("sample_neg single valid destination / no valid destination / empty batch")
+    r, c = np.array([0, 0], np.int32), np.array([1, 2], np.int32)
+    ref, g = O.build_csr(4, r, c, True), lp.lp_build_csr(4, dev_i32(r), dev_i32(c), True)
+    assert np.all(run_sampler(ref, g, np.zeros(500, np.int32), 2, 4, 99, 0) == 3)
+    r, c = np.array([0, 0, 0], np.int32), np.array([1, 2, 3], np.int32)
+    ref, g = O.build_csr(4, r, c, True), lp.lp_build_csr(4, dev_i32(r), dev_i32(c), True)
+    run_sampler(ref, g, np.zeros(5, np.int32), 1, 4, 99, 0)
+    out = lp.lp_sample_neg(g, dev_i32(np.zeros(0, np.int32)), 3, 4, 1, 1)
+    assert out.numel() == 0
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_sample_neg_workloads(name):
+    wl = make_workload(name, with_features=False)
+    say("sample_neg %s n_pos=%d k=%d" % (name, wl.n_pos, wl.k_neg))
+    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    run_sampler(ref, g, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+    run_sampler(ref, g, wl.pos_src[:1000], 4, wl.n_space, 1, 2 ** 33 + 5)
+
+
+# ------------------------------------------------------------------------------------------------ forward
+def toy_model(rng, dims, scale=0.3):
+    K = len(dims) - 1
+    Ws = [(rng.standard_normal((dims[k], dims[k + 1])) * scale).astype(np.float32) for k in range(K)]
+    Wn = [(rng.standard_normal((dims[k], dims[k + 1])) * scale).astype(np.float32) for k in range(K)]
+    b = [(rng.standard_normal(dims[k + 1]) * 0.2).astype(np.float32) for k in range(K)]
+    return Ws, Wn, b
+
+
+def graph_with_hub_and_empty_rows(rng, n, e, hub_deg):
+    r, c = random_pairs(rng, n - 50, e)             # the last 50 nodes stay isolated
+    hub_c = rng.choice(n - 50, hub_deg, replace=False).astype(np.int32)
+    r = np.concatenate([r, np.full(hub_deg, 3, np.int32)])
+    c = np.concatenate([c, hub_c])
+    return r, c
+
+
+@pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [36, 64, 32], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68],
+                                  [512, 64], [64, 512, 8]])
+@pytest.mark.parametrize("sym", [True, False])
+def test_forward_parity_widths_hub_and_empty_rows(dims, sym):
+    rng = np.random.default_rng(sum(dims) + sym)
+    n = 1500 + dims[0]                              # not a multiple of any tile size
+    r, c = graph_with_hub_and_empty_rows(rng, n, 4000, 700)
+    say("forward dims=%s sym=%s n=%d" % (dims, sym, n))
+    ref = O.build_csr(n, r, c, sym)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym)
+    Ws, Wn, b = toy_model(rng, dims)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    acts = lp.lp_sage_forward(g, make_model(Ws, Wn, b), dev_f32(X))
+    exp = O.sage_forward(ref, Ws, Wn, b, X)
+    for k in range(1, len(dims)):
+        assert_close(host(acts.A[k - 1]), exp.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(host(acts.H[k - 1]), exp.H[k], TOL_ACT, "H^%d" % k)
+    iso = np.flatnonzero(np.diff(ref.rowptr) == 0)
+    assert iso.size >= 50 and np.all(host(acts.A[0])[iso] == 0)
+
+
+def test_forward_without_row_order_and_single_node():
+    say("forward natural row order / one-node graph")
+    rng = np.random.default_rng(5)
+    n, dims = 300, [8, 16, 4]
+    r, c = random_pairs(rng, n, 900)
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True, with_row_order=False)
+    Ws, Wn, b = toy_model(rng, dims)
+    X = rng.standard_normal((n, 8)).astype(np.float32)
+    acts = lp.lp_sage_forward(g, make_model(Ws, Wn, b), dev_f32(X))
+    assert_close(host(acts.H[-1]), O.sage_forward(ref, Ws, Wn, b, X).H[-1], TOL_ACT, "H^K")
+    z = np.zeros(1, np.int32)
+    ref = O.build_csr(1, z, z, False)                # a single node with a self-loop
+    g = lp.lp_build_csr(1, dev_i32(z), dev_i32(z), False)
+    X = rng.standard_normal((1, 8)).astype(np.float32)
+    acts = lp.lp_sage_forward(g, make_model(Ws, Wn, b), dev_f32(X))
+    assert_close(host(acts.H[-1]), O.sage_forward(ref, Ws, Wn, b, X).H[-1], TOL_ACT, "H^K one node")
+
+
+# ------------------------------------------------------------------------------------------------ score / loss
+@pytest.mark.parametrize("F", [4, 32, 64, 100, 256, 512])
+def test_score_loss_parity(F):
+    rng = np.random.default_rng(F)
+    n, B, n_pos = 777, 5001, 1700
+    say("score_loss F=%d" % F)
+    H = (rng.standard_normal((n, F)) * (2.0 / np.sqrt(F)) ** 0.5).astype(np.float32)
+    H[0] *= 30.0                                     # some saturated scores
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    es[:40] = 0
+    ed[:20] = 0
+    s, loss, ds = lp.lp_score_loss(dev_f32(H), dev_i32(es), dev_i32(ed), n_pos)
+    s_ref, loss_ref, ds_ref = O.score_loss(H, es, ed, n_pos)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
+    assert_close(host(ds), ds_ref, TOL_ACT, "dscore")
+    s2, loss2, _ = lp.lp_score_loss(dev_f32(H), dev_i32(es), dev_i32(ed), n_pos)
+    assert host(loss2).tobytes() == host(loss).tobytes()        # fixed summation order
+
+
+def test_score_loss_zero_embeddings_and_empty_batch():
+    say("score_loss zeros / B=0")
+    H = np.zeros((10, 8), np.float32)
+    es, ed = np.arange(6, dtype=np.int32), np.arange(1, 7, dtype=np.int32)
+    s, loss, ds = lp.lp_score_loss(dev_f32(H), dev_i32(es), dev_i32(ed), 2)
+    assert np.all(host(s) == 0) and abs(float(host(loss)[0]) - np.log(2.0)) < 1e-6
+    np.testing.assert_allclose(host(ds), np.array([-0.5, -0.5, 0.5, 0.5, 0.5, 0.5]) / 6, rtol=1e-6)
+    z = np.zeros(0, np.int32)
+    s, loss, ds = lp.lp_score_loss(dev_f32(H), dev_i32(z), dev_i32(z), 0)
+    assert float(host(loss)[0]) == 0.0
+
+
+# ------------------------------------------------------------------------------------------------ backward
+def check_grads(grads, ref, K):
+    for k in range(K):
+        assert_close(host(grads.dW_self[k]), ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
+    if grads.dX is not None:
+        assert_close(host(grads.dX), ref.dX, TOL_GRAD, "dX")
+
+
+@pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8]])
+@pytest.mark.parametrize("sym", [True, False])
+def test_backward_parity(dims, sym):
+    rng = np.random.default_rng(1000 + sum(dims) + sym)
+    n = 1300 + dims[-1]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
+    say("backward dims=%s sym=%s n=%d" % (dims, sym, n))
+    ref = O.build_csr(n, r, c, sym)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 2500, 1000
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)      # repeated nodes and u == v included
+    model = make_model(Ws, Wn, b)
+    Xd = dev_f32(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    check_grads(grads, g_ref, len(dims) - 1)
+    # without dX the weight gradients are the same
+    grads2 = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
+    check_grads(grads2, g_ref, len(dims) - 1)
+
+
+def test_backward_empty_batch_gives_zero_gradients():
+    say("backward B=0")
+    rng = np.random.default_rng(3)
+    n, dims = 200, [8, 16, 4]
+    r, c = random_pairs(rng, n, 500)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims)
+    model = make_model(Ws, Wn, b)
+    Xd = dev_f32(rng.standard_normal((n, 8)))
+    acts = lp.lp_sage_forward(g, model, Xd)
+    z = dev_i32(np.zeros(0, np.int32))
+    grads = lp.lp_backward(g, model, Xd, acts, z, z, dev_f32(np.zeros(0)), want_dX=True)
+    for t in grads.dW_self + grads.dW_neigh + grads.dbias + [grads.dX]:
+        assert np.all(host(t) == 0)
+
+
+# ------------------------------------------------------------------------------------------------ whole step
+def whole_step(name):
+    wl = make_workload(name)
+    say("whole step %s N=%d nnz~%d B=%d" % (name, wl.n_nodes, 2 * wl.src.size, wl.batch_edges))
+    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    exp = O.train_step(ref, wl.W_self, wl.W_neigh, wl.bias, wl.X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space,
+                       wl.sampler_seed, wl.sampler_step)
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    check_csr(g, ref)
+    got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
+                  wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+    assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+    K = len(wl.dims) - 1
+    for k in range(1, K + 1):
+        assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+    assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
+    assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+    assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
+    check_grads(got.grads, exp.grads, K)
+
+
+def test_whole_step_C1():
+    whole_step("C1")
+
+
+def test_whole_step_C2_full_size():
+    whole_step("C2")
