@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark: one worker's link-prediction training step on one MI355X.
+
+A step is one pass of the whole hot path over one minibatch: lp_sample_neg -> lp_sage_forward (full-neighbour,
+all visible nodes) -> lp_score_loss -> lp_backward, with every input already resident in HBM.  The workload is
+the Collab-scale Chung-Lu configuration ("C2"): 235 000 nodes, ~2.4 M directed CSR entries, 128 -> 256 -> 256 ->
+256 GraphSAGE-mean in fp32, 65 536 positives + 65 536 negatives per step.  Prints ONE JSON line.
+
+The per-kernel numbers in "roofline" come from HIP events recorded by the library around each launch inside the
+timed region (lp_timing_enable); "cpu_baseline" times the CPU oracle, as it stands, on a stated fraction of the
+same workload.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+
+
+def spmm_bytes(n, nnz, F, backward):
+    """Algorithmic bytes of one CSR aggregation launch: gathered rows + column ids + row pointers + output row,
+    plus inverse degrees (forward) or the added/gating rows (backward)."""
+    b = nnz * (4 * F + 4) + (n + 1) * 4 + n * 4 * F
+    return b + (2 * n * 4 * F if backward else n * 4)
+
+
+def step_counts(n, nnz, dims):
+    """(spmm algorithmic bytes, NT flops, TN flops) of one step."""
+    K = len(dims) - 1
+    sp = sum(spmm_bytes(n, nnz, dims[k - 1], False) for k in range(1, K + 1))
+    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True) for k in range(2, K + 1))
+    nt = sum(2.0 * n * dims[k] * 2 * dims[k - 1] for k in range(1, K + 1))          # forward
+    nt += sum(2.0 * n * 2 * dims[k - 1] * dims[k] for k in range(2, K + 1))         # input gradients
+    tn = sum(2.0 * 2 * n * dims[k - 1] * dims[k] for k in range(1, K + 1))          # dW_self, dW_neigh
+    return sp, nt, tn
+
+
+def cpu_baseline(scale):
+    """Time the CPU oracle on a `scale` fraction of the workload (nodes, edges and batch all scaled)."""
+    from lp_workloads import make_workload
+    from oracle import lp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    wl = make_workload("C2", scale=scale)
+    g = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    t0 = time.perf_counter()
+    O.train_step(g, wl.W_self, wl.W_neigh, wl.bias, wl.X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space,
+                 wl.sampler_seed, wl.sampler_step)
+    dt = time.perf_counter() - t0
+    return {"value": wl.batch_edges / dt, "unit": "edges/s", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": "one full oracle step (numpy fp64) on the C2 generator at scale %.3g: %d nodes, %d directed "
+                      "entries, %d scored edges" % (scale, wl.n_nodes, g.nnz, wl.batch_edges)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--cpu-scale", type=float, default=0.25, help="fraction of the workload the CPU oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py measures one worker's step on ONE GPU; --gpus %d is not supported "
+                         "(no collectives are part of this build)\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2506_20818_amd as lp
+    from paper_2506_20818_amd import binding as B
+    from lp_workloads import make_workload
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = make_workload(args.workload)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+
+    rows, cols = i32(wl.src), i32(wl.dst)
+    lp.lp_build_csr(wl.n_nodes, rows, cols, True)                     # warm-up of the setup path
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = lp.lp_build_csr(wl.n_nodes, rows, cols, True)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+
+    model = lp.Model([f32(w) for w in wl.W_self], [f32(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+    X = f32(wl.X)
+    n_pos, k_neg, Bn = wl.n_pos, wl.k_neg, wl.batch_edges
+    pos_src = i32(wl.pos_src)
+    e_src = torch.empty(Bn, dtype=torch.int32, device=dev)
+    e_dst = torch.empty(Bn, dtype=torch.int32, device=dev)
+    e_src[:n_pos] = pos_src
+    e_dst[:n_pos] = i32(wl.pos_dst)
+    neg_src, neg_dst = e_src[n_pos:], e_dst[n_pos:]
+    acts = lp.Acts(wl.n_nodes, wl.dims, dev)
+    grads = lp.Grads(wl.n_nodes, wl.dims, dev)
+    ws_f = torch.empty(B.forward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(B.backward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
+    ws_l = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    scores = torch.empty(Bn, dtype=torch.float32, device=dev)
+    dscore = torch.empty(Bn, dtype=torch.float32, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def step(i):
+        lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
+        lp.lp_sage_forward(g, model, X, acts, ws_f)
+        lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
+        lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # un-instrumented pass, for reference
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(1000 + i)
+    torch.cuda.synchronize()
+    plain_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+
+    # timed region, with the library's per-launch HIP events switched on
+    lp.lp_timing_enable(True)
+    lp.lp_timing_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(2000 + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    classes = lp.lp_timing_collect()
+    lp.lp_timing_enable(False)
+    loss_val = float(loss.item())
+    ms_per_step = dt * 1e3 / max(args.steps, 1)
+
+    n, nnz = wl.n_nodes, g.nnz
+    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims)
+    per_step = {k: (ms / max(args.steps, 1), cnt // max(args.steps, 1)) for k, (ms, cnt) in classes.items()}
+
+    def hbm_line(cls, bytes_per_step):
+        ms, cnt = per_step[cls]
+        gbs = bytes_per_step / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"bound": "hbm", "kernel": cls, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "launches_per_step": cnt,
+                "avg_launch_ms": round(ms / max(cnt, 1), 4), "algorithmic_bytes_per_launch": int(bytes_per_step / max(cnt, 1))}
+
+    def mfma_line(cls, flops_per_step):
+        ms, cnt = per_step[cls]
+        tf = flops_per_step / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        return {"bound": "mfma", "kernel": cls, "achieved": round(tf, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tf / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None, "launches_per_step": cnt,
+                "avg_launch_ms": round(ms / max(cnt, 1), 4), "flops_per_launch": int(flops_per_step / max(cnt, 1))}
+
+    lines = {"spmm": hbm_line("spmm", sp_bytes), "gemm_nt": mfma_line("gemm_nt", nt_flops),
+             "gemm_tn": mfma_line("gemm_tn", tn_flops)}
+    dominant = max(lines, key=lambda c: per_step[c][0])
+
+    out = {
+        "metric": "train-step edges/sec (pos+neg) on 1 MI355X; SpMM achieved HBM GB/s",
+        "value": round(Bn / (ms_per_step * 1e-3), 1),
+        "unit": "edges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_without_events": round(plain_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: Chung-Lu power-law graph, %d nodes, %d directed CSR entries, GraphSAGE-mean %s, "
+                               "%d positives + %d uniform negatives per step, full-neighbour aggregation"
+                               % (args.workload, n, nnz, "->".join(map(str, wl.dims)), n_pos, n_pos * k_neg),
+                   "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg},
+        "loss": round(loss_val, 6),
+        "csr_build": {"seconds": round(build_s, 5), "input_edges_per_s": round(wl.src.size / build_s, 1)},
+        "roofline": lines[dominant],
+        "roofline_spmm": lines["spmm"],
+        "roofline_gemm_nt": lines["gemm_nt"],
+        "roofline_gemm_tn": lines["gemm_tn"],
+        "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_scale)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -22,6 +22,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued on it and, except for lp_build_csr, the call returns
  *    without waiting.
+ *  - Apart from the benchmark instrumentation at the end of this file the
+ *    library keeps no state between calls.
  *  - Return value: LP_OK or a negative LP_ERR_* code.  Arguments are checked on
  *    the host before anything is launched; a call that returns an error other
  *    than LP_ERR_HIP has launched nothing.  No exception crosses this ABI.
@@ -165,8 +167,8 @@ int lp_sample_neg(const lp_csr *g, int64_t n_pos, const int32_t *pos_src, int32_
  *   l_e = -[y ln sigma(s) + (1-y) ln(1-sigma(s))],  loss = (1/B) sum_e l_e,
  *   dscore_e = (sigma(s_e) - y_e) / B.
  * HK: device [n_nodes, F].  e_src, e_dst: device [B], ids in [0, n_nodes)
- * (an edge with an id outside is scored 0 and gets dscore 0, and still counts
- * in B).  scores: device [B].  loss: device float.  dscore: device [B] or NULL.
+ * (an edge with an id outside is scored 0, gets dscore 0, adds nothing to the
+ * loss sum and still counts in B).  scores: device [B].  loss: device float.  dscore: device [B] or NULL.
  * The loss is summed in a fixed order, so repeated calls give the same bits.
  */
 size_t lp_score_loss_workspace_bytes(int64_t B);
@@ -186,6 +188,27 @@ size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes);
 int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
                 const int32_t *e_src, const int32_t *e_dst, const float *dscore, lp_grads *out, void *ws,
                 size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Instrumentation for benchmarks (not part of the method).  While enabled, each
+ * kernel launch made by the calls above is bracketed by two HIP events on the
+ * launch stream.  lp_timing_collect waits for the recorded events, writes the
+ * summed milliseconds and launch counts per kernel class (arrays of at least
+ * LP_KC_COUNT entries) and forgets them.  Off by default.  This is the only
+ * process-wide state of the library; it is guarded by a mutex.
+ */
+enum {
+    LP_KC_SPMM = 0,     /* CSR mean aggregation, forward and transposed */
+    LP_KC_GEMM_NT = 1,  /* layer transform and input-gradient transform */
+    LP_KC_GEMM_TN = 2,  /* weight gradients (incl. the partial-sum reduction) */
+    LP_KC_SCATTER = 3,  /* edge gradient scatter */
+    LP_KC_SCORE = 4,    /* edge scores and loss */
+    LP_KC_SAMPLE = 5,   /* negative sampler */
+    LP_KC_OTHER = 6,    /* fills, bias gradients, weight transposes */
+    LP_KC_COUNT = 7
+};
+int lp_timing_enable(int on);
+int lp_timing_collect(double *ms_by_class, int64_t *launches_by_class, int32_t n_classes);
 
 #ifdef __cplusplus
 }

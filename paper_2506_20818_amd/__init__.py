@@ -19,4 +19,6 @@ from .binding import (  # noqa: F401
     lp_sample_neg,
     lp_score_loss,
     lp_strerror,
+    lp_timing_collect,
+    lp_timing_enable,
 )

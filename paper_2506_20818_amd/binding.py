@@ -61,6 +61,8 @@ EXPORTS = {
     "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
+    "lp_timing_enable": (C.c_int, [C.c_int]),
+    "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                               C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
                               C.c_size_t, C.c_void_p]),
@@ -278,3 +280,19 @@ def backward_workspace_bytes(m: Model, n_nodes: int) -> int:
 
 def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
     return int(load_library().lp_sage_forward_workspace_bytes(C.byref(m.c), n_nodes))
+
+
+KERNEL_CLASSES = ["spmm", "gemm_nt", "gemm_tn", "scatter", "score", "sample", "other"]
+
+
+def lp_timing_enable(on: bool) -> None:
+    _check(load_library().lp_timing_enable(1 if on else 0), "lp_timing_enable")
+
+
+def lp_timing_collect():
+    """Returns {class: (milliseconds, launches)} for the launches since the last collect."""
+    n = len(KERNEL_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(load_library().lp_timing_collect(ms, cnt, n), "lp_timing_collect")
+    return {KERNEL_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

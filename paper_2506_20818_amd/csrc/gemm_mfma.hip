@@ -25,10 +25,6 @@ constexpr int LDS_LD = BK + 4;
 __device__ inline v16f mfma32(float a, float b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
 
 // ------------------------------------------------------------------------------------------------ NT
-struct NtTile {  // which K-part and offset a K-tile index refers to
-    int s, k0;
-};
-
 template <int NB>  // 32-column blocks per wavefront: BN = 64 * NB
 __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(GemmNtArgs g) {
     constexpr int BN = 64 * NB;
@@ -304,6 +300,7 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         if (a.n_split < a.N && (!a.Bt[s][1] || !lp_aligned16(a.Bt[s][1]))) return LP_ERR_INVALID_ARG;
     }
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
+    LpTimedScope timed(LP_KC_GEMM_NT, st);
     const unsigned gx = (unsigned)lp_ceil_div(a.M, BM);
     if (a.N > 64) {
         hipLaunchKernelGGL((gemm_nt_kernel<2>), dim3(gx, (unsigned)lp_ceil_div(a.N, 128)), dim3(kThreads), 0, st, a);
@@ -325,6 +322,7 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
     if (!a.C || !a.partials) return LP_ERR_INVALID_ARG;
     if (a.Kn <= 0) return lp_launch_zero(a.C, (int64_t)a.Mw * a.Nw, st);
     if (!a.At || !a.B || !lp_aligned16(a.At) || !lp_aligned16(a.B)) return LP_ERR_INVALID_ARG;
+    LpTimedScope timed(LP_KC_GEMM_TN, st);
     const TnPlan p = plan_tn(a.Kn, a.Mw, a.Nw);
     const dim3 grid(p.tiles, p.splits);
     if (p.tm == 128 && p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
@@ -338,6 +336,7 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
 
 int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t st) {
     if (rows <= 0 || cols <= 0) return LP_OK;
+    LpTimedScope timed(LP_KC_OTHER, st);
     hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)lp_ceil_div(cols, 32), (unsigned)lp_ceil_div(rows, 32)), dim3(32, 8), 0,
                        st, in, rows, cols, out);
     return lp_after_launch();
@@ -350,6 +349,7 @@ size_t lp_colsum_partials_bytes(int32_t M, int32_t N) {
 int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *partials, hipStream_t st) {
     if (N <= 0) return LP_OK;
     if (M <= 0) return lp_launch_zero(out, N, st);
+    LpTimedScope timed(LP_KC_OTHER, st);
     const int nb = (int)lp_ceil_div(M, kColsumRows);
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(nb), dim3(kThreads), 0, st, in, M, N, partials);
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)lp_ceil_div(N, 256)), dim3(256), 0, st, partials, nb, (int64_t)N, out);
@@ -358,6 +358,7 @@ int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *p
 
 int lp_launch_zero(float *p, int64_t n, hipStream_t st) {
     if (n <= 0) return LP_OK;
+    LpTimedScope timed(LP_KC_OTHER, st);
     const int head = (int)((16 - (reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) / 4;  // floats before 16-byte alignment
     const int64_t h = head < n ? head : n;
     const int64_t n4 = (n - h) / 4;

@@ -24,6 +24,21 @@ static inline int64_t lp_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b
 static inline size_t lp_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 static inline bool lp_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---------------------------------------------------------------- instrumentation (lp_timing.hip)
+// Kernel classes of lp_timing_collect, in the order of LP_KC_* in lp.h.
+class LpTimedScope {
+public:
+    LpTimedScope(int cls, hipStream_t st);
+    ~LpTimedScope();
+    LpTimedScope(const LpTimedScope &) = delete;
+    LpTimedScope &operator=(const LpTimedScope &) = delete;
+
+private:
+    int cls_;
+    hipStream_t st_;
+    void *beg_;
+};
+
 // ---------------------------------------------------------------- sparse aggregation (spmm_mean.hip)
 // out[v, :] = rowscale(v) * sum_{u in row v of (rowptr, colidx)} in[u, :]  (+ addend[v, :])  (* [gate[v, :] > 0])
 //   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(256) void edge_grad_scatter_kernel(const float *__r
 int launch_edge_scatter(const float *H, int32_t n_nodes, int32_t F, int64_t B, const int32_t *e_src, const int32_t *e_dst,
                         const float *dscore, float *Gout, hipStream_t st) {
     if (B <= 0) return LP_OK;
+    LpTimedScope timed(LP_KC_SCATTER, st);
     int G = 8;
     while (G < 64 && G * 4 < F) G <<= 1;
     const unsigned grid = (unsigned)lp_ceil_div(B, 256 / G);

@@ -81,6 +81,7 @@ extern "C" int lp_sample_neg(const lp_csr *g, int64_t n_pos, const int32_t *pos_
     if (n_pos > 0 && k_neg > 0 && n_pos > (((int64_t)1 << 31) - 1) / k_neg) return LP_ERR_OUT_OF_RANGE;
     if (n_q == 0) return LP_OK;
     if (!pos_src || !neg_dst) return LP_ERR_INVALID_ARG;
+    LpTimedScope timed(LP_KC_SAMPLE, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(sample_neg_kernel, dim3((unsigned)lp_ceil_div(n_q, 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), g->rowptr, g->colidx, g->n_nodes, pos_src, n_q, k_neg,
                        (uint32_t)n_space, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),

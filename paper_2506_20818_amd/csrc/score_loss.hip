@@ -110,6 +110,7 @@ extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t
     const float *H = static_cast<const float *>(HK);
     const int G = group_lanes(F);
     const int nb = loss_blocks(B, G);
+    LpTimedScope timed(LP_KC_SCORE, st);
 #define LP_SCORE_CASE(g)                                                                                              \
     case g:                                                                                                           \
         hipLaunchKernelGGL((score_loss_kernel<g>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos_edges,    \

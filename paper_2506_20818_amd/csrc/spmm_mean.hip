@@ -99,6 +99,7 @@ int launch(const SpmmArgs &a, hipStream_t st) {
 int lp_launch_spmm(const SpmmArgs &a, hipStream_t st) {
     if (a.n_rows <= 0) return LP_OK;
     if (a.F <= 0 || (a.F & 3)) return LP_ERR_UNSUPPORTED;
+    LpTimedScope timed(LP_KC_SPMM, st);
     const int F4 = a.F >> 2;
     if (F4 <= 8) return launch<8, 1>(a, st);
     if (F4 <= 16) return launch<16, 1>(a, st);
