@@ -2,6 +2,8 @@
 
 Bars: CSR arrays and sampled negatives bit-exact; activations, scores and loss within 1e-4 relative;
 gradients within 1e-3 relative (per tensor, max-norm and 2-norm), all in fp32 on the GPU vs fp64 in the oracle.
+Gradient entries that hinge on a hidden unit within 5e-6 of the ReLU kink (where fp32 and fp64 may take
+different branches, both valid) get the oracle-computed width of that ambiguity as extra slack.
 """
 import numpy as np
 import pytest
@@ -215,13 +217,39 @@ def test_score_loss_zero_embeddings_and_empty_batch():
 
 
 # ------------------------------------------------------------------------------------------------ backward
-def check_grads(grads, ref, K):
+GATE_MARGIN = 5e-6      # |z| below this is a near-tie of the ReLU gate for fp32 arithmetic on O(1) activations
+
+
+def gate_slack(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref):
+    """Gradient entries that depend on hidden units sitting within GATE_MARGIN of the ReLU kink: the kernel
+    takes relu'(z) = [z > 0] on its fp32 z, the oracle on its fp64 z, and for such units either branch is a
+    correct answer.  Returns |g(+margin) - g(-margin)| per tensor, computed by the oracle alone."""
+    lo = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=GATE_MARGIN)
+    hi = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=-GATE_MARGIN)
+    return lo, hi
+
+
+def assert_grad_close(got, ref, lo, hi, what):
+    got = np.asarray(got, np.float64)
+    assert np.all(np.isfinite(got)), what
+    excess = np.maximum(np.abs(got - ref) - 2.0 * np.abs(hi - lo), 0.0)     # outside the near-tie band
+    m, l2 = np.abs(ref).max(), np.sqrt((ref * ref).sum())
+    e_max = excess.max() / m if m > 0 else excess.max()
+    e_l2 = np.sqrt((excess * excess).sum()) / l2 if l2 > 0 else np.sqrt((excess * excess).sum())
+    assert e_max <= TOL_GRAD and e_l2 <= TOL_GRAD, "%s: max-norm rel %.3e, 2-norm rel %.3e" % (what, e_max, e_l2)
+    # the band itself must be rare: it may not swallow the comparison
+    assert (np.abs(hi - lo) > TOL_GRAD * m).mean() < 0.02 if m > 0 else True, what + ": near-tie band too wide"
+
+
+def check_grads(grads, ref, K, lo=None, hi=None):
+    lo = ref if lo is None else lo
+    hi = ref if hi is None else hi
     for k in range(K):
-        assert_close(host(grads.dW_self[k]), ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
-        assert_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
-        assert_close(host(grads.dbias[k]), ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
+        assert_grad_close(host(grads.dW_self[k]), ref.dW_self[k], lo.dW_self[k], hi.dW_self[k], "dW_self^%d" % (k + 1))
+        assert_grad_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], lo.dW_neigh[k], hi.dW_neigh[k], "dW_neigh^%d" % (k + 1))
+        assert_grad_close(host(grads.dbias[k]), ref.dbias[k], lo.dbias[k], hi.dbias[k], "dbias^%d" % (k + 1))
     if grads.dX is not None:
-        assert_close(host(grads.dX), ref.dX, TOL_GRAD, "dX")
+        assert_grad_close(host(grads.dX), ref.dX, lo.dX, hi.dX, "dX")
 
 
 @pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8]])
@@ -246,11 +274,12 @@ def test_backward_parity(dims, sym):
     a_ref = O.sage_forward(ref, Ws, Wn, b, X)
     s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
     g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
     assert_close(host(s), s_ref, TOL_ACT, "scores")
-    check_grads(grads, g_ref, len(dims) - 1)
+    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
     # without dX the weight gradients are the same
     grads2 = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
-    check_grads(grads2, g_ref, len(dims) - 1)
+    check_grads(grads2, g_ref, len(dims) - 1, lo, hi)
 
 
 def test_backward_empty_batch_gives_zero_gradients():
@@ -288,7 +317,8 @@ def whole_step(name):
     assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
     assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
     assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
-    check_grads(got.grads, exp.grads, K)
+    lo, hi = gate_slack(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore)
+    check_grads(got.grads, exp.grads, K, lo, hi)
 
 
 def test_whole_step_C1():
