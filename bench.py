@@ -110,7 +110,7 @@ def main():
     acts = lp.Acts(wl.n_nodes, wl.dims, dev)
     grads = lp.Grads(wl.n_nodes, wl.dims, dev)
     ws_f = torch.empty(B.forward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(B.backward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(B.backward_workspace_bytes(model, wl.n_nodes, Bn), dtype=torch.uint8, device=dev)
     ws_l = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
     scores = torch.empty(Bn, dtype=torch.float32, device=dev)
     dscore = torch.empty(Bn, dtype=torch.float32, device=dev)

@@ -60,7 +60,7 @@ EXPORTS = {
     "lp_score_loss_workspace_bytes": (C.c_size_t, [C.c_int64]),
     "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
-    "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
+    "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
     "lp_timing_enable": (C.c_int, [C.c_int]),
     "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
@@ -268,14 +268,14 @@ def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tens
     if grads is None:
         grads = Grads(g.n_nodes, m.dims, X.device, want_dX)
     if ws is None:
-        ws = _ws(lib.lp_backward_workspace_bytes(C.byref(m.c), g.n_nodes), X.device)
+        ws = _ws(lib.lp_backward_workspace_bytes(C.byref(m.c), g.n_nodes, int(e_src.numel())), X.device)
     _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
                            _ptr(e_dst), _ptr(dscore), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward")
     return grads
 
 
-def backward_workspace_bytes(m: Model, n_nodes: int) -> int:
-    return int(load_library().lp_backward_workspace_bytes(C.byref(m.c), n_nodes))
+def backward_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:
+    return int(load_library().lp_backward_workspace_bytes(C.byref(m.c), n_nodes, B))
 
 
 def forward_workspace_bytes(m: Model, n_nodes: int) -> int:

@@ -231,12 +231,12 @@ __global__ void split_cols_kernel(const uint64_t *__restrict__ keys, int64_t n, 
 }
 
 // rowptr[r] = number of keys whose row is < r = first position with key >= (r << bits)
-__global__ void rowptr_kernel(const uint64_t *__restrict__ ukeys, const uint32_t *__restrict__ nnz_dev, int32_t n_nodes,
-                              int bits, int32_t *__restrict__ rowptr) {
+__global__ void rowptr_kernel(const uint64_t *__restrict__ ukeys, int64_t n_host, const uint32_t *__restrict__ nnz_dev,
+                              int32_t n_nodes, int bits, int32_t *__restrict__ rowptr) {
     int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r > n_nodes) return;
     const uint64_t target = (uint64_t)r << bits;
-    int64_t lo = 0, hi = (int64_t)*nnz_dev;
+    int64_t lo = 0, hi = nnz_dev ? (int64_t)*nnz_dev : n_host;
     while (lo < hi) {
         int64_t mid = (lo + hi) >> 1;
         if (ukeys[mid] < target) lo = mid + 1; else hi = mid;
@@ -266,11 +266,7 @@ __global__ void low_words_kernel(const uint64_t *__restrict__ keys, int64_t n, i
     if (i < n) out[i] = (int32_t)(uint32_t)keys[i];
 }
 
-inline int bits_for(int32_t n_nodes) {
-    int b = 1;
-    while (((int64_t)1 << b) < (int64_t)n_nodes) ++b;
-    return b;
-}
+inline int bits_for(int32_t n_nodes) { return lp_bits_for(n_nodes); }
 
 struct BuildWs {
     uint64_t *keys_a, *keys_b, *ukeys;
@@ -306,6 +302,26 @@ int order_rows(const int32_t *rowptr, int32_t n_nodes, int32_t *order, BuildWs &
 }
 
 }  // namespace
+
+int lp_bits_for(int64_t n_values) {
+    int b = 1;
+    while (((int64_t)1 << b) < n_values) ++b;
+    return b;
+}
+
+size_t lp_radix_sort_hist_words(int64_t n) { return radix_hist_words(n); }
+
+uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t st,
+                        int *status) {
+    return radix_sort(a, b, n, first_bit, n_bits, hist, st, status);
+}
+
+int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,
+                          int32_t *offsets, hipStream_t st) {
+    hipLaunchKernelGGL(rowptr_kernel, dim3((unsigned)lp_ceil_div((int64_t)n_rows + 1, 256)), dim3(256), 0, st, sorted, n_host,
+                       n_dev, n_rows, shift, offsets);
+    return lp_after_launch();
+}
 
 extern "C" size_t lp_build_csr_workspace_bytes(int32_t n_nodes, int64_t n_in, uint32_t flags) {
     if (n_nodes <= 0 || n_in < 0) return 0;
@@ -351,7 +367,7 @@ extern "C" int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, 
         };
         LP_TRY(device_exclusive_scan(is_first, emit, cap, w.scan_sums, w.scalars, st));
     }
-    hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, w.ukeys, w.scalars, n_nodes, bits, rowptr);
+    hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, w.ukeys, (int64_t)0, w.scalars, n_nodes, bits, rowptr);
     hipLaunchKernelGGL(inv_deg_kernel, dim3(g_nodes), dim3(256), 0, st, rowptr, n_nodes, inv_deg);
     LP_TRY(lp_after_launch());
 
@@ -377,7 +393,7 @@ extern "C" int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, 
             hipLaunchKernelGGL(split_cols_kernel, dim3((unsigned)lp_ceil_div(nnz, 256)), dim3(256), 0, st, tsorted, nnz,
                                bits, t_colidx);
         }
-        hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, tsorted, w.scalars, n_nodes, bits, t_rowptr);
+        hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, tsorted, (int64_t)0, w.scalars, n_nodes, bits, t_rowptr);
         LP_TRY(lp_after_launch());
     }
     if (row_order) LP_TRY(order_rows(rowptr, n_nodes, row_order, w, st));

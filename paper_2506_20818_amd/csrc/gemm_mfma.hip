@@ -232,14 +232,6 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
     }
 }
 
-__global__ void sum_partials_kernel(const float *__restrict__ partials, int n_parts, int64_t n, float *__restrict__ out) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    float s = 0.f;
-    for (int p = 0; p < n_parts; ++p) s += partials[(int64_t)p * n + i];
-    out[i] = s;
-}
-
 struct TnPlan {
     int tm, tn, tiles, splits, chunk;
 };
@@ -249,7 +241,7 @@ TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
     p.tm = Mw > 64 ? 128 : 64;
     p.tn = Nw > 64 ? 128 : 64;
     p.tiles = (int)(lp_ceil_div(Mw, p.tm) * lp_ceil_div(Nw, p.tn));
-    int64_t want = lp_ceil_div(1024, p.tiles);          // about four workgroups per compute unit
+    int64_t want = lp_ceil_div(512, p.tiles);           // about two workgroups per compute unit
     int64_t max_by_len = lp_ceil_div(Kn, 8 * BK);       // at least 256 nodes per workgroup
     int64_t s = want < max_by_len ? want : max_by_len;
     if (s < 1) s = 1;
@@ -270,16 +262,40 @@ __global__ void transpose_kernel(const float *__restrict__ in, int rows, int col
         if (orow0 + i < cols && ocol < rows) out[(int64_t)(orow0 + i) * rows + ocol] = tile[threadIdx.x][i];
 }
 
-constexpr int kColsumRows = 1024;
+constexpr int kColsumRows = 256;  // rows folded by one workgroup
 
-__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ in, int32_t M, int32_t N,
+// partials[chunk, c] = sum of in[r, c] over the rows r of the chunk, rows taken in a fixed order.
+// Workgroup: 64 column quads x 4 row lanes; grid (column groups of 256 floats, row chunks).
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ in, int64_t M, int64_t N4,
                                                                   float *__restrict__ partials) {
-    const int64_t r0 = (int64_t)blockIdx.x * kColsumRows;
+    __shared__ float4 red[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t c4 = (int64_t)blockIdx.x * 64 + tx;
+    const int64_t r0 = (int64_t)blockIdx.y * kColsumRows;
     const int64_t r1 = r0 + kColsumRows < M ? r0 + kColsumRows : M;
-    for (int c = threadIdx.x; c < N; c += kThreads) {
-        float s = 0.f;
-        for (int64_t r = r0; r < r1; ++r) s += in[r * N + c];
-        partials[(int64_t)blockIdx.x * N + c] = s;
+    const float4 *__restrict__ in4 = reinterpret_cast<const float4 *>(in);
+    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+    if (c4 < N4) {
+        int64_t r = r0 + ty;
+        for (; r + 12 < r1; r += 16) {
+            const float4 x0 = in4[r * N4 + c4], x1 = in4[(r + 4) * N4 + c4];
+            const float4 x2 = in4[(r + 8) * N4 + c4], x3 = in4[(r + 12) * N4 + c4];
+            acc0.x += x0.x; acc0.y += x0.y; acc0.z += x0.z; acc0.w += x0.w;
+            acc1.x += x1.x; acc1.y += x1.y; acc1.z += x1.z; acc1.w += x1.w;
+            acc0.x += x2.x; acc0.y += x2.y; acc0.z += x2.z; acc0.w += x2.w;
+            acc1.x += x3.x; acc1.y += x3.y; acc1.z += x3.z; acc1.w += x3.w;
+        }
+        for (; r < r1; r += 4) {
+            const float4 x0 = in4[r * N4 + c4];
+            acc0.x += x0.x; acc0.y += x0.y; acc0.z += x0.z; acc0.w += x0.w;
+        }
+    }
+    red[ty][tx] = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
+    __syncthreads();
+    if (ty == 0 && c4 < N4) {
+        const float4 a = red[0][tx], b = red[1][tx], c = red[2][tx], d = red[3][tx];
+        reinterpret_cast<float4 *>(partials)[(int64_t)blockIdx.y * N4 + c4] =
+            make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z), (a.w + b.w) + (c.w + d.w));
     }
 }
 
@@ -313,7 +329,7 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
 size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw) {
     if (Kn <= 0 || Mw <= 0 || Nw <= 0) return 0;
     const TnPlan p = plan_tn(Kn, Mw, Nw);
-    return lp_align_up(sizeof(float) * (size_t)p.splits * Mw * Nw);
+    return lp_align_up(sizeof(float) * (size_t)p.splits * Mw * Nw) + lp_colsum_partials_bytes(p.splits, (int64_t)Mw * Nw);
 }
 
 int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
@@ -329,9 +345,10 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
     else if (p.tm == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
     else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<1, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
     else hipLaunchKernelGGL((gemm_tn_kernel<1, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    LP_TRY(lp_after_launch());
+    // fold the partial tiles: a column sum of the [splits, Mw*Nw] matrix
     const int64_t n = (int64_t)a.Mw * a.Nw;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)lp_ceil_div(n, 256)), dim3(256), 0, st, a.partials, p.splits, n, a.C);
-    return lp_after_launch();
+    return lp_launch_colsum(a.partials, p.splits, n, a.C, a.partials + lp_align_up(sizeof(float) * (size_t)p.splits * n) / sizeof(float), st);
 }
 
 int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t st) {
@@ -342,17 +359,32 @@ int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out,
     return lp_after_launch();
 }
 
-size_t lp_colsum_partials_bytes(int32_t M, int32_t N) {
-    return lp_align_up(sizeof(float) * (size_t)lp_ceil_div(M > 0 ? M : 1, kColsumRows) * (size_t)(N > 0 ? N : 1));
+size_t lp_colsum_partials_bytes(int64_t M, int64_t N) {
+    // level sizes shrink by kColsumRows each time; two ping-pong areas of the first level's size are enough
+    const int64_t chunks = lp_ceil_div(M > 0 ? M : 1, kColsumRows);
+    return 2 * lp_align_up(sizeof(float) * (size_t)chunks * (size_t)(N > 0 ? N : 1));
 }
 
-int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *partials, hipStream_t st) {
+int lp_launch_colsum(const float *in, int64_t M, int64_t N, float *out, float *partials, hipStream_t st) {
     if (N <= 0) return LP_OK;
+    if (N & 3) return LP_ERR_UNSUPPORTED;
     if (M <= 0) return lp_launch_zero(out, N, st);
     LpTimedScope timed(LP_KC_OTHER, st);
-    const int nb = (int)lp_ceil_div(M, kColsumRows);
-    hipLaunchKernelGGL(colsum_partial_kernel, dim3(nb), dim3(kThreads), 0, st, in, M, N, partials);
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)lp_ceil_div(N, 256)), dim3(256), 0, st, partials, nb, (int64_t)N, out);
+    const int64_t N4 = N >> 2;
+    const size_t area = lp_align_up(sizeof(float) * (size_t)lp_ceil_div(M, kColsumRows) * (size_t)N) / sizeof(float);
+    const float *src = in;
+    int64_t rows = M;
+    int level = 0;
+    while (true) {
+        const int64_t chunks = lp_ceil_div(rows, kColsumRows);
+        float *dst = chunks == 1 ? out : partials + (level & 1) * area;
+        hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)lp_ceil_div(N4, 64), (unsigned)chunks), dim3(kThreads), 0, st,
+                           src, rows, N4, dst);
+        if (chunks == 1) break;
+        src = dst;
+        rows = chunks;
+        ++level;
+    }
     return lp_after_launch();
 }
 

@@ -40,7 +40,8 @@ private:
 };
 
 // ---------------------------------------------------------------- sparse aggregation (spmm_mean.hip)
-// out[v, :] = rowscale(v) * sum_{u in row v of (rowptr, colidx)} in[u, :]  (+ addend[v, :])  (* [gate[v, :] > 0])
+// out[v, :] = rowscale(v) * sum_{p in row v} w[p] * in[colidx[p], :]  (+ addend[v, :])  (* [gate[v, :] > 0])
+//   w[p] = 1 when w == nullptr
 //   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1
 // All matrices are [n_rows, F] fp32 with contiguous rows; F % 4 == 0.
 struct SpmmArgs {
@@ -50,10 +51,12 @@ struct SpmmArgs {
     const int32_t *colidx = nullptr;
     const int32_t *row_order = nullptr;  // optional processing order
     const float *inv_deg = nullptr;      // optional per-output-row scale
+    const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
     const float *in = nullptr;
     const float *addend = nullptr;       // optional [n_rows, F]
     const float *gate = nullptr;         // optional [n_rows, F]: output is zeroed where gate <= 0
     float *out = nullptr;
+    int timing_class = LP_KC_SPMM;       // class the launch is booked under by the instrumentation
 };
 int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
 
@@ -98,8 +101,22 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t stream);
 
 // out[c, r] = in[r, c] for a small [rows, cols] matrix (weights).
 int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t stream);
-// out[n] = sum_m in[m, n], fixed summation order; partials: lp_colsum_partials_bytes()
-size_t lp_colsum_partials_bytes(int32_t M, int32_t N);
-int lp_launch_colsum(const float *in, int32_t M, int32_t N, float *out, float *partials, hipStream_t stream);
+// out[n] = sum_m in[m, n] for a contiguous [M, N] matrix (N % 4 == 0), fixed summation order;
+// partials: lp_colsum_partials_bytes()
+size_t lp_colsum_partials_bytes(int64_t M, int64_t N);
+int lp_launch_colsum(const float *in, int64_t M, int64_t N, float *out, float *partials, hipStream_t stream);
 // fill n floats with zero (kernel, so that callers may capture it)
 int lp_launch_zero(float *p, int64_t n, hipStream_t stream);
+
+// ---------------------------------------------------------------- sorting (csr_build.hip)
+// Stable least-significant-digit radix sort of 64-bit keys on bits [first_bit, first_bit + n_bits), 8 bits per
+// pass.  `a` holds the input, `b` is a second buffer of n keys, `hist` has lp_radix_sort_hist_words(n) words.
+// Returns the buffer that holds the sorted keys (a or b).
+size_t lp_radix_sort_hist_words(int64_t n);
+uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t stream,
+                        int *status);
+// offsets[r] = number of sorted keys below (r << shift), r = 0..n_rows; the key count is *n_dev when n_dev is
+// given, else n_host.
+int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,
+                          int32_t *offsets, hipStream_t stream);
+int lp_bits_for(int64_t n_values);

@@ -4,8 +4,6 @@
 // gemm_mfma.hip plus the edge-gradient scatter below.
 #include "lp_internal.h"
 
-#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
-
 namespace {
 
 int check_model(const lp_model *m) {
@@ -50,67 +48,45 @@ int max_dim(const lp_model *m) {
 }
 
 // dL/dH^K: every scored edge (u, v) with weight g = dL/ds adds g*h_v to row u and g*h_u to row v.
-// A group of G lanes owns an edge; rows are updated with hardware fp32 atomic adds.
-template <int G>
-__global__ __launch_bounds__(256) void edge_grad_scatter_kernel(const float *__restrict__ H, int32_t n_nodes, int32_t F, int64_t B,
-                                                                const int32_t *__restrict__ e_src,
-                                                                const int32_t *__restrict__ e_dst,
-                                                                const float *__restrict__ dscore, float *__restrict__ Gout) {
-    const int sub = threadIdx.x % G;
-    const int64_t e = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
-    if (e >= B) return;
+// Instead of atomic adds, the 2B (node, other endpoint, g) entries are grouped by node with a stable radix
+// sort and each row is then summed by one wavefront in a fixed order: the result does not depend on scheduling,
+// and rows no edge touches are written as zeros by the same pass.
+__global__ void batch_keys_kernel(const int32_t *__restrict__ e_src, const int32_t *__restrict__ e_dst, int64_t B,
+                                  int32_t n_nodes, uint64_t *__restrict__ keys) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= 2 * B) return;
+    const int64_t e = j < B ? j : j - B;
     const int32_t u = e_src[e], v = e_dst[e];
-    if (u < 0 || u >= n_nodes || v < 0 || v >= n_nodes) return;
-    const float g = dscore[e];
-    const int F4 = F >> 2;
-    const float4 *hu = reinterpret_cast<const float4 *>(H + (int64_t)u * F);
-    const float4 *hv = reinterpret_cast<const float4 *>(H + (int64_t)v * F);
-    float *gu = Gout + (int64_t)u * F, *gv = Gout + (int64_t)v * F;
-    for (int j = sub; j < F4; j += G) {
-        const float4 a = hu[j], b = hv[j];
-        unsafeAtomicAdd(gu + 4 * j + 0, g * b.x);
-        unsafeAtomicAdd(gu + 4 * j + 1, g * b.y);
-        unsafeAtomicAdd(gu + 4 * j + 2, g * b.z);
-        unsafeAtomicAdd(gu + 4 * j + 3, g * b.w);
-        unsafeAtomicAdd(gv + 4 * j + 0, g * a.x);
-        unsafeAtomicAdd(gv + 4 * j + 1, g * a.y);
-        unsafeAtomicAdd(gv + 4 * j + 2, g * a.z);
-        unsafeAtomicAdd(gv + 4 * j + 3, g * a.w);
-    }
+    const bool ok = u >= 0 && u < n_nodes && v >= 0 && v < n_nodes;
+    const int32_t node = ok ? (j < B ? u : v) : n_nodes;  // edges with a bad id are parked behind the last row
+    keys[j] = ((uint64_t)(uint32_t)node << 32) | (uint32_t)j;
 }
 
-int launch_edge_scatter(const float *H, int32_t n_nodes, int32_t F, int64_t B, const int32_t *e_src, const int32_t *e_dst,
-                        const float *dscore, float *Gout, hipStream_t st) {
-    if (B <= 0) return LP_OK;
-    LpTimedScope timed(LP_KC_SCATTER, st);
-    int G = 8;
-    while (G < 64 && G * 4 < F) G <<= 1;
-    const unsigned grid = (unsigned)lp_ceil_div(B, 256 / G);
-#define LP_CASE(g)                                                                                                           \
-    case g:                                                                                                                  \
-        hipLaunchKernelGGL((edge_grad_scatter_kernel<g>), dim3(grid), dim3(256), 0, st, H, n_nodes, F, B, e_src, e_dst,      \
-                           dscore, Gout);                                                                                    \
-        break;
-    switch (G) {
-        LP_CASE(8)
-        LP_CASE(16)
-        LP_CASE(32)
-        default:
-            hipLaunchKernelGGL((edge_grad_scatter_kernel<64>), dim3(grid), dim3(256), 0, st, H, n_nodes, F, B, e_src, e_dst,
-                               dscore, Gout);
-    }
-#undef LP_CASE
-    return lp_after_launch();
+__global__ void batch_entries_kernel(const uint64_t *__restrict__ sorted, int64_t B, const int32_t *__restrict__ e_src,
+                                     const int32_t *__restrict__ e_dst, const float *__restrict__ dscore, int32_t n_nodes,
+                                     int32_t *__restrict__ col, float *__restrict__ w) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= 2 * B) return;
+    const uint64_t k = sorted[p];
+    const int64_t j = (int64_t)(uint32_t)k;
+    const int64_t e = j < B ? j : j - B;
+    const bool parked = (int32_t)(k >> 32) >= n_nodes;
+    col[p] = parked ? 0 : (j < B ? e_dst[e] : e_src[e]);
+    w[p] = parked ? 0.f : dscore[e];
 }
 
 struct BackwardWs {
     float *buf[3];
     float *tn_partials;
     float *colsum_partials;
+    uint64_t *keys_a, *keys_b;
+    uint32_t *hist;
+    int32_t *bptr, *bcol;
+    float *bw;
     size_t bytes;
 };
 
-BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes) {
+BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t B) {
     char *p = static_cast<char *>(ws);
     size_t off = 0;
     auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += lp_align_up(bytes); return reinterpret_cast<float *>(q); };
@@ -126,6 +102,13 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes) {
     }
     w.tn_partials = take(tn);
     w.colsum_partials = take(cs);
+    const size_t n2 = (size_t)(2 * (B > 0 ? B : 0) + 1);
+    w.keys_a = reinterpret_cast<uint64_t *>(take(sizeof(uint64_t) * n2));
+    w.keys_b = reinterpret_cast<uint64_t *>(take(sizeof(uint64_t) * n2));
+    w.hist = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * lp_radix_sort_hist_words((int64_t)n2)));
+    w.bptr = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * ((size_t)n_nodes + 1)));
+    w.bcol = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * n2));
+    w.bw = take(sizeof(float) * n2);
     w.bytes = off;
     return w;
 }
@@ -187,9 +170,9 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
     return LP_OK;
 }
 
-extern "C" size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
-    if (check_model(m) != LP_OK || n_nodes <= 0) return 0;
-    return carve_backward(nullptr, m, n_nodes).bytes;
+extern "C" size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes, int64_t B) {
+    if (check_model(m) != LP_OK || n_nodes <= 0 || B < 0) return 0;
+    return carve_backward(nullptr, m, n_nodes, B).bytes;
 }
 
 extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
@@ -205,15 +188,36 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     for (int k = 0; k < K; ++k)
         if (!out->dW_self[k] || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
     if (out->dX && !lp_aligned16(out->dX)) return LP_ERR_INVALID_ARG;
-    if (!ws || ws_bytes < lp_backward_workspace_bytes(m, g->n_nodes)) return LP_ERR_WORKSPACE;
+    if (!ws || ws_bytes < lp_backward_workspace_bytes(m, g->n_nodes, B)) return LP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    BackwardWs w = carve_backward(ws, m, g->n_nodes);
+    BackwardWs w = carve_backward(ws, m, g->n_nodes, B);
     const int32_t N = g->n_nodes;
 
     float *dZ = w.buf[0], *Q = w.buf[1], *R = w.buf[2];
     const float *HK = static_cast<const float *>(saved->H[K - 1]);
-    LP_TRY(lp_launch_zero(dZ, (int64_t)N * m->dims[K], st));
-    LP_TRY(launch_edge_scatter(HK, N, m->dims[K], B, e_src, e_dst, dscore, dZ, st));
+    if (B == 0) {
+        LP_TRY(lp_launch_zero(dZ, (int64_t)N * m->dims[K], st));
+    } else {
+        const int64_t n2 = 2 * B;
+        const unsigned g2 = (unsigned)lp_ceil_div(n2, 256);
+        const uint64_t *sorted;
+        {
+            LpTimedScope timed(LP_KC_SCATTER, st);
+            hipLaunchKernelGGL(batch_keys_kernel, dim3(g2), dim3(256), 0, st, e_src, e_dst, B, N, w.keys_a);
+            int status;
+            sorted = lp_radix_sort(w.keys_a, w.keys_b, n2, 32, lp_bits_for((int64_t)N + 1), w.hist, st, &status);
+            LP_TRY(status);
+            LP_TRY(lp_launch_row_offsets(sorted, n2, nullptr, N, 32, w.bptr, st));
+            hipLaunchKernelGGL(batch_entries_kernel, dim3(g2), dim3(256), 0, st, sorted, B, e_src, e_dst, dscore, N, w.bcol, w.bw);
+            LP_TRY(lp_after_launch());
+        }
+        SpmmArgs sc;
+        sc.n_rows = N; sc.F = m->dims[K];
+        sc.rowptr = w.bptr; sc.colidx = w.bcol; sc.w = w.bw;
+        sc.in = HK; sc.out = dZ;
+        sc.timing_class = LP_KC_SCATTER;
+        LP_TRY(lp_launch_spmm(sc, st));
+    }
 
     for (int k = K; k >= 1; --k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];

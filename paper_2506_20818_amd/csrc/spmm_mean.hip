@@ -18,7 +18,7 @@ constexpr int kUnroll = 4;
 __device__ inline float4 f4_add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
 // G: lanes per neighbour row (8..64), C: 16-byte chunks per lane (C > 1 only when G == 64 and F > 256)
-template <int G, int C>
+template <int G, int C, bool W>
 __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     constexpr int P = 64 / G;  // neighbours read per step
     const int lane = threadIdx.x & 63;
@@ -38,12 +38,16 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     for (int32_t base = lo; base < hi; base += 64) {
         const int cnt = min(64, hi - base);
         const int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
+        float mine_w = 1.f;
+        if (W) mine_w = lane < cnt ? a.w[base + lane] : 0.f;
         for (int j0 = 0; j0 < cnt; j0 += P * kUnroll) {
             float4 x[kUnroll][C];
+            float wj[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int j = j0 + u * P + sub;
                 const int32_t nb = __shfl(mine, j & 63, 64);
+                wj[u] = W ? __shfl(mine_w, j & 63, 64) : 1.f;
                 const bool on = lane_on && j < cnt;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
@@ -54,7 +58,16 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
 #pragma unroll
-                for (int c = 0; c < C; ++c) acc[c] = f4_add(acc[c], x[u][c]);
+                for (int c = 0; c < C; ++c) {
+                    if (W) {
+                        acc[c].x += wj[u] * x[u][c].x;
+                        acc[c].y += wj[u] * x[u][c].y;
+                        acc[c].z += wj[u] * x[u][c].z;
+                        acc[c].w += wj[u] * x[u][c].w;
+                    } else {
+                        acc[c] = f4_add(acc[c], x[u][c]);
+                    }
+                }
         }
     }
 #pragma unroll
@@ -90,7 +103,8 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
 template <int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
     const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kThreads / 64);
-    hipLaunchKernelGGL((spmm_rows_kernel<G, C>), dim3(grid), dim3(kThreads), 0, st, a);
+    if (a.w) hipLaunchKernelGGL((spmm_rows_kernel<G, C, true>), dim3(grid), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((spmm_rows_kernel<G, C, false>), dim3(grid), dim3(kThreads), 0, st, a);
     return lp_after_launch();
 }
 
@@ -99,7 +113,7 @@ int launch(const SpmmArgs &a, hipStream_t st) {
 int lp_launch_spmm(const SpmmArgs &a, hipStream_t st) {
     if (a.n_rows <= 0) return LP_OK;
     if (a.F <= 0 || (a.F & 3)) return LP_ERR_UNSUPPORTED;
-    LpTimedScope timed(LP_KC_SPMM, st);
+    LpTimedScope timed(a.timing_class, st);
     const int F4 = a.F >> 2;
     if (F4 <= 8) return launch<8, 1>(a, st);
     if (F4 <= 16) return launch<16, 1>(a, st);

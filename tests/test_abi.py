@@ -59,10 +59,11 @@ def test_workspace_queries_are_host_arithmetic():
     m = _model([128, 256, 256, 256])
     f1 = lib.lp_sage_forward_workspace_bytes(C.byref(m), 1000)
     assert f1 >= 4 * 2 * (128 * 256 + 2 * 256 * 256)
-    b1 = lib.lp_backward_workspace_bytes(C.byref(m), 1000)
-    b2 = lib.lp_backward_workspace_bytes(C.byref(m), 2000)
-    assert 3 * 1000 * 256 * 4 <= b1 < b2
-    assert lib.lp_backward_workspace_bytes(C.byref(_model([128, 255])), 1000) == 0
+    b1 = lib.lp_backward_workspace_bytes(C.byref(m), 1000, 100)
+    b2 = lib.lp_backward_workspace_bytes(C.byref(m), 2000, 100)
+    b3 = lib.lp_backward_workspace_bytes(C.byref(m), 2000, 100000)
+    assert 3 * 1000 * 256 * 4 <= b1 < b2 < b3
+    assert lib.lp_backward_workspace_bytes(C.byref(_model([128, 255])), 1000, 10) == 0
     assert lib.lp_score_loss_workspace_bytes(10) > 0
 
 
