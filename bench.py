@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--cpu-scale", type=float, default=0.25, help="fraction of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a dispatch of known size for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py measures one worker's step on ONE GPU; --gpus %d is not supported "
@@ -122,6 +124,14 @@ def main():
         lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
         lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)
 
+    if args.copy_calibration_mib > 0:
+        a = torch.zeros(args.copy_calibration_mib << 18, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -165,8 +175,19 @@ def main():
                 "frac": round(tf / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None, "launches_per_step": cnt,
                 "avg_launch_ms": round(ms / max(cnt, 1), 4), "flops_per_launch": int(flops_per_step / max(cnt, 1))}
 
+    # HBM bytes per launch from the committed rocprofv3 --pmc summaries (FETCH_SIZE and WRITE_SIZE runs of this
+    # same script, scaled by what a plain copy of known size reads); null when no summary covers the workload.
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh)
+
     lines = {"spmm": hbm_line("spmm", sp_bytes), "gemm_nt": mfma_line("gemm_nt", nt_flops),
              "gemm_tn": mfma_line("gemm_tn", tn_flops)}
+    for cls in lines:
+        t = traffic.get(cls + "_bytes_per_launch")
+        lines[cls]["traffic"] = int(t) if t else None
     dominant = max(lines, key=lambda c: per_step[c][0])
 
     out = {

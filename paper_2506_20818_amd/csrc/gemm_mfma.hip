@@ -13,6 +13,8 @@
 //   is split over the grid; partial tiles are written out and summed in a fixed order by a second kernel.
 #include "lp_internal.h"
 
+#include <cstdlib>
+
 namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -26,7 +28,7 @@ __device__ inline v16f mfma32(float a, float b, v16f c) { return __builtin_amdgc
 
 // ------------------------------------------------------------------------------------------------ NT
 template <int NB>  // 32-column blocks per wavefront: BN = 64 * NB
-__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(GemmNtArgs g) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_kernel(GemmNtArgs g) {
     constexpr int BN = 64 * NB;
     constexpr int WN = 32 * NB;                 // columns per wavefront
     constexpr int A_LOADS = BM * BK / 4 / kThreads;  // float4 per thread: 4
@@ -104,15 +106,23 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(GemmNtArgs g) {
 #pragma unroll
             for (int cb = 0; cb < NB; ++cb)
                 b[cb] = *reinterpret_cast<const float4 *>(&Bs[(wn * WN + cb * 32 + i32) * LDS_LD + kk * 8 + 4 * h]);
+            // k-major order: consecutive MFMAs write different accumulators
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < NB; ++cb) {
-                    acc[rb][cb] = mfma32(a[rb].x, b[cb].x, acc[rb][cb]);
-                    acc[rb][cb] = mfma32(a[rb].y, b[cb].y, acc[rb][cb]);
-                    acc[rb][cb] = mfma32(a[rb].z, b[cb].z, acc[rb][cb]);
-                    acc[rb][cb] = mfma32(a[rb].w, b[cb].w, acc[rb][cb]);
-                }
+                for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(a[rb].x, b[cb].x, acc[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(a[rb].y, b[cb].y, acc[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(a[rb].z, b[cb].z, acc[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(a[rb].w, b[cb].w, acc[rb][cb]);
         }
     }
 
@@ -318,7 +328,10 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
     LpTimedScope timed(LP_KC_GEMM_NT, st);
     const unsigned gx = (unsigned)lp_ceil_div(a.M, BM);
-    if (a.N > 64) {
+    static const int force_bn = getenv("LP_GEMM_NT_BN") ? atoi(getenv("LP_GEMM_NT_BN")) : 0;
+    if (a.N > 128 && force_bn != 128) {
+        hipLaunchKernelGGL((gemm_nt_kernel<4>), dim3(gx, (unsigned)lp_ceil_div(a.N, 256)), dim3(kThreads), 0, st, a);
+    } else if (a.N > 64) {
         hipLaunchKernelGGL((gemm_nt_kernel<2>), dim3(gx, (unsigned)lp_ceil_div(a.N, 128)), dim3(kThreads), 0, st, a);
     } else {
         hipLaunchKernelGGL((gemm_nt_kernel<1>), dim3(gx, 1), dim3(kThreads), 0, st, a);
