@@ -62,20 +62,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         const int ldb = s ? g.ldb[1] : g.ldb[0];
         const float *__restrict__ Bt0 = s ? g.Bt[1][0] : g.Bt[0][0];
         const float *__restrict__ Bt1 = s ? g.Bt[1][1] : g.Bt[0][1];
+        // out-of-range rows and k are read from a clamped (valid) address and then zeroed: no branches
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
             const int idx = p * kThreads + tid;
             const int row = idx >> 3, k = k0 + ((idx & 7) << 2);
             const int64_t m = m0 + row;
-            ra[p] = (m < g.M && k < K) ? *reinterpret_cast<const float4 *>(A + m * lda + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const bool ok = m < g.M && k < K;
+            const float4 v = *reinterpret_cast<const float4 *>(A + (m < g.M ? m : g.M - 1) * lda + (k < K ? k : K - 4));
+            ra[p] = make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int idx = p * kThreads + tid;
             const int row = idx >> 3, k = k0 + ((idx & 7) << 2);
             const int n = n0 + row;
-            const float *__restrict__ brow = n < g.n_split ? Bt0 + (int64_t)n * ldb : Bt1 + (int64_t)(n - g.n_split) * ldb;
-            rbv[p] = (n < g.N && k < K) ? *reinterpret_cast<const float4 *>(brow + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int nn = n < g.N ? n : g.N - 1;
+            const bool ok = n < g.N && k < K;
+            const float *__restrict__ brow = nn < g.n_split ? Bt0 + (int64_t)nn * ldb : Bt1 + (int64_t)(nn - g.n_split) * ldb;
+            const float4 v = *reinterpret_cast<const float4 *>(brow + (k < K ? k : K - 4));
+            rbv[p] = make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
         }
     };
     auto stash = [&]() {
@@ -126,26 +132,40 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         }
     }
 
-    // epilogue: accumulator register r of lane (j = lane % 32, h = lane / 32) is row 8*(r/4) + 4*h + r%4, column j
+    // epilogue: accumulator register r of lane (j = lane % 32, h = lane / 32) is row 8*(r/4) + 4*h + r%4, column j.
+    // Row scales are fetched up front so that the stores that follow need no waits between them.
+    float rs[2][16];
 #pragma unroll
-    for (int cb = 0; cb < NB; ++cb) {
-        const int n = n0 + wn * WN + cb * 32 + i32;
-        if (n >= g.N) continue;
-        const float bias = g.bias ? g.bias[n] : 0.f;
-        const bool second = n >= g.n_split;
-        float *__restrict__ C = second ? g.C[1] : g.C[0];
-        const int ldc = second ? g.ldc[1] : g.ldc[0];
-        const int nc = second ? n - g.n_split : n;
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rs[rb][r] = 1.f;
+    if (g.rowscale) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (m >= g.M) continue;
+                rs[rb][r] = g.rowscale[m < g.M ? m : g.M - 1];
+            }
+    }
+#pragma unroll
+    for (int cb = 0; cb < NB; ++cb) {
+        const int n = n0 + wn * WN + cb * 32 + i32;
+        const bool n_ok = n < g.N;
+        const float bias = (g.bias && n_ok) ? g.bias[n] : 0.f;
+        const bool second = n >= g.n_split;
+        float *__restrict__ C = second ? g.C[1] : g.C[0];
+        const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
+        C += second ? n - g.n_split : n;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 float y = acc[rb][cb][r] + bias;
                 if (g.relu) y = fmaxf(y, 0.f);
-                if (second && g.rowscale) y *= g.rowscale[m];
-                C[m * ldc + nc] = y;
+                y *= second ? rs[rb][r] : 1.f;
+                if (n_ok && m < g.M) C[m * ldc] = y;
             }
     }
 }

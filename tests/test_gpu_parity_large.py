@@ -1,0 +1,118 @@
+"""GPU parity at the larger benchmark shapes.
+
+C3 (one worker's view of a partitioned 1 M-node graph, 3 negatives per positive): the whole step, element by
+element.  C4 (2.9 M nodes, 29 M directed entries): CSR and negatives bit-exact in full; the floating-point calls
+are checked at full size on outputs the oracle can compute one by one - sampled rows of the aggregation and of
+the layer output, every score, and the weight gradients of a one-layer model (whose loss gradient only touches
+the batch endpoints, so the oracle needs those rows alone).
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2506_20818_amd as lp
+from lp_workloads import init_features, make_workload
+from oracle import lp_oracle as O
+from gpu_util import DEV, assert_close, dev_f32, dev_i32, host, make_model
+from test_gpu_parity import TOL_ACT, TOL_GRAD, check_csr, run_sampler, say, whole_step
+
+
+def test_whole_step_C3_worker_view():
+    whole_step("C3")
+
+
+@pytest.fixture(scope="module")
+def c4():
+    wl = make_workload("C4", with_features=False)
+    say("C4 graph: N=%d E=%d" % (wl.n_nodes, wl.src.size))
+    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    return wl, ref, g
+
+
+def test_C4_csr_and_negatives_bit_exact(c4):
+    wl, ref, g = c4
+    say("C4 csr + sampler")
+    check_csr(g, ref)
+    run_sampler(ref, g, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+
+
+def sample_rows(ref, rng, n_random=1500, n_hubs=20):
+    deg = np.diff(ref.rowptr)
+    hubs = np.argsort(deg)[-n_hubs:]
+    empty = np.flatnonzero(deg == 0)[:20]
+    return np.unique(np.concatenate([rng.integers(0, ref.n_nodes, n_random), hubs, empty]))
+
+
+@pytest.mark.parametrize("F", [128, 256])
+def test_C4_forward_one_layer_sampled_rows(c4, F):
+    wl, ref, g = c4
+    say("C4 forward F=%d sampled rows" % F)
+    rng = np.random.default_rng(40 + F)
+    X = init_features(wl.n_nodes, F, 500 + F)
+    Ws = (rng.standard_normal((F, 256)) / np.sqrt(2 * F)).astype(np.float32)
+    Wn = (rng.standard_normal((F, 256)) / np.sqrt(2 * F)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, 256).astype(np.float32)
+    # two layers so that the first one is rectified: rows of A^1 and H^1 are checked
+    W2 = np.zeros((256, 4), np.float32)
+    acts = lp.lp_sage_forward(g, make_model([Ws, W2], [Wn, W2], [b, np.zeros(4, np.float32)]), dev_f32(X))
+    rows = sample_rows(ref, rng)
+    a_ref = O.mean_aggregate(ref, X, rows)
+    h_ref = np.maximum(X[rows].astype(np.float64) @ Ws.astype(np.float64) + a_ref @ Wn.astype(np.float64) + b, 0.0)
+    ridx = torch.from_numpy(rows).to(DEV)
+    assert_close(host(acts.A[0][ridx]), a_ref, TOL_ACT, "A^1 rows")
+    assert_close(host(acts.H[0][ridx]), h_ref, TOL_ACT, "H^1 rows")
+    # invariants at full size: rows without neighbours aggregate to zero, everything is finite
+    iso = torch.from_numpy(np.flatnonzero(np.diff(ref.rowptr) == 0)).to(DEV)
+    assert float(acts.A[0][iso].abs().max()) == 0.0
+    assert bool(torch.isfinite(acts.H[0]).all())
+
+
+def test_C4_score_and_one_layer_backward(c4):
+    wl, ref, g = c4
+    say("C4 score + backward, one layer 256->256")
+    rng = np.random.default_rng(77)
+    F = 256
+    N = wl.n_nodes
+    X = init_features(N, F, 901)
+    Ws = (rng.standard_normal((F, F)) / np.sqrt(2 * F) * F ** -0.25).astype(np.float32)
+    Wn = (rng.standard_normal((F, F)) / np.sqrt(2 * F) * F ** -0.25).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, F).astype(np.float32)
+    neg, _ = O.sample_neg(ref, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+    es, ed = O.batch_edges(wl.pos_src, wl.pos_dst, neg, wl.k_neg)
+    model = make_model([Ws], [Wn], [b])
+    Xd = dev_f32(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), wl.n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+
+    # oracle on the rows the batch touches (dL/dH is zero elsewhere)
+    touched = np.unique(np.concatenate([es, ed]))
+    pos_of = np.full(N, -1, np.int64)
+    pos_of[touched] = np.arange(touched.size)
+    a_t = O.mean_aggregate(ref, X, touched)
+    x_t = X[touched].astype(np.float64)
+    h_t = x_t @ Ws.astype(np.float64) + a_t @ Wn.astype(np.float64) + b          # single layer: not rectified
+    s_ref, loss_ref, ds_ref = O.score_loss(h_t, pos_of[es], pos_of[ed], wl.n_pos)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
+    assert_close(host(ds), ds_ref, TOL_ACT, "dscore")
+    dZ_t = O.edge_grad_scatter(h_t, pos_of[es], pos_of[ed], ds_ref)             # rows of dL/dZ, compact
+    assert_close(host(grads.dbias[0]), dZ_t.sum(0), TOL_GRAD, "dbias")
+    assert_close(host(grads.dW_self[0]), x_t.T @ dZ_t, TOL_GRAD, "dW_self")
+    assert_close(host(grads.dW_neigh[0]), a_t.T @ dZ_t, TOL_GRAD, "dW_neigh")
+    # dX on sampled rows: dZ[u] W_self^T + sum over v with u in N(v) of dZ[v] W_neigh^T / |N(v)|
+    rows = sample_rows(ref, rng, n_random=400, n_hubs=5)
+    deg = np.diff(ref.rowptr).astype(np.float64)
+    T_t = dZ_t @ Wn.astype(np.float64).T
+    dX_ref = np.zeros((rows.size, F))
+    for i, u in enumerate(rows):
+        if pos_of[u] >= 0:
+            dX_ref[i] = dZ_t[pos_of[u]] @ Ws.astype(np.float64).T
+        vs = ref.t_colidx[ref.t_rowptr[u]:ref.t_rowptr[u + 1]]
+        vs = vs[pos_of[vs] >= 0]
+        if vs.size:
+            dX_ref[i] += (T_t[pos_of[vs]] / deg[vs, None]).sum(0)
+    assert_close(host(grads.dX[torch.from_numpy(rows).to(DEV)]), dX_ref, TOL_GRAD, "dX rows")
