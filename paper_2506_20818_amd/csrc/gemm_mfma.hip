@@ -18,6 +18,7 @@
 namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 128;
@@ -39,8 +40,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int n0 = blockIdx.y * BN;
+    // Workgroups are handed to the eight XCDs round-robin by linear id.  The column tiles of one row tile get ids
+    // that are 8 apart, so they run on the same XCD back to back and the second one finds the A rows in that L2.
+    const int col_tiles = (g.N + BN - 1) / BN;
+    const int slot = blockIdx.x >> 3;
+    const int64_t row_tile = (int64_t)(slot / col_tiles) * 8 + (blockIdx.x & 7);
+    if (row_tile * BM >= g.M) return;
+    const int64_t m0 = row_tile * BM;
+    const int n0 = (slot % col_tiles) * BN;
     const int tiles0 = (g.K[0] + BK - 1) / BK, tiles1 = (g.K[1] + BK - 1) / BK;
     const int n_tiles = tiles0 + tiles1;
 
@@ -168,6 +175,193 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 if (n_ok && m < g.M) C[m * ldc] = y;
             }
     }
+}
+
+// ------------------------------------------------------------------------------------------------ NT, fast path
+// Same product as gemm_nt_kernel for shapes whose K parts are multiples of 16 and whose column tiles do not
+// straddle n_split.  What makes it faster:
+//  * persistent workgroups (two per compute unit): a workgroup walks over row tiles b, b+G, b+2G, ... and, for each,
+//    over all column tiles, as ONE software pipeline.  The loads of the next tile's first K steps are already in
+//    flight while the current tile's results are stored, so only the very first tile pays the load latency, and
+//    the second column tile of a row tile finds the A rows in the XCD's L2;
+//  * K step 16 with two LDS stages and one barrier per step: while the MFMAs of step u run from stage u&1, step u+1
+//    (already in registers) is written to the other stage and the loads of step u+2 are issued;
+//  * addresses are a wavefront-uniform base plus a per-thread 32-bit offset that is set once per K part; rows and
+//    columns past the edge are clamped to the last valid one (their products land in outputs that are never stored);
+//  * LDS rows are padded to 20 floats: sixteen consecutive rows start in sixteen different groups of four banks.
+constexpr int FK = 16;
+constexpr int F_LD = FK + 4;
+
+template <int NB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
+    constexpr int BN = 64 * NB;
+    constexpr int WN = 32 * NB;
+    constexpr int A_LOADS = BM * FK / 4 / kThreads;  // 2
+    constexpr int B_LOADS = BN * FK / 4 / kThreads;  // NB
+    constexpr int STAGE = (BM + BN) * F_LD;          // floats per LDS stage
+    __shared__ float lds[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int col_tiles = (g.N + BN - 1) / BN;
+    const int64_t row_tiles = ((int64_t)g.M + BM - 1) / BM;
+    const int tiles0 = g.K[0] / FK, tiles1 = g.K[1] / FK;
+    const int n_tiles = tiles0 + tiles1;
+    if ((int64_t)blockIdx.x >= row_tiles || n_tiles == 0) return;
+    const int64_t my_rows = (row_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const int64_t n_work = my_rows * col_tiles;      // output tiles of this workgroup
+    const int64_t n_steps = n_work * n_tiles;
+
+    v16f acc[2][NB];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+
+    // load cursor: output tile fw, K step ft
+    int64_t fw = 0;
+    int ft = 0;
+    int64_t m0f = 0;
+    int n0f = 0, n_endf = 0;
+    bool secondf = false;
+    const char *abase = nullptr, *bbase = nullptr;
+    uint32_t aoff[A_LOADS], boff[B_LOADS];
+    v4f ra[A_LOADS], rbv[B_LOADS];  // plain vector registers: a struct copy would go through private memory
+
+#define LP_SET_PART(part)                                                                                              \
+    {                                                                                                                  \
+        const float *A_ = (part) ? g.A[1] : g.A[0];                                                                    \
+        const int64_t lda_ = (part) ? g.lda[1] : g.lda[0];                                                             \
+        const int64_t ldb_ = (part) ? g.ldb[1] : g.ldb[0];                                                             \
+        const float *Bt_ = secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1]) : ((part) ? g.Bt[1][0] : g.Bt[0][0]);          \
+        abase = reinterpret_cast<const char *>(A_ + m0f * lda_);                                                       \
+        bbase = reinterpret_cast<const char *>(Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_);               \
+        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
+            const int idx = p * kThreads + tid;                                                                        \
+            int64_t r = idx >> 2;                                                                                      \
+            r = m0f + r < g.M ? r : g.M - 1 - m0f;                                                                     \
+            aoff[p] = (uint32_t)((r * lda_ + ((idx & 3) << 2)) * 4);                                                   \
+        }                                                                                                              \
+        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
+            const int idx = p * kThreads + tid;                                                                        \
+            int64_t r = idx >> 2;                                                                                      \
+            r = n0f + r < n_endf ? r : n_endf - 1 - n0f;                                                               \
+            boff[p] = (uint32_t)((r * ldb_ + ((idx & 3) << 2)) * 4);                                                   \
+        }                                                                                                              \
+    }
+    // loads of the next K step in pipeline order (possibly the first step of the next output tile)
+#define LP_FETCH_NEXT()                                                                                                \
+    if (fw < n_work) {                                                                                                 \
+        if (ft == 0) {                                                                                                 \
+            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BM;                                           \
+            n0f = (int)(fw % col_tiles) * BN;                                                                          \
+            secondf = n0f >= g.n_split;                                                                                \
+            n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                              \
+            if (tiles0 > 0) LP_SET_PART(0) else LP_SET_PART(1)                                                         \
+        } else if (ft == tiles0) {                                                                                     \
+            LP_SET_PART(1)                                                                                             \
+        }                                                                                                              \
+        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) ra[p] = *reinterpret_cast<const v4f *>(abase + aoff[p]);   \
+        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) rbv[p] = *reinterpret_cast<const v4f *>(bbase + boff[p]);  \
+        abase += FK * 4;                                                                                               \
+        bbase += FK * 4;                                                                                               \
+        if (++ft == n_tiles) {                                                                                         \
+            ft = 0;                                                                                                    \
+            ++fw;                                                                                                      \
+        }                                                                                                              \
+    }
+#define LP_STASH(stage)                                                                                                \
+    {                                                                                                                  \
+        float *As_ = lds + (stage) * STAGE;                                                                            \
+        float *Bs_ = As_ + BM * F_LD;                                                                                  \
+        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
+            const int idx = p * kThreads + tid;                                                                        \
+            *reinterpret_cast<v4f *>(&As_[(idx >> 2) * F_LD + ((idx & 3) << 2)]) = ra[p];                              \
+        }                                                                                                              \
+        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
+            const int idx = p * kThreads + tid;                                                                        \
+            *reinterpret_cast<v4f *>(&Bs_[(idx >> 2) * F_LD + ((idx & 3) << 2)]) = rbv[p];                             \
+        }                                                                                                              \
+    }
+#define LP_COMPUTE(stage, kk)                                                                                          \
+    {                                                                                                                  \
+        const float *As_ = lds + (stage) * STAGE;                                                                      \
+        const float *Bs_ = As_ + BM * F_LD;                                                                            \
+        v4f a[2], b[NB];                                                                                               \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            a[rb] = *reinterpret_cast<const v4f *>(&As_[(wm * 64 + rb * 32 + i32) * F_LD + (kk) * 8 + 4 * h]);         \
+        _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                              \
+            b[cb] = *reinterpret_cast<const v4f *>(&Bs_[(wn * WN + cb * 32 + i32) * F_LD + (kk) * 8 + 4 * h]);         \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].x, a[rb].x, acc[rb][cb]);     \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].y, a[rb].y, acc[rb][cb]);     \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].z, a[rb].z, acc[rb][cb]);     \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].w, a[rb].w, acc[rb][cb]);     \
+    }
+
+    LP_FETCH_NEXT()
+    LP_STASH(0)
+    LP_FETCH_NEXT()
+    __syncthreads();
+    int64_t cw = 0;  // output tile being accumulated
+    int ct = 0;      // its K step
+    for (int64_t u = 0; u < n_steps; ++u) {
+        const int cur = (int)(u & 1);
+        LP_COMPUTE(cur, 0)
+        if (u + 1 < n_steps) LP_STASH(cur ^ 1)  // registers hold step u+1
+        LP_FETCH_NEXT()                         // step u+2
+        LP_COMPUTE(cur, 1)
+        __syncthreads();
+        if (++ct < n_tiles) continue;
+        ct = 0;
+        // ---- this output tile is complete: store it.  The MFMAs were fed with the weight tile as the row operand, so
+        // each 32x32 accumulator block is the TRANSPOSE of the output block: lane (j = lane % 32, h = lane / 32)
+        // holds output row j and, in registers 4q..4q+3, the four consecutive columns 8q + 4h .. + 3.  Every lane
+        // therefore stores 16 contiguous bytes at a time and needs a single row scale.
+        const int64_t m0 = ((int64_t)blockIdx.x + (cw / col_tiles) * gridDim.x) * BM;
+        const int n0 = (int)(cw % col_tiles) * BN;
+        ++cw;
+        const bool second = n0 >= g.n_split;
+        const bool scaled = g.rowscale && second;
+        float *__restrict__ Cb = second ? g.C[1] : g.C[0];
+        const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
+        const int ncol0 = (second ? n0 - g.n_split : n0) + wn * WN + 4 * h;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int64_t m = m0 + wm * 64 + rb * 32 + i32;
+            const bool m_ok = m < g.M;
+            const float rs = (scaled && m_ok) ? g.rowscale[m] : 1.f;
+            float *__restrict__ Crow = Cb + (m_ok ? m : 0) * ldc + ncol0;
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n0 + wn * WN + cb * 32 + 8 * q + 4 * h;
+                    const bool n_ok = n < g.N;
+                    v4f bias = {0.f, 0.f, 0.f, 0.f};
+                    if (g.bias && n_ok) bias = *reinterpret_cast<const v4f *>(g.bias + n);
+                    v4f y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float t = acc[rb][cb][4 * q + e] + bias[e];
+                        if (g.relu) t = fmaxf(t, 0.f);
+                        y[e] = t * rs;
+                        acc[rb][cb][4 * q + e] = 0.f;
+                    }
+                    if (m_ok && n_ok) *reinterpret_cast<v4f *>(Crow + cb * 32 + 8 * q) = y;
+                }
+        }
+    }
+#undef LP_SET_PART
+#undef LP_FETCH_NEXT
+#undef LP_STASH
+#undef LP_COMPUTE
 }
 
 // ------------------------------------------------------------------------------------------------ TN
@@ -337,6 +531,18 @@ __global__ void zero_kernel(float4 *__restrict__ p4, int64_t n4, float *__restri
 
 }  // namespace
 
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
 int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return LP_OK;
     for (int s = 0; s < 2; ++s) {
@@ -347,14 +553,29 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     }
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
     LpTimedScope timed(LP_KC_GEMM_NT, st);
-    const unsigned gx = (unsigned)lp_ceil_div(a.M, BM);
     static const int force_bn = getenv("LP_GEMM_NT_BN") ? atoi(getenv("LP_GEMM_NT_BN")) : 0;
-    if (a.N > 128 && force_bn != 128) {
-        hipLaunchKernelGGL((gemm_nt_kernel<4>), dim3(gx, (unsigned)lp_ceil_div(a.N, 256)), dim3(kThreads), 0, st, a);
+    static const int no_fast = getenv("LP_GEMM_NT_NOFAST") ? 1 : 0;
+    // fast path: K parts in whole steps, and no column tile straddling the output split
+    const int fast_bn = (a.N > 128 && force_bn != 128) ? 256 : 128;
+    const bool fast_ok = !no_fast && a.N > 64 && (a.K[0] % FK == 0) && (a.K[1] % FK == 0) && a.K[0] + a.K[1] > 0 &&
+                         (a.n_split >= a.N || a.n_split % fast_bn == 0);
+    auto grid_for = [&](int bn) {
+        const int64_t row_tiles8 = lp_ceil_div(lp_ceil_div(a.M, BM), 8) * 8;
+        return dim3((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
+    };
+    if (fast_ok) {
+        // persistent workgroups, two per compute unit
+        const int64_t row_tiles = lp_ceil_div(a.M, BM);
+        const int64_t slots = 2 * (int64_t)compute_units();
+        const dim3 pgrid((unsigned)(row_tiles < slots ? row_tiles : slots));
+        if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<4>), pgrid, dim3(kThreads), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nt_fast_kernel<2>), pgrid, dim3(kThreads), 0, st, a);
+    } else if (a.N > 128 && force_bn != 128) {
+        hipLaunchKernelGGL((gemm_nt_kernel<4>), grid_for(256), dim3(kThreads), 0, st, a);
     } else if (a.N > 64) {
-        hipLaunchKernelGGL((gemm_nt_kernel<2>), dim3(gx, (unsigned)lp_ceil_div(a.N, 128)), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((gemm_nt_kernel<2>), grid_for(128), dim3(kThreads), 0, st, a);
     } else {
-        hipLaunchKernelGGL((gemm_nt_kernel<1>), dim3(gx, 1), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((gemm_nt_kernel<1>), grid_for(64), dim3(kThreads), 0, st, a);
     }
     return lp_after_launch();
 }
