@@ -18,7 +18,9 @@
  *    *_workspace_bytes() function, which is pure host arithmetic.
  *  - Matrices are row-major and node-major: row v of a [N, F] matrix is the
  *    vector of node v.  Feature, activation and weight pointers must be
- *    16-byte aligned and every layer width must be a multiple of 4.
+ *    16-byte aligned and every layer width must be a multiple of 4 (of 8 with
+ *    LP_BF16, where those matrices hold bfloat16 and everything is still
+ *    accumulated in fp32; biases, scores, loss and gradients stay fp32).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued on it and, except for lp_build_csr, the call returns
  *    without waiting.
@@ -47,11 +49,14 @@ enum {
     LP_ERR_INVALID_ARG = -1,  /* null pointer, negative size, misaligned matrix, bad layer count */
     LP_ERR_OUT_OF_RANGE = -2, /* node id outside [0, n_nodes), or sizes beyond int32 indexing */
     LP_ERR_WORKSPACE = -3,    /* ws is NULL or smaller than *_workspace_bytes() */
-    LP_ERR_UNSUPPORTED = -4,  /* dtype other than LP_F32, or a width that is not a multiple of 4 */
+    LP_ERR_UNSUPPORTED = -4,  /* unknown dtype, or a width that is not a multiple of 4 (8 for LP_BF16) */
     LP_ERR_HIP = -5           /* the HIP runtime reported an error (no device, failed launch) */
 };
 
-enum { LP_F32 = 0 };
+enum {
+    LP_F32 = 0, /* fp32 storage */
+    LP_BF16 = 1 /* bfloat16 storage (features, weights, activations), fp32 accumulation, fp32 gradients */
+};
 
 /* flags of lp_build_csr */
 #define LP_SYMMETRIZE 1u /* every input pair (r, c) also counts as (c, r) */
@@ -77,12 +82,12 @@ typedef struct lp_csr {
  *   h'_v = max(z_v, 0) for k < K and z_v for k = K. */
 typedef struct lp_model {
     int32_t n_layers;                     /* K, 1..LP_MAX_LAYERS */
-    int32_t dtype;                        /* LP_F32 */
+    int32_t dtype;                        /* LP_F32 or LP_BF16: storage of X, W_self, W_neigh, A and H */
     int32_t dims[LP_MAX_LAYERS + 1];      /* F_0 .. F_K */
     int32_t reserved_;
     const void *W_self[LP_MAX_LAYERS];    /* device [F_{k-1}, F_k] */
     const void *W_neigh[LP_MAX_LAYERS];   /* device [F_{k-1}, F_k] */
-    const void *bias[LP_MAX_LAYERS];      /* device [F_k] */
+    const void *bias[LP_MAX_LAYERS];      /* device [F_k], always fp32 */
 } lp_model;
 
 /* Activations written by lp_sage_forward and read by lp_backward. */
@@ -91,12 +96,12 @@ typedef struct lp_acts {
     void *H[LP_MAX_LAYERS]; /* H[k-1]: device [n_nodes, F_k], output of layer k; H[K-1] are the embeddings */
 } lp_acts;
 
-/* Gradients written (overwritten, not accumulated) by lp_backward; always fp32. */
+/* Gradients written (overwritten, not accumulated) by lp_backward.  Weight and bias gradients are always fp32. */
 typedef struct lp_grads {
     float *dW_self[LP_MAX_LAYERS];  /* device [F_{k-1}, F_k] */
     float *dW_neigh[LP_MAX_LAYERS]; /* device [F_{k-1}, F_k] */
     float *dbias[LP_MAX_LAYERS];    /* device [F_k] */
-    float *dX;                      /* device [n_nodes, F_0] or NULL to skip the input gradient */
+    void *dX;                       /* device [n_nodes, F_0] in the model's storage type, or NULL to skip it */
 } lp_grads;
 
 /* Text for a status code (static storage, never NULL). */

@@ -265,18 +265,27 @@ def score_loss(HK: np.ndarray, e_src: np.ndarray, e_dst: np.ndarray, n_pos_edges
 # ==========================================================================
 # Backward: chain rule through scorer, layers and aggregation
 # ==========================================================================
-def mean_aggregate_adjoint(csr: CSR, T: np.ndarray) -> np.ndarray:
-    """Adjoint of mean_aggregate: node u receives T[v]/|N(v)| from every v that
-    aggregates from u.  Written as the scatter dual of the forward loop, from
-    the forward CSR alone."""
+def neighbour_sum_adjoint(csr: CSR, T: np.ndarray) -> np.ndarray:
+    """Adjoint of the plain neighbour sum: node u receives T[v] from every v that aggregates from u.  Written
+    as the scatter dual of the forward loop, from the forward CSR alone."""
     T = np.asarray(T, np.float64)
     out = np.zeros_like(T)
     rp, ci = csr.rowptr, csr.colidx
     for v in range(csr.n_nodes):
         lo, hi = rp[v], rp[v + 1]
         if hi > lo:
-            out[ci[lo:hi]] += T[v] / float(hi - lo)    # columns are distinct inside a row
+            out[ci[lo:hi]] += T[v]      # columns are distinct inside a row
     return out
+
+
+def inverse_degrees(csr: CSR) -> np.ndarray:
+    deg = np.diff(csr.rowptr.astype(np.int64)).astype(np.float64)
+    return np.divide(1.0, deg, out=np.zeros_like(deg), where=deg > 0)
+
+
+def mean_aggregate_adjoint(csr: CSR, T: np.ndarray) -> np.ndarray:
+    """Adjoint of mean_aggregate: node u receives T[v]/|N(v)| from every v that aggregates from u."""
+    return neighbour_sum_adjoint(csr, np.asarray(T, np.float64) * inverse_degrees(csr)[:, None])
 
 
 @dataclass
@@ -296,20 +305,27 @@ def edge_grad_scatter(HK: np.ndarray, e_src, e_dst, dscore) -> np.ndarray:
     return G
 
 
-def backward(csr: CSR, W_self, W_neigh, acts: Activations, e_src, e_dst, dscore, relu_margin: float = 0.0) -> Grads:
+def backward(csr: CSR, W_self, W_neigh, acts: Activations, e_src, e_dst, dscore, relu_margin: float = 0.0,
+             storage: str = "f32") -> Grads:
     """``relu_margin`` is 0 for the method itself: relu'(z) = [z > 0].  A test may pass +t and -t to find the
     gradient entries that depend on hidden units whose pre-activation lies within t of the kink, where a
-    lower-precision implementation may legitimately take the other branch."""
+    lower-precision implementation may legitimately take the other branch.
+
+    With ``storage="bf16"`` every node-sized matrix that a bf16 implementation keeps in memory is rounded to
+    bfloat16 where it is stored: dL/dH^K, the two products dZ W_self^T and (dZ W_neigh^T)/|N(v)|, and each
+    dL/dH^(k-1).  Weight and bias gradients are sums over those stored values and are not rounded."""
     K = len(W_self)
-    G = edge_grad_scatter(acts.H[K], e_src, e_dst, np.asarray(dscore, np.float64))
+    inv_d = inverse_degrees(csr)
+    G = _store(edge_grad_scatter(acts.H[K], e_src, e_dst, np.asarray(dscore, np.float64)), storage)
     dWs, dWn, db = [None] * K, [None] * K, [None] * K
     for k in range(K, 0, -1):
         dZ = G if k == K else G * (acts.Z[k] > relu_margin)
         db[k - 1] = dZ.sum(axis=0)
         dWs[k - 1] = acts.H[k - 1].T @ dZ
         dWn[k - 1] = acts.A[k].T @ dZ
-        T = dZ @ np.asarray(W_neigh[k - 1], np.float64).T
-        G = dZ @ np.asarray(W_self[k - 1], np.float64).T + mean_aggregate_adjoint(csr, T)
+        T = _store((dZ @ np.asarray(W_neigh[k - 1], np.float64).T) * inv_d[:, None], storage)
+        S = _store(dZ @ np.asarray(W_self[k - 1], np.float64).T, storage)
+        G = _store(S + neighbour_sum_adjoint(csr, T), storage)
     return Grads(dWs, dWn, db, G)
 
 
@@ -342,5 +358,5 @@ def train_step(csr: CSR, W_self, W_neigh, bias, X, pos_src, pos_dst, k_neg, n_sp
     e_src, e_dst = batch_edges(pos_src, pos_dst, neg_dst, k_neg)
     acts = sage_forward(csr, W_self, W_neigh, bias, X, storage)
     s, loss, ds = score_loss(acts.H[-1], e_src, e_dst, pos_src.size)
-    grads = backward(csr, W_self, W_neigh, acts, e_src, e_dst, ds)
+    grads = backward(csr, W_self, W_neigh, acts, e_src, e_dst, ds, storage=storage)
     return StepResult(neg_dst, e_src, e_dst, acts, s, loss, ds, grads)

@@ -13,6 +13,10 @@ import torch
 LP_MAX_LAYERS = 8
 LP_SYMMETRIZE = 1
 LP_F32 = 0
+LP_BF16 = 1
+
+_TORCH_OF = {LP_F32: torch.float32, LP_BF16: torch.bfloat16}
+_LP_OF = {torch.float32: LP_F32, torch.bfloat16: LP_BF16}
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -133,7 +137,8 @@ class Csr:
 
 
 class Model:
-    """Weights of the K layers: W_self[k], W_neigh[k] of shape [F_{k-1}, F_k] and bias[k] of shape [F_k]."""
+    """Weights of the K layers: W_self[k], W_neigh[k] of shape [F_{k-1}, F_k] (float32 or bfloat16, which selects
+    the storage type of the whole model) and bias[k] of shape [F_k] (always float32)."""
 
     def __init__(self, W_self: List[torch.Tensor], W_neigh: List[torch.Tensor], bias: List[torch.Tensor]):
         K = len(W_self)
@@ -141,13 +146,17 @@ class Model:
             raise ValueError("bad layer count")
         self.W_self, self.W_neigh, self.bias = list(W_self), list(W_neigh), list(bias)
         self.dims = [int(W_self[0].shape[0])] + [int(w.shape[1]) for w in W_self]
+        self.torch_dtype = W_self[0].dtype
+        if self.torch_dtype not in _LP_OF:
+            raise ValueError("weights must be float32 or bfloat16")
+        self.dtype = _LP_OF[self.torch_dtype]
         s = _ModelStruct()
-        s.n_layers, s.dtype = K, LP_F32
+        s.n_layers, s.dtype = K, self.dtype
         for k in range(K + 1):
             s.dims[k] = self.dims[k]
         for k in range(K):
             for t, nm in ((W_self[k], "W_self"), (W_neigh[k], "W_neigh")):
-                _need(t, torch.float32, nm)
+                _need(t, self.torch_dtype, nm)
                 if tuple(t.shape) != (self.dims[k], self.dims[k + 1]):
                     raise ValueError("%s[%d] has the wrong shape" % (nm, k))
             _need(bias[k], torch.float32, "bias")
@@ -158,10 +167,10 @@ class Model:
 class Acts:
     """Saved activations: A[k-1] = mean-aggregated input of layer k, H[k-1] = output of layer k."""
 
-    def __init__(self, n_nodes: int, dims: List[int], device):
+    def __init__(self, n_nodes: int, dims: List[int], device, dtype=torch.float32):
         K = len(dims) - 1
-        self.A = [torch.empty((n_nodes, dims[k]), dtype=torch.float32, device=device) for k in range(K)]
-        self.H = [torch.empty((n_nodes, dims[k + 1]), dtype=torch.float32, device=device) for k in range(K)]
+        self.A = [torch.empty((n_nodes, dims[k]), dtype=dtype, device=device) for k in range(K)]
+        self.H = [torch.empty((n_nodes, dims[k + 1]), dtype=dtype, device=device) for k in range(K)]
         s = _ActsStruct()
         for k in range(K):
             s.A[k], s.H[k] = self.A[k].data_ptr(), self.H[k].data_ptr()
@@ -169,13 +178,13 @@ class Acts:
 
 
 class Grads:
-    def __init__(self, n_nodes: int, dims: List[int], device, want_dX: bool = False):
+    def __init__(self, n_nodes: int, dims: List[int], device, want_dX: bool = False, dtype=torch.float32):
         K = len(dims) - 1
         mk = lambda *shape: torch.empty(shape, dtype=torch.float32, device=device)
         self.dW_self = [mk(dims[k], dims[k + 1]) for k in range(K)]
         self.dW_neigh = [mk(dims[k], dims[k + 1]) for k in range(K)]
         self.dbias = [mk(dims[k + 1]) for k in range(K)]
-        self.dX = mk(n_nodes, dims[0]) if want_dX else None
+        self.dX = torch.empty((n_nodes, dims[0]), dtype=dtype, device=device) if want_dX else None
         s = _GradsStruct()
         for k in range(K):
             s.dW_self[k], s.dW_neigh[k], s.dbias[k] = (self.dW_self[k].data_ptr(), self.dW_neigh[k].data_ptr(),
@@ -212,11 +221,11 @@ def lp_build_csr(n_nodes: int, rows: torch.Tensor, cols: torch.Tensor, symmetriz
 
 def lp_sage_forward(g: Csr, m: Model, X: torch.Tensor, acts: Optional[Acts] = None, ws: Optional[torch.Tensor] = None) -> Acts:
     lib = load_library()
-    _need(X, torch.float32, "X")
+    _need(X, m.torch_dtype, "X")
     if tuple(X.shape) != (g.n_nodes, m.dims[0]):
         raise ValueError("X has the wrong shape")
     if acts is None:
-        acts = Acts(g.n_nodes, m.dims, X.device)
+        acts = Acts(g.n_nodes, m.dims, X.device, m.torch_dtype)
     if ws is None:
         ws = _ws(lib.lp_sage_forward_workspace_bytes(C.byref(m.c), g.n_nodes), X.device)
     _check(lib.lp_sage_forward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), _ptr(ws), ws.numel(), _stream()),
@@ -241,7 +250,9 @@ def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_
                   scores: Optional[torch.Tensor] = None, loss: Optional[torch.Tensor] = None,
                   dscore: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
     lib = load_library()
-    _need(HK, torch.float32, "HK")
+    if HK.dtype not in _LP_OF:
+        raise ValueError("HK must be float32 or bfloat16")
+    _need(HK, HK.dtype, "HK")
     _need(e_src, torch.int32, "e_src")
     _need(e_dst, torch.int32, "e_dst")
     B = int(e_src.numel())
@@ -254,7 +265,7 @@ def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_
         dscore = torch.empty(B, dtype=torch.float32, device=dev)
     if ws is None:
         ws = _ws(lib.lp_score_loss_workspace_bytes(B), dev)
-    _check(lib.lp_score_loss(_ptr(HK), HK.shape[0], HK.shape[1], LP_F32, B, n_pos_edges, _ptr(e_src), _ptr(e_dst),
+    _check(lib.lp_score_loss(_ptr(HK), HK.shape[0], HK.shape[1], _LP_OF[HK.dtype], B, n_pos_edges, _ptr(e_src), _ptr(e_dst),
                              _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(ws), ws.numel(), _stream()), "lp_score_loss")
     return scores, loss, dscore
 
@@ -263,10 +274,10 @@ def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tens
                 dscore: torch.Tensor, grads: Optional[Grads] = None, ws: Optional[torch.Tensor] = None,
                 want_dX: bool = False) -> Grads:
     lib = load_library()
-    _need(X, torch.float32, "X")
+    _need(X, m.torch_dtype, "X")
     _need(dscore, torch.float32, "dscore")
     if grads is None:
-        grads = Grads(g.n_nodes, m.dims, X.device, want_dX)
+        grads = Grads(g.n_nodes, m.dims, X.device, want_dX, m.torch_dtype)
     if ws is None:
         ws = _ws(lib.lp_backward_workspace_bytes(C.byref(m.c), g.n_nodes, int(e_src.numel())), X.device)
     _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),

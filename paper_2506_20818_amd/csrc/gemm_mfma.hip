@@ -63,12 +63,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     auto fetch = [&](int t) {
         const int s = t < tiles0 ? 0 : 1;
         const int k0 = (s ? t - tiles0 : t) * BK;
-        const float *__restrict__ A = s ? g.A[1] : g.A[0];  // explicit selects keep the argument block in SGPRs
+        const float *__restrict__ A = static_cast<const float *>(s ? g.A[1] : g.A[0]);  // explicit selects keep the argument block in SGPRs
         const int K = s ? g.K[1] : g.K[0];
         const int lda = s ? g.lda[1] : g.lda[0];
         const int ldb = s ? g.ldb[1] : g.ldb[0];
-        const float *__restrict__ Bt0 = s ? g.Bt[1][0] : g.Bt[0][0];
-        const float *__restrict__ Bt1 = s ? g.Bt[1][1] : g.Bt[0][1];
+        const float *__restrict__ Bt0 = static_cast<const float *>(s ? g.Bt[1][0] : g.Bt[0][0]);
+        const float *__restrict__ Bt1 = static_cast<const float *>(s ? g.Bt[1][1] : g.Bt[0][1]);
         // out-of-range rows and k are read from a clamped (valid) address and then zeroed: no branches
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         const bool n_ok = n < g.N;
         const float bias = (g.bias && n_ok) ? g.bias[n] : 0.f;
         const bool second = n >= g.n_split;
-        float *__restrict__ C = second ? g.C[1] : g.C[0];
+        float *__restrict__ C = static_cast<float *>(second ? g.C[1] : g.C[0]);
         const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
         C += second ? n - g.n_split : n;
 #pragma unroll
@@ -233,10 +233,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 
 #define LP_SET_PART(part)                                                                                              \
     {                                                                                                                  \
-        const float *A_ = (part) ? g.A[1] : g.A[0];                                                                    \
+        const float *A_ = static_cast<const float *>((part) ? g.A[1] : g.A[0]);                                        \
         const int64_t lda_ = (part) ? g.lda[1] : g.lda[0];                                                             \
         const int64_t ldb_ = (part) ? g.ldb[1] : g.ldb[0];                                                             \
-        const float *Bt_ = secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1]) : ((part) ? g.Bt[1][0] : g.Bt[0][0]);          \
+        const float *Bt_ = static_cast<const float *>(secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1])                     \
+                                                              : ((part) ? g.Bt[1][0] : g.Bt[0][0]));                   \
         abase = reinterpret_cast<const char *>(A_ + m0f * lda_);                                                       \
         bbase = reinterpret_cast<const char *>(Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_);               \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         ++cw;
         const bool second = n0 >= g.n_split;
         const bool scaled = g.rowscale && second;
-        float *__restrict__ Cb = second ? g.C[1] : g.C[0];
+        float *__restrict__ Cb = static_cast<float *>(second ? g.C[1] : g.C[0]);
         const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
         const int ncol0 = (second ? n0 - g.n_split : n0) + wn * WN + 4 * h;
 #pragma unroll
@@ -364,12 +365,150 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #undef LP_COMPUTE
 }
 
+// ------------------------------------------------------------------------------------------------ NT, bfloat16
+// Same product with bfloat16 operands and fp32 accumulation (v_mfma_f32_32x32x16_bf16: lane half h supplies the
+// eight consecutive k values 8h..8h+7 of a 16-wide step, i.e. one 16-byte LDS read).  K step 64; LDS rows hold
+// 64 + 8 elements (144 bytes = 36 banks: eight consecutive rows start in eight different groups of four banks).
+// The weight tile is the row operand of the MFMA, so an accumulator block is the transposed output block and a
+// lane owns four consecutive columns of one output row: results are rounded to bfloat16 and stored 8 bytes at a time.
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int HK = 64;
+constexpr int H_LD = HK + 8;
+
+template <int NB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_bf16_kernel(GemmNtArgs g) {
+    constexpr int BN = 64 * NB;
+    constexpr int WN = 32 * NB;
+    constexpr int A_LOADS = BM * HK / 8 / kThreads;  // 16-byte vectors per thread: 4
+    constexpr int B_LOADS = BN * HK / 8 / kThreads;  // NB * 2
+    __shared__ lp_bf16_t As[BM * H_LD];
+    __shared__ lp_bf16_t Bs[BN * H_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int col_tiles = (g.N + BN - 1) / BN;
+    const int slot = blockIdx.x >> 3;
+    const int64_t row_tile = (int64_t)(slot / col_tiles) * 8 + (blockIdx.x & 7);
+    if (row_tile * BM >= g.M) return;
+    const int64_t m0 = row_tile * BM;
+    const int n0 = (slot % col_tiles) * BN;
+    const int tiles0 = (g.K[0] + HK - 1) / HK, tiles1 = (g.K[1] + HK - 1) / HK;
+    const int n_tiles = tiles0 + tiles1;
+
+    v16f acc[2][NB];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+
+    v4i ra[A_LOADS], rbv[B_LOADS];
+    const v4i zero = {0, 0, 0, 0};
+    for (int t = 0; t <= n_tiles; ++t) {
+        if (t > 0) {
+            __syncthreads();  // previous tile fully consumed
+#pragma unroll
+            for (int p = 0; p < A_LOADS; ++p) {
+                const int idx = p * kThreads + tid;
+                *reinterpret_cast<v4i *>(&As[(idx >> 3) * H_LD + ((idx & 7) << 3)]) = ra[p];
+            }
+#pragma unroll
+            for (int p = 0; p < B_LOADS; ++p) {
+                const int idx = p * kThreads + tid;
+                *reinterpret_cast<v4i *>(&Bs[(idx >> 3) * H_LD + ((idx & 7) << 3)]) = rbv[p];
+            }
+            __syncthreads();
+        }
+        if (t < n_tiles) {  // global loads of tile t overlap the MFMAs of tile t-1 below
+            const int part = t < tiles0 ? 0 : 1;
+            const int k0 = (part ? t - tiles0 : t) * HK;
+            const lp_bf16_t *__restrict__ A = static_cast<const lp_bf16_t *>(part ? g.A[1] : g.A[0]);
+            const int K = part ? g.K[1] : g.K[0];
+            const int64_t lda = part ? g.lda[1] : g.lda[0];
+            const int64_t ldb = part ? g.ldb[1] : g.ldb[0];
+            const lp_bf16_t *__restrict__ Bt0 = static_cast<const lp_bf16_t *>(part ? g.Bt[1][0] : g.Bt[0][0]);
+            const lp_bf16_t *__restrict__ Bt1 = static_cast<const lp_bf16_t *>(part ? g.Bt[1][1] : g.Bt[0][1]);
+#pragma unroll
+            for (int p = 0; p < A_LOADS; ++p) {
+                const int idx = p * kThreads + tid;
+                const int k = k0 + ((idx & 7) << 3);
+                int64_t m = m0 + (idx >> 3);
+                m = m < g.M ? m : g.M - 1;  // rows past the edge only feed outputs that are never stored
+                const v4i v = *reinterpret_cast<const v4i *>(A + m * lda + (k < K ? k : K - 8));
+                ra[p] = k < K ? v : zero;
+            }
+#pragma unroll
+            for (int p = 0; p < B_LOADS; ++p) {
+                const int idx = p * kThreads + tid;
+                const int k = k0 + ((idx & 7) << 3);
+                int n = n0 + (idx >> 3);
+                n = n < g.N ? n : g.N - 1;
+                const lp_bf16_t *__restrict__ brow = n < g.n_split ? Bt0 + (int64_t)n * ldb : Bt1 + (int64_t)(n - g.n_split) * ldb;
+                const v4i v = *reinterpret_cast<const v4i *>(brow + (k < K ? k : K - 8));
+                rbv[p] = k < K ? v : zero;
+            }
+        }
+        if (t == 0) continue;
+#pragma unroll
+        for (int kk = 0; kk < HK / 16; ++kk) {
+            v4i a[2], b[NB];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+                a[rb] = *reinterpret_cast<const v4i *>(&As[(wm * 64 + rb * 32 + i32) * H_LD + kk * 16 + 8 * h]);
+#pragma unroll
+            for (int cb = 0; cb < NB; ++cb)
+                b[cb] = *reinterpret_cast<const v4i *>(&Bs[(wn * WN + cb * 32 + i32) * H_LD + kk * 16 + 8 * h]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, b[cb]), __builtin_bit_cast(v8bf, a[rb]),
+                                                                          acc[rb][cb], 0, 0, 0);
+        }
+    }
+
+    // transposed accumulator blocks: lane (j = lane % 32, h) holds output row j, columns 8q + 4h .. + 3 in registers 4q..4q+3
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int64_t m = m0 + wm * 64 + rb * 32 + i32;
+        const bool m_ok = m < g.M;
+        const float rs_row = (g.rowscale && m_ok) ? g.rowscale[m] : 1.f;
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + cb * 32 + 8 * q + 4 * h;
+                const bool n_ok = n < g.N;
+                const bool second = n >= g.n_split;
+                v4f bias = {0.f, 0.f, 0.f, 0.f};
+                if (g.bias && n_ok) bias = *reinterpret_cast<const v4f *>(g.bias + n);
+                const float rs = second ? rs_row : 1.f;
+                uint32_t packed[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    float t0 = acc[rb][cb][4 * q + 2 * e] + bias[2 * e], t1 = acc[rb][cb][4 * q + 2 * e + 1] + bias[2 * e + 1];
+                    if (g.relu) { t0 = fmaxf(t0, 0.f); t1 = fmaxf(t1, 0.f); }
+                    packed[e] = (uint32_t)lp_f32_to_bf16(t0 * rs) | ((uint32_t)lp_f32_to_bf16(t1 * rs) << 16);
+                }
+                if (m_ok && n_ok) {
+                    lp_bf16_t *__restrict__ C = static_cast<lp_bf16_t *>(second ? g.C[1] : g.C[0]);
+                    const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
+                    *reinterpret_cast<uint2 *>(C + m * ldc + (second ? n - g.n_split : n)) = make_uint2(packed[0], packed[1]);
+                }
+            }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ TN
 constexpr int TN_LD = 128 + 4;
 
-template <int MB, int NBk>  // 32-row / 32-column blocks per wavefront: tile (64*MB) x (64*NBk)
+template <typename T, int MB, int NBk>  // storage type; 32-row / 32-column blocks per wavefront: tile (64*MB) x (64*NBk)
 __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chunk) {
     constexpr int TM = 64 * MB, TNn = 64 * NBk;
+    constexpr int VE = LpVec<T>::N;  // elements per 16-byte load; bfloat16 is widened to fp32 on its way into LDS
     __shared__ float As[BK * TN_LD];
     __shared__ float Bs[BK * TN_LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -379,6 +518,8 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
     const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TNn;
     const int64_t kbeg = (int64_t)blockIdx.y * chunk;
     const int64_t kend = kbeg + chunk < g.Kn ? kbeg + chunk : g.Kn;
+    const T *__restrict__ At = static_cast<const T *>(g.At);
+    const T *__restrict__ Bm = static_cast<const T *>(g.B);
 
     v16f acc[MB][NBk];
 #pragma unroll
@@ -388,37 +529,45 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
 
-    constexpr int A_LOADS = BK * TM / 4 / kThreads;   // 4 or 2
-    constexpr int B_LOADS = BK * TNn / 4 / kThreads;
-    float4 ra[A_LOADS], rbv[B_LOADS];
+    constexpr int A_LOADS = BK * TM / VE / kThreads;
+    constexpr int B_LOADS = BK * TNn / VE / kThreads;
+    float ra[A_LOADS][VE], rbv[B_LOADS][VE];
     auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
             const int idx = p * kThreads + tid;
-            const int kr = idx / (TM / 4), c = (idx % (TM / 4)) << 2;
+            const int kr = idx / (TM / VE), c = (idx % (TM / VE)) * VE;
             const int64_t k = k0 + kr;
-            ra[p] = (k < kend && m0 + c < g.Mw) ? *reinterpret_cast<const float4 *>(g.At + k * g.lda + m0 + c)
-                                                : make_float4(0.f, 0.f, 0.f, 0.f);
+            const bool ok = k < kend && m0 + c < g.Mw;
+            LpVec<T>::load(At + (ok ? k : kbeg) * g.lda + (ok ? m0 + c : 0), ra[p]);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) ra[p][e] = ok ? ra[p][e] : 0.f;
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int idx = p * kThreads + tid;
-            const int kr = idx / (TNn / 4), c = (idx % (TNn / 4)) << 2;
+            const int kr = idx / (TNn / VE), c = (idx % (TNn / VE)) * VE;
             const int64_t k = k0 + kr;
-            rbv[p] = (k < kend && n0 + c < g.Nw) ? *reinterpret_cast<const float4 *>(g.B + k * g.ldb + n0 + c)
-                                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+            const bool ok = k < kend && n0 + c < g.Nw;
+            LpVec<T>::load(Bm + (ok ? k : kbeg) * g.ldb + (ok ? n0 + c : 0), rbv[p]);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) rbv[p][e] = ok ? rbv[p][e] : 0.f;
         }
     };
     auto stash = [&]() {
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
             const int idx = p * kThreads + tid;
-            *reinterpret_cast<float4 *>(&As[(idx / (TM / 4)) * TN_LD + ((idx % (TM / 4)) << 2)]) = ra[p];
+            float *dst = &As[(idx / (TM / VE)) * TN_LD + (idx % (TM / VE)) * VE];
+#pragma unroll
+            for (int e = 0; e < VE; e += 4) *reinterpret_cast<float4 *>(dst + e) = make_float4(ra[p][e], ra[p][e + 1], ra[p][e + 2], ra[p][e + 3]);
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int idx = p * kThreads + tid;
-            *reinterpret_cast<float4 *>(&Bs[(idx / (TNn / 4)) * TN_LD + ((idx % (TNn / 4)) << 2)]) = rbv[p];
+            float *dst = &Bs[(idx / (TNn / VE)) * TN_LD + (idx % (TNn / VE)) * VE];
+#pragma unroll
+            for (int e = 0; e < VE; e += 4) *reinterpret_cast<float4 *>(dst + e) = make_float4(rbv[p][e], rbv[p][e + 1], rbv[p][e + 2], rbv[p][e + 3]);
         }
     };
 
@@ -475,8 +624,9 @@ TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
 }
 
 // ------------------------------------------------------------------------------------------------ small helpers
-__global__ void transpose_kernel(const float *__restrict__ in, int rows, int cols, float *__restrict__ out) {
-    __shared__ float tile[32][33];
+template <typename T>
+__global__ void transpose_kernel(const T *__restrict__ in, int rows, int cols, T *__restrict__ out) {
+    __shared__ T tile[32][33];
     const int c = blockIdx.x * 32 + threadIdx.x, r0 = blockIdx.y * 32;
     for (int i = threadIdx.y; i < 32; i += blockDim.y)
         if (r0 + i < rows && c < cols) tile[i][threadIdx.x] = in[(int64_t)(r0 + i) * cols + c];
@@ -488,38 +638,50 @@ __global__ void transpose_kernel(const float *__restrict__ in, int rows, int col
 
 constexpr int kColsumRows = 256;  // rows folded by one workgroup
 
-// partials[chunk, c] = sum of in[r, c] over the rows r of the chunk, rows taken in a fixed order.
-// Workgroup: 64 column quads x 4 row lanes; grid (column groups of 256 floats, row chunks).
-__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ in, int64_t M, int64_t N4,
+// partials[chunk, c] = sum of in[r, c] over the rows r of the chunk, rows taken in a fixed order, summed in fp32.
+// Workgroup: 64 column vectors (16 bytes each) x 4 row lanes; grid (column groups, row chunks).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T *__restrict__ in, int64_t M, int64_t NV,
                                                                   float *__restrict__ partials) {
-    __shared__ float4 red[4][64];
+    constexpr int VE = LpVec<T>::N;
+    __shared__ float red[4][64][VE];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int64_t c4 = (int64_t)blockIdx.x * 64 + tx;
+    const int64_t cv = (int64_t)blockIdx.x * 64 + tx;
     const int64_t r0 = (int64_t)blockIdx.y * kColsumRows;
     const int64_t r1 = r0 + kColsumRows < M ? r0 + kColsumRows : M;
-    const float4 *__restrict__ in4 = reinterpret_cast<const float4 *>(in);
-    float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
-    if (c4 < N4) {
+    float acc0[VE], acc1[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) acc0[e] = acc1[e] = 0.f;
+    if (cv < NV) {
         int64_t r = r0 + ty;
         for (; r + 12 < r1; r += 16) {
-            const float4 x0 = in4[r * N4 + c4], x1 = in4[(r + 4) * N4 + c4];
-            const float4 x2 = in4[(r + 8) * N4 + c4], x3 = in4[(r + 12) * N4 + c4];
-            acc0.x += x0.x; acc0.y += x0.y; acc0.z += x0.z; acc0.w += x0.w;
-            acc1.x += x1.x; acc1.y += x1.y; acc1.z += x1.z; acc1.w += x1.w;
-            acc0.x += x2.x; acc0.y += x2.y; acc0.z += x2.z; acc0.w += x2.w;
-            acc1.x += x3.x; acc1.y += x3.y; acc1.z += x3.z; acc1.w += x3.w;
+            float x0[VE], x1[VE], x2[VE], x3[VE];
+            LpVec<T>::load(in + (r * NV + cv) * VE, x0);
+            LpVec<T>::load(in + ((r + 4) * NV + cv) * VE, x1);
+            LpVec<T>::load(in + ((r + 8) * NV + cv) * VE, x2);
+            LpVec<T>::load(in + ((r + 12) * NV + cv) * VE, x3);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                acc0[e] += x0[e];
+                acc1[e] += x1[e];
+                acc0[e] += x2[e];
+                acc1[e] += x3[e];
+            }
         }
         for (; r < r1; r += 4) {
-            const float4 x0 = in4[r * N4 + c4];
-            acc0.x += x0.x; acc0.y += x0.y; acc0.z += x0.z; acc0.w += x0.w;
+            float x0[VE];
+            LpVec<T>::load(in + (r * NV + cv) * VE, x0);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc0[e] += x0[e];
         }
     }
-    red[ty][tx] = make_float4(acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w);
+#pragma unroll
+    for (int e = 0; e < VE; ++e) red[ty][tx][e] = acc0[e] + acc1[e];
     __syncthreads();
-    if (ty == 0 && c4 < N4) {
-        const float4 a = red[0][tx], b = red[1][tx], c = red[2][tx], d = red[3][tx];
-        reinterpret_cast<float4 *>(partials)[(int64_t)blockIdx.y * N4 + c4] =
-            make_float4((a.x + b.x) + (c.x + d.x), (a.y + b.y) + (c.y + d.y), (a.z + b.z) + (c.z + d.z), (a.w + b.w) + (c.w + d.w));
+    if (ty == 0 && cv < NV) {
+#pragma unroll
+        for (int e = 0; e < VE; ++e)
+            partials[((int64_t)blockIdx.y * NV + cv) * VE + e] = (red[0][tx][e] + red[1][tx][e]) + (red[2][tx][e] + red[3][tx][e]);
     }
 }
 
@@ -547,12 +709,24 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return LP_OK;
     for (int s = 0; s < 2; ++s) {
         if (a.K[s] <= 0) continue;
-        if ((a.K[s] & 3) || (a.lda[s] & 3) || (a.ldb[s] & 3)) return LP_ERR_UNSUPPORTED;
+        const int ve = lp_vec_elems(a.dtype);
+        if ((a.K[s] % ve) || (a.lda[s] % ve) || (a.ldb[s] % ve)) return LP_ERR_UNSUPPORTED;
         if (!a.A[s] || !a.Bt[s][0] || !lp_aligned16(a.A[s]) || !lp_aligned16(a.Bt[s][0])) return LP_ERR_INVALID_ARG;
         if (a.n_split < a.N && (!a.Bt[s][1] || !lp_aligned16(a.Bt[s][1]))) return LP_ERR_INVALID_ARG;
     }
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
+    if (a.dtype != LP_F32 && a.dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     LpTimedScope timed(LP_KC_GEMM_NT, st);
+    if (a.dtype == LP_BF16) {
+        if ((a.N & 3) || (a.n_split & 3) || (a.ldc[0] & 3) || (a.n_split < a.N && (a.ldc[1] & 3))) return LP_ERR_UNSUPPORTED;
+        const int bn = a.N > 128 ? 256 : (a.N > 64 ? 128 : 64);
+        const int64_t row_tiles8 = lp_ceil_div(lp_ceil_div(a.M, BM), 8) * 8;
+        const dim3 grid((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
+        if (bn == 256) hipLaunchKernelGGL((gemm_nt_bf16_kernel<4>), grid, dim3(kThreads), 0, st, a);
+        else if (bn == 128) hipLaunchKernelGGL((gemm_nt_bf16_kernel<2>), grid, dim3(kThreads), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nt_bf16_kernel<1>), grid, dim3(kThreads), 0, st, a);
+        return lp_after_launch();
+    }
     static const int force_bn = getenv("LP_GEMM_NT_BN") ? atoi(getenv("LP_GEMM_NT_BN")) : 0;
     static const int no_fast = getenv("LP_GEMM_NT_NOFAST") ? 1 : 0;
     // fast path: K parts in whole steps, and no column tile straddling the output split
@@ -588,28 +762,41 @@ size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw) {
 
 int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
     if (a.Mw <= 0 || a.Nw <= 0) return LP_OK;
-    if ((a.Mw & 3) || (a.Nw & 3) || (a.lda & 3) || (a.ldb & 3)) return LP_ERR_UNSUPPORTED;
+    const int ve = lp_vec_elems(a.dtype);
+    if ((a.dtype != LP_F32 && a.dtype != LP_BF16) || (a.Mw % ve) || (a.Nw % ve) || (a.lda % ve) || (a.ldb % ve)) return LP_ERR_UNSUPPORTED;
     if (!a.C || !a.partials) return LP_ERR_INVALID_ARG;
     if (a.Kn <= 0) return lp_launch_zero(a.C, (int64_t)a.Mw * a.Nw, st);
     if (!a.At || !a.B || !lp_aligned16(a.At) || !lp_aligned16(a.B)) return LP_ERR_INVALID_ARG;
     LpTimedScope timed(LP_KC_GEMM_TN, st);
     const TnPlan p = plan_tn(a.Kn, a.Mw, a.Nw);
     const dim3 grid(p.tiles, p.splits);
-    if (p.tm == 128 && p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
-    else if (p.tm == 128) hipLaunchKernelGGL((gemm_tn_kernel<2, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
-    else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<1, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);
-    else hipLaunchKernelGGL((gemm_tn_kernel<1, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
+#define LP_TN_LAUNCH(T)                                                                                                   \
+    if (p.tm == 128 && p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<T, 2, 2>), grid, dim3(kThreads), 0, st, a, p.chunk); \
+    else if (p.tm == 128) hipLaunchKernelGGL((gemm_tn_kernel<T, 2, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);           \
+    else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<T, 1, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);           \
+    else hipLaunchKernelGGL((gemm_tn_kernel<T, 1, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
+    if (a.dtype == LP_BF16) {
+        LP_TN_LAUNCH(lp_bf16_t)
+    } else {
+        LP_TN_LAUNCH(float)
+    }
+#undef LP_TN_LAUNCH
     LP_TRY(lp_after_launch());
     // fold the partial tiles: a column sum of the [splits, Mw*Nw] matrix
     const int64_t n = (int64_t)a.Mw * a.Nw;
-    return lp_launch_colsum(a.partials, p.splits, n, a.C, a.partials + lp_align_up(sizeof(float) * (size_t)p.splits * n) / sizeof(float), st);
+    return lp_launch_colsum(a.partials, LP_F32, p.splits, n, a.C, a.partials + lp_align_up(sizeof(float) * (size_t)p.splits * n) / sizeof(float), st);
 }
 
-int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t st) {
+int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, int dtype, hipStream_t st) {
     if (rows <= 0 || cols <= 0) return LP_OK;
     LpTimedScope timed(LP_KC_OTHER, st);
-    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)lp_ceil_div(cols, 32), (unsigned)lp_ceil_div(rows, 32)), dim3(32, 8), 0,
-                       st, in, rows, cols, out);
+    const dim3 grid((unsigned)lp_ceil_div(cols, 32), (unsigned)lp_ceil_div(rows, 32));
+    if (dtype == LP_BF16)
+        hipLaunchKernelGGL((transpose_kernel<lp_bf16_t>), grid, dim3(32, 8), 0, st, static_cast<const lp_bf16_t *>(in), rows, cols,
+                           static_cast<lp_bf16_t *>(out));
+    else
+        hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(32, 8), 0, st, static_cast<const float *>(in), rows, cols,
+                           static_cast<float *>(out));
     return lp_after_launch();
 }
 
@@ -619,23 +806,28 @@ size_t lp_colsum_partials_bytes(int64_t M, int64_t N) {
     return 2 * lp_align_up(sizeof(float) * (size_t)chunks * (size_t)(N > 0 ? N : 1));
 }
 
-int lp_launch_colsum(const float *in, int64_t M, int64_t N, float *out, float *partials, hipStream_t st) {
+int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t st) {
     if (N <= 0) return LP_OK;
-    if (N & 3) return LP_ERR_UNSUPPORTED;
+    if (N % lp_vec_elems(dtype)) return LP_ERR_UNSUPPORTED;
     if (M <= 0) return lp_launch_zero(out, N, st);
     LpTimedScope timed(LP_KC_OTHER, st);
-    const int64_t N4 = N >> 2;
     const size_t area = lp_align_up(sizeof(float) * (size_t)lp_ceil_div(M, kColsumRows) * (size_t)N) / sizeof(float);
-    const float *src = in;
+    const void *src = in;
+    int src_dtype = dtype;
     int64_t rows = M;
     int level = 0;
     while (true) {
         const int64_t chunks = lp_ceil_div(rows, kColsumRows);
         float *dst = chunks == 1 ? out : partials + (level & 1) * area;
-        hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)lp_ceil_div(N4, 64), (unsigned)chunks), dim3(kThreads), 0, st,
-                           src, rows, N4, dst);
+        const int64_t NV = N / lp_vec_elems(src_dtype);
+        const dim3 grid((unsigned)lp_ceil_div(NV, 64), (unsigned)chunks);
+        if (src_dtype == LP_BF16)
+            hipLaunchKernelGGL((colsum_partial_kernel<lp_bf16_t>), grid, dim3(kThreads), 0, st, static_cast<const lp_bf16_t *>(src), rows, NV, dst);
+        else
+            hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(kThreads), 0, st, static_cast<const float *>(src), rows, NV, dst);
         if (chunks == 1) break;
         src = dst;
+        src_dtype = LP_F32;  // the partial sums are fp32
         rows = chunks;
         ++level;
     }

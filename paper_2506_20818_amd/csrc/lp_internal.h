@@ -43,8 +43,9 @@ private:
 // out[v, :] = rowscale(v) * sum_{p in row v} w[p] * in[colidx[p], :]  (+ addend[v, :])  (* [gate[v, :] > 0])
 //   w[p] = 1 when w == nullptr
 //   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1
-// All matrices are [n_rows, F] fp32 with contiguous rows; F % 4 == 0.
+// All matrices are [n_rows, F] in the storage type `dtype` with contiguous rows; F is a multiple of 4 (fp32) or 8 (bf16).
 struct SpmmArgs {
+    int32_t dtype = LP_F32;              // storage of in, addend, gate and out
     int32_t n_rows = 0;
     int32_t F = 0;
     const int32_t *rowptr = nullptr;
@@ -52,10 +53,10 @@ struct SpmmArgs {
     const int32_t *row_order = nullptr;  // optional processing order
     const float *inv_deg = nullptr;      // optional per-output-row scale
     const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
-    const float *in = nullptr;
-    const float *addend = nullptr;       // optional [n_rows, F]
-    const float *gate = nullptr;         // optional [n_rows, F]: output is zeroed where gate <= 0
-    float *out = nullptr;
+    const void *in = nullptr;
+    const void *addend = nullptr;        // optional [n_rows, F]
+    const void *gate = nullptr;          // optional [n_rows, F]: output is zeroed where gate <= 0
+    void *out = nullptr;
     int timing_class = LP_KC_SPMM;       // class the launch is booked under by the instrumentation
 };
 int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
@@ -68,17 +69,18 @@ int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
 // Epilogue: + bias[n] (optional), max(.,0) (optional); columns n >= n_split are multiplied by
 // rowscale[m] (optional) and go to C[1] (leading dimension ldc[1]) at column n - n_split, the others to C[0].
 struct GemmNtArgs {
+    int32_t dtype = LP_F32;              // storage of A, Bt and C (bias and rowscale are always fp32)
     int32_t M = 0, N = 0;
     int32_t n_split = 0;                 // == N when the output is not split
-    const float *A[2] = {nullptr, nullptr};
+    const void *A[2] = {nullptr, nullptr};
     int32_t lda[2] = {0, 0};
     int32_t K[2] = {0, 0};
-    const float *Bt[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+    const void *Bt[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
     int32_t ldb[2] = {0, 0};
     const float *bias = nullptr;
     bool relu = false;
     const float *rowscale = nullptr;
-    float *C[2] = {nullptr, nullptr};
+    void *C[2] = {nullptr, nullptr};
     int32_t ldc[2] = {0, 0};
 };
 int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t stream);
@@ -87,11 +89,12 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t stream);
 // Also accumulates nothing else; partial sums of the row chunks go to `partials` and are then added up in a
 // fixed order, so the result does not depend on scheduling.
 struct GemmTnArgs {
+    int32_t dtype = LP_F32;              // storage of At and B; C and the partial sums are fp32
     int32_t Kn = 0;                      // reduction length (number of nodes)
     int32_t Mw = 0, Nw = 0;              // output shape
-    const float *At = nullptr;           // [Kn, Mw], leading dimension lda
+    const void *At = nullptr;            // [Kn, Mw], leading dimension lda
     int32_t lda = 0;
-    const float *B = nullptr;            // [Kn, Nw], leading dimension ldb
+    const void *B = nullptr;             // [Kn, Nw], leading dimension ldb
     int32_t ldb = 0;
     float *C = nullptr;                  // [Mw, Nw] contiguous
     float *partials = nullptr;           // workspace, lp_gemm_tn_partials_bytes()
@@ -99,13 +102,13 @@ struct GemmTnArgs {
 size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw);
 int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t stream);
 
-// out[c, r] = in[r, c] for a small [rows, cols] matrix (weights).
-int lp_launch_transpose(const float *in, int32_t rows, int32_t cols, float *out, hipStream_t stream);
-// out[n] = sum_m in[m, n] for a contiguous [M, N] matrix (N % 4 == 0), fixed summation order;
-// partials: lp_colsum_partials_bytes()
+// out[c, r] = in[r, c] for a small [rows, cols] matrix (weights) of 4-byte or 2-byte elements.
+int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, int dtype, hipStream_t stream);
+// out[n] = sum_m in[m, n] for a contiguous [M, N] matrix stored as `dtype` (N a multiple of its vector width);
+// fp32 sums in a fixed order; partials: lp_colsum_partials_bytes()
 size_t lp_colsum_partials_bytes(int64_t M, int64_t N);
-int lp_launch_colsum(const float *in, int64_t M, int64_t N, float *out, float *partials, hipStream_t stream);
-// fill n floats with zero (kernel, so that callers may capture it)
+int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t stream);
+// fill n floats with zero (a kernel, so that callers may capture it); n floats = 2n bfloat16
 int lp_launch_zero(float *p, int64_t n, hipStream_t stream);
 
 // ---------------------------------------------------------------- sorting (csr_build.hip)
@@ -120,3 +123,51 @@ uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int 
 int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,
                           int32_t *offsets, hipStream_t stream);
 int lp_bits_for(int64_t n_values);
+
+// ---------------------------------------------------------------- storage types
+// LP_F32 matrices hold floats; LP_BF16 matrices hold raw bfloat16 bit patterns (uint16_t).  All arithmetic is fp32.
+typedef uint16_t lp_bf16_t;
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ float lp_bf16_to_f32(lp_bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ lp_bf16_t lp_f32_to_bf16(float x) {  // round to nearest, ties to even
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (lp_bf16_t)0x7fc0;  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (lp_bf16_t)(u >> 16);
+}
+
+// One 16-byte vector of a matrix row: 4 floats or 8 bfloat16 values, handled as fp32 in registers.
+template <typename T> struct LpVec;
+template <> struct LpVec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void load(const float *p, float (&v)[4]) {
+        const float4 x = *reinterpret_cast<const float4 *>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[4]) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct LpVec<lp_bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const lp_bf16_t *p, float (&v)[8]) {
+        const uint4 x = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(lp_bf16_t *p, const float (&v)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)lp_f32_to_bf16(v[2 * i]) | ((uint32_t)lp_f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+#endif
+
+static inline int lp_elem_bytes(int dtype) { return dtype == LP_BF16 ? 2 : 4; }
+static inline int lp_vec_elems(int dtype) { return dtype == LP_BF16 ? 8 : 4; }

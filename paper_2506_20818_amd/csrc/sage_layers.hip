@@ -8,10 +8,10 @@ namespace {
 
 int check_model(const lp_model *m) {
     if (!m || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
-    if (m->dtype != LP_F32) return LP_ERR_UNSUPPORTED;
+    if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
-        if ((m->dims[k] & 3) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;
+        if ((m->dims[k] % lp_vec_elems(m->dtype)) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;
     }
     for (int k = 0; k < m->n_layers; ++k) {
         if (!m->W_self[k] || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
@@ -35,7 +35,7 @@ int check_acts(const lp_model *m, const lp_acts *a) {
     return LP_OK;
 }
 
-size_t transposed_weight_floats(const lp_model *m) {
+size_t transposed_weight_elems(const lp_model *m) {
     size_t n = 0;
     for (int k = 0; k < m->n_layers; ++k) n += 2 * lp_align_up((size_t)m->dims[k] * m->dims[k + 1], 64);
     return n;
@@ -76,7 +76,7 @@ __global__ void batch_entries_kernel(const uint64_t *__restrict__ sorted, int64_
 }
 
 struct BackwardWs {
-    float *buf[3];
+    void *buf[3];  // [n_nodes, max width] in the model's storage type
     float *tn_partials;
     float *colsum_partials;
     uint64_t *keys_a, *keys_b;
@@ -91,7 +91,7 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
     size_t off = 0;
     auto take = [&](size_t bytes) { char *q = p ? p + off : nullptr; off += lp_align_up(bytes); return reinterpret_cast<float *>(q); };
     BackwardWs w;
-    const size_t big = sizeof(float) * (size_t)n_nodes * (size_t)max_dim(m);
+    const size_t big = (size_t)lp_elem_bytes(m->dtype) * (size_t)n_nodes * (size_t)max_dim(m);
     for (int i = 0; i < 3; ++i) w.buf[i] = take(big);
     size_t tn = 0, cs = 0;
     for (int k = 0; k < m->n_layers; ++k) {
@@ -118,7 +118,7 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
 extern "C" size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
     (void)n_nodes;
     if (check_model(m) != LP_OK) return 0;
-    return lp_align_up(sizeof(float) * transposed_weight_floats(m));
+    return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m));
 }
 
 extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws, size_t ws_bytes,
@@ -129,14 +129,17 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
     if (!X || !lp_aligned16(X)) return LP_ERR_INVALID_ARG;
     if (!ws || ws_bytes < lp_sage_forward_workspace_bytes(m, g->n_nodes)) return LP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *wt = static_cast<float *>(ws);
+    const int dt = m->dtype;
+    const size_t eb = (size_t)lp_elem_bytes(dt);
+    char *wt = static_cast<char *>(ws);
     const int K = m->n_layers;
-    const float *Hprev = static_cast<const float *>(X);
+    const void *Hprev = X;
     for (int k = 1; k <= K; ++k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
-        float *A = static_cast<float *>(saved->A[k - 1]);
-        float *H = static_cast<float *>(saved->H[k - 1]);
+        void *A = saved->A[k - 1];
+        void *H = saved->H[k - 1];
         SpmmArgs sp;
+        sp.dtype = dt;
         sp.n_rows = g->n_nodes;
         sp.F = Fi;
         sp.rowptr = g->rowptr;
@@ -147,11 +150,13 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         sp.out = A;
         LP_TRY(lp_launch_spmm(sp, st));
         // the NT product wants the reduction index contiguous: W^T is [Fo, Fi]
-        float *WsT = wt, *WnT = wt + lp_align_up((size_t)Fi * Fo, 64);
-        wt += 2 * lp_align_up((size_t)Fi * Fo, 64);
-        LP_TRY(lp_launch_transpose(static_cast<const float *>(m->W_self[k - 1]), Fi, Fo, WsT, st));
-        LP_TRY(lp_launch_transpose(static_cast<const float *>(m->W_neigh[k - 1]), Fi, Fo, WnT, st));
+        const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
+        void *WsT = wt, *WnT = wt + wbytes;
+        wt += 2 * wbytes;
+        LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
+        LP_TRY(lp_launch_transpose(m->W_neigh[k - 1], Fi, Fo, WnT, dt, st));
         GemmNtArgs ge;
+        ge.dtype = dt;
         ge.M = g->n_nodes;
         ge.N = Fo;
         ge.n_split = Fo;
@@ -193,10 +198,11 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     BackwardWs w = carve_backward(ws, m, g->n_nodes, B);
     const int32_t N = g->n_nodes;
 
-    float *dZ = w.buf[0], *Q = w.buf[1], *R = w.buf[2];
-    const float *HK = static_cast<const float *>(saved->H[K - 1]);
+    const int dt = m->dtype;
+    void *dZ = w.buf[0], *Q = w.buf[1], *R = w.buf[2];
+    const void *HK = saved->H[K - 1];
     if (B == 0) {
-        LP_TRY(lp_launch_zero(dZ, (int64_t)N * m->dims[K], st));
+        LP_TRY(lp_launch_zero(static_cast<float *>(dZ), (int64_t)N * m->dims[K] * lp_elem_bytes(dt) / 4, st));
     } else {
         const int64_t n2 = 2 * B;
         const unsigned g2 = (unsigned)lp_ceil_div(n2, 256);
@@ -212,6 +218,7 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
             LP_TRY(lp_after_launch());
         }
         SpmmArgs sc;
+        sc.dtype = dt;
         sc.n_rows = N; sc.F = m->dims[K];
         sc.rowptr = w.bptr; sc.colidx = w.bcol; sc.w = w.bw;
         sc.in = HK; sc.out = dZ;
@@ -221,10 +228,11 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
 
     for (int k = K; k >= 1; --k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
-        const float *Hin = k > 1 ? static_cast<const float *>(saved->H[k - 2]) : static_cast<const float *>(X);
-        const float *Ak = static_cast<const float *>(saved->A[k - 1]);
-        LP_TRY(lp_launch_colsum(dZ, N, Fo, out->dbias[k - 1], w.colsum_partials, st));
+        const void *Hin = k > 1 ? saved->H[k - 2] : X;
+        const void *Ak = saved->A[k - 1];
+        LP_TRY(lp_launch_colsum(dZ, dt, N, Fo, out->dbias[k - 1], w.colsum_partials, st));
         GemmTnArgs tn;
+        tn.dtype = dt;
         tn.Kn = N; tn.Mw = Fi; tn.Nw = Fo;
         tn.B = dZ; tn.ldb = Fo;
         tn.partials = w.tn_partials;
@@ -235,10 +243,11 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         if (k == 1 && !out->dX) break;
         // [dZ W_self^T | diag(inv_deg) dZ W_neigh^T] -> Q, R
         GemmNtArgs ge;
+        ge.dtype = dt;
         ge.M = N; ge.N = 2 * Fi; ge.n_split = Fi;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
-        ge.Bt[0][0] = static_cast<const float *>(m->W_self[k - 1]);
-        ge.Bt[0][1] = static_cast<const float *>(m->W_neigh[k - 1]);
+        ge.Bt[0][0] = m->W_self[k - 1];
+        ge.Bt[0][1] = m->W_neigh[k - 1];
         ge.ldb[0] = Fo;
         ge.rowscale = g->inv_deg;
         ge.C[0] = Q; ge.C[1] = R;
@@ -246,13 +255,15 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         LP_TRY(lp_launch_gemm_nt(ge, st));
         // G^{k-1} = (Q + sum over the transposed CSR of R) gated by relu'(z^{k-1}) = [h^{k-1} > 0]
         SpmmArgs sp;
+        sp.dtype = dt;
         sp.n_rows = N; sp.F = Fi;
         sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
         sp.in = R; sp.addend = Q;
         sp.gate = k > 1 ? Hin : nullptr;
-        sp.out = k > 1 ? Q : out->dX;
+        sp.out = k > 1 ? Q : static_cast<void *>(out->dX);
+        sp.dtype = dt;
         LP_TRY(lp_launch_spmm(sp, st));
-        float *t = dZ; dZ = Q; Q = t;
+        void *t = dZ; dZ = Q; Q = t;
     }
     return LP_OK;
 }

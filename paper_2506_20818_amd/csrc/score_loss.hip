@@ -1,7 +1,8 @@
 // lp_score_loss: dot-product edge scores (Eq. 2 of the paper), binary cross-entropy with labels 1/0 and the
 // batch mean (Algorithm 1, per-edge loop and "Compute L^i"; Sec. IV-B last paragraph), plus dL/ds.
 //
-// A group of G = F/4 lanes (power of two, at most a wavefront) owns one edge: each lane loads 16 bytes of both
+// A group of G lanes (power of two, at most a wavefront) owns one edge: each lane loads 16 bytes (4 floats or
+// 8 bfloat16) of both
 // endpoint rows, and the products are summed across the group with xor-shuffles (a segmented reduction inside
 // the wavefront).  The loss is reduced block by block and then by one block, always in the same order.
 #include "lp_internal.h"
@@ -18,8 +19,8 @@ __device__ inline float group_sum(float v) {
     return v;
 }
 
-template <int G>
-__global__ __launch_bounds__(kThreads) void score_loss_kernel(const float *__restrict__ H, int32_t n_nodes, int32_t F,
+template <typename T, int G>
+__global__ __launch_bounds__(kThreads) void score_loss_kernel(const T *__restrict__ H, int32_t n_nodes, int32_t F,
                                                               int64_t B, int64_t n_pos, const int32_t *__restrict__ e_src,
                                                               const int32_t *__restrict__ e_dst, float *__restrict__ scores,
                                                               float *__restrict__ dscore, float *__restrict__ partial) {
@@ -29,18 +30,21 @@ __global__ __launch_bounds__(kThreads) void score_loss_kernel(const float *__res
     const int64_t gid = (int64_t)blockIdx.x * groups_per_block + threadIdx.x / G;
     const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
     const float invB = 1.0f / (float)B;
-    const int F4 = F >> 2;
+    constexpr int VE = LpVec<T>::N;
+    const int FV = F / VE;
     float acc = 0.0f;
     for (int64_t e = gid; e < B; e += n_groups) {
         const int32_t u = e_src[e], v = e_dst[e];
         const bool ok = u >= 0 && u < n_nodes && v >= 0 && v < n_nodes;
         float s = 0.0f;
         if (ok) {
-            const float4 *hu = reinterpret_cast<const float4 *>(H + (int64_t)u * F);
-            const float4 *hv = reinterpret_cast<const float4 *>(H + (int64_t)v * F);
-            for (int j = sub; j < F4; j += G) {
-                const float4 a = hu[j], b = hv[j];
-                s += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+            const T *hu = H + (int64_t)u * F, *hv = H + (int64_t)v * F;
+            for (int j = sub; j < FV; j += G) {
+                float a[VE], b[VE];
+                LpVec<T>::load(hu + j * VE, a);
+                LpVec<T>::load(hv + j * VE, b);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) s += a[e] * b[e];
             }
         }
         s = group_sum<G>(s);
@@ -83,10 +87,22 @@ int loss_blocks(int64_t B, int G) {
     return (int)nb;
 }
 
-int group_lanes(int F) {
+int group_lanes(int F, int vec) {
     int g = 8;
-    while (g < 64 && g * 4 < F) g <<= 1;
+    while (g < 64 && g * vec < F) g <<= 1;
     return g;
+}
+
+template <typename T>
+void launch_score(int G, int nb, hipStream_t st, const void *HK, int32_t n_nodes, int32_t F, int64_t B, int64_t n_pos,
+                  const int32_t *e_src, const int32_t *e_dst, float *scores, float *dscore, float *partial) {
+    const T *H = static_cast<const T *>(HK);
+    switch (G) {
+        case 8: hipLaunchKernelGGL((score_loss_kernel<T, 8>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
+        case 16: hipLaunchKernelGGL((score_loss_kernel<T, 16>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
+        case 32: hipLaunchKernelGGL((score_loss_kernel<T, 32>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
+        default: hipLaunchKernelGGL((score_loss_kernel<T, 64>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial);
+    }
 }
 
 }  // namespace
@@ -101,30 +117,17 @@ extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t
                              size_t ws_bytes, void *stream) {
     if (!HK || n_nodes <= 0 || F <= 0 || B < 0 || n_pos_edges < 0 || n_pos_edges > B || !loss) return LP_ERR_INVALID_ARG;
     if (B > 0 && (!e_src || !e_dst || !scores)) return LP_ERR_INVALID_ARG;
-    if (dtype != LP_F32 || (F & 3)) return LP_ERR_UNSUPPORTED;
+    if ((dtype != LP_F32 && dtype != LP_BF16) || F % lp_vec_elems(dtype)) return LP_ERR_UNSUPPORTED;
     if (!lp_aligned16(HK)) return LP_ERR_INVALID_ARG;
     if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
     if (!ws || ws_bytes < lp_score_loss_workspace_bytes(B)) return LP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *partial = static_cast<float *>(ws);
-    const float *H = static_cast<const float *>(HK);
-    const int G = group_lanes(F);
+    const int G = group_lanes(F, lp_vec_elems(dtype));
     const int nb = loss_blocks(B, G);
     LpTimedScope timed(LP_KC_SCORE, st);
-#define LP_SCORE_CASE(g)                                                                                              \
-    case g:                                                                                                           \
-        hipLaunchKernelGGL((score_loss_kernel<g>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos_edges,    \
-                           e_src, e_dst, scores, dscore, partial);                                                    \
-        break;
-    switch (G) {
-        LP_SCORE_CASE(8)
-        LP_SCORE_CASE(16)
-        LP_SCORE_CASE(32)
-        default:
-            hipLaunchKernelGGL((score_loss_kernel<64>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos_edges,
-                               e_src, e_dst, scores, dscore, partial);
-    }
-#undef LP_SCORE_CASE
+    if (dtype == LP_BF16) launch_score<lp_bf16_t>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
+    else launch_score<float>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, B, loss);
     return lp_after_launch();
 }

@@ -1,0 +1,150 @@
+"""GPU parity of the bfloat16-storage path (features, weights and activations in bf16, fp32 accumulation).
+
+The oracle receives the same bf16-valued inputs, works in fp64 and rounds to bf16 exactly where the library stores
+a bf16 matrix.  Both sides then differ by fp32-vs-fp64 accumulation noise, which now and then lands on the other
+side of a bf16 rounding boundary (one bf16 ulp = 2^-8 relative).  Bars: activations, scores, loss 2^-7 relative;
+gradients 2e-2 relative (per tensor, max-norm and 2-norm).  The paper fixes no precision; these bounds are this
+repository's choice for the bf16 configuration.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2506_20818_amd as lp
+from lp_workloads import make_workload, to_bf16_grid
+from oracle import lp_oracle as O
+from gpu_util import DEV, assert_close, dev_f32, dev_i32, host
+from test_gpu_parity import graph_with_hub_and_empty_rows, random_pairs, say, toy_model
+
+TOL_ACT = 2.0 ** -7
+TOL_GRAD = 2e-2
+
+
+def dev_bf16(a):
+    return dev_f32(a).to(torch.bfloat16)        # exact: the values are already on the bf16 grid
+
+
+def hostf(t):
+    return host(t.float())
+
+
+def bf16_model(Ws, Wn, b):
+    return lp.Model([dev_bf16(w) for w in Ws], [dev_bf16(w) for w in Wn], [dev_f32(x) for x in b])
+
+
+def grid(arrs):
+    return [to_bf16_grid(a) for a in arrs]
+
+
+@pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24], [512, 64], [64, 1024, 8]])
+@pytest.mark.parametrize("sym", [True, False])
+def test_forward_parity_bf16(dims, sym):
+    rng = np.random.default_rng(sum(dims) + sym)
+    n = 1500 + dims[0]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 4000, 700)
+    say("bf16 forward dims=%s sym=%s n=%d" % (dims, sym, n))
+    ref = O.build_csr(n, r, c, sym)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym)
+    Ws, Wn, b = toy_model(rng, dims)
+    Ws, Wn = grid(Ws), grid(Wn)
+    X = to_bf16_grid(rng.standard_normal((n, dims[0])).astype(np.float32))
+    acts = lp.lp_sage_forward(g, bf16_model(Ws, Wn, b), dev_bf16(X))
+    assert acts.H[-1].dtype == torch.bfloat16
+    exp = O.sage_forward(ref, Ws, Wn, b, X, storage="bf16")
+    for k in range(1, len(dims)):
+        assert_close(hostf(acts.A[k - 1]), exp.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(hostf(acts.H[k - 1]), exp.H[k], TOL_ACT, "H^%d" % k)
+
+
+@pytest.mark.parametrize("F", [8, 64, 104, 512])
+def test_score_loss_parity_bf16(F):
+    rng = np.random.default_rng(F)
+    n, B, n_pos = 777, 5001, 1700
+    say("bf16 score_loss F=%d" % F)
+    H = to_bf16_grid((rng.standard_normal((n, F)) * (2.0 / np.sqrt(F)) ** 0.5).astype(np.float32))
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    s, loss, ds = lp.lp_score_loss(dev_bf16(H), dev_i32(es), dev_i32(ed), n_pos)
+    s_ref, loss_ref, ds_ref = O.score_loss(H, es, ed, n_pos)
+    assert_close(host(s), s_ref, 1e-4, "scores")            # the dot product itself is fp32 on exact inputs
+    assert abs(float(host(loss)[0]) - loss_ref) <= 1e-4 * abs(loss_ref)
+    assert_close(host(ds), ds_ref, 1e-4, "dscore")
+
+
+def check_grads(grads, ref, K):
+    for k in range(K):
+        assert_close(host(grads.dW_self[k]), ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
+    if grads.dX is not None:
+        assert_close(hostf(grads.dX), ref.dX, TOL_GRAD, "dX")
+
+
+@pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24]])
+@pytest.mark.parametrize("sym", [True, False])
+def test_backward_parity_bf16(dims, sym):
+    rng = np.random.default_rng(2000 + sum(dims) + sym)
+    n = 1300 + dims[-1]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
+    say("bf16 backward dims=%s sym=%s n=%d" % (dims, sym, n))
+    ref = O.build_csr(n, r, c, sym)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    Ws, Wn = grid(Ws), grid(Wn)
+    X = to_bf16_grid(rng.standard_normal((n, dims[0])).astype(np.float32))
+    B, n_pos = 2500, 1000
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    model = bf16_model(Ws, Wn, b)
+    Xd = dev_bf16(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X, storage="bf16")
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="bf16")
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
+    check_grads(grads, g_ref, len(dims) - 1)
+
+
+def whole_step_bf16(name, scale=1.0):
+    wl = make_workload(name, scale=scale)
+    say("bf16 whole step %s scale=%g N=%d nnz~%d B=%d dims=%s" % (name, scale, wl.n_nodes, 2 * wl.src.size, wl.batch_edges, wl.dims))
+    Ws, Wn, X = grid(wl.W_self), grid(wl.W_neigh), to_bf16_grid(wl.X)
+    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    exp = O.train_step(ref, Ws, Wn, wl.bias, X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed,
+                       wl.sampler_step, storage="bf16")
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    model = bf16_model(Ws, Wn, wl.bias)
+    Xd = dev_bf16(X)
+    n_pos, B = wl.n_pos, wl.batch_edges
+    e_src = torch.empty(B, dtype=torch.int32, device=DEV)
+    e_dst = torch.empty(B, dtype=torch.int32, device=DEV)
+    e_src[:n_pos] = dev_i32(wl.pos_src)
+    e_dst[:n_pos] = dev_i32(wl.pos_dst)
+    lp.lp_sample_neg(g, dev_i32(wl.pos_src), wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step,
+                     neg_dst=e_dst[n_pos:], neg_src=e_src[n_pos:])
+    assert np.array_equal(host(e_dst), exp.e_dst) and np.array_equal(host(e_src), exp.e_src)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, e_src, e_dst, ds)
+    K = len(wl.dims) - 1
+    for k in range(1, K + 1):
+        assert_close(hostf(acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(hostf(acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+    assert_close(host(s), exp.scores, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+    check_grads(grads, exp.grads, K)
+
+
+def test_whole_step_C1_bf16():
+    whole_step_bf16("C1")
+
+
+def test_whole_step_C5_shape_one_eighth_scale():
+    # one worker's share of the partitioned graph at hidden 512 and 4 negatives per positive, on the generator
+    # scaled to 1/8 so that the fp64 oracle finishes in about a minute
+    whole_step_bf16("C5_keep0.2", scale=0.125)

@@ -282,3 +282,29 @@ def test_train_step_assembles_the_batch_in_the_documented_order():
     assert np.array_equal(res.e_src, np.concatenate([es, np.repeat(es, 2)]))
     assert np.array_equal(res.e_dst[:6], ed) and np.array_equal(res.e_dst[6:], res.neg_dst)
     assert res.scores.size == 18
+
+
+def test_bf16_storage_mode_is_the_same_mathematics_with_rounded_stores():
+    # small integers keep every intermediate exactly representable in bfloat16: both storage modes must agree
+    rng = np.random.default_rng(12)
+    g = O.build_csr(6, np.array([0, 1, 2, 3]), np.array([1, 2, 3, 4]), True)     # degrees 1 and 2 only
+    Ws = [rng.integers(-2, 3, (2, 2)).astype(np.float64) for _ in range(2)]
+    Wn = [rng.integers(-2, 3, (2, 2)).astype(np.float64) * 2 for _ in range(2)]   # even: halves stay integers
+    b = [rng.integers(-1, 2, 2).astype(np.float64) for _ in range(2)]
+    X = rng.integers(-2, 3, (6, 2)).astype(np.float64) * 2
+    a32 = O.sage_forward(g, Ws, Wn, b, X, storage="f32")
+    a16 = O.sage_forward(g, Ws, Wn, b, X, storage="bf16")
+    for k in (1, 2):
+        assert np.array_equal(a32.H[k], a16.H[k]) and np.array_equal(a32.A[k], a16.A[k])
+    # with generic inputs every stored activation of the bf16 mode lies on the bfloat16 grid
+    X = rng.standard_normal((6, 2))
+    a16 = O.sage_forward(g, Ws, Wn, b, X, storage="bf16")
+    for k in (1, 2):
+        assert np.array_equal(a16.H[k], O._round_bf16(a16.H[k])) and np.array_equal(a16.A[k], O._round_bf16(a16.A[k]))
+    es, ed = np.array([0, 2], np.int32), np.array([1, 5], np.int32)
+    _, _, ds = O.score_loss(a16.H[-1], es, ed, 1)
+    g16 = O.backward(g, Ws, Wn, a16, es, ed, ds, storage="bf16")
+    g32 = O.backward(g, Ws, Wn, a16, es, ed, ds, storage="f32")
+    assert np.array_equal(g16.dX, O._round_bf16(g16.dX))
+    for x, y in zip(g16.dW_self + g16.dW_neigh, g32.dW_self + g32.dW_neigh):
+        assert np.abs(x - y).max() <= 0.02 * np.abs(y).max()          # bf16 rounding noise only (2^-8 per stored value)
