@@ -24,18 +24,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 
 
-def spmm_bytes(n, nnz, F, backward):
+BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix
+
+
+def spmm_bytes(n, nnz, F, backward, eb=4):
     """Algorithmic bytes of one CSR aggregation launch: gathered rows + column ids + row pointers + output row,
-    plus inverse degrees (forward) or the added/gating rows (backward)."""
-    b = nnz * (4 * F + 4) + (n + 1) * 4 + n * 4 * F
-    return b + (2 * n * 4 * F if backward else n * 4)
+    plus inverse degrees (forward) or the added/gating rows (backward).  eb = bytes per stored element."""
+    b = nnz * (eb * F + 4) + (n + 1) * 4 + n * eb * F
+    return b + (2 * n * eb * F if backward else n * 4)
 
 
-def step_counts(n, nnz, dims):
+def step_counts(n, nnz, dims, eb=4):
     """(spmm algorithmic bytes, NT flops, TN flops) of one step."""
     K = len(dims) - 1
-    sp = sum(spmm_bytes(n, nnz, dims[k - 1], False) for k in range(1, K + 1))
-    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True) for k in range(2, K + 1))
+    sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K + 1))
+    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K + 1))
     nt = sum(2.0 * n * dims[k] * 2 * dims[k - 1] for k in range(1, K + 1))          # forward
     nt += sum(2.0 * n * 2 * dims[k - 1] * dims[k] for k in range(2, K + 1))         # input gradients
     tn = sum(2.0 * 2 * n * dims[k - 1] * dims[k] for k in range(1, K + 1))          # dW_self, dW_neigh
@@ -100,8 +103,11 @@ def main():
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
 
-    model = lp.Model([f32(w) for w in wl.W_self], [f32(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
-    X = f32(wl.X)
+    bf16 = wl.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32      # storage type of features and weights
+    model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+    X = st(wl.X)
     n_pos, k_neg, Bn = wl.n_pos, wl.k_neg, wl.batch_edges
     pos_src = i32(wl.pos_src)
     e_src = torch.empty(Bn, dtype=torch.int32, device=dev)
@@ -109,8 +115,8 @@ def main():
     e_src[:n_pos] = pos_src
     e_dst[:n_pos] = i32(wl.pos_dst)
     neg_src, neg_dst = e_src[n_pos:], e_dst[n_pos:]
-    acts = lp.Acts(wl.n_nodes, wl.dims, dev)
-    grads = lp.Grads(wl.n_nodes, wl.dims, dev)
+    acts = lp.Acts(wl.n_nodes, wl.dims, dev, tdt)
+    grads = lp.Grads(wl.n_nodes, wl.dims, dev, dtype=tdt)
     ws_f = torch.empty(B.forward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(B.backward_workspace_bytes(model, wl.n_nodes, Bn), dtype=torch.uint8, device=dev)
     ws_l = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
@@ -158,7 +164,7 @@ def main():
     ms_per_step = dt * 1e3 / max(args.steps, 1)
 
     n, nnz = wl.n_nodes, g.nnz
-    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims)
+    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, 2 if bf16 else 4)
     per_step = {k: (ms / max(args.steps, 1), cnt // max(args.steps, 1)) for k, (ms, cnt) in classes.items()}
 
     def hbm_line(cls, bytes_per_step):
@@ -168,11 +174,11 @@ def main():
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "launches_per_step": cnt,
                 "avg_launch_ms": round(ms / max(cnt, 1), 4), "algorithmic_bytes_per_launch": int(bytes_per_step / max(cnt, 1))}
 
-    def mfma_line(cls, flops_per_step):
+    def mfma_line(cls, flops_per_step, peak=MFMA_FP32_PEAK_TFLOPS):
         ms, cnt = per_step[cls]
         tf = flops_per_step / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
-        return {"bound": "mfma", "kernel": cls, "achieved": round(tf, 2), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tf / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": None, "launches_per_step": cnt,
+        return {"bound": "mfma", "kernel": cls, "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(tf / peak, 4), "traffic": None, "launches_per_step": cnt,
                 "avg_launch_ms": round(ms / max(cnt, 1), 4), "flops_per_launch": int(flops_per_step / max(cnt, 1))}
 
     # HBM bytes per launch from the committed rocprofv3 --pmc summaries (FETCH_SIZE and WRITE_SIZE runs of this
@@ -183,7 +189,9 @@ def main():
         with open(tpath) as fh:
             traffic = json.load(fh)
 
-    lines = {"spmm": hbm_line("spmm", sp_bytes), "gemm_nt": mfma_line("gemm_nt", nt_flops),
+    # with bf16 storage the NT products run on the bf16 matrix cores; the TN products widen to fp32 first
+    lines = {"spmm": hbm_line("spmm", sp_bytes),
+             "gemm_nt": mfma_line("gemm_nt", nt_flops, BF16_MFMA_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS),
              "gemm_tn": mfma_line("gemm_tn", tn_flops)}
     for cls in lines:
         t = traffic.get(cls + "_bytes_per_launch")
@@ -202,9 +210,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: Chung-Lu power-law graph, %d nodes, %d directed CSR entries, GraphSAGE-mean %s, "
+        "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, GraphSAGE-mean %s, "
                                "%d positives + %d uniform negatives per step, full-neighbour aggregation"
                                % (args.workload, n, nnz, "->".join(map(str, wl.dims)), n_pos, n_pos * k_neg),
                    "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg},

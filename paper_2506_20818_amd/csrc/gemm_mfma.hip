@@ -538,20 +538,18 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
             const int idx = p * kThreads + tid;
             const int kr = idx / (TM / VE), c = (idx % (TM / VE)) * VE;
             const int64_t k = k0 + kr;
-            const bool ok = k < kend && m0 + c < g.Mw;
-            LpVec<T>::load(At + (ok ? k : kbeg) * g.lda + (ok ? m0 + c : 0), ra[p]);
 #pragma unroll
-            for (int e = 0; e < VE; ++e) ra[p][e] = ok ? ra[p][e] : 0.f;
+            for (int e = 0; e < VE; ++e) ra[p][e] = 0.f;
+            if (k < kend && m0 + c < g.Mw) LpVec<T>::load(At + k * g.lda + m0 + c, ra[p]);
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int idx = p * kThreads + tid;
             const int kr = idx / (TNn / VE), c = (idx % (TNn / VE)) * VE;
             const int64_t k = k0 + kr;
-            const bool ok = k < kend && n0 + c < g.Nw;
-            LpVec<T>::load(Bm + (ok ? k : kbeg) * g.ldb + (ok ? n0 + c : 0), rbv[p]);
 #pragma unroll
-            for (int e = 0; e < VE; ++e) rbv[p][e] = ok ? rbv[p][e] : 0.f;
+            for (int e = 0; e < VE; ++e) rbv[p][e] = 0.f;
+            if (k < kend && n0 + c < g.Nw) LpVec<T>::load(Bm + k * g.ldb + n0 + c, rbv[p]);
         }
     };
     auto stash = [&]() {
@@ -693,7 +691,7 @@ __global__ void zero_kernel(float4 *__restrict__ p4, int64_t n4, float *__restri
 
 }  // namespace
 
-static int compute_units() {
+int lp_compute_units() {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -740,7 +738,7 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (fast_ok) {
         // persistent workgroups, two per compute unit
         const int64_t row_tiles = lp_ceil_div(a.M, BM);
-        const int64_t slots = 2 * (int64_t)compute_units();
+        const int64_t slots = 2 * (int64_t)lp_compute_units();
         const dim3 pgrid((unsigned)(row_tiles < slots ? row_tiles : slots));
         if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<4>), pgrid, dim3(kThreads), 0, st, a);
         else hipLaunchKernelGGL((gemm_nt_fast_kernel<2>), pgrid, dim3(kThreads), 0, st, a);

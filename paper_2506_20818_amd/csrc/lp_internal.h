@@ -169,5 +169,8 @@ template <> struct LpVec<lp_bf16_t> {
 };
 #endif
 
+// number of compute units of the current device (cached)
+int lp_compute_units();
+
 static inline int lp_elem_bytes(int dtype) { return dtype == LP_BF16 ? 2 : 4; }
 static inline int lp_vec_elems(int dtype) { return dtype == LP_BF16 ? 8 : 4; }
