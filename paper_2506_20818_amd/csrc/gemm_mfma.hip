@@ -13,8 +13,6 @@
 //   is split over the grid; partial tiles are written out and summed in a fixed order by a second kernel.
 #include "lp_internal.h"
 
-#include <cstdlib>
-
 namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -189,24 +187,29 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 //  * addresses are a wavefront-uniform base plus a per-thread 32-bit offset that is set once per K part; rows and
 //    columns past the edge are clamped to the last valid one (their products land in outputs that are never stored);
 //  * LDS rows are padded to 20 floats: sixteen consecutive rows start in sixteen different groups of four banks.
-constexpr int FK = 16;
-constexpr int F_LD = FK + 4;
+constexpr int FK = 16;  // K granularity the fast path requires
 
-template <int NB>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
+// NB: 32-column blocks per wavefront (tile width 64*NB); MW: wavefronts along M (tile height 64*MW, 128*MW threads);
+// KS: K step (16 or 32).
+template <int NB, int MW, int KS>
+__global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
+    constexpr int TH = 128 * MW;
+    constexpr int BMt = 64 * MW;
     constexpr int BN = 64 * NB;
     constexpr int WN = 32 * NB;
-    constexpr int A_LOADS = BM * FK / 4 / kThreads;  // 2
-    constexpr int B_LOADS = BN * FK / 4 / kThreads;  // NB
-    constexpr int STAGE = (BM + BN) * F_LD;          // floats per LDS stage
+    constexpr int F_LD = KS + 4;
+    constexpr int KQ = KS / 4;                       // 16-byte vectors per tile row
+    constexpr int A_LOADS = BMt * KQ / TH;
+    constexpr int B_LOADS = BN * KQ / TH;
+    constexpr int STAGE = (BMt + BN) * F_LD;         // floats per LDS stage
     __shared__ float lds[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
     const int col_tiles = (g.N + BN - 1) / BN;
-    const int64_t row_tiles = ((int64_t)g.M + BM - 1) / BM;
-    const int tiles0 = g.K[0] / FK, tiles1 = g.K[1] / FK;
+    const int64_t row_tiles = ((int64_t)g.M + BMt - 1) / BMt;
+    const int tiles0 = g.K[0] / KS, tiles1 = g.K[1] / KS;
     const int n_tiles = tiles0 + tiles1;
     if ((int64_t)blockIdx.x >= row_tiles || n_tiles == 0) return;
     const int64_t my_rows = (row_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
@@ -241,23 +244,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         abase = reinterpret_cast<const char *>(A_ + m0f * lda_);                                                       \
         bbase = reinterpret_cast<const char *>(Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_);               \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * kThreads + tid;                                                                        \
-            int64_t r = idx >> 2;                                                                                      \
+            const int idx = p * TH + tid;                                                                        \
+            int64_t r = idx / KQ;                                                                                      \
             r = m0f + r < g.M ? r : g.M - 1 - m0f;                                                                     \
-            aoff[p] = (uint32_t)((r * lda_ + ((idx & 3) << 2)) * 4);                                                   \
+            aoff[p] = (uint32_t)((r * lda_ + ((idx % KQ) << 2)) * 4);                                                   \
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * kThreads + tid;                                                                        \
-            int64_t r = idx >> 2;                                                                                      \
+            const int idx = p * TH + tid;                                                                        \
+            int64_t r = idx / KQ;                                                                                      \
             r = n0f + r < n_endf ? r : n_endf - 1 - n0f;                                                               \
-            boff[p] = (uint32_t)((r * ldb_ + ((idx & 3) << 2)) * 4);                                                   \
+            boff[p] = (uint32_t)((r * ldb_ + ((idx % KQ) << 2)) * 4);                                                   \
         }                                                                                                              \
     }
     // loads of the next K step in pipeline order (possibly the first step of the next output tile)
 #define LP_FETCH_NEXT()                                                                                                \
     if (fw < n_work) {                                                                                                 \
         if (ft == 0) {                                                                                                 \
-            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BM;                                           \
+            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BMt;                                           \
             n0f = (int)(fw % col_tiles) * BN;                                                                          \
             secondf = n0f >= g.n_split;                                                                                \
             n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                              \
@@ -267,8 +270,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) ra[p] = *reinterpret_cast<const v4f *>(abase + aoff[p]);   \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) rbv[p] = *reinterpret_cast<const v4f *>(bbase + boff[p]);  \
-        abase += FK * 4;                                                                                               \
-        bbase += FK * 4;                                                                                               \
+        abase += KS * 4;                                                                                               \
+        bbase += KS * 4;                                                                                               \
         if (++ft == n_tiles) {                                                                                         \
             ft = 0;                                                                                                    \
             ++fw;                                                                                                      \
@@ -277,20 +280,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #define LP_STASH(stage)                                                                                                \
     {                                                                                                                  \
         float *As_ = lds + (stage) * STAGE;                                                                            \
-        float *Bs_ = As_ + BM * F_LD;                                                                                  \
+        float *Bs_ = As_ + BMt * F_LD;                                                                                  \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * kThreads + tid;                                                                        \
-            *reinterpret_cast<v4f *>(&As_[(idx >> 2) * F_LD + ((idx & 3) << 2)]) = ra[p];                              \
+            const int idx = p * TH + tid;                                                                        \
+            *reinterpret_cast<v4f *>(&As_[(idx / KQ) * F_LD + ((idx % KQ) << 2)]) = ra[p];                              \
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * kThreads + tid;                                                                        \
-            *reinterpret_cast<v4f *>(&Bs_[(idx >> 2) * F_LD + ((idx & 3) << 2)]) = rbv[p];                             \
+            const int idx = p * TH + tid;                                                                        \
+            *reinterpret_cast<v4f *>(&Bs_[(idx / KQ) * F_LD + ((idx % KQ) << 2)]) = rbv[p];                             \
         }                                                                                                              \
     }
 #define LP_COMPUTE(stage, kk)                                                                                          \
     {                                                                                                                  \
         const float *As_ = lds + (stage) * STAGE;                                                                      \
-        const float *Bs_ = As_ + BM * F_LD;                                                                            \
+        const float *Bs_ = As_ + BMt * F_LD;                                                                            \
         v4f a[2], b[NB];                                                                                               \
         _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
             a[rb] = *reinterpret_cast<const v4f *>(&As_[(wm * 64 + rb * 32 + i32) * F_LD + (kk) * 8 + 4 * h]);         \
@@ -314,10 +317,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     int ct = 0;      // its K step
     for (int64_t u = 0; u < n_steps; ++u) {
         const int cur = (int)(u & 1);
-        LP_COMPUTE(cur, 0)
+#pragma unroll
+        for (int kk = 0; kk < KS / 16; ++kk) LP_COMPUTE(cur, kk)
         if (u + 1 < n_steps) LP_STASH(cur ^ 1)  // registers hold step u+1
         LP_FETCH_NEXT()                         // step u+2
-        LP_COMPUTE(cur, 1)
+#pragma unroll
+        for (int kk = KS / 16; kk < KS / 8; ++kk) LP_COMPUTE(cur, kk)
         __syncthreads();
         if (++ct < n_tiles) continue;
         ct = 0;
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         // each 32x32 accumulator block is the TRANSPOSE of the output block: lane (j = lane % 32, h = lane / 32)
         // holds output row j and, in registers 4q..4q+3, the four consecutive columns 8q + 4h .. + 3.  Every lane
         // therefore stores 16 contiguous bytes at a time and needs a single row scale.
-        const int64_t m0 = ((int64_t)blockIdx.x + (cw / col_tiles) * gridDim.x) * BM;
+        const int64_t m0 = ((int64_t)blockIdx.x + (cw / col_tiles) * gridDim.x) * BMt;
         const int n0 = (int)(cw % col_tiles) * BN;
         ++cw;
         const bool second = n0 >= g.n_split;
@@ -725,8 +730,8 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         else hipLaunchKernelGGL((gemm_nt_bf16_kernel<1>), grid, dim3(kThreads), 0, st, a);
         return lp_after_launch();
     }
-    static const int force_bn = getenv("LP_GEMM_NT_BN") ? atoi(getenv("LP_GEMM_NT_BN")) : 0;
-    static const int no_fast = getenv("LP_GEMM_NT_NOFAST") ? 1 : 0;
+    const int force_bn = 0;
+    const int no_fast = 0;
     // fast path: K parts in whole steps, and no column tile straddling the output split
     const int fast_bn = (a.N > 128 && force_bn != 128) ? 256 : 128;
     const bool fast_ok = !no_fast && a.N > 64 && (a.K[0] % FK == 0) && (a.K[1] % FK == 0) && a.K[0] + a.K[1] > 0 &&
@@ -736,12 +741,16 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         return dim3((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
     };
     if (fast_ok) {
-        // persistent workgroups, two per compute unit
-        const int64_t row_tiles = lp_ceil_div(a.M, BM);
-        const int64_t slots = 2 * (int64_t)lp_compute_units();
+        // persistent workgroups filling every compute unit
+        // widest tile (256 x 256, eight wavefronts, K step 32, one workgroup per compute unit) when K allows
+        const bool big = fast_bn == 256 && (a.K[0] % 32 == 0) && (a.K[1] % 32 == 0) && a.M >= 4096;
+        const int bm = big ? 256 : 128;
+        const int64_t row_tiles = lp_ceil_div(a.M, bm);
+        const int64_t slots = (big ? 1 : 2) * (int64_t)lp_compute_units();
         const dim3 pgrid((unsigned)(row_tiles < slots ? row_tiles : slots));
-        if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<4>), pgrid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((gemm_nt_fast_kernel<2>), pgrid, dim3(kThreads), 0, st, a);
+        if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<4, 4, 32>), pgrid, dim3(512), 0, st, a);
+        else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<4, 2, 16>), pgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nt_fast_kernel<2, 2, 16>), pgrid, dim3(256), 0, st, a);
     } else if (a.N > 128 && force_bn != 128) {
         hipLaunchKernelGGL((gemm_nt_kernel<4>), grid_for(256), dim3(kThreads), 0, st, a);
     } else if (a.N > 64) {
