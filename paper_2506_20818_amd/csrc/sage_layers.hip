@@ -83,6 +83,7 @@ struct BackwardWs {
     uint32_t *hist;
     int32_t *bptr, *bcol;
     float *bw;
+    int32_t *long_queue;
     size_t bytes;
 };
 
@@ -109,6 +110,7 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
     w.bptr = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * ((size_t)n_nodes + 1)));
     w.bcol = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * n2));
     w.bw = take(sizeof(float) * n2);
+    w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(n_nodes)));
     w.bytes = off;
     return w;
 }
@@ -116,9 +118,8 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
 }  // namespace
 
 extern "C" size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
-    (void)n_nodes;
-    if (check_model(m) != LP_OK) return 0;
-    return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m));
+    if (check_model(m) != LP_OK || n_nodes <= 0) return 0;
+    return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m)) + lp_spmm_queue_bytes(n_nodes);
 }
 
 extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws, size_t ws_bytes,
@@ -132,6 +133,7 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
     const int dt = m->dtype;
     const size_t eb = (size_t)lp_elem_bytes(dt);
     char *wt = static_cast<char *>(ws);
+    int32_t *long_queue = reinterpret_cast<int32_t *>(wt + lp_align_up(eb * transposed_weight_elems(m)));
     const int K = m->n_layers;
     const void *Hprev = X;
     for (int k = 1; k <= K; ++k) {
@@ -146,6 +148,8 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         sp.colidx = g->colidx;
         sp.row_order = g->row_order;
         sp.inv_deg = g->inv_deg;
+        sp.n_entries = g->nnz;
+        sp.long_queue = long_queue;
         sp.in = Hprev;
         sp.out = A;
         LP_TRY(lp_launch_spmm(sp, st));
@@ -221,6 +225,7 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         sc.dtype = dt;
         sc.n_rows = N; sc.F = m->dims[K];
         sc.rowptr = w.bptr; sc.colidx = w.bcol; sc.w = w.bw;
+        sc.n_entries = n2; sc.long_queue = w.long_queue;
         sc.in = HK; sc.out = dZ;
         sc.timing_class = LP_KC_SCATTER;
         LP_TRY(lp_launch_spmm(sc, st));
@@ -258,6 +263,7 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         sp.dtype = dt;
         sp.n_rows = N; sp.F = Fi;
         sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
+        sp.n_entries = g->nnz; sp.long_queue = w.long_queue;
         sp.in = R; sp.addend = Q;
         sp.gate = k > 1 ? Hin : nullptr;
         sp.out = k > 1 ? Q : static_cast<void *>(out->dX);

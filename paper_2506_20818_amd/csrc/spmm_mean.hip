@@ -3,51 +3,48 @@
 //
 //   out[v, :] = rowscale(v) * sum_{p in row v} w[p] * in[colidx[p], :]   (+ addend[v, :])   (zeroed where gate <= 0)
 //
-// One wavefront owns one output row.  A neighbour row is read by G lanes with one 16-byte load each (4 floats or
-// 8 bfloat16; fully coalesced: 64 lanes cover 1 KiB); when G < 64 the wavefront reads 64/G neighbours at once and
-// folds the partial sums with xor-shuffles at the end.  Neighbour ids are fetched 64 at a time (coalesced) and
-// handed to the lanes that need them through the LDS crossbar (ds_bpermute), four rows in flight per lane.
-// Rows are visited in `row_order` (longest first) when given, so that hub rows start early and never form the tail.
+// Ordinary rows: one wavefront owns one output row.  A neighbour row is read by G lanes with one 16-byte load each
+// (4 floats or 8 bfloat16; fully coalesced: 64 lanes cover 1 KiB); when G < 64 the wavefront reads 64/G neighbours
+// at once and folds the partial sums with xor-shuffles at the end.  Neighbour ids are fetched 64 at a time
+// (coalesced) and handed to the lanes that need them through the LDS crossbar (ds_bpermute), several rows in flight
+// per lane.  Rows are visited in `row_order` (longest first) when given, so that long rows start early.
+//
+// Hub rows: a single wavefront keeps only a few KiB in flight, so a row with thousands of neighbours would take
+// longer than the rest of the launch together (power-law graphs have such rows).  When the caller supplies a queue,
+// a wavefront that meets a row of at least kLongRow neighbours appends it to the queue instead, and a second launch
+// gives every queued row to a whole workgroup of sixteen wavefronts: wavefront w takes the 64-neighbour blocks
+// w, w+16, ... and the sixteen partial sums are added in wavefront order through LDS.  Which workgroup serves which
+// queued row depends on scheduling; the value computed for a row does not.
 // Sums are always accumulated in fp32, whatever the storage type.
 #include "lp_internal.h"
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
+constexpr int kLongThreads = 1024;
+constexpr int kLongWaves = kLongThreads / 64;
 
+// Accumulates the 64-neighbour blocks first, first + stride, ... (< hi) of one CSR row into acc.
 // T: storage type, G: lanes per neighbour row (8..64), C: 16-byte chunks per lane (C > 1 only when G == 64),
-// W: per-entry weights
-template <typename T, int G, int C, bool W>
-__global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
+// W: per-entry weights, U: neighbour rows in flight per lane.
+template <typename T, int G, int C, bool W, int U>
+__device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__restrict__ in, int32_t first, int32_t hi,
+                                                  int32_t stride, int lane, float (&acc)[C][LpVec<T>::N]) {
     constexpr int P = 64 / G;  // neighbours read per step
     constexpr int VE = LpVec<T>::N;
-    const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (r >= a.n_rows) return;
-    const int32_t v = a.row_order ? a.row_order[r] : (int32_t)r;
     const int sub = lane / G, fl = lane % G;
     const int FV = a.F / VE;           // 16-byte vectors per row
     const bool lane_on = fl < FV;      // F/VE need not be a power of two
-    const T *__restrict__ in = static_cast<const T *>(a.in);
-    const int32_t lo = a.rowptr[v], hi = a.rowptr[v + 1];
-
-    float acc[C][VE];
-#pragma unroll
-    for (int c = 0; c < C; ++c)
-#pragma unroll
-        for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
-
-    for (int32_t base = lo; base < hi; base += 64) {
+    for (int32_t base = first; base < hi; base += stride) {
         const int cnt = min(64, hi - base);
         const int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
         float mine_w = 1.f;
         if (W) mine_w = lane < cnt ? a.w[base + lane] : 0.f;
-        for (int j0 = 0; j0 < cnt; j0 += P * kUnroll) {
-            float x[kUnroll][C][VE];
-            float wj[kUnroll];
+        for (int j0 = 0; j0 < cnt; j0 += P * U) {
+            float x[U][C][VE];
+            float wj[U];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * P + sub;
                 const int32_t nb = __shfl(mine, j & 63, 64);
                 wj[u] = W ? __shfl(mine_w, j & 63, 64) : 1.f;
@@ -60,7 +57,7 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int c = 0; c < C; ++c)
 #pragma unroll
@@ -70,35 +67,116 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
                     }
         }
     }
+}
+
+// Lanes with the same position inside their group of G add up their partial sums (all lanes end with the total).
+template <int G, int C, int VE>
+__device__ __forceinline__ void fold_groups(float (&acc)[C][VE]) {
 #pragma unroll
     for (int d = G; d < 64; d <<= 1)
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
             for (int e = 0; e < VE; ++e) acc[c][e] += __shfl_xor(acc[c][e], d, 64);
-    if (sub != 0 || !lane_on) return;
+}
+
+// Scale, optional addend, optional gate, store: 16 bytes of output row v starting at vector column colv.
+template <typename T>
+__device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int FV, int colv, float scale,
+                                              const float (&sum)[LpVec<T>::N]) {
+    constexpr int VE = LpVec<T>::N;
+    const int64_t o = ((int64_t)v * FV + colv) * VE;
+    float y[VE];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) y[e] = sum[e] * scale;
+    if (a.addend) {
+        float t[VE];
+        LpVec<T>::load(static_cast<const T *>(a.addend) + o, t);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) y[e] += t[e];
+    }
+    if (a.gate) {
+        float gt[VE];
+        LpVec<T>::load(static_cast<const T *>(a.gate) + o, gt);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) y[e] = gt[e] > 0.f ? y[e] : 0.f;
+    }
+    LpVec<T>::store(static_cast<T *>(a.out) + o, y);
+}
+
+template <typename T, int G, int C, bool W>
+__global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
+    constexpr int VE = LpVec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (r >= a.n_rows) return;
+    const int32_t v = a.row_order ? a.row_order[r] : (int32_t)r;
+    const int sub = lane / G, fl = lane % G;
+    const int FV = a.F / VE;
+    const int32_t lo = a.rowptr[v], hi = a.rowptr[v + 1];
+    if (a.long_queue && hi - lo >= a.long_threshold) {  // a hub: leave it to a whole workgroup of the second launch
+        if (lane == 0) a.long_queue[1 + atomicAdd(a.long_queue, 1)] = v;
+        return;
+    }
+
+    float acc[C][VE];
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
+    accumulate_blocks<T, G, C, W, 4>(a, static_cast<const T *>(a.in), lo, hi, 64, lane, acc);
+    fold_groups<G, C, VE>(acc);
+    if (sub != 0 || fl >= FV) return;
     const float scale = a.inv_deg ? a.inv_deg[v] : 1.0f;
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int colv = fl + 64 * c;
         if (C > 1 && colv >= FV) break;
-        const int64_t o = ((int64_t)v * FV + colv) * VE;
-        float y[VE];
+        finish_vector<T>(a, v, FV, colv, scale, acc[c]);
+    }
+}
+
+// One workgroup of sixteen wavefronts per queued row; workgroup b serves queue entries b, b + gridDim.x, ...
+template <typename T, int G, int C, bool W>
+__global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a) {
+    constexpr int VE = LpVec<T>::N;
+    constexpr int U = C == 1 ? 8 : 4;
+    __shared__ float red[kLongWaves][G][VE];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane / G, fl = lane % G;
+    const int FV = a.F / VE;
+    const int32_t n_queued = a.long_queue[0];
+    for (int32_t i = blockIdx.x; i < n_queued; i += gridDim.x) {  // uniform over the workgroup
+        const int32_t v = a.long_queue[1 + i];
+        const int32_t lo = a.rowptr[v], hi = a.rowptr[v + 1];
+        float acc[C][VE];
 #pragma unroll
-        for (int e = 0; e < VE; ++e) y[e] = acc[c][e] * scale;
-        if (a.addend) {
-            float t[VE];
-            LpVec<T>::load(static_cast<const T *>(a.addend) + o, t);
+        for (int c = 0; c < C; ++c)
 #pragma unroll
-            for (int e = 0; e < VE; ++e) y[e] += t[e];
+            for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
+        accumulate_blocks<T, G, C, W, U>(a, static_cast<const T *>(a.in), lo + 64 * wave, hi, 64 * kLongWaves, lane, acc);
+        fold_groups<G, C, VE>(acc);
+        const float scale = a.inv_deg ? a.inv_deg[v] : 1.0f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (sub == 0) {
+#pragma unroll
+                for (int e = 0; e < VE; ++e) red[wave][fl][e] = acc[c][e];
+            }
+            __syncthreads();
+            const int colv = fl + 64 * c;
+            if (wave == 0 && sub == 0 && colv < FV) {
+                float sum[VE];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) sum[e] = red[0][fl][e];
+#pragma unroll
+                for (int w = 1; w < kLongWaves; ++w)
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) sum[e] += red[w][fl][e];
+                finish_vector<T>(a, v, FV, colv, scale, sum);
+            }
+            __syncthreads();
         }
-        if (a.gate) {
-            float gt[VE];
-            LpVec<T>::load(static_cast<const T *>(a.gate) + o, gt);
-#pragma unroll
-            for (int e = 0; e < VE; ++e) y[e] = gt[e] > 0.f ? y[e] : 0.f;
-        }
-        LpVec<T>::store(static_cast<T *>(a.out) + o, y);
     }
 }
 
@@ -107,6 +185,16 @@ int launch(const SpmmArgs &a, hipStream_t st) {
     const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kThreads / 64);
     if (a.w) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, true>), dim3(grid), dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, false>), dim3(grid), dim3(kThreads), 0, st, a);
+    if (a.long_queue) {
+        // no more rows can be queued than fit the entry count; two workgroups per compute unit walk the queue
+        const int64_t most = a.n_entries / a.long_threshold;
+        const int64_t slots = 2 * (int64_t)lp_compute_units();
+        const unsigned lgrid = (unsigned)(most < slots ? most : slots);
+        if (lgrid > 0) {
+            if (a.w) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, true>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            else hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, false>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+        }
+    }
     return lp_after_launch();
 }
 
@@ -124,9 +212,15 @@ int dispatch(const SpmmArgs &a, hipStream_t st) {
 
 }  // namespace
 
-int lp_launch_spmm(const SpmmArgs &a, hipStream_t st) {
-    if (a.n_rows <= 0) return LP_OK;
-    if (a.F <= 0 || a.F % lp_vec_elems(a.dtype)) return LP_ERR_UNSUPPORTED;
+size_t lp_spmm_queue_bytes(int32_t n_rows) { return lp_align_up(sizeof(int32_t) * ((size_t)(n_rows > 0 ? n_rows : 0) + 1)); }
+
+int lp_launch_spmm(const SpmmArgs &args, hipStream_t st) {
+    if (args.n_rows <= 0) return LP_OK;
+    if (args.F <= 0 || args.F % lp_vec_elems(args.dtype)) return LP_ERR_UNSUPPORTED;
+    SpmmArgs a = args;
+    a.long_threshold = kSpmmLongRow;
+    if (a.n_entries < a.long_threshold) a.long_queue = nullptr;  // no row can be that long
+    if (a.long_queue) LP_TRY(lp_launch_zero(reinterpret_cast<float *>(a.long_queue), 1, st));  // queue length
     LpTimedScope timed(a.timing_class, st);
     if (a.dtype == LP_BF16) return dispatch<lp_bf16_t>(a, st);
     if (a.dtype == LP_F32) return dispatch<float>(a, st);

@@ -282,6 +282,46 @@ def test_backward_parity(dims, sym):
     check_grads(grads2, g_ref, len(dims) - 1, lo, hi)
 
 
+@pytest.mark.parametrize("dims", [[16, 32, 8], [128, 256, 64], [64, 520, 8]])
+def test_hub_rows_served_by_a_whole_workgroup(dims):
+    """Rows of 512 or more entries take the workgroup-per-row path of the aggregation: hubs of 511 (stays on the
+    wavefront path), 512, 1023, 1025 and 3000 neighbours in the graph (rows, and columns of the transpose), and a
+    node that is an endpoint of 1700 scored edges in the batch."""
+    rng = np.random.default_rng(77 + dims[0])
+    n = 3300
+    r, c = random_pairs(rng, n, 5000)
+    for hub, deg in ((5, 511), (9, 512), (100, 1023), (2000, 1025), (3299, 3000)):
+        r = np.concatenate([r, np.full(deg, hub, np.int32)])
+        c = np.concatenate([c, rng.choice(n, deg, replace=False).astype(np.int32)])
+    say("hub rows dims=%s n=%d" % (dims, n))
+    ref = O.build_csr(n, r, c, False)
+    assert np.diff(ref.rowptr).max() >= 3000
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), False)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.2)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 4000, 1500
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    es[:1200] = 7                                    # batch hub: 1200 times a source, 500 times a destination
+    ed[3500:] = 7
+    model = make_model(Ws, Wn, b)
+    Xd = dev_f32(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    for k in range(1, len(dims)):
+        assert_close(host(acts.A[k - 1]), a_ref.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(host(acts.H[k - 1]), a_ref.H[k], TOL_ACT, "H^%d" % k)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
+    # same bits when repeated: the hub sums do not depend on which workgroup serves which row
+    again = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    assert np.array_equal(host(again.dX), host(grads.dX)) and np.array_equal(host(again.dW_neigh[0]), host(grads.dW_neigh[0]))
+
+
 def test_backward_empty_batch_gives_zero_gradients():
     say("backward B=0")
     rng = np.random.default_rng(3)
