@@ -189,10 +189,11 @@ def main():
         with open(tpath) as fh:
             traffic = json.load(fh)
 
-    # with bf16 storage the NT products run on the bf16 matrix cores; the TN products widen to fp32 first
+    # with bf16 storage both kinds of product run on the bf16 matrix cores (fp32 accumulation)
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS
     lines = {"spmm": hbm_line("spmm", sp_bytes),
-             "gemm_nt": mfma_line("gemm_nt", nt_flops, BF16_MFMA_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS),
-             "gemm_tn": mfma_line("gemm_tn", tn_flops)}
+             "gemm_nt": mfma_line("gemm_nt", nt_flops, mfma_peak),
+             "gemm_tn": mfma_line("gemm_tn", tn_flops, mfma_peak)}
     for cls in lines:
         t = traffic.get(cls + "_bytes_per_launch")
         lines[cls]["traffic"] = int(t) if t else None

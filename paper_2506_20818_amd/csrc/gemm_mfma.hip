@@ -608,6 +608,117 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
     }
 }
 
+// ------------------------------------------------------------------------------------------------ TN, bfloat16
+// Weight gradients from bfloat16 operands on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation):
+// the products of bfloat16 values are exact in fp32, so this computes the same sums as widening to fp32 first.
+// The MFMA wants, per lane, eight consecutive values of the reduction index (nodes) for one fixed column, while
+// memory holds node-major rows.  Each loader thread therefore fetches an 8 (nodes) x 8 (columns) block as eight
+// 16-byte row pieces, transposes it in registers (byte permutes) and writes eight 16-byte column pieces to an LDS
+// tile laid out [column][node]; lanes are assigned so that eight neighbouring lanes write 128 contiguous bytes.
+// Workgroups are numbered so that all tiles of one node chunk run on the same XCD and share its L2.
+constexpr int TK = 64;          // nodes per step
+constexpr int T_LD = TK + 8;    // LDS row: 64 nodes + 8 of padding (144 bytes)
+
+template <int MB, int NBk>  // 32-row / 32-column blocks per wavefront: tile (64*MB) x (64*NBk)
+__global__ __launch_bounds__(kThreads) void gemm_tn_bf16_kernel(GemmTnArgs g, int chunk, int splits) {
+    constexpr int TM = 64 * MB, TNn = 64 * NBk;
+    static_assert(TM + TNn <= kThreads, "one loader task per thread");
+    __shared__ lp_bf16_t As[TM * T_LD];
+    __shared__ lp_bf16_t Bs[TNn * T_LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int tiles_n = (g.Nw + TNn - 1) / TNn;
+    const int tiles = ((g.Mw + TM - 1) / TM) * tiles_n;
+    // linear workgroup ids go round-robin over the eight XCDs: id % 8 picks the XCD, and with it the node chunk
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int tile = slot % tiles;
+    const int split = (slot / tiles) * 8 + xcd;
+    if (split >= splits) return;
+    const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TNn;
+    const int64_t kbeg = (int64_t)split * chunk;
+    const int64_t kend = kbeg + chunk < g.Kn ? kbeg + chunk : g.Kn;
+
+    // loader task of this thread: threads [0, TM) serve At, threads [TM, TM + TNn) serve B
+    const bool loads_a = tid < TM;
+    const int task = loads_a ? tid : tid - TM;
+    const bool has_task = tid < TM + TNn;
+    const int q = task & 7, c = task >> 3;                       // node chunk (8 nodes), column chunk (8 columns)
+    const lp_bf16_t *__restrict__ src = static_cast<const lp_bf16_t *>(loads_a ? g.At : g.B);
+    const int64_t ld = loads_a ? g.lda : g.ldb;
+    const int col = (loads_a ? m0 : n0) + 8 * c;
+    const bool col_ok = has_task && col < (loads_a ? g.Mw : g.Nw);
+    lp_bf16_t *__restrict__ dst = (loads_a ? As : Bs) + (8 * c) * T_LD + 8 * q;
+
+    v16f acc[MB][NBk];
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NBk; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+
+    v4i rows[8];
+    const v4i zero = {0, 0, 0, 0};
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t k = k0 + 8 * q + e;
+            rows[e] = zero;
+            if (col_ok && k < kend) rows[e] = *reinterpret_cast<const v4i *>(src + k * ld + col);
+        }
+    };
+    auto stash = [&]() {
+        if (!has_task) return;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {  // column j of the block: nodes 0..7, two per 32-bit word
+            v4i o;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                o[d] = (int)__builtin_amdgcn_perm((uint32_t)rows[2 * d + 1][j >> 1], (uint32_t)rows[2 * d][j >> 1],
+                                                  (j & 1) ? 0x07060302u : 0x05040100u);
+            *reinterpret_cast<v4i *>(dst + j * T_LD) = o;
+        }
+    };
+
+    if (kbeg < kend) fetch(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += TK) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (k0 + TK < kend) fetch(k0 + TK);
+#pragma unroll
+        for (int kk = 0; kk < TK / 16; ++kk) {
+            v4i a[MB], b[NBk];
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb)
+                a[rb] = *reinterpret_cast<const v4i *>(&As[(wm * 32 * MB + rb * 32 + i32) * T_LD + kk * 16 + 8 * h]);
+#pragma unroll
+            for (int cb = 0; cb < NBk; ++cb)
+                b[cb] = *reinterpret_cast<const v4i *>(&Bs[(wn * 32 * NBk + cb * 32 + i32) * T_LD + kk * 16 + 8 * h]);
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < NBk; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[rb]), __builtin_bit_cast(v8bf, b[cb]),
+                                                                          acc[rb][cb], 0, 0, 0);
+        }
+    }
+    float *__restrict__ P = g.partials + (int64_t)split * g.Mw * g.Nw;
+#pragma unroll
+    for (int cb = 0; cb < NBk; ++cb) {
+        const int n = n0 + wn * 32 * NBk + cb * 32 + i32;
+        if (n >= g.Nw) continue;
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 32 * MB + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < g.Mw) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
+            }
+    }
+}
+
 struct TnPlan {
     int tm, tn, tiles, splits, chunk;
 };
@@ -621,7 +732,7 @@ TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
     int64_t max_by_len = lp_ceil_div(Kn, 8 * BK);       // at least 256 nodes per workgroup
     int64_t s = want < max_by_len ? want : max_by_len;
     if (s < 1) s = 1;
-    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), BK) * BK);
+    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), 64) * 64);
     p.splits = (int)lp_ceil_div(Kn, p.chunk);
     return p;
 }
@@ -783,7 +894,11 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
     else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_kernel<T, 1, 2>), grid, dim3(kThreads), 0, st, a, p.chunk);           \
     else hipLaunchKernelGGL((gemm_tn_kernel<T, 1, 1>), grid, dim3(kThreads), 0, st, a, p.chunk);
     if (a.dtype == LP_BF16) {
-        LP_TN_LAUNCH(lp_bf16_t)
+        const dim3 bgrid((unsigned)(p.tiles * lp_ceil_div(p.splits, 8) * 8));
+        if (p.tm == 128 && p.tn == 128) hipLaunchKernelGGL((gemm_tn_bf16_kernel<2, 2>), bgrid, dim3(kThreads), 0, st, a, p.chunk, p.splits);
+        else if (p.tm == 128) hipLaunchKernelGGL((gemm_tn_bf16_kernel<2, 1>), bgrid, dim3(kThreads), 0, st, a, p.chunk, p.splits);
+        else if (p.tn == 128) hipLaunchKernelGGL((gemm_tn_bf16_kernel<1, 2>), bgrid, dim3(kThreads), 0, st, a, p.chunk, p.splits);
+        else hipLaunchKernelGGL((gemm_tn_bf16_kernel<1, 1>), bgrid, dim3(kThreads), 0, st, a, p.chunk, p.splits);
     } else {
         LP_TN_LAUNCH(float)
     }
