@@ -176,40 +176,70 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 }
 
 // ------------------------------------------------------------------------------------------------ NT, fast path
-// Same product as gemm_nt_kernel for shapes whose K parts are multiples of 16 and whose column tiles do not
-// straddle n_split.  What makes it faster:
-//  * persistent workgroups (two per compute unit): a workgroup walks over row tiles b, b+G, b+2G, ... and, for each,
-//    over all column tiles, as ONE software pipeline.  The loads of the next tile's first K steps are already in
-//    flight while the current tile's results are stored, so only the very first tile pays the load latency, and
-//    the second column tile of a row tile finds the A rows in the XCD's L2;
-//  * K step 16 with two LDS stages and one barrier per step: while the MFMAs of step u run from stage u&1, step u+1
-//    (already in registers) is written to the other stage and the loads of step u+2 are issued;
-//  * addresses are a wavefront-uniform base plus a per-thread 32-bit offset that is set once per K part; rows and
-//    columns past the edge are clamped to the last valid one (their products land in outputs that are never stored);
-//  * LDS rows are padded to 20 floats: sixteen consecutive rows start in sixteen different groups of four banks.
-constexpr int FK = 16;  // K granularity the fast path requires
+// Same product as gemm_nt_kernel for shapes whose K parts are whole K steps and whose column tiles do not
+// straddle n_split, for fp32 and for bfloat16 storage.  What makes it faster:
+//  * persistent workgroups: a workgroup walks over row tiles b, b+G, b+2G, ... and, for each, over all column
+//    tiles, as ONE software pipeline.  The loads of the next tile's first K steps are already in flight while the
+//    current tile's results are stored, so only the very first tile pays the load latency, and the second column
+//    tile of a row tile finds the A rows in the XCD's L2;
+//  * two LDS stages and one barrier per K step: while the MFMAs of step u run from stage u&1, step u+1 (already
+//    in registers) is written to the other stage and the loads of step u+2 are issued;
+//  * addresses are a wavefront-uniform base plus a per-thread 32-bit byte offset that is set once per K part; rows
+//    and columns past the edge are clamped to the last valid one (their products land in outputs never stored);
+//  * LDS rows are padded by 16 bytes, so consecutive rows start in different groups of four banks.
+// Everything is laid out in bytes: a K step covers KSB bytes of every operand row (KSB/4 fp32 or KSB/2 bfloat16
+// values), and a 32-byte group of a row feeds four fp32 MFMAs (k pairs) or one bf16 MFMA (sixteen k), with lane
+// half h owning bytes 16h..16h+15 of the group for both operands.
+// The weight tile is the row operand of the MFMAs, so each 32x32 accumulator block is the TRANSPOSE of the output
+// block: lane (j = lane % 32, h = lane / 32) holds output row j and, in registers 4q..4q+3, the four consecutive
+// columns 8q + 4h .. + 3.  Every lane therefore stores whole 16-byte (fp32) or 8-byte (bfloat16) pieces and needs
+// a single row scale.
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
-// NB: 32-column blocks per wavefront (tile width 64*NB); MW: wavefronts along M (tile height 64*MW, 128*MW threads);
-// KS: K step (16 or 32).
-template <int NB, int MW, int KS>
+template <typename T> struct NtElem;
+template <> struct NtElem<float> {
+    static constexpr int STEPS = 4;  // MFMAs per 32-byte group: one per fp32 value of the lane's 16 bytes
+    static __device__ __forceinline__ void mfma_step(v16f &acc, const v4i &w, const v4i &x, int s) {
+        acc = mfma32(__builtin_bit_cast(v4f, w)[s], __builtin_bit_cast(v4f, x)[s], acc);
+    }
+    static __device__ __forceinline__ void store4(float *p, const float (&y)[4]) {
+        *reinterpret_cast<v4f *>(p) = v4f{y[0], y[1], y[2], y[3]};
+    }
+};
+template <> struct NtElem<lp_bf16_t> {
+    static constexpr int STEPS = 1;
+    static __device__ __forceinline__ void mfma_step(v16f &acc, const v4i &w, const v4i &x, int) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, w), __builtin_bit_cast(v8bf, x), acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void store4(lp_bf16_t *p, const float (&y)[4]) {
+        *reinterpret_cast<uint2 *>(p) = make_uint2((uint32_t)lp_f32_to_bf16(y[0]) | ((uint32_t)lp_f32_to_bf16(y[1]) << 16),
+                                                   (uint32_t)lp_f32_to_bf16(y[2]) | ((uint32_t)lp_f32_to_bf16(y[3]) << 16));
+    }
+};
+
+// T: storage type; NB: 32-column blocks per wavefront (tile width 64*NB); MW: wavefronts along M (tile height 64*MW,
+// 128*MW threads); KSB: bytes of every operand row consumed per K step (64 or 128).
+template <typename T, int NB, int MW, int KSB>
 __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
+    constexpr int ES = (int)sizeof(T);
     constexpr int TH = 128 * MW;
     constexpr int BMt = 64 * MW;
     constexpr int BN = 64 * NB;
     constexpr int WN = 32 * NB;
-    constexpr int F_LD = KS + 4;
-    constexpr int KQ = KS / 4;                       // 16-byte vectors per tile row
+    constexpr int ROWB = KSB + 16;                   // bytes per LDS row
+    constexpr int KQ = KSB / 16;                     // 16-byte vectors per tile row
     constexpr int A_LOADS = BMt * KQ / TH;
     constexpr int B_LOADS = BN * KQ / TH;
-    constexpr int STAGE = (BMt + BN) * F_LD;         // floats per LDS stage
-    __shared__ float lds[2 * STAGE];
+    constexpr int STAGE = (BMt + BN) * ROWB;         // bytes per LDS stage
+    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
     const int col_tiles = (g.N + BN - 1) / BN;
     const int64_t row_tiles = ((int64_t)g.M + BMt - 1) / BMt;
-    const int tiles0 = g.K[0] / KS, tiles1 = g.K[1] / KS;
+    const int tiles0 = g.K[0] * ES / KSB, tiles1 = g.K[1] * ES / KSB;
     const int n_tiles = tiles0 + tiles1;
     if ((int64_t)blockIdx.x >= row_tiles || n_tiles == 0) return;
     const int64_t my_rows = (row_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
@@ -232,35 +262,35 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     bool secondf = false;
     const char *abase = nullptr, *bbase = nullptr;
     uint32_t aoff[A_LOADS], boff[B_LOADS];
-    v4f ra[A_LOADS], rbv[B_LOADS];  // plain vector registers: a struct copy would go through private memory
+    v4i ra[A_LOADS], rbv[B_LOADS];  // plain vector registers: a struct copy would go through private memory
 
 #define LP_SET_PART(part)                                                                                              \
     {                                                                                                                  \
-        const float *A_ = static_cast<const float *>((part) ? g.A[1] : g.A[0]);                                        \
-        const int64_t lda_ = (part) ? g.lda[1] : g.lda[0];                                                             \
-        const int64_t ldb_ = (part) ? g.ldb[1] : g.ldb[0];                                                             \
-        const float *Bt_ = static_cast<const float *>(secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1])                     \
-                                                              : ((part) ? g.Bt[1][0] : g.Bt[0][0]));                   \
-        abase = reinterpret_cast<const char *>(A_ + m0f * lda_);                                                       \
-        bbase = reinterpret_cast<const char *>(Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_);               \
+        const char *A_ = static_cast<const char *>((part) ? g.A[1] : g.A[0]);                                          \
+        const int64_t lda_ = (int64_t)((part) ? g.lda[1] : g.lda[0]) * ES;                                             \
+        const int64_t ldb_ = (int64_t)((part) ? g.ldb[1] : g.ldb[0]) * ES;                                             \
+        const char *Bt_ = static_cast<const char *>(secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1])                       \
+                                                            : ((part) ? g.Bt[1][0] : g.Bt[0][0]));                     \
+        abase = A_ + m0f * lda_;                                                                                       \
+        bbase = Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_;                                               \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                        \
+            const int idx = p * TH + tid;                                                                              \
             int64_t r = idx / KQ;                                                                                      \
             r = m0f + r < g.M ? r : g.M - 1 - m0f;                                                                     \
-            aoff[p] = (uint32_t)((r * lda_ + ((idx % KQ) << 2)) * 4);                                                   \
+            aoff[p] = (uint32_t)(r * lda_ + ((idx % KQ) << 4));                                                        \
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                        \
+            const int idx = p * TH + tid;                                                                              \
             int64_t r = idx / KQ;                                                                                      \
             r = n0f + r < n_endf ? r : n_endf - 1 - n0f;                                                               \
-            boff[p] = (uint32_t)((r * ldb_ + ((idx % KQ) << 2)) * 4);                                                   \
+            boff[p] = (uint32_t)(r * ldb_ + ((idx % KQ) << 4));                                                        \
         }                                                                                                              \
     }
     // loads of the next K step in pipeline order (possibly the first step of the next output tile)
 #define LP_FETCH_NEXT()                                                                                                \
     if (fw < n_work) {                                                                                                 \
         if (ft == 0) {                                                                                                 \
-            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BMt;                                           \
+            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BMt;                                          \
             n0f = (int)(fw % col_tiles) * BN;                                                                          \
             secondf = n0f >= g.n_split;                                                                                \
             n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                              \
@@ -268,10 +298,10 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         } else if (ft == tiles0) {                                                                                     \
             LP_SET_PART(1)                                                                                             \
         }                                                                                                              \
-        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) ra[p] = *reinterpret_cast<const v4f *>(abase + aoff[p]);   \
-        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) rbv[p] = *reinterpret_cast<const v4f *>(bbase + boff[p]);  \
-        abase += KS * 4;                                                                                               \
-        bbase += KS * 4;                                                                                               \
+        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) ra[p] = *reinterpret_cast<const v4i *>(abase + aoff[p]);   \
+        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) rbv[p] = *reinterpret_cast<const v4i *>(bbase + boff[p]);  \
+        abase += KSB;                                                                                                  \
+        bbase += KSB;                                                                                                  \
         if (++ft == n_tiles) {                                                                                         \
             ft = 0;                                                                                                    \
             ++fw;                                                                                                      \
@@ -279,34 +309,30 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     }
 #define LP_STASH(stage)                                                                                                \
     {                                                                                                                  \
-        float *As_ = lds + (stage) * STAGE;                                                                            \
-        float *Bs_ = As_ + BMt * F_LD;                                                                                  \
+        char *As_ = lds + (stage) * STAGE;                                                                             \
+        char *Bs_ = As_ + BMt * ROWB;                                                                                  \
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                        \
-            *reinterpret_cast<v4f *>(&As_[(idx / KQ) * F_LD + ((idx % KQ) << 2)]) = ra[p];                              \
+            const int idx = p * TH + tid;                                                                              \
+            *reinterpret_cast<v4i *>(As_ + (idx / KQ) * ROWB + ((idx % KQ) << 4)) = ra[p];                             \
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                        \
-            *reinterpret_cast<v4f *>(&Bs_[(idx / KQ) * F_LD + ((idx % KQ) << 2)]) = rbv[p];                             \
+            const int idx = p * TH + tid;                                                                              \
+            *reinterpret_cast<v4i *>(Bs_ + (idx / KQ) * ROWB + ((idx % KQ) << 4)) = rbv[p];                            \
         }                                                                                                              \
     }
 #define LP_COMPUTE(stage, kk)                                                                                          \
     {                                                                                                                  \
-        const float *As_ = lds + (stage) * STAGE;                                                                      \
-        const float *Bs_ = As_ + BMt * F_LD;                                                                            \
-        v4f a[2], b[NB];                                                                                               \
+        const char *As_ = lds + (stage) * STAGE;                                                                       \
+        const char *Bs_ = As_ + BMt * ROWB;                                                                            \
+        v4i a[2], b[NB];                                                                                               \
         _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            a[rb] = *reinterpret_cast<const v4f *>(&As_[(wm * 64 + rb * 32 + i32) * F_LD + (kk) * 8 + 4 * h]);         \
+            a[rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);       \
         _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                              \
-            b[cb] = *reinterpret_cast<const v4f *>(&Bs_[(wn * WN + cb * 32 + i32) * F_LD + (kk) * 8 + 4 * h]);         \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].x, a[rb].x, acc[rb][cb]);     \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].y, a[rb].y, acc[rb][cb]);     \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].z, a[rb].z, acc[rb][cb]);     \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = mfma32(b[cb].w, a[rb].w, acc[rb][cb]);     \
+            b[cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);       \
+        /* k-major order: consecutive MFMAs write different accumulators */                                            \
+        _Pragma("unroll") for (int s_ = 0; s_ < NtElem<T>::STEPS; ++s_)                                                \
+            _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                           \
+                _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) NtElem<T>::mfma_step(acc[rb][cb], b[cb], a[rb], s_); \
     }
 
     LP_FETCH_NEXT()
@@ -318,24 +344,21 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     for (int64_t u = 0; u < n_steps; ++u) {
         const int cur = (int)(u & 1);
 #pragma unroll
-        for (int kk = 0; kk < KS / 16; ++kk) LP_COMPUTE(cur, kk)
+        for (int kk = 0; kk < KSB / 64; ++kk) LP_COMPUTE(cur, kk)
         if (u + 1 < n_steps) LP_STASH(cur ^ 1)  // registers hold step u+1
         LP_FETCH_NEXT()                         // step u+2
 #pragma unroll
-        for (int kk = KS / 16; kk < KS / 8; ++kk) LP_COMPUTE(cur, kk)
+        for (int kk = KSB / 64; kk < KSB / 32; ++kk) LP_COMPUTE(cur, kk)
         __syncthreads();
         if (++ct < n_tiles) continue;
         ct = 0;
-        // ---- this output tile is complete: store it.  The MFMAs were fed with the weight tile as the row operand, so
-        // each 32x32 accumulator block is the TRANSPOSE of the output block: lane (j = lane % 32, h = lane / 32)
-        // holds output row j and, in registers 4q..4q+3, the four consecutive columns 8q + 4h .. + 3.  Every lane
-        // therefore stores 16 contiguous bytes at a time and needs a single row scale.
+        // ---- this output tile is complete: store it (transposed accumulator blocks, see the head of this section)
         const int64_t m0 = ((int64_t)blockIdx.x + (cw / col_tiles) * gridDim.x) * BMt;
         const int n0 = (int)(cw % col_tiles) * BN;
         ++cw;
         const bool second = n0 >= g.n_split;
         const bool scaled = g.rowscale && second;
-        float *__restrict__ Cb = static_cast<float *>(second ? g.C[1] : g.C[0]);
+        T *__restrict__ Cb = static_cast<T *>(second ? g.C[1] : g.C[0]);
         const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
         const int ncol0 = (second ? n0 - g.n_split : n0) + wn * WN + 4 * h;
 #pragma unroll
@@ -343,7 +366,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
             const int64_t m = m0 + wm * 64 + rb * 32 + i32;
             const bool m_ok = m < g.M;
             const float rs = (scaled && m_ok) ? g.rowscale[m] : 1.f;
-            float *__restrict__ Crow = Cb + (m_ok ? m : 0) * ldc + ncol0;
+            T *__restrict__ Crow = Cb + (m_ok ? m : 0) * ldc + ncol0;
 #pragma unroll
             for (int cb = 0; cb < NB; ++cb)
 #pragma unroll
@@ -352,7 +375,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
                     const bool n_ok = n < g.N;
                     v4f bias = {0.f, 0.f, 0.f, 0.f};
                     if (g.bias && n_ok) bias = *reinterpret_cast<const v4f *>(g.bias + n);
-                    v4f y;
+                    float y[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         float t = acc[rb][cb][4 * q + e] + bias[e];
@@ -360,7 +383,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
                         y[e] = t * rs;
                         acc[rb][cb][4 * q + e] = 0.f;
                     }
-                    if (m_ok && n_ok) *reinterpret_cast<v4f *>(Crow + cb * 32 + 8 * q) = y;
+                    if (m_ok && n_ok) NtElem<T>::store4(Crow + cb * 32 + 8 * q, y);
                 }
         }
     }
@@ -376,8 +399,6 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 // 64 + 8 elements (144 bytes = 36 banks: eight consecutive rows start in eight different groups of four banks).
 // The weight tile is the row operand of the MFMA, so an accumulator block is the transposed output block and a
 // lane owns four consecutive columns of one output row: results are rounded to bfloat16 and stored 8 bytes at a time.
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int HK = 64;
 constexpr int H_LD = HK + 8;
 
@@ -831,38 +852,38 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
     if (a.dtype != LP_F32 && a.dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     LpTimedScope timed(LP_KC_GEMM_NT, st);
-    if (a.dtype == LP_BF16) {
-        if ((a.N & 3) || (a.n_split & 3) || (a.ldc[0] & 3) || (a.n_split < a.N && (a.ldc[1] & 3))) return LP_ERR_UNSUPPORTED;
-        const int bn = a.N > 128 ? 256 : (a.N > 64 ? 128 : 64);
-        const int64_t row_tiles8 = lp_ceil_div(lp_ceil_div(a.M, BM), 8) * 8;
-        const dim3 grid((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
-        if (bn == 256) hipLaunchKernelGGL((gemm_nt_bf16_kernel<4>), grid, dim3(kThreads), 0, st, a);
-        else if (bn == 128) hipLaunchKernelGGL((gemm_nt_bf16_kernel<2>), grid, dim3(kThreads), 0, st, a);
-        else hipLaunchKernelGGL((gemm_nt_bf16_kernel<1>), grid, dim3(kThreads), 0, st, a);
-        return lp_after_launch();
-    }
-    const int force_bn = 0;
-    const int no_fast = 0;
-    // fast path: K parts in whole steps, and no column tile straddling the output split
-    const int fast_bn = (a.N > 128 && force_bn != 128) ? 256 : 128;
-    const bool fast_ok = !no_fast && a.N > 64 && (a.K[0] % FK == 0) && (a.K[1] % FK == 0) && a.K[0] + a.K[1] > 0 &&
+    const bool bf16 = a.dtype == LP_BF16;
+    if (bf16 && ((a.N & 3) || (a.n_split & 3) || (a.ldc[0] & 3) || (a.n_split < a.N && (a.ldc[1] & 3)))) return LP_ERR_UNSUPPORTED;
+    // fast path: K parts in whole steps (64 bytes of a row, 128 for the widest tile), no column tile straddling the
+    // output split
+    const int es = lp_elem_bytes(a.dtype);
+    const int fast_bn = a.N > 128 ? 256 : 128;
+    const bool fast_ok = a.N > 64 && (a.K[0] * es % 64 == 0) && (a.K[1] * es % 64 == 0) && a.K[0] + a.K[1] > 0 &&
                          (a.n_split >= a.N || a.n_split % fast_bn == 0);
     auto grid_for = [&](int bn) {
         const int64_t row_tiles8 = lp_ceil_div(lp_ceil_div(a.M, BM), 8) * 8;
         return dim3((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
     };
     if (fast_ok) {
-        // persistent workgroups filling every compute unit
-        // widest tile (256 x 256, eight wavefronts, K step 32, one workgroup per compute unit) when K allows
-        const bool big = fast_bn == 256 && (a.K[0] % 32 == 0) && (a.K[1] % 32 == 0) && a.M >= 4096;
+        // persistent workgroups filling every compute unit; the widest tile (256 x 256, eight wavefronts, 128-byte
+        // K step, one workgroup per compute unit) when K allows
+        const bool big = fast_bn == 256 && (a.K[0] * es % 128 == 0) && (a.K[1] * es % 128 == 0) && a.M >= 4096;
         const int bm = big ? 256 : 128;
         const int64_t row_tiles = lp_ceil_div(a.M, bm);
         const int64_t slots = (big ? 1 : 2) * (int64_t)lp_compute_units();
         const dim3 pgrid((unsigned)(row_tiles < slots ? row_tiles : slots));
-        if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<4, 4, 32>), pgrid, dim3(512), 0, st, a);
-        else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<4, 2, 16>), pgrid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((gemm_nt_fast_kernel<2, 2, 16>), pgrid, dim3(256), 0, st, a);
-    } else if (a.N > 128 && force_bn != 128) {
+#define LP_NT_FAST(T)                                                                                          \
+        if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 4, 128>), pgrid, dim3(512), 0, st, a);           \
+        else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 2, 64>), pgrid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64>), pgrid, dim3(256), 0, st, a);
+        if (bf16) { LP_NT_FAST(lp_bf16_t) } else { LP_NT_FAST(float) }
+#undef LP_NT_FAST
+    } else if (bf16) {
+        const int bn = a.N > 128 ? 256 : (a.N > 64 ? 128 : 64);
+        if (bn == 256) hipLaunchKernelGGL((gemm_nt_bf16_kernel<4>), grid_for(256), dim3(kThreads), 0, st, a);
+        else if (bn == 128) hipLaunchKernelGGL((gemm_nt_bf16_kernel<2>), grid_for(128), dim3(kThreads), 0, st, a);
+        else hipLaunchKernelGGL((gemm_nt_bf16_kernel<1>), grid_for(64), dim3(kThreads), 0, st, a);
+    } else if (a.N > 128) {
         hipLaunchKernelGGL((gemm_nt_kernel<4>), grid_for(256), dim3(kThreads), 0, st, a);
     } else if (a.N > 64) {
         hipLaunchKernelGGL((gemm_nt_kernel<2>), grid_for(128), dim3(kThreads), 0, st, a);
