@@ -34,14 +34,25 @@ def spmm_bytes(n, nnz, F, backward, eb=4):
     return b + (2 * n * eb * F if backward else n * 4)
 
 
-def step_counts(n, nnz, dims, eb=4):
-    """(spmm algorithmic bytes, NT flops, TN flops) of one step."""
+def spmm_bytes_listed(n, nnz, F, n_t, nnz_t, eb=4):
+    """The transposed aggregation of the last layer: its input has rows only for the n_t nodes that are an endpoint
+    of a scored edge, so of the nnz entries only the nnz_t that point at such a node gather a row; every entry still
+    reads its column id and its 4-byte slot of the node -> row table."""
+    return nnz * 8 + nnz_t * eb * F + (n + 1) * 4 + n * 4 + 2 * n * eb * F + n_t * eb * F
+
+
+def step_counts(n, nnz, dims, n_t, nnz_t, eb=4):
+    """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer's backward products run over the
+    n_t endpoint rows only (every other row of dL/dH^K is exactly zero)."""
     K = len(dims) - 1
     sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K + 1))
-    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K + 1))
-    nt = sum(2.0 * n * dims[k] * 2 * dims[k - 1] for k in range(1, K + 1))          # forward
-    nt += sum(2.0 * n * 2 * dims[k - 1] * dims[k] for k in range(2, K + 1))         # input gradients
-    tn = sum(2.0 * 2 * n * dims[k - 1] * dims[k] for k in range(1, K + 1))          # dW_self, dW_neigh
+    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K))
+    if K >= 2:
+        sp += spmm_bytes_listed(n, nnz, dims[K - 1], n_t, nnz_t, eb)
+    rows = lambda k: n_t if k == K else n
+    nt = sum(2.0 * n * dims[k] * 2 * dims[k - 1] for k in range(1, K + 1))                # forward
+    nt += sum(2.0 * rows(k) * 2 * dims[k - 1] * dims[k] for k in range(2, K + 1))         # input gradients
+    tn = sum(2.0 * 2 * rows(k) * dims[k - 1] * dims[k] for k in range(1, K + 1))          # dW_self, dW_neigh
     return sp, nt, tn
 
 
@@ -163,8 +174,19 @@ def main():
     loss_val = float(loss.item())
     ms_per_step = dt * 1e3 / max(args.steps, 1)
 
+    # accounting only (outside the timed region): how many nodes are an endpoint of a scored edge in the timed steps,
+    # and how many CSR entries point at one of them
+    deg = (g.rowptr[1:] - g.rowptr[:-1]).to(torch.int64)
+    n_t_sum = nnz_t_sum = 0
+    for i in range(args.steps):
+        lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, 2000 + i, neg_dst=neg_dst, neg_src=neg_src)
+        touched = torch.unique(torch.cat([e_src, e_dst]).to(torch.int64))
+        n_t_sum += int(touched.numel())
+        nnz_t_sum += int(deg[touched].sum().item())
+    n_t, nnz_t = n_t_sum / max(args.steps, 1), nnz_t_sum / max(args.steps, 1)
+
     n, nnz = wl.n_nodes, g.nnz
-    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, 2 if bf16 else 4)
+    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, n_t, nnz_t, 2 if bf16 else 4)
     per_step = {k: (ms / max(args.steps, 1), cnt // max(args.steps, 1)) for k, (ms, cnt) in classes.items()}
 
     def hbm_line(cls, bytes_per_step):
@@ -216,7 +238,8 @@ def main():
         "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, GraphSAGE-mean %s, "
                                "%d positives + %d uniform negatives per step, full-neighbour aggregation"
                                % (args.workload, n, nnz, "->".join(map(str, wl.dims)), n_pos, n_pos * k_neg),
-                   "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg},
+                   "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg,
+                   "batch_endpoint_nodes": round(n_t, 1)},
         "loss": round(loss_val, 6),
         "csr_build": {"seconds": round(build_s, 5), "input_edges_per_s": round(wl.src.size / build_s, 1)},
         "roofline": lines[dominant],

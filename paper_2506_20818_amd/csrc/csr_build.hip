@@ -323,6 +323,32 @@ int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t
     return lp_after_launch();
 }
 
+__global__ void compact_tail_kernel(const int32_t *__restrict__ offsets, int32_t n_rows, const int32_t *__restrict__ count,
+                                    int32_t *__restrict__ ptr) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) ptr[*count] = offsets[n_rows];
+}
+
+size_t lp_compact_rows_ws_bytes(int32_t n_rows) {
+    return lp_align_up(sizeof(uint32_t) * (size_t)(lp_ceil_div((int64_t)(n_rows > 0 ? n_rows : 1), kTile) + 8));
+}
+
+int lp_launch_compact_rows(const int32_t *offsets, int32_t n_rows, int32_t *list, int32_t *index, int32_t *ptr,
+                           int32_t *count_dev, void *scan_ws, hipStream_t st) {
+    if (n_rows <= 0) return LP_OK;
+    auto occupied = [offsets] __device__(int64_t v) { return (uint32_t)(offsets[v + 1] > offsets[v]); };
+    auto emit = [offsets, list, index, ptr] __device__(int64_t v, uint32_t pos, uint32_t flag) {
+        index[v] = flag ? (int32_t)pos : -1;
+        if (flag) {
+            list[pos] = (int32_t)v;
+            ptr[pos] = offsets[v];
+        }
+    };
+    LP_TRY(device_exclusive_scan(occupied, emit, (int64_t)n_rows, static_cast<uint32_t *>(scan_ws),
+                                 reinterpret_cast<uint32_t *>(count_dev), st));
+    hipLaunchKernelGGL(compact_tail_kernel, dim3(1), dim3(64), 0, st, offsets, n_rows, count_dev, ptr);
+    return lp_after_launch();
+}
+
 extern "C" size_t lp_build_csr_workspace_bytes(int32_t n_nodes, int64_t n_in, uint32_t flags) {
     if (n_nodes <= 0 || n_in < 0) return 0;
     return carve(nullptr, n_nodes, n_in, flags).bytes;

@@ -38,12 +38,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
+    const int M_ = g.m_dev ? min(*g.m_dev, g.M) : g.M;  // rows actually present
     // Workgroups are handed to the eight XCDs round-robin by linear id.  The column tiles of one row tile get ids
     // that are 8 apart, so they run on the same XCD back to back and the second one finds the A rows in that L2.
     const int col_tiles = (g.N + BN - 1) / BN;
     const int slot = blockIdx.x >> 3;
     const int64_t row_tile = (int64_t)(slot / col_tiles) * 8 + (blockIdx.x & 7);
-    if (row_tile * BM >= g.M) return;
+    if (row_tile * BM >= M_) return;
     const int64_t m0 = row_tile * BM;
     const int n0 = (slot % col_tiles) * BN;
     const int tiles0 = (g.K[0] + BK - 1) / BK, tiles1 = (g.K[1] + BK - 1) / BK;
@@ -73,8 +74,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             const int idx = p * kThreads + tid;
             const int row = idx >> 3, k = k0 + ((idx & 7) << 2);
             const int64_t m = m0 + row;
-            const bool ok = m < g.M && k < K;
-            const float4 v = *reinterpret_cast<const float4 *>(A + (m < g.M ? m : g.M - 1) * lda + (k < K ? k : K - 4));
+            const bool ok = m < M_ && k < K;
+            const float4 v = *reinterpret_cast<const float4 *>(A + (m < M_ ? m : M_ - 1) * lda + (k < K ? k : K - 4));
             ra[p] = make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
         }
 #pragma unroll
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                rs[rb][r] = g.rowscale[m < g.M ? m : g.M - 1];
+                { const int64_t mm = m < M_ ? m : M_ - 1; rs[rb][r] = g.rowscale[g.rowscale_index ? g.rowscale_index[mm] : mm]; }
             }
     }
 #pragma unroll
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 float y = acc[rb][cb][r] + bias;
                 if (g.relu) y = fmaxf(y, 0.f);
                 y *= second ? rs[rb][r] : 1.f;
-                if (n_ok && m < g.M) C[m * ldc] = y;
+                if (n_ok && m < M_) C[m * ldc] = y;
             }
     }
 }
@@ -237,8 +238,9 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
+    const int M_ = g.m_dev ? min(*g.m_dev, g.M) : g.M;  // rows actually present
     const int col_tiles = (g.N + BN - 1) / BN;
-    const int64_t row_tiles = ((int64_t)g.M + BMt - 1) / BMt;
+    const int64_t row_tiles = ((int64_t)M_ + BMt - 1) / BMt;
     const int tiles0 = g.K[0] * ES / KSB, tiles1 = g.K[1] * ES / KSB;
     const int n_tiles = tiles0 + tiles1;
     if ((int64_t)blockIdx.x >= row_tiles || n_tiles == 0) return;
@@ -276,7 +278,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
             const int idx = p * TH + tid;                                                                              \
             int64_t r = idx / KQ;                                                                                      \
-            r = m0f + r < g.M ? r : g.M - 1 - m0f;                                                                     \
+            r = m0f + r < M_ ? r : M_ - 1 - m0f;                                                                     \
             aoff[p] = (uint32_t)(r * lda_ + ((idx % KQ) << 4));                                                        \
         }                                                                                                              \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
@@ -364,8 +366,8 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             const int64_t m = m0 + wm * 64 + rb * 32 + i32;
-            const bool m_ok = m < g.M;
-            const float rs = (scaled && m_ok) ? g.rowscale[m] : 1.f;
+            const bool m_ok = m < M_;
+            const float rs = (scaled && m_ok) ? g.rowscale[g.rowscale_index ? g.rowscale_index[m] : m] : 1.f;
             T *__restrict__ Crow = Cb + (m_ok ? m : 0) * ldc + ncol0;
 #pragma unroll
             for (int cb = 0; cb < NB; ++cb)
@@ -414,10 +416,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
+    const int M_ = g.m_dev ? min(*g.m_dev, g.M) : g.M;  // rows actually present
     const int col_tiles = (g.N + BN - 1) / BN;
     const int slot = blockIdx.x >> 3;
     const int64_t row_tile = (int64_t)(slot / col_tiles) * 8 + (blockIdx.x & 7);
-    if (row_tile * BM >= g.M) return;
+    if (row_tile * BM >= M_) return;
     const int64_t m0 = row_tile * BM;
     const int n0 = (slot % col_tiles) * BN;
     const int tiles0 = (g.K[0] + HK - 1) / HK, tiles1 = (g.K[1] + HK - 1) / HK;
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 const int idx = p * kThreads + tid;
                 const int k = k0 + ((idx & 7) << 3);
                 int64_t m = m0 + (idx >> 3);
-                m = m < g.M ? m : g.M - 1;  // rows past the edge only feed outputs that are never stored
+                m = m < M_ ? m : M_ - 1;  // rows past the edge only feed outputs that are never stored
                 const v4i v = *reinterpret_cast<const v4i *>(A + m * lda + (k < K ? k : K - 8));
                 ra[p] = k < K ? v : zero;
             }
@@ -500,8 +503,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
         const int64_t m = m0 + wm * 64 + rb * 32 + i32;
-        const bool m_ok = m < g.M;
-        const float rs_row = (g.rowscale && m_ok) ? g.rowscale[m] : 1.f;
+        const bool m_ok = m < M_;
+        const float rs_row = (g.rowscale && m_ok) ? g.rowscale[g.rowscale_index ? g.rowscale_index[m] : m] : 1.f;
 #pragma unroll
         for (int cb = 0; cb < NB; ++cb)
 #pragma unroll
@@ -542,8 +545,13 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
     const int i32 = lane & 31, h = lane >> 5;
     const int tiles_n = (g.Nw + TNn - 1) / TNn;
     const int m0 = (blockIdx.x / tiles_n) * TM, n0 = (blockIdx.x % tiles_n) * TNn;
+    int64_t Kn_ = g.Kn;
+    if (g.kn_dev) {  // reduction length read on the device: share what is really there evenly among the splits
+        Kn_ = min((int64_t)*g.kn_dev, (int64_t)g.Kn);
+        chunk = (int)(((Kn_ + gridDim.y - 1) / gridDim.y + BK - 1) / BK * BK);
+    }
     const int64_t kbeg = (int64_t)blockIdx.y * chunk;
-    const int64_t kend = kbeg + chunk < g.Kn ? kbeg + chunk : g.Kn;
+    const int64_t kend = kbeg + chunk < Kn_ ? kbeg + chunk : Kn_;
     const T *__restrict__ At = static_cast<const T *>(g.At);
     const T *__restrict__ Bm = static_cast<const T *>(g.B);
 
@@ -558,6 +566,14 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
     constexpr int A_LOADS = BK * TM / VE / kThreads;
     constexpr int B_LOADS = BK * TNn / VE / kThreads;
     float ra[A_LOADS][VE], rbv[B_LOADS][VE];
+    int64_t arow[A_LOADS];  // rows of At for the next fetch, looked up one step ahead so that a fetch is one round trip
+    auto lookup = [&](int64_t k0) {
+#pragma unroll
+        for (int p = 0; p < A_LOADS; ++p) {
+            const int64_t k = k0 + (p * kThreads + tid) / (TM / VE);
+            arow[p] = (g.at_index && k < kend) ? (int64_t)g.at_index[k] : k;
+        }
+    };
     auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
@@ -566,7 +582,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
             const int64_t k = k0 + kr;
 #pragma unroll
             for (int e = 0; e < VE; ++e) ra[p][e] = 0.f;
-            if (k < kend && m0 + c < g.Mw) LpVec<T>::load(At + k * g.lda + m0 + c, ra[p]);
+            if (k < kend && m0 + c < g.Mw) LpVec<T>::load(At + arow[p] * g.lda + m0 + c, ra[p]);
         }
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
@@ -577,6 +593,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
             for (int e = 0; e < VE; ++e) rbv[p][e] = 0.f;
             if (k < kend && n0 + c < g.Nw) LpVec<T>::load(Bm + k * g.ldb + n0 + c, rbv[p]);
         }
+        lookup(k0 + BK);
     };
     auto stash = [&]() {
 #pragma unroll
@@ -595,6 +612,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmTnArgs g, int chu
         }
     };
 
+    lookup(kbeg);
     if (kbeg < kend) fetch(kbeg);
     for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();
@@ -657,8 +675,13 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_bf16_kernel(GemmTnArgs g, in
     const int split = (slot / tiles) * 8 + xcd;
     if (split >= splits) return;
     const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TNn;
+    int64_t Kn_ = g.Kn;
+    if (g.kn_dev) {  // reduction length read on the device: share what is really there evenly among the splits
+        Kn_ = min((int64_t)*g.kn_dev, (int64_t)g.Kn);
+        chunk = (int)(((Kn_ + splits - 1) / splits + TK - 1) / TK * TK);
+    }
     const int64_t kbeg = (int64_t)split * chunk;
-    const int64_t kend = kbeg + chunk < g.Kn ? kbeg + chunk : g.Kn;
+    const int64_t kend = kbeg + chunk < Kn_ ? kbeg + chunk : Kn_;
 
     // loader task of this thread: threads [0, TM) serve At, threads [TM, TM + TNn) serve B
     const bool loads_a = tid < TM;
@@ -667,6 +690,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_bf16_kernel(GemmTnArgs g, in
     const int q = task & 7, c = task >> 3;                       // node chunk (8 nodes), column chunk (8 columns)
     const lp_bf16_t *__restrict__ src = static_cast<const lp_bf16_t *>(loads_a ? g.At : g.B);
     const int64_t ld = loads_a ? g.lda : g.ldb;
+    const int32_t *__restrict__ row_of = loads_a ? g.at_index : nullptr;
     const int col = (loads_a ? m0 : n0) + 8 * c;
     const bool col_ok = has_task && col < (loads_a ? g.Mw : g.Nw);
     lp_bf16_t *__restrict__ dst = (loads_a ? As : Bs) + (8 * c) * T_LD + 8 * q;
@@ -681,13 +705,22 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_bf16_kernel(GemmTnArgs g, in
 
     v4i rows[8];
     const v4i zero = {0, 0, 0, 0};
+    int64_t srow[8];  // source rows of the next fetch, looked up one step ahead so that a fetch is one round trip
+    auto lookup = [&](int64_t k0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t k = k0 + 8 * q + e;
+            srow[e] = (row_of && col_ok && k < kend) ? (int64_t)row_of[k] : k;
+        }
+    };
     auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int64_t k = k0 + 8 * q + e;
             rows[e] = zero;
-            if (col_ok && k < kend) rows[e] = *reinterpret_cast<const v4i *>(src + k * ld + col);
+            if (col_ok && k < kend) rows[e] = *reinterpret_cast<const v4i *>(src + srow[e] * ld + col);
         }
+        lookup(k0 + TK);
     };
     auto stash = [&]() {
         if (!has_task) return;
@@ -702,6 +735,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_bf16_kernel(GemmTnArgs g, in
         }
     };
 
+    lookup(kbeg);
     if (kbeg < kend) fetch(kbeg);
     for (int64_t k0 = kbeg; k0 < kend; k0 += TK) {
         __syncthreads();
@@ -777,7 +811,8 @@ constexpr int kColsumRows = 256;  // rows folded by one workgroup
 // Workgroup: 64 column vectors (16 bytes each) x 4 row lanes; grid (column groups, row chunks).
 template <typename T>
 __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const T *__restrict__ in, int64_t M, int64_t NV,
-                                                                  float *__restrict__ partials) {
+                                                                  float *__restrict__ partials, const int32_t *__restrict__ m_dev) {
+    if (m_dev) M = *m_dev < M ? *m_dev : M;  // rows actually present
     constexpr int VE = LpVec<T>::N;
     __shared__ float red[4][64][VE];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -949,7 +984,8 @@ size_t lp_colsum_partials_bytes(int64_t M, int64_t N) {
     return 2 * lp_align_up(sizeof(float) * (size_t)chunks * (size_t)(N > 0 ? N : 1));
 }
 
-int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t st) {
+int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t st,
+                     const int32_t *m_dev) {
     if (N <= 0) return LP_OK;
     if (N % lp_vec_elems(dtype)) return LP_ERR_UNSUPPORTED;
     if (M <= 0) return lp_launch_zero(out, N, st);
@@ -965,9 +1001,11 @@ int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out
         const int64_t NV = N / lp_vec_elems(src_dtype);
         const dim3 grid((unsigned)lp_ceil_div(NV, 64), (unsigned)chunks);
         if (src_dtype == LP_BF16)
-            hipLaunchKernelGGL((colsum_partial_kernel<lp_bf16_t>), grid, dim3(kThreads), 0, st, static_cast<const lp_bf16_t *>(src), rows, NV, dst);
+            hipLaunchKernelGGL((colsum_partial_kernel<lp_bf16_t>), grid, dim3(kThreads), 0, st, static_cast<const lp_bf16_t *>(src), rows, NV, dst,
+                               level == 0 ? m_dev : nullptr);
         else
-            hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(kThreads), 0, st, static_cast<const float *>(src), rows, NV, dst);
+            hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, dim3(kThreads), 0, st, static_cast<const float *>(src), rows, NV, dst,
+                               level == 0 ? m_dev : nullptr);
         if (chunks == 1) break;
         src = dst;
         src_dtype = LP_F32;  // the partial sums are fp32

@@ -43,6 +43,8 @@ private:
 // out[v, :] = rowscale(v) * sum_{p in row v} w[p] * in[colidx[p], :]  (+ addend[v, :])  (* [gate[v, :] > 0])
 //   w[p] = 1 when w == nullptr
 //   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1
+// With `in_index`, `in` and `addend` hold only some rows: node u lives in row in_index[u], and a negative entry
+// stands for an all-zero row.  With `n_rows_dev` the number of output rows is read on the device (at most n_rows).
 // All matrices are [n_rows, F] in the storage type `dtype` with contiguous rows; F is a multiple of 4 (fp32) or 8 (bf16).
 struct SpmmArgs {
     int32_t dtype = LP_F32;              // storage of in, addend, gate and out
@@ -55,6 +57,8 @@ struct SpmmArgs {
     const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
     const void *in = nullptr;
     const void *addend = nullptr;        // optional [n_rows, F]
+    const int32_t *in_index = nullptr;   // optional [number of nodes]: row of `in` / `addend` that holds a node, or < 0
+    const int32_t *n_rows_dev = nullptr; // optional device scalar: rows actually present (<= n_rows)
     const void *gate = nullptr;          // optional [n_rows, F]: output is zeroed where gate <= 0
     void *out = nullptr;
     int64_t n_entries = 0;               // entries of colidx (bounds how many rows can be long)
@@ -86,6 +90,8 @@ struct GemmNtArgs {
     const float *bias = nullptr;
     bool relu = false;
     const float *rowscale = nullptr;
+    const int32_t *rowscale_index = nullptr;  // optional [M]: row m is scaled by rowscale[rowscale_index[m]]
+    const int32_t *m_dev = nullptr;           // optional device scalar: rows actually present (<= M)
     void *C[2] = {nullptr, nullptr};
     int32_t ldc[2] = {0, 0};
 };
@@ -100,6 +106,8 @@ struct GemmTnArgs {
     int32_t Mw = 0, Nw = 0;              // output shape
     const void *At = nullptr;            // [Kn, Mw], leading dimension lda
     int32_t lda = 0;
+    const int32_t *at_index = nullptr;   // optional [Kn]: reduction step k reads row at_index[k] of At (B stays direct)
+    const int32_t *kn_dev = nullptr;     // optional device scalar: reduction length actually present (<= Kn)
     const void *B = nullptr;             // [Kn, Nw], leading dimension ldb
     int32_t ldb = 0;
     float *C = nullptr;                  // [Mw, Nw] contiguous
@@ -113,7 +121,8 @@ int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, i
 // out[n] = sum_m in[m, n] for a contiguous [M, N] matrix stored as `dtype` (N a multiple of its vector width);
 // fp32 sums in a fixed order; partials: lp_colsum_partials_bytes()
 size_t lp_colsum_partials_bytes(int64_t M, int64_t N);
-int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t stream);
+int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out, float *partials, hipStream_t stream,
+                     const int32_t *m_dev = nullptr);  // m_dev: optional device scalar, rows actually present (<= M)
 // fill n floats with zero (a kernel, so that callers may capture it); n floats = 2n bfloat16
 int lp_launch_zero(float *p, int64_t n, hipStream_t stream);
 
@@ -129,6 +138,13 @@ uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int 
 int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,
                           int32_t *offsets, hipStream_t stream);
 int lp_bits_for(int64_t n_values);
+// Rows of a CSR row-pointer array that are not empty: list[i] = i-th such row (ascending), index[v] = position of
+// row v in the list or -1, ptr[i] = offsets[list[i]] for i < count and ptr[count] = offsets[n_rows], *count_dev =
+// their number.  list and ptr have room for cap + 1 entries, where the caller guarantees count <= cap;
+// scan_ws: lp_compact_rows_ws_bytes(n_rows).
+size_t lp_compact_rows_ws_bytes(int32_t n_rows);
+int lp_launch_compact_rows(const int32_t *offsets, int32_t n_rows, int32_t *list, int32_t *index, int32_t *ptr,
+                           int32_t *count_dev, void *scan_ws, hipStream_t stream);
 
 // ---------------------------------------------------------------- storage types
 // LP_F32 matrices hold floats; LP_BF16 matrices hold raw bfloat16 bit patterns (uint16_t).  All arithmetic is fp32.

@@ -84,8 +84,16 @@ struct BackwardWs {
     int32_t *bptr, *bcol;
     float *bw;
     int32_t *long_queue;
+    int32_t *touched, *touched_index, *touched_ptr, *n_touched;  // rows of dL/dH^K that receive anything
+    void *compact_ws;
     size_t bytes;
 };
+
+// At most this many nodes can be an endpoint of one of B scored edges.
+int32_t touched_cap(int32_t n_nodes, int64_t B) {
+    const int64_t two_b = 2 * (B > 0 ? B : 0);
+    return (int32_t)(two_b < n_nodes ? two_b : n_nodes);
+}
 
 BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t B) {
     char *p = static_cast<char *>(ws);
@@ -111,6 +119,12 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
     w.bcol = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * n2));
     w.bw = take(sizeof(float) * n2);
     w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(n_nodes)));
+    const size_t cap = (size_t)touched_cap(n_nodes, B);
+    w.touched = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (cap + 1)));
+    w.touched_index = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (size_t)n_nodes));
+    w.touched_ptr = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (cap + 1)));
+    w.n_touched = reinterpret_cast<int32_t *>(take(256));
+    w.compact_ws = take(lp_compact_rows_ws_bytes(n_nodes));
     w.bytes = off;
     return w;
 }
@@ -205,9 +219,22 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     const int dt = m->dtype;
     void *dZ = w.buf[0], *Q = w.buf[1], *R = w.buf[2];
     const void *HK = saved->H[K - 1];
-    if (B == 0) {
-        LP_TRY(lp_launch_zero(static_cast<float *>(dZ), (int64_t)N * m->dims[K] * lp_elem_bytes(dt) / 4, st));
-    } else {
+    if (B == 0) {  // an empty batch has a zero loss: every gradient is zero
+        for (int k = 0; k < K; ++k) {
+            const int64_t nw = (int64_t)m->dims[k] * m->dims[k + 1];
+            LP_TRY(lp_launch_zero(out->dW_self[k], nw, st));
+            LP_TRY(lp_launch_zero(out->dW_neigh[k], nw, st));
+            LP_TRY(lp_launch_zero(out->dbias[k], m->dims[k + 1], st));
+        }
+        if (out->dX) LP_TRY(lp_launch_zero(static_cast<float *>(out->dX), (int64_t)N * m->dims[0] * lp_elem_bytes(dt) / 4, st));
+        return LP_OK;
+    }
+
+    // dL/dH^K is non-zero only on rows that are an endpoint of a scored edge.  Those rows are listed (ascending) and
+    // the whole last layer works on that list: its gradient matrix, both weight-gradient products and the input-
+    // gradient product have one row per listed node, and only the aggregation that follows widens back to all nodes.
+    const int32_t cap = touched_cap(N, B);
+    {
         const int64_t n2 = 2 * B;
         const unsigned g2 = (unsigned)lp_ceil_div(n2, 256);
         const uint64_t *sorted;
@@ -220,11 +247,12 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
             LP_TRY(lp_launch_row_offsets(sorted, n2, nullptr, N, 32, w.bptr, st));
             hipLaunchKernelGGL(batch_entries_kernel, dim3(g2), dim3(256), 0, st, sorted, B, e_src, e_dst, dscore, N, w.bcol, w.bw);
             LP_TRY(lp_after_launch());
+            LP_TRY(lp_launch_compact_rows(w.bptr, N, w.touched, w.touched_index, w.touched_ptr, w.n_touched, w.compact_ws, st));
         }
         SpmmArgs sc;
         sc.dtype = dt;
-        sc.n_rows = N; sc.F = m->dims[K];
-        sc.rowptr = w.bptr; sc.colidx = w.bcol; sc.w = w.bw;
+        sc.n_rows = cap; sc.n_rows_dev = w.n_touched; sc.F = m->dims[K];
+        sc.rowptr = w.touched_ptr; sc.colidx = w.bcol; sc.w = w.bw;
         sc.n_entries = n2; sc.long_queue = w.long_queue;
         sc.in = HK; sc.out = dZ;
         sc.timing_class = LP_KC_SCATTER;
@@ -235,10 +263,15 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
         const void *Hin = k > 1 ? saved->H[k - 2] : X;
         const void *Ak = saved->A[k - 1];
-        LP_TRY(lp_launch_colsum(dZ, dt, N, Fo, out->dbias[k - 1], w.colsum_partials, st));
+        const bool listed = k == K;               // dZ holds one row per listed node instead of one per node
+        const int32_t rows = listed ? cap : N;    // host-side bound; the exact count is read on the device
+        const int32_t *rows_dev = listed ? w.n_touched : nullptr;
+        const int32_t *row_of = listed ? w.touched : nullptr;
+        LP_TRY(lp_launch_colsum(dZ, dt, rows, Fo, out->dbias[k - 1], w.colsum_partials, st, rows_dev));
         GemmTnArgs tn;
         tn.dtype = dt;
-        tn.Kn = N; tn.Mw = Fi; tn.Nw = Fo;
+        tn.Kn = rows; tn.kn_dev = rows_dev; tn.at_index = row_of;
+        tn.Mw = Fi; tn.Nw = Fo;
         tn.B = dZ; tn.ldb = Fo;
         tn.partials = w.tn_partials;
         tn.At = Hin; tn.lda = Fi; tn.C = out->dW_self[k - 1];
@@ -249,12 +282,13 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         // [dZ W_self^T | diag(inv_deg) dZ W_neigh^T] -> Q, R
         GemmNtArgs ge;
         ge.dtype = dt;
-        ge.M = N; ge.N = 2 * Fi; ge.n_split = Fi;
+        ge.M = rows; ge.m_dev = rows_dev;
+        ge.N = 2 * Fi; ge.n_split = Fi;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
         ge.Bt[0][0] = m->W_self[k - 1];
         ge.Bt[0][1] = m->W_neigh[k - 1];
         ge.ldb[0] = Fo;
-        ge.rowscale = g->inv_deg;
+        ge.rowscale = g->inv_deg; ge.rowscale_index = row_of;
         ge.C[0] = Q; ge.C[1] = R;
         ge.ldc[0] = ge.ldc[1] = Fi;
         LP_TRY(lp_launch_gemm_nt(ge, st));
@@ -265,11 +299,17 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
         sp.n_entries = g->nnz; sp.long_queue = w.long_queue;
         sp.in = R; sp.addend = Q;
+        sp.in_index = listed ? w.touched_index : nullptr;
         sp.gate = k > 1 ? Hin : nullptr;
-        sp.out = k > 1 ? Q : static_cast<void *>(out->dX);
-        sp.dtype = dt;
-        LP_TRY(lp_launch_spmm(sp, st));
-        void *t = dZ; dZ = Q; Q = t;
+        if (listed) {
+            // Q and R hold listed rows only; the result has every row and replaces the (finished) listed dZ
+            sp.out = k > 1 ? dZ : static_cast<void *>(out->dX);
+            LP_TRY(lp_launch_spmm(sp, st));
+        } else {
+            sp.out = k > 1 ? Q : static_cast<void *>(out->dX);
+            LP_TRY(lp_launch_spmm(sp, st));
+            void *t = dZ; dZ = Q; Q = t;
+        }
     }
     return LP_OK;
 }

@@ -37,7 +37,8 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
     const bool lane_on = fl < FV;      // F/VE need not be a power of two
     for (int32_t base = first; base < hi; base += stride) {
         const int cnt = min(64, hi - base);
-        const int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
+        int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
+        if (a.in_index) mine = lane < cnt ? a.in_index[mine] : -1;  // row of `in` that holds the neighbour, < 0: a zero row
         float mine_w = 1.f;
         if (W) mine_w = lane < cnt ? a.w[base + lane] : 0.f;
         for (int j0 = 0; j0 < cnt; j0 += P * U) {
@@ -48,7 +49,7 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
                 const int j = j0 + u * P + sub;
                 const int32_t nb = __shfl(mine, j & 63, 64);
                 wj[u] = W ? __shfl(mine_w, j & 63, 64) : 1.f;
-                const bool on = lane_on && j < cnt;
+                const bool on = lane_on && j < cnt && nb >= 0;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
 #pragma unroll
@@ -90,10 +91,13 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
 #pragma unroll
     for (int e = 0; e < VE; ++e) y[e] = sum[e] * scale;
     if (a.addend) {
-        float t[VE];
-        LpVec<T>::load(static_cast<const T *>(a.addend) + o, t);
+        const int32_t ar = a.in_index ? a.in_index[v] : v;
+        if (ar >= 0) {
+            float t[VE];
+            LpVec<T>::load(static_cast<const T *>(a.addend) + ((int64_t)ar * FV + colv) * VE, t);
 #pragma unroll
-        for (int e = 0; e < VE; ++e) y[e] += t[e];
+            for (int e = 0; e < VE; ++e) y[e] += t[e];
+        }
     }
     if (a.gate) {
         float gt[VE];
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (r >= a.n_rows) return;
+    if (r >= a.n_rows || (a.n_rows_dev && r >= *a.n_rows_dev)) return;
     const int32_t v = a.row_order ? a.row_order[r] : (int32_t)r;
     const int sub = lane / G, fl = lane % G;
     const int FV = a.F / VE;
