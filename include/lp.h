@@ -197,6 +197,39 @@ int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts
                 size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * lp_sparsify - the degree-based graph sparsifier (Algorithm 1, "Graph
+ * Sparsification"; Sec. IV-B, second paragraph; Theorems 1 and 2): n_draws edges
+ * are drawn independently and with replacement from one partition's edge list,
+ * edge (u, v) with probability p proportional to 1/d_u + 1/d_v, where d is the
+ * number of listed edges at a node; a drawn edge carries weight 1/(n_draws p)
+ * and repeated draws add up.  Done once per partition, before training.
+ *
+ * So that every implementation draws the same edges, all decisions are taken
+ * on integers: q_e = floor(2^32/d_u) + floor(2^32/d_v), Q = sum of q_e,
+ * p_e = q_e/Q; draw l forms r = word0 * 2^32 + word1 of Philox4x32-10 with
+ * counter (l_lo, l_hi, 0, 0) and key (seed_lo, seed_hi), t = floor(r Q / 2^64),
+ * and takes the edge e with cum_e <= t < cum_e + q_e (cum = running sum of q in
+ * input order).
+ *
+ * eu, ev: device [n_edges], the undirected edges, each listed once, no
+ * self-pairs (an edge listed twice counts twice towards the degrees and can be
+ * drawn under either index).  Outputs (device), each with room for
+ * min(n_edges, n_draws) entries: kept_edge = indices of the distinct drawn
+ * edges, ascending; kept_u / kept_v (may be NULL) = their end points as listed;
+ * kept_count (may be NULL) = times drawn; kept_weight = count / (n_draws p).
+ * *n_kept_out (HOST pointer) receives their number.
+ *
+ * This call waits for the stream before it returns.  Errors:
+ * LP_ERR_OUT_OF_RANGE if an id lies outside [0, n_nodes) (detected on the
+ * device without any out-of-bounds access; outputs are then undefined) or if
+ * n_edges >= 2^31.
+ */
+size_t lp_sparsify_workspace_bytes(int32_t n_nodes, int64_t n_edges);
+int lp_sparsify(int32_t n_nodes, int64_t n_edges, const int32_t *eu, const int32_t *ev, int64_t n_draws, uint64_t seed,
+                int32_t *kept_edge, int32_t *kept_u, int32_t *kept_v, int32_t *kept_count, float *kept_weight,
+                int64_t *n_kept_out, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each
  * kernel launch made by the calls above is bracketed by two HIP events on the
  * launch stream.  lp_timing_collect waits for the recorded events, writes the

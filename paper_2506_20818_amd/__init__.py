@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     Grads,
     LpError,
     Model,
+    Sparsified,
     lib_path,
     load_library,
     lp_backward,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     lp_sage_forward,
     lp_sample_neg,
     lp_score_loss,
+    lp_sparsify,
     lp_strerror,
     lp_timing_collect,
     lp_timing_enable,

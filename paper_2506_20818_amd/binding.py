@@ -65,6 +65,9 @@ EXPORTS = {
     "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
+    "lp_sparsify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64]),
+    "lp_sparsify": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_timing_enable": (C.c_int, [C.c_int]),
     "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
@@ -283,6 +286,39 @@ def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tens
     _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
                            _ptr(e_dst), _ptr(dscore), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward")
     return grads
+
+
+class Sparsified:
+    """Result of lp_sparsify: indices of the distinct drawn edges (ascending), their end points, how often each
+    was drawn and its weight."""
+
+    def __init__(self, kept_edge, kept_u, kept_v, count, weight):
+        self.kept_edge, self.kept_u, self.kept_v, self.count, self.weight = kept_edge, kept_u, kept_v, count, weight
+
+
+def lp_sparsify(n_nodes: int, eu: torch.Tensor, ev: torch.Tensor, n_draws: int, seed: int,
+                ws: Optional[torch.Tensor] = None) -> Sparsified:
+    lib = load_library()
+    _need(eu, torch.int32, "eu")
+    _need(ev, torch.int32, "ev")
+    dev = eu.device
+    m = int(eu.numel())
+    cap = max(1, min(m, int(n_draws)))
+    i32 = lambda: torch.empty(cap, dtype=torch.int32, device=dev)
+    kept_edge, kept_u, kept_v, count = i32(), i32(), i32(), i32()
+    weight = torch.empty(cap, dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = _ws(lib.lp_sparsify_workspace_bytes(n_nodes, m), dev)
+    n_kept = C.c_int64(0)
+    _check(lib.lp_sparsify(n_nodes, m, _ptr(eu), _ptr(ev), int(n_draws), int(seed), _ptr(kept_edge), _ptr(kept_u),
+                           _ptr(kept_v), _ptr(count), _ptr(weight), C.byref(n_kept), _ptr(ws), ws.numel(), _stream()),
+           "lp_sparsify")
+    n = int(n_kept.value)
+    return Sparsified(kept_edge[:n], kept_u[:n], kept_v[:n], count[:n], weight[:n])
+
+
+def sparsify_workspace_bytes(n_nodes: int, n_edges: int) -> int:
+    return int(load_library().lp_sparsify_workspace_bytes(n_nodes, n_edges))
 
 
 def backward_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:

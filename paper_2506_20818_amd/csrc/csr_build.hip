@@ -7,103 +7,12 @@
 // The graph definition this realises: Sec. II-A (edge set over node pairs) and Sec. IV-A (neighbour sets,
 // degrees) of the paper.  Any correct sort yields the same bytes because the output is sorted and unique.
 #include "lp_internal.h"
+#include "lp_scan.h"
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kItems = 8;
-constexpr int kTile = kThreads * kItems;  // keys per block
+using namespace lp_scan;
 constexpr int kWaveChunk = 64 * kItems;   // keys per wavefront
-
-// ------------------------------------------------------------------ block-wide exclusive prefix sum
-__device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
-    return v;
-}
-
-// 256 threads; returns the exclusive prefix of v over the block and the block total.
-__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *lds4, uint32_t &total) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    uint32_t inc = wave_inclusive_scan(v);
-    __syncthreads();
-    if (lane == 63) lds4[w] = inc;
-    __syncthreads();
-    uint32_t off = 0;
-    uint32_t t = 0;
-#pragma unroll
-    for (int i = 0; i < kThreads / 64; ++i) {
-        uint32_t s = lds4[i];
-        if (i < w) off += s;
-        t += s;
-    }
-    total = t;
-    return off + inc - v;
-}
-
-// ------------------------------------------------------------------ device-wide exclusive scan of f(i), i < n
-template <class F>
-__global__ __launch_bounds__(kThreads) void scan_reduce_kernel(F f, int64_t n, uint32_t *block_sums) {
-    __shared__ uint32_t lds4[4];
-    const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
-    uint32_t s = 0;
-#pragma unroll
-    for (int i = 0; i < kItems; ++i)
-        if (base + i < n) s += f(base + i);
-    uint32_t total;
-    block_exclusive_scan(s, lds4, total);
-    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
-}
-
-// one block: block_sums[i] <- exclusive prefix; *total <- sum
-__global__ __launch_bounds__(kThreads) void scan_spine_kernel(uint32_t *block_sums, int64_t nb, uint32_t *total_out) {
-    __shared__ uint32_t lds4[4];
-    uint32_t carry = 0;
-    for (int64_t base = 0; base < nb; base += kThreads) {
-        int64_t i = base + threadIdx.x;
-        uint32_t v = i < nb ? block_sums[i] : 0u;
-        uint32_t total;
-        uint32_t ex = block_exclusive_scan(v, lds4, total);
-        if (i < nb) block_sums[i] = carry + ex;
-        carry += total;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0 && total_out) *total_out = carry;
-}
-
-// sink(i, exclusive_prefix_of_i, f(i)) is called for every i < n
-template <class F, class S>
-__global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64_t n, const uint32_t *block_sums) {
-    __shared__ uint32_t lds4[4];
-    const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
-    uint32_t v[kItems];
-    uint32_t s = 0;
-#pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        v[i] = (base + i < n) ? f(base + i) : 0u;
-        s += v[i];
-    }
-    uint32_t total;
-    uint32_t run = block_sums[blockIdx.x] + block_exclusive_scan(s, lds4, total);
-#pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        if (base + i < n) sink(base + i, run, v[i]);
-        run += v[i];
-    }
-}
-
-template <class F, class S>
-int device_exclusive_scan(F f, S sink, int64_t n, uint32_t *block_sums, uint32_t *total_out, hipStream_t st) {
-    const int64_t nb = lp_ceil_div(n > 0 ? n : 1, kTile);
-    hipLaunchKernelGGL((scan_reduce_kernel<F>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, n, block_sums);
-    hipLaunchKernelGGL(scan_spine_kernel, dim3(1), dim3(kThreads), 0, st, block_sums, nb, total_out);
-    hipLaunchKernelGGL((scan_apply_kernel<F, S>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, sink, n, block_sums);
-    return lp_after_launch();
-}
 
 // ------------------------------------------------------------------ radix sort of 64-bit keys, one 8-bit digit per pass
 __global__ __launch_bounds__(kThreads) void rs_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, int shift,
@@ -186,7 +95,7 @@ uint64_t *radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_b
         hipLaunchKernelGGL(rs_hist_kernel, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
         auto load = [hist] __device__(int64_t i) { return hist[i]; };
         auto store = [hist] __device__(int64_t i, uint32_t ex, uint32_t) { hist[i] = ex; };
-        int s = device_exclusive_scan(load, store, 256 * nb, spine, nullptr, st);
+        int s = device_exclusive_scan<uint32_t>(load, store, 256 * nb, spine, nullptr, st);
         if (s != LP_OK) { *status = s; return a; }
         hipLaunchKernelGGL(rs_scatter_kernel, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
         uint64_t *t = a; a = b; b = t;
@@ -343,7 +252,7 @@ int lp_launch_compact_rows(const int32_t *offsets, int32_t n_rows, int32_t *list
             ptr[pos] = offsets[v];
         }
     };
-    LP_TRY(device_exclusive_scan(occupied, emit, (int64_t)n_rows, static_cast<uint32_t *>(scan_ws),
+    LP_TRY(device_exclusive_scan<uint32_t>(occupied, emit, (int64_t)n_rows, static_cast<uint32_t *>(scan_ws),
                                  reinterpret_cast<uint32_t *>(count_dev), st));
     hipLaunchKernelGGL(compact_tail_kernel, dim3(1), dim3(64), 0, st, offsets, n_rows, count_dev, ptr);
     return lp_after_launch();
@@ -391,7 +300,7 @@ extern "C" int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, 
                 colidx[pos] = (int32_t)(k & ((1ull << mbits) - 1ull));
             }
         };
-        LP_TRY(device_exclusive_scan(is_first, emit, cap, w.scan_sums, w.scalars, st));
+        LP_TRY(device_exclusive_scan<uint32_t>(is_first, emit, cap, w.scan_sums, w.scalars, st));
     }
     hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, w.ukeys, (int64_t)0, w.scalars, n_nodes, bits, rowptr);
     hipLaunchKernelGGL(inv_deg_kernel, dim3(g_nodes), dim3(256), 0, st, rowptr, n_nodes, inv_deg);

@@ -1,0 +1,112 @@
+// Device-wide exclusive prefix sums over a functor (reduce, spine, apply: three launches), for 32- or 64-bit
+// unsigned values.  Integer sums are associative, so the result does not depend on how the work is split.
+// Everything here has internal linkage: each translation unit that includes this header gets its own kernels.
+#pragma once
+
+#include "lp_internal.h"
+
+namespace lp_scan {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kItems = 8;
+constexpr int kTile = kThreads * kItems;  // values per block
+
+// words of block-sum workspace (of the value type) for a scan over n values
+inline size_t block_sum_count(int64_t n) { return (size_t)(lp_ceil_div(n > 0 ? n : 1, kTile) + 8); }
+
+// ------------------------------------------------------------------ block-wide exclusive prefix sum
+template <class V>
+__device__ inline V wave_inclusive_scan(V v) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        V o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// 256 threads; returns the exclusive prefix of v over the block and the block total.
+template <class V>
+__device__ inline V block_exclusive_scan(V v, V *lds4, V &total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    V inc = wave_inclusive_scan(v);
+    __syncthreads();
+    if (lane == 63) lds4[w] = inc;
+    __syncthreads();
+    V off = 0;
+    V t = 0;
+#pragma unroll
+    for (int i = 0; i < kThreads / 64; ++i) {
+        V s = lds4[i];
+        if (i < w) off += s;
+        t += s;
+    }
+    total = t;
+    return off + inc - v;
+}
+
+// ------------------------------------------------------------------ device-wide exclusive scan of f(i), i < n
+template <class V, class F>
+__global__ __launch_bounds__(kThreads) void scan_reduce_kernel(F f, int64_t n, V *block_sums) {
+    __shared__ V lds4[4];
+    const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
+    V s = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+        if (base + i < n) s += f(base + i);
+    V total;
+    block_exclusive_scan(s, lds4, total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// one block: block_sums[i] <- exclusive prefix; *total <- sum
+template <class V>
+__global__ __launch_bounds__(kThreads) void scan_spine_kernel(V *block_sums, int64_t nb, V *total_out) {
+    __shared__ V lds4[4];
+    V carry = 0;
+    for (int64_t base = 0; base < nb; base += kThreads) {
+        int64_t i = base + threadIdx.x;
+        V v = i < nb ? block_sums[i] : 0u;
+        V total;
+        V ex = block_exclusive_scan(v, lds4, total);
+        if (i < nb) block_sums[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = carry;
+}
+
+// sink(i, exclusive_prefix_of_i, f(i)) is called for every i < n
+template <class V, class F, class S>
+__global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64_t n, const V *block_sums) {
+    __shared__ V lds4[4];
+    const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
+    V v[kItems];
+    V s = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        v[i] = (base + i < n) ? f(base + i) : 0u;
+        s += v[i];
+    }
+    V total;
+    V run = block_sums[blockIdx.x] + block_exclusive_scan(s, lds4, total);
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        if (base + i < n) sink(base + i, run, v[i]);
+        run += v[i];
+    }
+}
+
+template <class V, class F, class S>
+int device_exclusive_scan(F f, S sink, int64_t n, V *block_sums, V *total_out, hipStream_t st) {
+    const int64_t nb = lp_ceil_div(n > 0 ? n : 1, kTile);
+    hipLaunchKernelGGL((scan_reduce_kernel<V, F>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, n, block_sums);
+    hipLaunchKernelGGL((scan_spine_kernel<V>), dim3(1), dim3(kThreads), 0, st, block_sums, nb, total_out);
+    hipLaunchKernelGGL((scan_apply_kernel<V, F, S>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, sink, n, block_sums);
+    return lp_after_launch();
+}
+
+}  // namespace
+}  // namespace lp_scan

@@ -2,26 +2,9 @@
 // samples").  One thread per sample; the random stream is the counter-based Philox4x32-10 generator of Salmon,
 // Moraes, Dror and Shaw (SC'11), so a sample's value depends only on (seed, step, sample index, attempt).
 #include "lp_internal.h"
+#include "lp_philox.h"
 
 namespace {
-
-struct U4 { uint32_t x, y, z, w; };
-
-__device__ inline U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c.x;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c.z;
-        U4 n;
-        n.x = (uint32_t)(p1 >> 32) ^ c.y ^ k0;
-        n.y = (uint32_t)p1;
-        n.z = (uint32_t)(p0 >> 32) ^ c.w ^ k1;
-        n.w = (uint32_t)p0;
-        c = n;
-    }
-    return c;
-}
 
 __device__ inline bool row_contains(const int32_t *__restrict__ colidx, int32_t lo, int32_t hi, int32_t c) {
     const int32_t end = hi;
@@ -45,7 +28,7 @@ __global__ __launch_bounds__(256) void sample_neg_kernel(const int32_t *__restri
     int32_t c = 0;
     bool found = false;
     for (int blk = 0; blk < 4 && !found; ++blk) {
-        const U4 r = philox4x32_10(U4{(uint32_t)q, (uint32_t)blk, step_lo, step_hi}, seed_lo, seed_hi);
+        const LpU4 r = lp_philox4x32_10(LpU4{(uint32_t)q, (uint32_t)blk, step_lo, step_hi}, seed_lo, seed_hi);
         const uint32_t word[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

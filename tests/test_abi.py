@@ -136,3 +136,25 @@ def test_sampler_and_loss_reject_bad_arguments_on_the_host():
     assert sl(loss=None) == -1
     assert sl(ws=None) == -3
     assert sl(B_=1 << 31, npos=0) == -2
+
+
+def test_sparsify_rejects_bad_arguments_on_the_host():
+    lib = B.load_library()
+    n_kept = C.c_int64(-1)
+    p = C.c_void_p(0x1000)
+    sp = lambda n=10, m=4, L=3, eu=p, kept=p, out=C.byref(n_kept), ws=p, wsb=1 << 30: lib.lp_sparsify(
+        n, m, eu, p, L, 7, kept, None, None, None, p, out, ws, wsb, None)
+    assert sp(n=0) == -1
+    assert sp(m=-1) == -1
+    assert sp(L=-1) == -1
+    assert sp(out=None) == -1
+    assert sp(m=1 << 31) == -2
+    assert sp(eu=None) == -1
+    assert sp(kept=None) == -1
+    assert sp(ws=None) == -3
+    assert sp(wsb=64) == -3
+    assert sp(m=0) == 0 and n_kept.value == 0          # nothing to draw from: no launch, no error
+    n_kept.value = -1
+    assert sp(L=0) == 0 and n_kept.value == 0
+    a, b = lib.lp_sparsify_workspace_bytes(1000, 5000), lib.lp_sparsify_workspace_bytes(1000, 50000)
+    assert 0 < a < b and lib.lp_sparsify_workspace_bytes(0, 5) == 0
