@@ -77,6 +77,60 @@ def cpu_baseline(scale):
                       "entries, %d scored edges" % (scale, wl.n_nodes, g.nnz, wl.batch_edges)}
 
 
+def sparsify_task(args):
+    """Second measurement: the sparsification pass of Algorithm 1 over all partitions of a partitioned graph
+    (the paper's Table II times this step).  One "step" = sparsify every partition once at level alpha."""
+    import numpy as np
+    import torch
+
+    import paper_2506_20818_amd as lp
+    from paper_2506_20818_amd import binding as B
+    from lp_workloads import make_partitioned
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    name = args.workload if args.workload in ("C3", "C5_keep1") else "C3"
+    pin = make_partitioned(name, with_features=False, alpha=args.alpha)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    parts = [(i32(u), i32(v)) for u, v in pin.edges]
+    ws = [torch.empty(B.sparsify_workspace_bytes(pin.n_nodes, int(u.numel())), dtype=torch.uint8, device=dev) for u, _ in parts]
+    total_edges = sum(int(u.numel()) for u, _ in parts)
+
+    def step():
+        kept = 0
+        for j, (u, v) in enumerate(parts):
+            kept += int(lp.lp_sparsify(pin.n_nodes, u, v, pin.n_draws(j), pin.sparsify_seeds[j], ws[j]).kept_edge.numel())
+        return kept
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        kept = step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / max(args.steps, 1)
+    # algorithmic traffic of one partition: edge list read twice (degrees, weights) + random degree reads, weights
+    # written and scanned (8 B each way twice), ~log2(m) 8-byte probes per draw, counts zeroed/read, output
+    out = {"metric": "sparsification pass over all partitions (Algorithm 1, sparsification loop): input edges/s",
+           "value": round(total_edges / dt, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u64", "data": "synthetic",
+           "config": {"workload": "%s graph, %d nodes, %d-way random node partition with halo edges in both partitions, "
+                                  "%d edges summed over partitions, level alpha=%.2f" % (name, pin.n_nodes, pin.parts, total_edges, pin.alpha),
+                      "kept_edges": kept, "kept_fraction": round(kept / total_edges, 4)}}
+    if not args.no_cpu_baseline:
+        from oracle import sparsify_oracle as S
+        t0 = time.perf_counter()
+        j = 0
+        r = S.sparsify(pin.n_nodes, pin.edges[j][0], pin.edges[j][1], pin.n_draws(j), pin.sparsify_seeds[j])
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(pin.edges[j][0].size / cdt, 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
+                               "seconds": round(cdt, 3),
+                               "sample": "the numpy oracle on partition 0 only (%d edges, %d draws)" % (pin.edges[j][0].size, pin.n_draws(j))}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +139,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--cpu-scale", type=float, default=0.25, help="fraction of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify"],
+                    help="train_step: the headline metric; sparsify: the sparsification pass over all partitions")
+    ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a dispatch of known size for counter runs)")
     args = ap.parse_args()
@@ -92,6 +149,9 @@ def main():
         sys.stderr.write("bench.py measures one worker's step on ONE GPU; --gpus %d is not supported "
                          "(no collectives are part of this build)\n" % args.gpus)
         sys.exit(2)
+
+    if args.task == "sparsify":
+        return sparsify_task(args)
 
     import numpy as np
     import torch

@@ -8,9 +8,12 @@ bytes.
 """
 from .graphs import (  # noqa: F401
     CONFIGS,
+    PartitionedInputs,
     Workload,
     chung_lu_edges,
+    make_partitioned,
     make_workload,
+    partition_edge_lists,
     uniform_edges,
     worker_view,
 )

@@ -129,6 +129,21 @@ def worker_view(u: np.ndarray, v: np.ndarray, n_nodes: int, parts: int, worker: 
             int(old_of_new.size), int(owned.size), old_of_new)
 
 
+def partition_edge_lists(u: np.ndarray, v: np.ndarray, n_nodes: int, parts: int, part_seed: int):
+    """Uniform random node partition with the paper's halo rule (Sec. IV-B: cross-partition edges are kept in
+    both partitions, so every owned node keeps its full neighbour list).
+
+    Returns (part [n_nodes], edges) where edges[j] = (u_j, v_j) are the edges with at least one end in part j,
+    in input order, node ids unchanged."""
+    part = np.random.default_rng(part_seed).integers(0, parts, size=n_nodes)
+    pu, pv = part[u], part[v]
+    edges = []
+    for j in range(parts):
+        sel = (pu == j) | (pv == j)
+        edges.append((u[sel].copy(), v[sel].copy()))
+    return part, edges
+
+
 # --------------------------------------------------------------------------
 # workload table
 # --------------------------------------------------------------------------
@@ -159,6 +174,67 @@ for _keep, _kseed in ((1.0, 33), (0.5, 34), (0.2, 35)):
         view=dict(parts=4, worker=0, keep=_keep),
         dims=[128, 512, 512, 512], n_pos=131_072, k_neg=4, dtype="bf16",
         seeds=dict(graph=3, perm=13, part=23, keep=_kseed, x=103, w=204, batch=304))
+
+
+@dataclass
+class PartitionedInputs:
+    """Inputs of one worker under the paper's own data layout: its partition in full, the other partitions as
+    edge lists that the code under test has to sparsify (level alpha, one seed per partition), all nodes visible."""
+    name: str
+    n_nodes: int
+    parts: int
+    worker: int
+    part: np.ndarray                     # int [n_nodes]: owner of each node
+    edges: List[tuple]                   # edges[j] = (u, v) int32 arrays of partition j (halo edges included)
+    alpha: float                         # draws per partition = floor(alpha * |E^j|)
+    sparsify_seeds: List[int]
+    dims: List[int]
+    k_neg: int
+    pos_src: np.ndarray                  # positives are edges of the worker's own partition
+    pos_dst: np.ndarray
+    sampler_seed: int
+    sampler_step: int
+    X: Optional[np.ndarray] = None
+    W_self: List[np.ndarray] = field(default_factory=list)
+    W_neigh: List[np.ndarray] = field(default_factory=list)
+    bias: List[np.ndarray] = field(default_factory=list)
+
+    def n_draws(self, j: int) -> int:
+        return int(self.alpha * self.edges[j][0].size)
+
+    def visible_edges(self, kept: List[tuple]):
+        """Edge list of the worker's visible graph: its own partition plus the given sparsified remote edge
+        lists (kept[j] = (u, v) for j != worker; entry `worker` is ignored).  Plain concatenation: pairs that
+        occur more than once collapse when the CSR is built."""
+        us = [self.edges[self.worker][0]] + [kept[j][0] for j in range(self.parts) if j != self.worker]
+        vs = [self.edges[self.worker][1]] + [kept[j][1] for j in range(self.parts) if j != self.worker]
+        return np.concatenate(us).astype(np.int32), np.concatenate(vs).astype(np.int32)
+
+
+def make_partitioned(name: str = "C3", with_features: bool = True, scale: float = 1.0, alpha: float = 0.15) -> PartitionedInputs:
+    """The graph of workload `name` split over its workers the paper's way (random node partition, halo edges in
+    both partitions), with the sparsification left to the code under test."""
+    cfg = CONFIGS[name]
+    sd = cfg["seeds"]
+    n = max(8, int(round(cfg["n_nodes"] * scale)))
+    m = max(8, int(round(cfg["m"] * scale)))
+    w_max = cfg.get("w_max")
+    if w_max is not None and scale != 1.0:
+        w_max = max(4.0, w_max * scale)
+    u, v = chung_lu_edges(n, m, cfg["gamma"], sd["graph"], sd["perm"], w_max)
+    vw = cfg["view"]
+    part, edges = partition_edge_lists(u, v, n, vw["parts"], sd["part"])
+    own_u, own_v = edges[vw["worker"]]
+    n_pos = min(own_u.size, max(1, int(round(cfg["n_pos"] * scale))))
+    pick = np.random.default_rng(sd["batch"]).permutation(own_u.size)[:n_pos]
+    pin = PartitionedInputs(name=name + "s", n_nodes=n, parts=vw["parts"], worker=vw["worker"], part=part, edges=edges,
+                            alpha=alpha, sparsify_seeds=[0x5A000000 + sd["keep"] * 16 + j for j in range(vw["parts"])],
+                            dims=list(cfg["dims"]), k_neg=cfg["k_neg"], pos_src=own_u[pick].copy(), pos_dst=own_v[pick].copy(),
+                            sampler_seed=0x5EED0000 + sd["batch"], sampler_step=7)
+    pin.W_self, pin.W_neigh, pin.bias = init_model(pin.dims, sd["w"])
+    if with_features:
+        pin.X = init_features(n, pin.dims[0], sd["x"])
+    return pin
 
 
 @dataclass

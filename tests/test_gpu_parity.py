@@ -340,8 +340,11 @@ def test_backward_empty_batch_gives_zero_gradients():
 
 # ------------------------------------------------------------------------------------------------ whole step
 def whole_step(name):
-    wl = make_workload(name)
-    say("whole step %s N=%d nnz~%d B=%d" % (name, wl.n_nodes, 2 * wl.src.size, wl.batch_edges))
+    run_whole_step(make_workload(name))
+
+
+def run_whole_step(wl):
+    say("whole step %s N=%d nnz~%d B=%d" % (wl.name, wl.n_nodes, 2 * wl.src.size, wl.batch_edges))
     ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
     exp = O.train_step(ref, wl.W_self, wl.W_neigh, wl.bias, wl.X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space,
                        wl.sampler_seed, wl.sampler_step)

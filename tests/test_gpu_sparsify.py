@@ -73,3 +73,29 @@ def test_sparsify_collab_scale_at_the_default_level():
     r = check(wl.n_nodes, wl.src, wl.dst, L, 42)
     # at level 0.15 at least 85 % of the edges are removed; repeated draws of low-degree edges remove a little more
     assert 0.5 * L < r.kept_edge.size <= L
+
+
+def test_training_step_on_the_papers_worker_view():
+    """One worker the paper's way (Sec. IV-A/B): its own partition in full (halo edges included), every other
+    partition sparsified at level 0.15 by lp_sparsify, all nodes visible and in the negative sample space.  The
+    sparsified edge lists must equal the oracle's bit for bit; the training step on the assembled graph is then
+    compared with the oracle's step on the same graph.  One tenth of the C3 graph (100 000 nodes)."""
+    from lp_workloads import Workload, make_partitioned
+    from test_gpu_parity import run_whole_step
+    pin = make_partitioned("C3", scale=0.1)
+    say("paper view: N=%d parts=%d own edges=%d" % (pin.n_nodes, pin.parts, pin.edges[pin.worker][0].size))
+    kept = [None] * pin.parts
+    for j in range(pin.parts):
+        if j == pin.worker:
+            continue
+        eu, ev = pin.edges[j]
+        ref = check(pin.n_nodes, eu, ev, pin.n_draws(j), pin.sparsify_seeds[j])
+        got = lp.lp_sparsify(pin.n_nodes, dev_i32(eu), dev_i32(ev), pin.n_draws(j), pin.sparsify_seeds[j])
+        kept[j] = (host(got.kept_u), host(got.kept_v))           # the HIP path's own output feeds the HIP step
+        assert np.array_equal(kept[j][0], eu[ref.kept_edge]) and np.array_equal(kept[j][1], ev[ref.kept_edge])
+    u, v = pin.visible_edges(kept)
+    wl = Workload(name=pin.name, n_nodes=pin.n_nodes, n_owned=int((pin.part == pin.worker).sum()), src=u, dst=v,
+                  dims=pin.dims, k_neg=pin.k_neg, n_space=pin.n_nodes, pos_src=pin.pos_src, pos_dst=pin.pos_dst,
+                  sampler_seed=pin.sampler_seed, sampler_step=pin.sampler_step, dtype="f32", X=pin.X,
+                  W_self=pin.W_self, W_neigh=pin.W_neigh, bias=pin.bias)
+    run_whole_step(wl)
