@@ -104,6 +104,13 @@ typedef struct lp_grads {
     void *dX;                       /* device [n_nodes, F_0] in the model's storage type, or NULL to skip it */
 } lp_grads;
 
+/* Adam moments, one fp32 array per parameter tensor, same shapes as lp_grads; the caller zeroes them before the
+ * first lp_adam_step. */
+typedef struct lp_opt_state {
+    float *m_W_self[LP_MAX_LAYERS], *m_W_neigh[LP_MAX_LAYERS], *m_bias[LP_MAX_LAYERS];
+    float *v_W_self[LP_MAX_LAYERS], *v_W_neigh[LP_MAX_LAYERS], *v_bias[LP_MAX_LAYERS];
+} lp_opt_state;
+
 /* Text for a status code (static storage, never NULL). */
 const char *lp_strerror(int status);
 
@@ -228,6 +235,27 @@ size_t lp_sparsify_workspace_bytes(int32_t n_nodes, int64_t n_edges);
 int lp_sparsify(int32_t n_nodes, int64_t n_edges, const int32_t *eu, const int32_t *ev, int64_t n_draws, uint64_t seed,
                 int32_t *kept_edge, int32_t *kept_u, int32_t *kept_v, int32_t *kept_count, float *kept_weight,
                 int64_t *n_kept_out, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_sgd_step, lp_adam_step - the weight update that ends a training step
+ * (Algorithm 1, "Update W <- W - eta grad L(W)"; "Hyperparameters": Adam,
+ * learning rate 0.001).  Both update every parameter tensor of the model IN
+ * PLACE (the weights that lp_model points at are written, although the struct
+ * declares them const for the other calls) from the gradients in `g`, in one
+ * kernel launch, and return without waiting.
+ *   sgd:  w <- w - lr g
+ *   adam: m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2;
+ *         w <- w - lr (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps),   t = t_step = 1, 2, ...
+ * Arithmetic is fp32.  With LP_BF16 the weight matrices are widened, updated
+ * and rounded back to bfloat16 (nearest even); biases, gradients and moments
+ * are fp32 throughout.  Averaging gradients over workers, where there are
+ * several, is the caller's business and comes before this call.
+ * Errors: LP_ERR_INVALID_ARG for a NULL tensor, t_step < 1, beta outside [0,1),
+ * a negative eps or a non-finite learning rate.
+ */
+int lp_sgd_step(const lp_model *m, const lp_grads *g, float lr, void *stream);
+int lp_adam_step(const lp_model *m, const lp_grads *g, const lp_opt_state *s, int64_t t_step, float lr, float beta1,
+                 float beta2, float eps, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each

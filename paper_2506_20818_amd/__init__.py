@@ -7,6 +7,7 @@ library raises.
 from .binding import (  # noqa: F401
     LP_SYMMETRIZE,
     Acts,
+    AdamState,
     Csr,
     Grads,
     LpError,
@@ -16,7 +17,9 @@ from .binding import (  # noqa: F401
     load_library,
     lp_backward,
     lp_build_csr,
+    lp_adam_step,
     lp_sage_forward,
+    lp_sgd_step,
     lp_sample_neg,
     lp_score_loss,
     lp_sparsify,

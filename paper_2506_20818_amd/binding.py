@@ -50,6 +50,10 @@ class _GradsStruct(C.Structure):
                 ("dbias", C.c_void_p * LP_MAX_LAYERS), ("dX", C.c_void_p)]
 
 
+class _OptStateStruct(C.Structure):
+    _fields_ = [(n, C.c_void_p * LP_MAX_LAYERS) for n in ("m_W_self", "m_W_neigh", "m_bias", "v_W_self", "v_W_neigh", "v_bias")]
+
+
 EXPORTS = {
     "lp_strerror": (C.c_char_p, [C.c_int]),
     "lp_build_csr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_uint32]),
@@ -68,6 +72,9 @@ EXPORTS = {
     "lp_sparsify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64]),
     "lp_sparsify": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_sgd_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.c_float, C.c_void_p]),
+    "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
+                               C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "lp_timing_enable": (C.c_int, [C.c_int]),
     "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
@@ -286,6 +293,30 @@ def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tens
     _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
                            _ptr(e_dst), _ptr(dscore), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward")
     return grads
+
+
+class AdamState:
+    """Zero-initialised first and second moments for every parameter tensor of a model."""
+
+    def __init__(self, m: Model):
+        z = lambda t: torch.zeros(t.shape, dtype=torch.float32, device=t.device)
+        self.m_W_self, self.m_W_neigh, self.m_bias = [z(t) for t in m.W_self], [z(t) for t in m.W_neigh], [z(t) for t in m.bias]
+        self.v_W_self, self.v_W_neigh, self.v_bias = [z(t) for t in m.W_self], [z(t) for t in m.W_neigh], [z(t) for t in m.bias]
+        s = _OptStateStruct()
+        for name in ("m_W_self", "m_W_neigh", "m_bias", "v_W_self", "v_W_neigh", "v_bias"):
+            for k, t in enumerate(getattr(self, name)):
+                getattr(s, name)[k] = t.data_ptr()
+        self.c = s
+
+
+def lp_sgd_step(m: Model, grads: Grads, lr: float) -> None:
+    _check(load_library().lp_sgd_step(C.byref(m.c), C.byref(grads.c), lr, _stream()), "lp_sgd_step")
+
+
+def lp_adam_step(m: Model, grads: Grads, state: AdamState, t_step: int, lr: float = 1e-3, beta1: float = 0.9,
+                 beta2: float = 0.999, eps: float = 1e-8) -> None:
+    _check(load_library().lp_adam_step(C.byref(m.c), C.byref(grads.c), C.byref(state.c), int(t_step), lr, beta1, beta2, eps,
+                                       _stream()), "lp_adam_step")
 
 
 class Sparsified:

@@ -158,3 +158,26 @@ def test_sparsify_rejects_bad_arguments_on_the_host():
     assert sp(L=0) == 0 and n_kept.value == 0
     a, b = lib.lp_sparsify_workspace_bytes(1000, 5000), lib.lp_sparsify_workspace_bytes(1000, 50000)
     assert 0 < a < b and lib.lp_sparsify_workspace_bytes(0, 5) == 0
+
+
+def test_optimizer_steps_reject_bad_arguments_on_the_host():
+    lib = B.load_library()
+    good = _model([128, 256, 256])
+    grads, state = B._GradsStruct(), B._OptStateStruct()
+    for k in range(2):
+        grads.dW_self[k] = grads.dW_neigh[k] = grads.dbias[k] = 0x1000
+        for name in ("m_W_self", "m_W_neigh", "m_bias", "v_W_self", "v_W_neigh", "v_bias"):
+            getattr(state, name)[k] = 0x1000
+    sgd = lambda m=good, g=grads, lr=0.1: lib.lp_sgd_step(C.byref(m), C.byref(g), lr, None)
+    assert sgd(m=_model([128, 256], null_w=True)) == -1
+    assert sgd(g=B._GradsStruct()) == -1
+    assert sgd(lr=float("nan")) == -1
+    assert sgd(m=_model([128, 256], dtype=5)) == -4
+    adam = lambda m=good, g=grads, s=state, t=1, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8: lib.lp_adam_step(
+        C.byref(m), C.byref(g), C.byref(s), t, lr, b1, b2, eps, None)
+    assert adam(t=0) == -1
+    assert adam(b1=1.0) == -1
+    assert adam(b2=-0.1) == -1
+    assert adam(eps=-1.0) == -1
+    assert adam(s=B._OptStateStruct()) == -1
+    assert adam(g=B._GradsStruct()) == -1
