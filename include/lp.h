@@ -43,6 +43,7 @@ extern "C" {
 #endif
 
 #define LP_MAX_LAYERS 8
+#define LP_MAX_FANOUT 64 /* most neighbours one node may draw per hop in lp_sample_blocks */
 
 enum {
     LP_OK = 0,
@@ -103,6 +104,29 @@ typedef struct lp_grads {
     float *dbias[LP_MAX_LAYERS];    /* device [F_k] */
     void *dX;                       /* device [n_nodes, F_0] in the model's storage type, or NULL to skip it */
 } lp_grads;
+
+/* The computational graph of one mini-batch with sampled neighbourhoods (Sec. II-B, last paragraph; Fig. 1b), as K
+ * bipartite blocks over ONE node list: frontier k = the first n[k] entries of `nodes`, n[K] <= ... <= n[0]; frontier
+ * K holds the end points of the scored edges.  Block k (arrays with index k-1) lists, for every node of frontier k,
+ * the positions (in frontier k-1) of its sampled neighbours.  All arrays are caller-allocated device memory, sized
+ * by the host-side bounds cap / cap_entries that lp_blocks_bounds computes; the exact sizes n[] live on the device. */
+typedef struct lp_blocks {
+    int32_t n_layers;                       /* K */
+    int32_t n_graph_nodes;                  /* nodes of the graph the blocks are sampled from */
+    int64_t n_edges;                        /* B, scored edges of the batch */
+    int32_t cap[LP_MAX_LAYERS + 1];         /* cap[k] >= n[k] */
+    int32_t reserved_;
+    int64_t cap_entries[LP_MAX_LAYERS];     /* cap_entries[k-1] >= entries of block k */
+    int32_t *n;                             /* device [K+1] */
+    int32_t *nodes;                         /* device [cap[0]]: graph ids */
+    int32_t *index;                         /* device [n_graph_nodes]: position of a node in `nodes`, or -1 */
+    int32_t *ptr[LP_MAX_LAYERS];            /* device [cap[k]+1]: row pointers of block k */
+    int32_t *col[LP_MAX_LAYERS];            /* device [cap_entries[k-1]]: positions in frontier k-1, draw order */
+    float *inv_cnt[LP_MAX_LAYERS];          /* device [cap[k]]: 1/(sampled neighbours), 0 for none */
+    int32_t *t_ptr[LP_MAX_LAYERS];          /* device [cap[k-1]+1]: transposed block, rows = positions in frontier k-1 */
+    int32_t *t_col[LP_MAX_LAYERS];          /* device [cap_entries[k-1]]: positions in frontier k, by entry index */
+    int32_t *e_src_pos, *e_dst_pos;         /* device [B]: the scored edges in positions of frontier K (-1: id out of range) */
+} lp_blocks;
 
 /* Adam moments, one fp32 array per parameter tensor, same shapes as lp_grads; the caller zeroes them before the
  * first lp_adam_step. */
@@ -256,6 +280,53 @@ int lp_sparsify(int32_t n_nodes, int64_t n_edges, const int32_t *eu, const int32
 int lp_sgd_step(const lp_model *m, const lp_grads *g, float lr, void *stream);
 int lp_adam_step(const lp_model *m, const lp_grads *g, const lp_opt_state *s, int64_t t_step, float lr, float beta1,
                  float beta2, float eps, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Sampled-neighbourhood training step (the paper's mini-batch mode: Sec. II-B,
+ * last paragraph; Fig. 1b; "Hyperparameters": 25, 10, 5 neighbours for the
+ * first, second, third hop).
+ *
+ * lp_blocks_bounds: pure host arithmetic; cap [K+1] and cap_entries [K] for a
+ * graph of n_nodes / nnz entries, B scored edges and fan-outs fanout[0..K-1]
+ * (fanout[0] = first hop = layer K; each in 1..LP_MAX_FANOUT).
+ *
+ * lp_sample_blocks: fills `out` (whose arrays and cap fields the caller set up
+ * from the bounds) for the batch e_src/e_dst (device [B]; ids outside the graph
+ * are ignored and get position -1).  Frontier K = the distinct end points,
+ * ascending.  At hop h = 1..K (layer k = K+1-h) every node v of frontier k
+ * draws min(|N(v)|, fanout[h-1]) distinct neighbours uniformly without
+ * replacement: a partial Fisher-Yates shuffle of the positions 0..d-1 of its
+ * sorted neighbour list, swap t exchanging position t with position
+ * t + floor(word * (d-t) / 2^32), word = word (t mod 4) of Philox4x32-10 with
+ * counter (v, hop*2^16 + t div 4, step_lo, step_hi) and key (seed_lo, seed_hi);
+ * the sample is positions 0..f-1 in that order; a node with d <= f takes its
+ * whole list in order.  Frontier k-1 = frontier k followed by the drawn nodes
+ * that are new, ascending.  The transposed block lists, for every position of
+ * frontier k-1, the rows that drew it, ordered by entry index.  Exactly one
+ * result is correct.  Returns without waiting for the stream.
+ *
+ * lp_sage_forward_blocks: Eq. (1) on the blocks.  X: device [n_graph_nodes, F_0];
+ * X_frontier: device [cap[0], F_0], receives the feature rows of frontier 0;
+ * saved->A[k-1]: device [cap[k], F_{k-1}], saved->H[k-1]: device [cap[k], F_k];
+ * row i belongs to nodes[i].  The embeddings of the batch end points are the
+ * first n[K] rows of saved->H[K-1]; score them with lp_score_loss(H, cap[K],
+ * ..., e_src_pos, e_dst_pos, ...).
+ *
+ * lp_backward_blocks: weight and bias gradients of the batch loss through the
+ * blocks (dscore from lp_score_loss); out->dX is ignored.  Fixed summation
+ * order: repeated calls give the same bits.
+ */
+int lp_blocks_bounds(int32_t n_nodes, int64_t nnz, int64_t B, int32_t K, const int32_t *fanout, int32_t *cap,
+                     int64_t *cap_entries);
+size_t lp_sample_blocks_workspace_bytes(int32_t n_nodes, int64_t nnz, int64_t B, int32_t K, const int32_t *fanout);
+int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src, const int32_t *e_dst, int32_t K, const int32_t *fanout,
+                     uint64_t seed, uint64_t step, lp_blocks *out, void *ws, size_t ws_bytes, void *stream);
+size_t lp_forward_blocks_workspace_bytes(const lp_model *m, const lp_blocks *b);
+int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, const void *X, void *X_frontier, lp_acts *saved, void *ws,
+                           size_t ws_bytes, void *stream);
+size_t lp_backward_blocks_workspace_bytes(const lp_model *m, const lp_blocks *b);
+int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved, const float *dscore,
+                       lp_grads *out, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each

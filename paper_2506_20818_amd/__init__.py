@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     LP_SYMMETRIZE,
     Acts,
     AdamState,
+    BlockActs,
+    Blocks,
     Csr,
     Grads,
     LpError,
@@ -16,9 +18,12 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     lp_backward,
+    lp_backward_blocks,
     lp_build_csr,
     lp_adam_step,
     lp_sage_forward,
+    lp_sage_forward_blocks,
+    lp_sample_blocks,
     lp_sgd_step,
     lp_sample_neg,
     lp_score_loss,

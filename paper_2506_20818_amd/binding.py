@@ -50,6 +50,19 @@ class _GradsStruct(C.Structure):
                 ("dbias", C.c_void_p * LP_MAX_LAYERS), ("dX", C.c_void_p)]
 
 
+LP_MAX_FANOUT = 64
+
+
+class _BlocksStruct(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_graph_nodes", C.c_int32), ("n_edges", C.c_int64),
+                ("cap", C.c_int32 * (LP_MAX_LAYERS + 1)), ("reserved_", C.c_int32),
+                ("cap_entries", C.c_int64 * LP_MAX_LAYERS),
+                ("n", C.c_void_p), ("nodes", C.c_void_p), ("index", C.c_void_p),
+                ("ptr", C.c_void_p * LP_MAX_LAYERS), ("col", C.c_void_p * LP_MAX_LAYERS),
+                ("inv_cnt", C.c_void_p * LP_MAX_LAYERS), ("t_ptr", C.c_void_p * LP_MAX_LAYERS),
+                ("t_col", C.c_void_p * LP_MAX_LAYERS), ("e_src_pos", C.c_void_p), ("e_dst_pos", C.c_void_p)]
+
+
 class _OptStateStruct(C.Structure):
     _fields_ = [(n, C.c_void_p * LP_MAX_LAYERS) for n in ("m_W_self", "m_W_neigh", "m_bias", "v_W_self", "v_W_neigh", "v_bias")]
 
@@ -72,6 +85,17 @@ EXPORTS = {
     "lp_sparsify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64]),
     "lp_sparsify": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
                               C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_blocks_bounds": (C.c_int, [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int64)]),
+    "lp_sample_blocks_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int32)]),
+    "lp_sample_blocks": (C.c_int, [C.POINTER(_CsrStruct), C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                   C.c_uint64, C.c_uint64, C.POINTER(_BlocksStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_forward_blocks_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.POINTER(_BlocksStruct)]),
+    "lp_sage_forward_blocks": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.c_void_p,
+                                         C.POINTER(_ActsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_backward_blocks_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.POINTER(_BlocksStruct)]),
+    "lp_backward_blocks": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
+                                     C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_sgd_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.c_float, C.c_void_p]),
     "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
                                C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
@@ -293,6 +317,104 @@ def lp_backward(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tens
     _check(lib.lp_backward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
                            _ptr(e_dst), _ptr(dscore), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward")
     return grads
+
+
+class Blocks:
+    """Device arrays of one mini-batch's sampled computational graph (see lp_blocks in include/lp.h), sized by
+    lp_blocks_bounds.  Reusable across batches of the same size on the same graph."""
+
+    def __init__(self, g: Csr, B: int, fanout: List[int]):
+        lib = load_library()
+        K = len(fanout)
+        self.K, self.B, self.fanout = K, int(B), [int(f) for f in fanout]
+        self.fan_c = (C.c_int32 * K)(*self.fanout)
+        cap = (C.c_int32 * (K + 1))()
+        cap_e = (C.c_int64 * K)()
+        _check(lib.lp_blocks_bounds(g.n_nodes, g.nnz, self.B, K, self.fan_c, cap, cap_e), "lp_blocks_bounds")
+        self.cap, self.cap_entries = [int(x) for x in cap], [int(x) for x in cap_e]
+        dev = g.rowptr.device
+        i32 = lambda n: torch.empty(max(int(n), 1), dtype=torch.int32, device=dev)
+        self.n = i32(K + 1)
+        self.nodes, self.index = i32(self.cap[0]), i32(g.n_nodes)
+        self.ptr = [i32(self.cap[k] + 1) for k in range(1, K + 1)]
+        self.col = [i32(self.cap_entries[k - 1]) for k in range(1, K + 1)]
+        self.inv_cnt = [torch.empty(max(self.cap[k], 1), dtype=torch.float32, device=dev) for k in range(1, K + 1)]
+        self.t_ptr = [i32(self.cap[k - 1] + 1) for k in range(1, K + 1)]
+        self.t_col = [i32(self.cap_entries[k - 1]) for k in range(1, K + 1)]
+        self.e_src_pos, self.e_dst_pos = i32(self.B), i32(self.B)
+        s = _BlocksStruct()
+        s.n_layers, s.n_graph_nodes, s.n_edges = K, g.n_nodes, self.B
+        for k in range(K + 1):
+            s.cap[k] = self.cap[k]
+        for k in range(K):
+            s.cap_entries[k] = self.cap_entries[k]
+            s.ptr[k], s.col[k], s.inv_cnt[k] = self.ptr[k].data_ptr(), self.col[k].data_ptr(), self.inv_cnt[k].data_ptr()
+            s.t_ptr[k], s.t_col[k] = self.t_ptr[k].data_ptr(), self.t_col[k].data_ptr()
+        s.n, s.nodes, s.index = self.n.data_ptr(), self.nodes.data_ptr(), self.index.data_ptr()
+        s.e_src_pos, s.e_dst_pos = self.e_src_pos.data_ptr(), self.e_dst_pos.data_ptr()
+        self.c = s
+        self.sample_ws = _ws(lib.lp_sample_blocks_workspace_bytes(g.n_nodes, g.nnz, self.B, K, self.fan_c), dev)
+
+
+class BlockActs:
+    """Activations of the sampled step: X_frontier [cap[0], F_0], A[k-1] [cap[k], F_{k-1}], H[k-1] [cap[k], F_k]."""
+
+    def __init__(self, b: Blocks, dims: List[int], device, dtype=torch.float32):
+        K = len(dims) - 1
+        self.X_frontier = torch.empty((max(b.cap[0], 1), dims[0]), dtype=dtype, device=device)
+        self.A = [torch.empty((max(b.cap[k + 1], 1), dims[k]), dtype=dtype, device=device) for k in range(K)]
+        self.H = [torch.empty((max(b.cap[k + 1], 1), dims[k + 1]), dtype=dtype, device=device) for k in range(K)]
+        s = _ActsStruct()
+        for k in range(K):
+            s.A[k], s.H[k] = self.A[k].data_ptr(), self.H[k].data_ptr()
+        self.c = s
+
+
+def lp_sample_blocks(g: Csr, e_src: torch.Tensor, e_dst: torch.Tensor, fanout: List[int], seed: int, step: int,
+                     blocks: Optional[Blocks] = None) -> Blocks:
+    _need(e_src, torch.int32, "e_src")
+    _need(e_dst, torch.int32, "e_dst")
+    if blocks is None:
+        blocks = Blocks(g, int(e_src.numel()), fanout)
+    _check(load_library().lp_sample_blocks(C.byref(g.c), blocks.B, _ptr(e_src), _ptr(e_dst), blocks.K, blocks.fan_c, seed, step,
+                                           C.byref(blocks.c), _ptr(blocks.sample_ws), blocks.sample_ws.numel(), _stream()),
+           "lp_sample_blocks")
+    return blocks
+
+
+def lp_sage_forward_blocks(b: Blocks, m: Model, X: torch.Tensor, acts: Optional[BlockActs] = None,
+                           ws: Optional[torch.Tensor] = None) -> BlockActs:
+    lib = load_library()
+    _need(X, m.torch_dtype, "X")
+    if acts is None:
+        acts = BlockActs(b, m.dims, X.device, m.torch_dtype)
+    if ws is None:
+        ws = _ws(lib.lp_forward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)), X.device)
+    _check(lib.lp_sage_forward_blocks(C.byref(b.c), C.byref(m.c), _ptr(X), _ptr(acts.X_frontier), C.byref(acts.c), _ptr(ws),
+                                      ws.numel(), _stream()), "lp_sage_forward_blocks")
+    return acts
+
+
+def lp_backward_blocks(b: Blocks, m: Model, acts: BlockActs, dscore: torch.Tensor, grads: Optional[Grads] = None,
+                       ws: Optional[torch.Tensor] = None) -> Grads:
+    lib = load_library()
+    _need(dscore, torch.float32, "dscore")
+    dev = dscore.device
+    if grads is None:
+        grads = Grads(1, m.dims, dev, False, m.torch_dtype)
+    if ws is None:
+        ws = _ws(lib.lp_backward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)), dev)
+    _check(lib.lp_backward_blocks(C.byref(b.c), C.byref(m.c), _ptr(acts.X_frontier), C.byref(acts.c), _ptr(dscore),
+                                  C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward_blocks")
+    return grads
+
+
+def forward_blocks_workspace_bytes(m: Model, b: Blocks) -> int:
+    return int(load_library().lp_forward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)))
+
+
+def backward_blocks_workspace_bytes(m: Model, b: Blocks) -> int:
+    return int(load_library().lp_backward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)))
 
 
 class AdamState:

@@ -59,6 +59,7 @@ struct SpmmArgs {
     const void *addend = nullptr;        // optional [n_rows, F]
     const int32_t *in_index = nullptr;   // optional [number of nodes]: row of `in` / `addend` that holds a node, or < 0
     const int32_t *n_rows_dev = nullptr; // optional device scalar: rows actually present (<= n_rows)
+    const int32_t *addend_rows_dev = nullptr;  // optional device scalar: only rows below it have an addend row
     const void *gate = nullptr;          // optional [n_rows, F]: output is zeroed where gate <= 0
     void *out = nullptr;
     int64_t n_entries = 0;               // entries of colidx (bounds how many rows can be long)
@@ -145,6 +146,17 @@ int lp_bits_for(int64_t n_values);
 size_t lp_compact_rows_ws_bytes(int32_t n_rows);
 int lp_launch_compact_rows(const int32_t *offsets, int32_t n_rows, int32_t *list, int32_t *index, int32_t *ptr,
                            int32_t *count_dev, void *scan_ws, hipStream_t stream);
+
+// ---------------------------------------------------------------- scored edges grouped by end point (sage_layers.hip)
+// Every scored edge (u, v) with weight g = dL/ds sends g*h_v to row u and g*h_u to row v.  The 2B (row, other end,
+// g) entries are grouped by row with a stable radix sort: ptr [n_rows + 1], col / w [2B] in row order.  Edges with
+// an end outside [0, n_rows) are left out.
+struct BatchGroupWs {
+    uint64_t *keys_a, *keys_b;  // [2B + 1] each
+    uint32_t *hist;             // lp_radix_sort_hist_words(2B + 1)
+};
+int lp_group_batch_by_row(const int32_t *e_src, const int32_t *e_dst, const float *dscore, int64_t B, int32_t n_rows,
+                          const BatchGroupWs &ws, int32_t *ptr, int32_t *col, float *w, hipStream_t stream);
 
 // ---------------------------------------------------------------- storage types
 // LP_F32 matrices hold floats; LP_BF16 matrices hold raw bfloat16 bit patterns (uint16_t).  All arithmetic is fp32.

@@ -131,6 +131,19 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
 
 }  // namespace
 
+int lp_group_batch_by_row(const int32_t *e_src, const int32_t *e_dst, const float *dscore, int64_t B, int32_t n_rows,
+                          const BatchGroupWs &ws, int32_t *ptr, int32_t *col, float *w, hipStream_t st) {
+    const int64_t n2 = 2 * B;
+    const unsigned g2 = (unsigned)lp_ceil_div(n2, 256);
+    hipLaunchKernelGGL(batch_keys_kernel, dim3(g2), dim3(256), 0, st, e_src, e_dst, B, n_rows, ws.keys_a);
+    int status;
+    const uint64_t *sorted = lp_radix_sort(ws.keys_a, ws.keys_b, n2, 32, lp_bits_for((int64_t)n_rows + 1), ws.hist, st, &status);
+    LP_TRY(status);
+    LP_TRY(lp_launch_row_offsets(sorted, n2, nullptr, n_rows, 32, ptr, st));
+    hipLaunchKernelGGL(batch_entries_kernel, dim3(g2), dim3(256), 0, st, sorted, B, e_src, e_dst, dscore, n_rows, col, w);
+    return lp_after_launch();
+}
+
 extern "C" size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
     if (check_model(m) != LP_OK || n_nodes <= 0) return 0;
     return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m)) + lp_spmm_queue_bytes(n_nodes);
@@ -236,17 +249,10 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     const int32_t cap = touched_cap(N, B);
     {
         const int64_t n2 = 2 * B;
-        const unsigned g2 = (unsigned)lp_ceil_div(n2, 256);
-        const uint64_t *sorted;
         {
             LpTimedScope timed(LP_KC_SCATTER, st);
-            hipLaunchKernelGGL(batch_keys_kernel, dim3(g2), dim3(256), 0, st, e_src, e_dst, B, N, w.keys_a);
-            int status;
-            sorted = lp_radix_sort(w.keys_a, w.keys_b, n2, 32, lp_bits_for((int64_t)N + 1), w.hist, st, &status);
-            LP_TRY(status);
-            LP_TRY(lp_launch_row_offsets(sorted, n2, nullptr, N, 32, w.bptr, st));
-            hipLaunchKernelGGL(batch_entries_kernel, dim3(g2), dim3(256), 0, st, sorted, B, e_src, e_dst, dscore, N, w.bcol, w.bw);
-            LP_TRY(lp_after_launch());
+            BatchGroupWs gw{w.keys_a, w.keys_b, w.hist};
+            LP_TRY(lp_group_batch_by_row(e_src, e_dst, dscore, B, N, gw, w.bptr, w.bcol, w.bw, st));
             LP_TRY(lp_launch_compact_rows(w.bptr, N, w.touched, w.touched_index, w.touched_ptr, w.n_touched, w.compact_ws, st));
         }
         SpmmArgs sc;

@@ -91,7 +91,8 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
 #pragma unroll
     for (int e = 0; e < VE; ++e) y[e] = sum[e] * scale;
     if (a.addend) {
-        const int32_t ar = a.in_index ? a.in_index[v] : v;
+        int32_t ar = a.in_index ? a.in_index[v] : v;
+        if (a.addend_rows_dev && v >= *a.addend_rows_dev) ar = -1;
         if (ar >= 0) {
             float t[VE];
             LpVec<T>::load(static_cast<const T *>(a.addend) + ((int64_t)ar * FV + colv) * VE, t);
