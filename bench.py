@@ -131,6 +131,88 @@ def sparsify_task(args):
     print(json.dumps(out), flush=True)
 
 
+def sampled_step_task(args):
+    """Third measurement: the paper's own mini-batch mode.  One step = negatives, sampled computational graph
+    (fan-outs 25/10/5), forward, loss, backward and an Adam update, for one batch of --n-pos positives."""
+    import numpy as np
+    import torch
+
+    import paper_2506_20818_amd as lp
+    from paper_2506_20818_amd import binding as B
+    from lp_workloads import make_workload
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = make_workload(args.workload)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+    g = lp.lp_build_csr(wl.n_nodes, i32(wl.src), i32(wl.dst), True)
+    bf16 = wl.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32
+    model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+    X = st(wl.X)
+    n_pos = min(args.n_pos, wl.n_pos)
+    k_neg = wl.k_neg
+    Bn = n_pos * (1 + k_neg)
+    fanout = [int(x) for x in args.fanout.split(",")]
+    pos_src = i32(wl.pos_src[:n_pos])
+    e_src = torch.empty(Bn, dtype=torch.int32, device=dev)
+    e_dst = torch.empty(Bn, dtype=torch.int32, device=dev)
+    e_src[:n_pos] = pos_src
+    e_dst[:n_pos] = i32(wl.pos_dst[:n_pos])
+    neg_src, neg_dst = e_src[n_pos:], e_dst[n_pos:]
+    blocks = lp.Blocks(g, Bn, fanout)
+    acts = lp.BlockActs(blocks, wl.dims, dev, tdt)
+    grads = lp.Grads(1, wl.dims, dev, dtype=tdt)
+    adam = lp.AdamState(model)
+    ws_f = torch.empty(B.forward_blocks_workspace_bytes(model, blocks), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(B.backward_blocks_workspace_bytes(model, blocks), dtype=torch.uint8, device=dev)
+    ws_l = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    scores = torch.empty(Bn, dtype=torch.float32, device=dev)
+    dscore = torch.empty(Bn, dtype=torch.float32, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    counter = [0]
+
+    def step(i):
+        counter[0] += 1
+        lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
+        lp.lp_sample_blocks(g, e_src, e_dst, fanout, wl.sampler_seed + 1, i, blocks)
+        lp.lp_sage_forward_blocks(blocks, model, X, acts, ws_f)
+        lp.lp_score_loss(acts.H[-1], blocks.e_src_pos, blocks.e_dst_pos, n_pos, scores, loss, dscore, ws_l)
+        lp.lp_backward_blocks(blocks, model, acts, dscore, grads, ws_b)
+        lp.lp_adam_step(model, grads, adam, counter[0], lr=1e-3)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    first_loss = None
+    lp.lp_timing_enable(True)
+    lp.lp_timing_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(1000 + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    classes = lp.lp_timing_collect()
+    lp.lp_timing_enable(False)
+    ms = dt * 1e3 / max(args.steps, 1)
+    frontiers = [int(x) for x in blocks.n.cpu().tolist()]
+    entries = [int(blocks.ptr[k][frontiers[k + 1]].item()) for k in range(len(fanout))]
+    out = {"metric": "sampled-neighbourhood train-step edges/sec (pos+neg), Adam update included, on 1 MI355X",
+           "value": round(Bn / (ms * 1e-3), 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+           "config": {"workload": "%s graph (%d nodes, %d directed entries), GraphSAGE-mean %s, %d positives + %d negatives per "
+                                  "step, fan-outs %s (first hop first)" % (args.workload, wl.n_nodes, g.nnz, "->".join(map(str, wl.dims)),
+                                                                           n_pos, n_pos * k_neg, fanout),
+                      "frontier_sizes_layer0_to_K": frontiers, "block_entries_layer1_to_K": entries},
+           "loss": round(float(loss.item()), 6),
+           "kernel_ms_per_step": {k: round(v[0] / max(args.steps, 1), 4) for k, v in classes.items()}}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,8 +221,11 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--cpu-scale", type=float, default=0.25, help="fraction of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify"],
-                    help="train_step: the headline metric; sparsify: the sparsification pass over all partitions")
+    ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
+                    help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "
+                         "sampled_step: the mini-batch mode with sampled neighbourhoods")
+    ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
+    ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
     ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a dispatch of known size for counter runs)")
@@ -152,6 +237,8 @@ def main():
 
     if args.task == "sparsify":
         return sparsify_task(args)
+    if args.task == "sampled_step":
+        return sampled_step_task(args)
 
     import numpy as np
     import torch

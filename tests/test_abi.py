@@ -181,3 +181,71 @@ def test_optimizer_steps_reject_bad_arguments_on_the_host():
     assert adam(eps=-1.0) == -1
     assert adam(s=B._OptStateStruct()) == -1
     assert adam(g=B._GradsStruct()) == -1
+
+
+def _blocks(K=3, n_graph=1000, n_edges=64, fan=(25, 10, 5), nnz=5000):
+    lib = B.load_library()
+    b = B._BlocksStruct()
+    b.n_layers, b.n_graph_nodes, b.n_edges = K, n_graph, n_edges
+    cap = (C.c_int32 * (K + 1))()
+    cap_e = (C.c_int64 * K)()
+    fan_c = (C.c_int32 * K)(*fan)
+    assert lib.lp_blocks_bounds(n_graph, nnz, n_edges, K, fan_c, cap, cap_e) == 0
+    for k in range(K + 1):
+        b.cap[k] = cap[k]
+    for k in range(K):
+        b.cap_entries[k] = cap_e[k]
+        b.ptr[k] = b.col[k] = b.inv_cnt[k] = b.t_ptr[k] = b.t_col[k] = 0x1000
+    b.n = b.nodes = b.index = b.e_src_pos = b.e_dst_pos = 0x1000
+    return b, fan_c
+
+
+def test_blocks_bounds_and_argument_checks_on_the_host():
+    lib = B.load_library()
+    cap = (C.c_int32 * 4)()
+    cap_e = (C.c_int64 * 3)()
+    fan = (C.c_int32 * 3)(25, 10, 5)
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, fan, cap, cap_e) == 0
+    assert list(cap) == [1000, 1000, 416, 16] and list(cap_e) == [5000, 4160, 400]      # min(N, c(1+f)), min(nnz, c f)
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 0, fan, cap, cap_e) == -1
+    assert lib.lp_blocks_bounds(0, 5000, 8, 3, fan, cap, cap_e) == -1
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(25, 0, 5), cap, cap_e) == -4
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(25, 65, 5), cap, cap_e) == -4
+    assert lib.lp_blocks_bounds(1000, 5000, 1 << 30, 3, fan, cap, cap_e) == -2
+    assert lib.lp_sample_blocks_workspace_bytes(1000, 5000, 8, 3, fan) > 0
+    g = _csr(n=1000, nnz=5000)
+    b, fan_c = _blocks()
+    p = C.c_void_p(0x1000)
+    sb = lambda graph=g, B_=64, es=p, blk=b, ws=p, wsb=1 << 40, K=3: lib.lp_sample_blocks(
+        C.byref(graph), B_, es, p, K, fan_c, 1, 2, C.byref(blk), ws, wsb, None)
+    assert sb(es=None) == -1
+    assert sb(B_=32) == -1                                 # the blocks were sized for another batch
+    assert sb(K=2) == -1
+    assert sb(ws=None) == -3
+    assert sb(wsb=64) == -3
+    small, _ = _blocks()
+    small.cap[0] = 10                                      # below the bound (and below cap[1])
+    assert sb(blk=small) == -1
+    no_ptr, _ = _blocks()
+    no_ptr.ptr[1] = None
+    assert sb(blk=no_ptr) == -1
+    m = _model([128, 256, 256, 256])
+    acts, grads = B._ActsStruct(), B._GradsStruct()
+    for k in range(3):
+        acts.A[k] = acts.H[k] = 0x1000
+        grads.dW_self[k] = grads.dW_neigh[k] = grads.dbias[k] = 0x1000
+    fwd = lambda model=m, blk=b, x=p, xf=p, ws=p, wsb=1 << 40: lib.lp_sage_forward_blocks(
+        C.byref(blk), C.byref(model), x, xf, C.byref(acts), ws, wsb, None)
+    assert fwd(model=_model([128, 256, 256])) == -1        # layer count differs from the blocks'
+    assert fwd(model=_model([128, 256, 256, 250])) == -4
+    assert fwd(x=None) == -1
+    assert fwd(xf=C.c_void_p(0x1004)) == -1
+    assert fwd(ws=None) == -3
+    bwd = lambda blk=b, ds=p, gr=grads, ws=p, wsb=1 << 40: lib.lp_backward_blocks(
+        C.byref(blk), C.byref(m), p, C.byref(acts), ds, C.byref(gr), ws, wsb, None)
+    assert bwd(ds=None) == -1
+    assert bwd(gr=B._GradsStruct()) == -1
+    assert bwd(ws=None) == -3
+    assert bwd(wsb=128) == -3
+    assert lib.lp_backward_blocks_workspace_bytes(C.byref(m), C.byref(b)) > 0
+    assert lib.lp_forward_blocks_workspace_bytes(C.byref(_model([128, 256])), C.byref(b)) == 0
