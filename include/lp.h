@@ -59,6 +59,12 @@ enum {
     LP_BF16 = 1 /* bfloat16 storage (features, weights, activations), fp32 accumulation, fp32 gradients */
 };
 
+/* layer types of lp_model */
+enum {
+    LP_LAYER_SAGE_MEAN = 0, /* z_v = h_v W_self + mean_{u in N(v)} h_u W_neigh + b */
+    LP_LAYER_GCN = 1        /* z_v = sum_{u in N(v)} h_u / sqrt(|N(v)| |N(u)|) W_neigh + b; W_self is not used */
+};
+
 /* flags of lp_build_csr */
 #define LP_SYMMETRIZE 1u /* every input pair (r, c) also counts as (c, r) */
 
@@ -78,14 +84,19 @@ typedef struct lp_csr {
     const int32_t *t_row_order;/* device [n_nodes] or NULL: same for the transposed CSR */
 } lp_csr;
 
-/* K-layer GraphSAGE-mean model.  Layer k = 1..K maps width dims[k-1] to dims[k]:
- *   z_v = h_v W_self[k-1] + mean_{u in N(v)} h_u W_neigh[k-1] + bias[k-1]
+/* K-layer model.  Layer k = 1..K maps width dims[k-1] to dims[k]:
+ *   LP_LAYER_SAGE_MEAN (GraphSAGE with mean aggregator, the model of the benchmark configurations):
+ *     z_v = h_v W_self[k-1] + mean_{u in N(v)} h_u W_neigh[k-1] + bias[k-1]
+ *   LP_LAYER_GCN (the paper's second representative model, "Hyperparameters"; the graph convolution of Kipf and
+ *   Welling): z_v = sum_{u in N(v)} h_u / sqrt(|N(v)| |N(u)|) W_neigh[k-1] + bias[k-1], on a CSR that already
+ *     contains the self-pair (v, v) of every node (append them to the pair list given to lp_build_csr), so that
+ *     |N(v)| is the degree plus one.  W_self and dW_self are ignored and may be NULL.
  *   h'_v = max(z_v, 0) for k < K and z_v for k = K. */
 typedef struct lp_model {
     int32_t n_layers;                     /* K, 1..LP_MAX_LAYERS */
     int32_t dtype;                        /* LP_F32 or LP_BF16: storage of X, W_self, W_neigh, A and H */
     int32_t dims[LP_MAX_LAYERS + 1];      /* F_0 .. F_K */
-    int32_t reserved_;
+    int32_t layer_type;                   /* LP_LAYER_SAGE_MEAN or LP_LAYER_GCN */
     const void *W_self[LP_MAX_LAYERS];    /* device [F_{k-1}, F_k] */
     const void *W_neigh[LP_MAX_LAYERS];   /* device [F_{k-1}, F_k] */
     const void *bias[LP_MAX_LAYERS];      /* device [F_k], always fp32 */

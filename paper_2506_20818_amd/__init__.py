@@ -5,6 +5,8 @@ runs in the HIP kernels of liblp_mi355x.so.  There is no CPU fallback: importing
 library raises.
 """
 from .binding import (  # noqa: F401
+    LP_LAYER_GCN,
+    LP_LAYER_SAGE_MEAN,
     LP_SYMMETRIZE,
     Acts,
     AdamState,

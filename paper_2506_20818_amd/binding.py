@@ -14,6 +14,8 @@ LP_MAX_LAYERS = 8
 LP_SYMMETRIZE = 1
 LP_F32 = 0
 LP_BF16 = 1
+LP_LAYER_SAGE_MEAN = 0
+LP_LAYER_GCN = 1
 
 _TORCH_OF = {LP_F32: torch.float32, LP_BF16: torch.bfloat16}
 _LP_OF = {torch.float32: LP_F32, torch.bfloat16: LP_BF16}
@@ -36,7 +38,7 @@ class _CsrStruct(C.Structure):
 
 class _ModelStruct(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("dtype", C.c_int32), ("dims", C.c_int32 * (LP_MAX_LAYERS + 1)),
-                ("reserved_", C.c_int32),
+                ("layer_type", C.c_int32),
                 ("W_self", C.c_void_p * LP_MAX_LAYERS), ("W_neigh", C.c_void_p * LP_MAX_LAYERS),
                 ("bias", C.c_void_p * LP_MAX_LAYERS)]
 
@@ -174,27 +176,36 @@ class Model:
     """Weights of the K layers: W_self[k], W_neigh[k] of shape [F_{k-1}, F_k] (float32 or bfloat16, which selects
     the storage type of the whole model) and bias[k] of shape [F_k] (always float32)."""
 
-    def __init__(self, W_self: List[torch.Tensor], W_neigh: List[torch.Tensor], bias: List[torch.Tensor]):
-        K = len(W_self)
-        if not (1 <= K <= LP_MAX_LAYERS and len(W_neigh) == K and len(bias) == K):
+    def __init__(self, W_self: Optional[List[torch.Tensor]], W_neigh: List[torch.Tensor], bias: List[torch.Tensor],
+                 layer_type: int = LP_LAYER_SAGE_MEAN):
+        """layer_type LP_LAYER_GCN: one weight matrix per layer (given as W_neigh), W_self is None."""
+        K = len(W_neigh)
+        gcn = layer_type == LP_LAYER_GCN
+        if W_self is None:
+            W_self = [None] * K
+        if not (1 <= K <= LP_MAX_LAYERS and len(W_self) == K and len(bias) == K):
             raise ValueError("bad layer count")
+        self.layer_type = layer_type
         self.W_self, self.W_neigh, self.bias = list(W_self), list(W_neigh), list(bias)
-        self.dims = [int(W_self[0].shape[0])] + [int(w.shape[1]) for w in W_self]
-        self.torch_dtype = W_self[0].dtype
+        self.dims = [int(W_neigh[0].shape[0])] + [int(w.shape[1]) for w in W_neigh]
+        self.torch_dtype = W_neigh[0].dtype
         if self.torch_dtype not in _LP_OF:
             raise ValueError("weights must be float32 or bfloat16")
         self.dtype = _LP_OF[self.torch_dtype]
         s = _ModelStruct()
-        s.n_layers, s.dtype = K, self.dtype
+        s.n_layers, s.dtype, s.layer_type = K, self.dtype, layer_type
         for k in range(K + 1):
             s.dims[k] = self.dims[k]
         for k in range(K):
             for t, nm in ((W_self[k], "W_self"), (W_neigh[k], "W_neigh")):
+                if t is None and gcn and nm == "W_self":
+                    continue
                 _need(t, self.torch_dtype, nm)
                 if tuple(t.shape) != (self.dims[k], self.dims[k + 1]):
                     raise ValueError("%s[%d] has the wrong shape" % (nm, k))
             _need(bias[k], torch.float32, "bias")
-            s.W_self[k], s.W_neigh[k], s.bias[k] = W_self[k].data_ptr(), W_neigh[k].data_ptr(), bias[k].data_ptr()
+            s.W_self[k] = W_self[k].data_ptr() if W_self[k] is not None else None
+            s.W_neigh[k], s.bias[k] = W_neigh[k].data_ptr(), bias[k].data_ptr()
         self.c = s
 
 
@@ -421,7 +432,7 @@ class AdamState:
     """Zero-initialised first and second moments for every parameter tensor of a model."""
 
     def __init__(self, m: Model):
-        z = lambda t: torch.zeros(t.shape, dtype=torch.float32, device=t.device)
+        z = lambda t: torch.zeros(t.shape if t is not None else (1,), dtype=torch.float32, device=m.bias[0].device)
         self.m_W_self, self.m_W_neigh, self.m_bias = [z(t) for t in m.W_self], [z(t) for t in m.W_neigh], [z(t) for t in m.bias]
         self.v_W_self, self.v_W_neigh, self.v_bias = [z(t) for t in m.W_self], [z(t) for t in m.W_neigh], [z(t) for t in m.bias]
         s = _OptStateStruct()

@@ -191,6 +191,7 @@ int check_blocks(const lp_blocks *b, bool need_transposed) {
 int check_block_model(const lp_model *m, const lp_blocks *b) {
     if (!m || m->n_layers != b->n_layers) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (m->layer_type != LP_LAYER_SAGE_MEAN) return LP_ERR_UNSUPPORTED;  // sampled blocks: GraphSAGE-mean layers only
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
         if ((m->dims[k] % lp_vec_elems(m->dtype)) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;

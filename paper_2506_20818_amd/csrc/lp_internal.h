@@ -55,6 +55,8 @@ struct SpmmArgs {
     const int32_t *row_order = nullptr;  // optional processing order
     const float *inv_deg = nullptr;      // optional per-output-row scale
     const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
+    bool sym_norm = false;               // symmetric normalisation: entry p weighs sqrt(inv_deg[colidx[p]]), row v is
+                                         // scaled by sqrt(inv_deg[v]) (inv_deg required, w unused)
     const void *in = nullptr;
     const void *addend = nullptr;        // optional [n_rows, F]
     const int32_t *in_index = nullptr;   // optional [number of nodes]: row of `in` / `addend` that holds a node, or < 0

@@ -56,6 +56,7 @@ __global__ __launch_bounds__(256) void adam_kernel(TensorTable t, float lr, floa
 int fill_table(const lp_model *m, const lp_grads *g, const lp_opt_state *s, bool need_state, TensorTable &t, int64_t &n_max) {
     if (!m || !g || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
     if (need_state && !s) return LP_ERR_INVALID_ARG;
     t.count = 0;
     n_max = 0;
@@ -67,6 +68,7 @@ int fill_table(const lp_model *m, const lp_grads *g, const lp_opt_state *s, bool
         float *mo[3] = {s ? s->m_W_self[k] : nullptr, s ? s->m_W_neigh[k] : nullptr, s ? s->m_bias[k] : nullptr};
         float *ve[3] = {s ? s->v_W_self[k] : nullptr, s ? s->v_W_neigh[k] : nullptr, s ? s->v_bias[k] : nullptr};
         for (int j = 0; j < 3; ++j) {
+            if (j == 0 && m->layer_type == LP_LAYER_GCN) continue;  // a GCN layer has no self weight
             if (!w[j] || !gr[j] || (need_state && (!mo[j] || !ve[j]))) return LP_ERR_INVALID_ARG;
             const int i = t.count++;
             t.w[i] = const_cast<void *>(w[j]);

@@ -9,13 +9,15 @@ namespace {
 int check_model(const lp_model *m) {
     if (!m || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
+    const bool has_self = m->layer_type == LP_LAYER_SAGE_MEAN;
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
         if ((m->dims[k] % lp_vec_elems(m->dtype)) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;
     }
     for (int k = 0; k < m->n_layers; ++k) {
-        if (!m->W_self[k] || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
-        if (!lp_aligned16(m->W_self[k]) || !lp_aligned16(m->W_neigh[k])) return LP_ERR_INVALID_ARG;
+        if ((has_self && !m->W_self[k]) || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
+        if ((has_self && !lp_aligned16(m->W_self[k])) || !lp_aligned16(m->W_neigh[k])) return LP_ERR_INVALID_ARG;
     }
     return LP_OK;
 }
@@ -162,6 +164,7 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
     char *wt = static_cast<char *>(ws);
     int32_t *long_queue = reinterpret_cast<int32_t *>(wt + lp_align_up(eb * transposed_weight_elems(m)));
     const int K = m->n_layers;
+    const bool gcn = m->layer_type == LP_LAYER_GCN;
     const void *Hprev = X;
     for (int k = 1; k <= K; ++k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
@@ -175,6 +178,7 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         sp.colidx = g->colidx;
         sp.row_order = g->row_order;
         sp.inv_deg = g->inv_deg;
+        sp.sym_norm = gcn;   // 1/sqrt(d_v d_u) per entry instead of 1/d_v per row
         sp.n_entries = g->nnz;
         sp.long_queue = long_queue;
         sp.in = Hprev;
@@ -184,7 +188,7 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
         void *WsT = wt, *WnT = wt + wbytes;
         wt += 2 * wbytes;
-        LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
+        if (!gcn) LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
         LP_TRY(lp_launch_transpose(m->W_neigh[k - 1], Fi, Fo, WnT, dt, st));
         GemmNtArgs ge;
         ge.dtype = dt;
@@ -193,7 +197,8 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         ge.n_split = Fo;
         ge.A[0] = Hprev; ge.A[1] = A;
         ge.lda[0] = ge.lda[1] = Fi;
-        ge.K[0] = ge.K[1] = Fi;
+        ge.K[0] = gcn ? 0 : Fi;   // no self path in a GCN layer
+        ge.K[1] = Fi;
         ge.Bt[0][0] = WsT; ge.Bt[1][0] = WnT;
         ge.ldb[0] = ge.ldb[1] = Fi;
         ge.bias = static_cast<const float *>(m->bias[k - 1]);
@@ -221,8 +226,9 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     if (B > 0 && (!e_src || !e_dst || !dscore)) return LP_ERR_INVALID_ARG;
     if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
     const int K = m->n_layers;
+    const bool gcn = m->layer_type == LP_LAYER_GCN;
     for (int k = 0; k < K; ++k)
-        if (!out->dW_self[k] || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
+        if ((!gcn && !out->dW_self[k]) || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
     if (out->dX && !lp_aligned16(out->dX)) return LP_ERR_INVALID_ARG;
     if (!ws || ws_bytes < lp_backward_workspace_bytes(m, g->n_nodes, B)) return LP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -235,7 +241,7 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
     if (B == 0) {  // an empty batch has a zero loss: every gradient is zero
         for (int k = 0; k < K; ++k) {
             const int64_t nw = (int64_t)m->dims[k] * m->dims[k + 1];
-            LP_TRY(lp_launch_zero(out->dW_self[k], nw, st));
+            if (!gcn) LP_TRY(lp_launch_zero(out->dW_self[k], nw, st));
             LP_TRY(lp_launch_zero(out->dW_neigh[k], nw, st));
             LP_TRY(lp_launch_zero(out->dbias[k], m->dims[k + 1], st));
         }
@@ -280,23 +286,31 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         tn.Mw = Fi; tn.Nw = Fo;
         tn.B = dZ; tn.ldb = Fo;
         tn.partials = w.tn_partials;
-        tn.At = Hin; tn.lda = Fi; tn.C = out->dW_self[k - 1];
-        LP_TRY(lp_launch_gemm_tn(tn, st));
+        tn.lda = Fi;
+        if (!gcn) {
+            tn.At = Hin; tn.C = out->dW_self[k - 1];
+            LP_TRY(lp_launch_gemm_tn(tn, st));
+        }
         tn.At = Ak; tn.C = out->dW_neigh[k - 1];
         LP_TRY(lp_launch_gemm_tn(tn, st));
         if (k == 1 && !out->dX) break;
-        // [dZ W_self^T | diag(inv_deg) dZ W_neigh^T] -> Q, R
         GemmNtArgs ge;
         ge.dtype = dt;
         ge.M = rows; ge.m_dev = rows_dev;
-        ge.N = 2 * Fi; ge.n_split = Fi;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
-        ge.Bt[0][0] = m->W_self[k - 1];
-        ge.Bt[0][1] = m->W_neigh[k - 1];
         ge.ldb[0] = Fo;
-        ge.rowscale = g->inv_deg; ge.rowscale_index = row_of;
-        ge.C[0] = Q; ge.C[1] = R;
-        ge.ldc[0] = ge.ldc[1] = Fi;
+        if (gcn) {   // dZ W^T -> R; the normalisation is applied by the aggregation that follows
+            ge.N = Fi; ge.n_split = Fi;
+            ge.Bt[0][0] = m->W_neigh[k - 1];
+            ge.C[0] = R; ge.ldc[0] = Fi;
+        } else {     // [dZ W_self^T | diag(inv_deg) dZ W_neigh^T] -> Q, R
+            ge.N = 2 * Fi; ge.n_split = Fi;
+            ge.Bt[0][0] = m->W_self[k - 1];
+            ge.Bt[0][1] = m->W_neigh[k - 1];
+            ge.rowscale = g->inv_deg; ge.rowscale_index = row_of;
+            ge.C[0] = Q; ge.C[1] = R;
+            ge.ldc[0] = ge.ldc[1] = Fi;
+        }
         LP_TRY(lp_launch_gemm_nt(ge, st));
         // G^{k-1} = (Q + sum over the transposed CSR of R) gated by relu'(z^{k-1}) = [h^{k-1} > 0]
         SpmmArgs sp;
@@ -304,7 +318,8 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         sp.n_rows = N; sp.F = Fi;
         sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
         sp.n_entries = g->nnz; sp.long_queue = w.long_queue;
-        sp.in = R; sp.addend = Q;
+        sp.in = R; sp.addend = gcn ? nullptr : Q;
+        if (gcn) { sp.inv_deg = g->inv_deg; sp.sym_norm = true; }
         sp.in_index = listed ? w.touched_index : nullptr;
         sp.gate = k > 1 ? Hin : nullptr;
         if (listed) {

@@ -38,9 +38,9 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
     for (int32_t base = first; base < hi; base += stride) {
         const int cnt = min(64, hi - base);
         int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
-        if (a.in_index) mine = lane < cnt ? a.in_index[mine] : -1;  // row of `in` that holds the neighbour, < 0: a zero row
         float mine_w = 1.f;
-        if (W) mine_w = lane < cnt ? a.w[base + lane] : 0.f;
+        if (W) mine_w = lane < cnt ? (a.sym_norm ? sqrtf(a.inv_deg[mine]) : a.w[base + lane]) : 0.f;
+        if (a.in_index) mine = lane < cnt ? a.in_index[mine] : -1;  // row of `in` that holds the neighbour, < 0: a zero row
         for (int j0 = 0; j0 < cnt; j0 += P * U) {
             float x[U][C][VE];
             float wj[U];
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     accumulate_blocks<T, G, C, W, 4>(a, static_cast<const T *>(a.in), lo, hi, 64, lane, acc);
     fold_groups<G, C, VE>(acc);
     if (sub != 0 || fl >= FV) return;
-    const float scale = a.inv_deg ? a.inv_deg[v] : 1.0f;
+    const float scale = a.inv_deg ? (a.sym_norm ? sqrtf(a.inv_deg[v]) : a.inv_deg[v]) : 1.0f;
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int colv = fl + 64 * c;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
             for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
         accumulate_blocks<T, G, C, W, U>(a, static_cast<const T *>(a.in), lo + 64 * wave, hi, 64 * kLongWaves, lane, acc);
         fold_groups<G, C, VE>(acc);
-        const float scale = a.inv_deg ? a.inv_deg[v] : 1.0f;
+        const float scale = a.inv_deg ? (a.sym_norm ? sqrtf(a.inv_deg[v]) : a.inv_deg[v]) : 1.0f;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             if (sub == 0) {
@@ -188,7 +188,8 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
 template <typename T, int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
     const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kThreads / 64);
-    if (a.w) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, true>), dim3(grid), dim3(kThreads), 0, st, a);
+    const bool weighted = a.w || a.sym_norm;
+    if (weighted) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, true>), dim3(grid), dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, false>), dim3(grid), dim3(kThreads), 0, st, a);
     if (a.long_queue) {
         // no more rows can be queued than fit the entry count; two workgroups per compute unit walk the queue
@@ -196,7 +197,7 @@ int launch(const SpmmArgs &a, hipStream_t st) {
         const int64_t slots = 2 * (int64_t)lp_compute_units();
         const unsigned lgrid = (unsigned)(most < slots ? most : slots);
         if (lgrid > 0) {
-            if (a.w) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, true>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            if (weighted) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, true>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
             else hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, false>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
         }
     }
@@ -222,6 +223,7 @@ size_t lp_spmm_queue_bytes(int32_t n_rows) { return lp_align_up(sizeof(int32_t) 
 int lp_launch_spmm(const SpmmArgs &args, hipStream_t st) {
     if (args.n_rows <= 0) return LP_OK;
     if (args.F <= 0 || args.F % lp_vec_elems(args.dtype)) return LP_ERR_UNSUPPORTED;
+    if (args.sym_norm && !args.inv_deg) return LP_ERR_INVALID_ARG;
     SpmmArgs a = args;
     a.long_threshold = kSpmmLongRow;
     if (a.n_entries < a.long_threshold) a.long_queue = nullptr;  // no row can be that long
