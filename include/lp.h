@@ -43,6 +43,7 @@ extern "C" {
 #endif
 
 #define LP_MAX_LAYERS 8
+#define LP_MAX_MLP_LAYERS 4 /* linear layers of the MLP edge predictor */
 #define LP_MAX_FANOUT 64 /* most neighbours one node may draw per hop in lp_sample_blocks */
 
 enum {
@@ -138,6 +139,28 @@ typedef struct lp_blocks {
     int32_t *t_col[LP_MAX_LAYERS];          /* device [cap_entries[k-1]]: positions in frontier k, by entry index */
     int32_t *e_src_pos, *e_dst_pos;         /* device [B]: the scored edges in positions of frontier K (-1: id out of range) */
 } lp_blocks;
+
+/* MLP edge predictor: x_e = h_u * h_v (element-wise), u^j = relu(u^(j-1) W[j-1] + bias[j-1]) for j < L,
+ * s_e = u^(L-1) W[L-1] + bias[L-1].  dims[0] = width of the embeddings, dims[L] = 1. */
+typedef struct lp_mlp {
+    int32_t n_layers;                       /* L, 1..LP_MAX_MLP_LAYERS */
+    int32_t dtype;                          /* LP_F32 or LP_BF16: storage of W, of the products and of the hidden layers */
+    int32_t dims[LP_MAX_MLP_LAYERS + 1];
+    int32_t reserved_;
+    const void *W[LP_MAX_MLP_LAYERS];       /* device [dims[j], dims[j+1]] */
+    const float *bias[LP_MAX_MLP_LAYERS];   /* device [dims[j+1]], fp32 */
+} lp_mlp;
+
+/* Written by lp_mlp_score_loss, read by lp_mlp_backward. */
+typedef struct lp_mlp_acts {
+    void *X;                                /* device [B, dims[0]]: products of the end-point embeddings */
+    void *U[LP_MAX_MLP_LAYERS];             /* U[j-1]: device [B, dims[j]], hidden layer j = 1..L-1 */
+} lp_mlp_acts;
+
+typedef struct lp_mlp_grads {
+    float *dW[LP_MAX_MLP_LAYERS];           /* device [dims[j], dims[j+1]], fp32 */
+    float *dbias[LP_MAX_MLP_LAYERS];        /* device [dims[j+1]], fp32 */
+} lp_mlp_grads;
 
 /* Adam moments, one fp32 array per parameter tensor, same shapes as lp_grads; the caller zeroes them before the
  * first lp_adam_step. */
@@ -338,6 +361,35 @@ int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, const void *X,
 size_t lp_backward_blocks_workspace_bytes(const lp_model *m, const lp_blocks *b);
 int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved, const float *dscore,
                        lp_grads *out, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * MLP edge predictor (Eq. 2 with the MLP the paper's experiments use, see
+ * "Hyperparameters": a 3-layer MLP, hidden width 256) in place of the dot
+ * product.  The two end-point embeddings are combined by their element-wise
+ * product (the dot product is the special case of one layer of ones).
+ *
+ * lp_mlp_score_loss: scores, loss and dscore as lp_score_loss, but
+ * s_e = MLP(H[e_src[e]] * H[e_dst[e]]); HK has the storage type p->dtype and
+ * width p->dims[0].  Fills `saved`.  An edge with an id outside [0, n_nodes)
+ * is scored 0, gets dscore 0 and adds nothing to the loss sum.
+ *
+ * lp_mlp_backward: gradients of the predictor's weights and biases, and
+ * edge_grad (device [B, dims[0]], storage type) = dL/d(h_u * h_v) per scored edge.
+ *
+ * lp_backward_edge_grads: lp_backward with dL/dH^K seeded from edge_grad
+ * (row u receives edge_grad_e * h_v, row v receives edge_grad_e * h_u) instead
+ * of from dscore; everything else is identical.
+ */
+size_t lp_mlp_score_loss_workspace_bytes(const lp_mlp *p, int64_t B);
+int lp_mlp_score_loss(const void *HK, int32_t n_nodes, int64_t B, int64_t n_pos_edges, const int32_t *e_src, const int32_t *e_dst,
+                      const lp_mlp *p, lp_mlp_acts *saved, float *scores, float *loss, float *dscore, void *ws, size_t ws_bytes,
+                      void *stream);
+size_t lp_mlp_backward_workspace_bytes(const lp_mlp *p, int64_t B);
+int lp_mlp_backward(const lp_mlp *p, const lp_mlp_acts *saved, int64_t B, const float *dscore, lp_mlp_grads *out, void *edge_grad,
+                    void *ws, size_t ws_bytes, void *stream);
+int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                           const int32_t *e_src, const int32_t *e_dst, const void *edge_grad, lp_grads *out, void *ws,
+                           size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each

@@ -306,17 +306,23 @@ def edge_grad_scatter(HK: np.ndarray, e_src, e_dst, dscore) -> np.ndarray:
 
 
 def backward(csr: CSR, W_self, W_neigh, acts: Activations, e_src, e_dst, dscore, relu_margin: float = 0.0,
-             storage: str = "f32") -> Grads:
+             storage: str = "f32", seed_grad: Optional[np.ndarray] = None) -> Grads:
     """``relu_margin`` is 0 for the method itself: relu'(z) = [z > 0].  A test may pass +t and -t to find the
     gradient entries that depend on hidden units whose pre-activation lies within t of the kink, where a
     lower-precision implementation may legitimately take the other branch.
 
     With ``storage="bf16"`` every node-sized matrix that a bf16 implementation keeps in memory is rounded to
     bfloat16 where it is stored: dL/dH^K, the two products dZ W_self^T and (dZ W_neigh^T)/|N(v)|, and each
-    dL/dH^(k-1).  Weight and bias gradients are sums over those stored values and are not rounded."""
+    dL/dH^(k-1).  Weight and bias gradients are sums over those stored values and are not rounded.
+
+    ``seed_grad``: dL/dH^K given directly by a scorer other than the dot product (e_src, e_dst and dscore are then
+    not used); the walk through the layers is the same."""
     K = len(W_self)
     inv_d = inverse_degrees(csr)
-    G = _store(edge_grad_scatter(acts.H[K], e_src, e_dst, np.asarray(dscore, np.float64)), storage)
+    if seed_grad is not None:
+        G = _store(np.asarray(seed_grad, np.float64), storage)
+    else:
+        G = _store(edge_grad_scatter(acts.H[K], e_src, e_dst, np.asarray(dscore, np.float64)), storage)
     dWs, dWn, db = [None] * K, [None] * K, [None] * K
     for k in range(K, 0, -1):
         dZ = G if k == K else G * (acts.Z[k] > relu_margin)

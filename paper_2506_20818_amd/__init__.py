@@ -15,12 +15,18 @@ from .binding import (  # noqa: F401
     Csr,
     Grads,
     LpError,
+    Mlp,
+    MlpActs,
+    MlpGrads,
     Model,
     Sparsified,
     lib_path,
     load_library,
     lp_backward,
     lp_backward_blocks,
+    lp_backward_edge_grads,
+    lp_mlp_backward,
+    lp_mlp_score_loss,
     lp_build_csr,
     lp_adam_step,
     lp_sage_forward,

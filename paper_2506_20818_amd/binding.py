@@ -53,6 +53,20 @@ class _GradsStruct(C.Structure):
 
 
 LP_MAX_FANOUT = 64
+LP_MAX_MLP_LAYERS = 4
+
+
+class _MlpStruct(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("dtype", C.c_int32), ("dims", C.c_int32 * (LP_MAX_MLP_LAYERS + 1)),
+                ("reserved_", C.c_int32), ("W", C.c_void_p * LP_MAX_MLP_LAYERS), ("bias", C.c_void_p * LP_MAX_MLP_LAYERS)]
+
+
+class _MlpActsStruct(C.Structure):
+    _fields_ = [("X", C.c_void_p), ("U", C.c_void_p * LP_MAX_MLP_LAYERS)]
+
+
+class _MlpGradsStruct(C.Structure):
+    _fields_ = [("dW", C.c_void_p * LP_MAX_MLP_LAYERS), ("dbias", C.c_void_p * LP_MAX_MLP_LAYERS)]
 
 
 class _BlocksStruct(C.Structure):
@@ -98,6 +112,16 @@ EXPORTS = {
     "lp_backward_blocks_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.POINTER(_BlocksStruct)]),
     "lp_backward_blocks": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                                      C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_mlp_score_loss_workspace_bytes": (C.c_size_t, [C.POINTER(_MlpStruct), C.c_int64]),
+    "lp_mlp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(_MlpStruct),
+                                    C.POINTER(_MlpActsStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                    C.c_void_p]),
+    "lp_mlp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_MlpStruct), C.c_int64]),
+    "lp_mlp_backward": (C.c_int, [C.POINTER(_MlpStruct), C.POINTER(_MlpActsStruct), C.c_int64, C.c_void_p,
+                                  C.POINTER(_MlpGradsStruct), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_backward_edge_grads": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
+                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
+                                         C.c_size_t, C.c_void_p]),
     "lp_sgd_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.c_float, C.c_void_p]),
     "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
                                C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
@@ -426,6 +450,100 @@ def forward_blocks_workspace_bytes(m: Model, b: Blocks) -> int:
 
 def backward_blocks_workspace_bytes(m: Model, b: Blocks) -> int:
     return int(load_library().lp_backward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)))
+
+
+class Mlp:
+    """Weights of the MLP edge predictor: W[j] of shape [dims[j], dims[j+1]] (float32 or bfloat16), the last one
+    [dims[L-1], 1]; bias[j] of shape [dims[j+1]] (float32)."""
+
+    def __init__(self, W: List[torch.Tensor], bias: List[torch.Tensor]):
+        L = len(W)
+        if not (1 <= L <= LP_MAX_MLP_LAYERS and len(bias) == L):
+            raise ValueError("bad layer count")
+        self.W, self.bias = list(W), list(bias)
+        self.dims = [int(W[0].shape[0])] + [int(w.shape[1]) for w in W]
+        self.torch_dtype = W[0].dtype
+        self.dtype = _LP_OF[self.torch_dtype]
+        s = _MlpStruct()
+        s.n_layers, s.dtype = L, self.dtype
+        for j in range(L + 1):
+            s.dims[j] = self.dims[j]
+        for j in range(L):
+            _need(W[j], self.torch_dtype, "W")
+            _need(bias[j], torch.float32, "bias")
+            s.W[j], s.bias[j] = W[j].data_ptr(), bias[j].data_ptr()
+        self.c = s
+
+
+class MlpActs:
+    def __init__(self, p: Mlp, B: int, device):
+        L = len(p.W)
+        self.X = torch.empty((max(B, 1), p.dims[0]), dtype=p.torch_dtype, device=device)
+        self.U = [torch.empty((max(B, 1), p.dims[j]), dtype=p.torch_dtype, device=device) for j in range(1, L)]
+        s = _MlpActsStruct()
+        s.X = self.X.data_ptr()
+        for j, t in enumerate(self.U):
+            s.U[j] = t.data_ptr()
+        self.c = s
+
+
+class MlpGrads:
+    def __init__(self, p: Mlp, device):
+        L = len(p.W)
+        self.dW = [torch.empty((p.dims[j], p.dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
+        self.dbias = [torch.empty(p.dims[j + 1], dtype=torch.float32, device=device) for j in range(L)]
+        s = _MlpGradsStruct()
+        for j in range(L):
+            s.dW[j], s.dbias[j] = self.dW[j].data_ptr(), self.dbias[j].data_ptr()
+        self.c = s
+
+
+def lp_mlp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_pos_edges: int, p: Mlp,
+                      acts: Optional[MlpActs] = None):
+    lib = load_library()
+    _need(HK, p.torch_dtype, "HK")
+    _need(e_src, torch.int32, "e_src")
+    _need(e_dst, torch.int32, "e_dst")
+    B, dev = int(e_src.numel()), HK.device
+    if acts is None:
+        acts = MlpActs(p, B, dev)
+    scores = torch.empty(B, dtype=torch.float32, device=dev)
+    dscore = torch.empty(B, dtype=torch.float32, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ws = _ws(lib.lp_mlp_score_loss_workspace_bytes(C.byref(p.c), B), dev)
+    _check(lib.lp_mlp_score_loss(_ptr(HK), HK.shape[0], B, n_pos_edges, _ptr(e_src), _ptr(e_dst), C.byref(p.c), C.byref(acts.c),
+                                 _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(ws), ws.numel(), _stream()), "lp_mlp_score_loss")
+    return scores, loss, dscore, acts
+
+
+def lp_mlp_backward(p: Mlp, acts: MlpActs, dscore: torch.Tensor, grads: Optional[MlpGrads] = None):
+    """Returns (MlpGrads, edge_grad [B, dims[0]])."""
+    lib = load_library()
+    _need(dscore, torch.float32, "dscore")
+    B, dev = int(dscore.numel()), dscore.device
+    if grads is None:
+        grads = MlpGrads(p, dev)
+    edge_grad = torch.empty((max(B, 1), p.dims[0]), dtype=p.torch_dtype, device=dev)
+    ws = _ws(lib.lp_mlp_backward_workspace_bytes(C.byref(p.c), B), dev)
+    _check(lib.lp_mlp_backward(C.byref(p.c), C.byref(acts.c), B, _ptr(dscore), C.byref(grads.c), _ptr(edge_grad), _ptr(ws),
+                               ws.numel(), _stream()), "lp_mlp_backward")
+    return grads, edge_grad
+
+
+def lp_backward_edge_grads(g: Csr, m: Model, X: torch.Tensor, acts: Acts, e_src: torch.Tensor, e_dst: torch.Tensor,
+                           edge_grad: torch.Tensor, grads: Optional[Grads] = None, ws: Optional[torch.Tensor] = None,
+                           want_dX: bool = False) -> Grads:
+    lib = load_library()
+    _need(X, m.torch_dtype, "X")
+    _need(edge_grad, m.torch_dtype, "edge_grad")
+    if grads is None:
+        grads = Grads(g.n_nodes, m.dims, X.device, want_dX, m.torch_dtype)
+    if ws is None:
+        ws = _ws(lib.lp_backward_workspace_bytes(C.byref(m.c), g.n_nodes, int(e_src.numel())), X.device)
+    _check(lib.lp_backward_edge_grads(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), int(e_src.numel()), _ptr(e_src),
+                                      _ptr(e_dst), _ptr(edge_grad), C.byref(grads.c), _ptr(ws), ws.numel(), _stream()),
+           "lp_backward_edge_grads")
+    return grads
 
 
 class AdamState:

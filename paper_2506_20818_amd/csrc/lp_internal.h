@@ -55,6 +55,8 @@ struct SpmmArgs {
     const int32_t *row_order = nullptr;  // optional processing order
     const float *inv_deg = nullptr;      // optional per-output-row scale
     const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
+    const void *entry_rows = nullptr;    // optional matrix with rows of F values (storage type): entry p is multiplied
+    const int32_t *entry_row_index = nullptr;  // element-wise by its row entry_row_index[p] (instead of a scalar weight)
     bool sym_norm = false;               // symmetric normalisation: entry p weighs sqrt(inv_deg[colidx[p]]), row v is
                                          // scaled by sqrt(inv_deg[v]) (inv_deg required, w unused)
     const void *in = nullptr;
@@ -157,6 +159,8 @@ struct BatchGroupWs {
     uint64_t *keys_a, *keys_b;  // [2B + 1] each
     uint32_t *hist;             // lp_radix_sort_hist_words(2B + 1)
 };
+// With dscore == nullptr the per-entry output is the index of the scored edge (as int32 in the storage of `w`)
+// instead of its weight.
 int lp_group_batch_by_row(const int32_t *e_src, const int32_t *e_dst, const float *dscore, int64_t B, int32_t n_rows,
                           const BatchGroupWs &ws, int32_t *ptr, int32_t *col, float *w, hipStream_t stream);
 

@@ -74,7 +74,8 @@ __global__ void batch_entries_kernel(const uint64_t *__restrict__ sorted, int64_
     const int64_t e = j < B ? j : j - B;
     const bool parked = (int32_t)(k >> 32) >= n_nodes;
     col[p] = parked ? 0 : (j < B ? e_dst[e] : e_src[e]);
-    w[p] = parked ? 0.f : dscore[e];
+    if (dscore) w[p] = parked ? 0.f : dscore[e];
+    else reinterpret_cast<int32_t *>(w)[p] = (int32_t)e;   // which scored edge the entry belongs to
 }
 
 struct BackwardWs {
@@ -216,14 +217,17 @@ extern "C" size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes
     return carve_backward(nullptr, m, n_nodes, B).bytes;
 }
 
-extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
-                           const int32_t *e_src, const int32_t *e_dst, const float *dscore, lp_grads *out, void *ws,
-                           size_t ws_bytes, void *stream) {
+// dscore (one scalar per scored edge, dot-product scorer) or edge_grad (one row dL/d(h_u * h_v) per scored edge,
+// any scorer that works on the element-wise product) seeds dL/dH^K; everything after that is common.
+static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                         const int32_t *e_src, const int32_t *e_dst, const float *dscore, const void *edge_grad, lp_grads *out,
+                         void *ws, size_t ws_bytes, void *stream) {
     LP_TRY(check_model(m));
     LP_TRY(check_graph(g, true));
     LP_TRY(check_acts(m, saved));
     if (!X || !lp_aligned16(X) || !out || B < 0) return LP_ERR_INVALID_ARG;
-    if (B > 0 && (!e_src || !e_dst || !dscore)) return LP_ERR_INVALID_ARG;
+    if (B > 0 && (!e_src || !e_dst || (!dscore && !edge_grad))) return LP_ERR_INVALID_ARG;
+    if (edge_grad && !lp_aligned16(edge_grad)) return LP_ERR_INVALID_ARG;
     if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
     const int K = m->n_layers;
     const bool gcn = m->layer_type == LP_LAYER_GCN;
@@ -264,7 +268,9 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         SpmmArgs sc;
         sc.dtype = dt;
         sc.n_rows = cap; sc.n_rows_dev = w.n_touched; sc.F = m->dims[K];
-        sc.rowptr = w.touched_ptr; sc.colidx = w.bcol; sc.w = w.bw;
+        sc.rowptr = w.touched_ptr; sc.colidx = w.bcol;
+        if (dscore) sc.w = w.bw;
+        else { sc.entry_rows = edge_grad; sc.entry_row_index = reinterpret_cast<const int32_t *>(w.bw); }
         sc.n_entries = n2; sc.long_queue = w.long_queue;
         sc.in = HK; sc.out = dZ;
         sc.timing_class = LP_KC_SCATTER;
@@ -333,4 +339,18 @@ extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, co
         }
     }
     return LP_OK;
+}
+
+extern "C" int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                           const int32_t *e_src, const int32_t *e_dst, const float *dscore, lp_grads *out, void *ws,
+                           size_t ws_bytes, void *stream) {
+    if (B > 0 && !dscore) return LP_ERR_INVALID_ARG;
+    return backward_impl(g, m, X, saved, B, e_src, e_dst, dscore, nullptr, out, ws, ws_bytes, stream);
+}
+
+extern "C" int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
+                                      const int32_t *e_src, const int32_t *e_dst, const void *edge_grad, lp_grads *out, void *ws,
+                                      size_t ws_bytes, void *stream) {
+    if (B > 0 && !edge_grad) return LP_ERR_INVALID_ARG;
+    return backward_impl(g, m, X, saved, B, e_src, e_dst, nullptr, edge_grad, out, ws, ws_bytes, stream);
 }

@@ -26,8 +26,9 @@ constexpr int kLongWaves = kLongThreads / 64;
 
 // Accumulates the 64-neighbour blocks first, first + stride, ... (< hi) of one CSR row into acc.
 // T: storage type, G: lanes per neighbour row (8..64), C: 16-byte chunks per lane (C > 1 only when G == 64),
-// W: per-entry weights, U: neighbour rows in flight per lane.
-template <typename T, int G, int C, bool W, int U>
+// W: 0 = no weights, 1 = one scalar per entry, 2 = one row of `entry_rows` per entry (multiplied element-wise),
+// U: neighbour rows in flight per lane.
+template <typename T, int G, int C, int W, int U>
 __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__restrict__ in, int32_t first, int32_t hi,
                                                   int32_t stride, int lane, float (&acc)[C][LpVec<T>::N]) {
     constexpr int P = 64 / G;  // neighbours read per step
@@ -39,22 +40,33 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
         const int cnt = min(64, hi - base);
         int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
         float mine_w = 1.f;
-        if (W) mine_w = lane < cnt ? (a.sym_norm ? sqrtf(a.inv_deg[mine]) : a.w[base + lane]) : 0.f;
+        if (W == 1) mine_w = lane < cnt ? (a.sym_norm ? sqrtf(a.inv_deg[mine]) : a.w[base + lane]) : 0.f;
+        int32_t mine_row = 0;
+        if (W == 2) mine_row = lane < cnt ? a.entry_row_index[base + lane] : 0;
         if (a.in_index) mine = lane < cnt ? a.in_index[mine] : -1;  // row of `in` that holds the neighbour, < 0: a zero row
         for (int j0 = 0; j0 < cnt; j0 += P * U) {
             float x[U][C][VE];
+            float rw[W == 2 ? U : 1][C][VE];
             float wj[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * P + sub;
                 const int32_t nb = __shfl(mine, j & 63, 64);
-                wj[u] = W ? __shfl(mine_w, j & 63, 64) : 1.f;
+                wj[u] = W == 1 ? __shfl(mine_w, j & 63, 64) : 1.f;
+                const int32_t er = W == 2 ? __shfl(mine_row, j & 63, 64) : 0;
                 const bool on = lane_on && j < cnt && nb >= 0;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
 #pragma unroll
                     for (int e = 0; e < VE; ++e) x[u][c][e] = 0.f;
-                    if (on && (C == 1 || fl + 64 * c < FV)) LpVec<T>::load(in + ((int64_t)nb * FV + fl + 64 * c) * VE, x[u][c]);
+                    if (W == 2) {
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) rw[u][c][e] = 0.f;
+                    }
+                    if (on && (C == 1 || fl + 64 * c < FV)) {
+                        LpVec<T>::load(in + ((int64_t)nb * FV + fl + 64 * c) * VE, x[u][c]);
+                        if (W == 2) LpVec<T>::load(static_cast<const T *>(a.entry_rows) + ((int64_t)er * FV + fl + 64 * c) * VE, rw[u][c]);
+                    }
                 }
             }
 #pragma unroll
@@ -63,7 +75,8 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
                 for (int c = 0; c < C; ++c)
 #pragma unroll
                     for (int e = 0; e < VE; ++e) {
-                        if (W) acc[c][e] += wj[u] * x[u][c][e];
+                        if (W == 1) acc[c][e] += wj[u] * x[u][c][e];
+                        else if (W == 2) acc[c][e] += rw[u][c][e] * x[u][c][e];
                         else acc[c][e] += x[u][c][e];
                     }
         }
@@ -109,7 +122,7 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
     LpVec<T>::store(static_cast<T *>(a.out) + o, y);
 }
 
-template <typename T, int G, int C, bool W>
+template <typename T, int G, int C, int W>
 __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
     const int lane = threadIdx.x & 63;
@@ -142,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
 }
 
 // One workgroup of sixteen wavefronts per queued row; workgroup b serves queue entries b, b + gridDim.x, ...
-template <typename T, int G, int C, bool W>
+template <typename T, int G, int C, int W>
 __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
     constexpr int U = C == 1 ? 8 : 4;
@@ -188,17 +201,19 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
 template <typename T, int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
     const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kThreads / 64);
-    const bool weighted = a.w || a.sym_norm;
-    if (weighted) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, true>), dim3(grid), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, false>), dim3(grid), dim3(kThreads), 0, st, a);
+    const int mode = a.entry_rows ? 2 : ((a.w || a.sym_norm) ? 1 : 0);
+    if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kThreads), 0, st, a);
     if (a.long_queue) {
         // no more rows can be queued than fit the entry count; two workgroups per compute unit walk the queue
         const int64_t most = a.n_entries / a.long_threshold;
         const int64_t slots = 2 * (int64_t)lp_compute_units();
         const unsigned lgrid = (unsigned)(most < slots ? most : slots);
         if (lgrid > 0) {
-            if (weighted) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, true>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
-            else hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, false>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            if (mode == 2) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 2>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            else if (mode == 1) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 1>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            else hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 0>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
         }
     }
     return lp_after_launch();
@@ -224,6 +239,7 @@ int lp_launch_spmm(const SpmmArgs &args, hipStream_t st) {
     if (args.n_rows <= 0) return LP_OK;
     if (args.F <= 0 || args.F % lp_vec_elems(args.dtype)) return LP_ERR_UNSUPPORTED;
     if (args.sym_norm && !args.inv_deg) return LP_ERR_INVALID_ARG;
+    if (args.entry_rows && !args.entry_row_index) return LP_ERR_INVALID_ARG;
     SpmmArgs a = args;
     a.long_threshold = kSpmmLongRow;
     if (a.n_entries < a.long_threshold) a.long_queue = nullptr;  // no row can be that long
