@@ -312,6 +312,11 @@ int lp_sparsify(int32_t n_nodes, int64_t n_edges, const int32_t *eu, const int32
  * a negative eps or a non-finite learning rate.
  */
 int lp_sgd_step(const lp_model *m, const lp_grads *g, float lr, void *stream);
+/* The same two updates for one tensor of n elements (dtype = storage of w; grad, m, v fp32): for parameters that
+ * live outside lp_model, such as the MLP edge predictor's. */
+int lp_sgd_update_tensor(void *w, int32_t dtype, const float *grad, int64_t n, float lr, void *stream);
+int lp_adam_update_tensor(void *w, int32_t dtype, const float *grad, float *m, float *v, int64_t n, int64_t t_step, float lr,
+                          float beta1, float beta2, float eps, void *stream);
 int lp_adam_step(const lp_model *m, const lp_grads *g, const lp_opt_state *s, int64_t t_step, float lr, float beta1,
                  float beta2, float eps, void *stream);
 

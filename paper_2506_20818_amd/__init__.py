@@ -29,10 +29,12 @@ from .binding import (  # noqa: F401
     lp_mlp_score_loss,
     lp_build_csr,
     lp_adam_step,
+    lp_adam_update_tensor,
     lp_sage_forward,
     lp_sage_forward_blocks,
     lp_sample_blocks,
     lp_sgd_step,
+    lp_sgd_update_tensor,
     lp_sample_neg,
     lp_score_loss,
     lp_sparsify,

@@ -122,6 +122,9 @@ EXPORTS = {
     "lp_backward_edge_grads": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                                          C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
                                          C.c_size_t, C.c_void_p]),
+    "lp_sgd_update_tensor": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_float, C.c_void_p]),
+    "lp_adam_update_tensor": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                        C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "lp_sgd_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.c_float, C.c_void_p]),
     "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
                                C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
@@ -558,6 +561,22 @@ class AdamState:
             for k, t in enumerate(getattr(self, name)):
                 getattr(s, name)[k] = t.data_ptr()
         self.c = s
+
+
+def lp_adam_update_tensor(w: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, t_step: int, lr: float = 1e-3,
+                          beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    for t, nm in ((grad, "grad"), (m, "m"), (v, "v")):
+        _need(t, torch.float32, nm)
+    _need(w, w.dtype, "w")
+    _check(load_library().lp_adam_update_tensor(_ptr(w), _LP_OF[w.dtype], _ptr(grad), _ptr(m), _ptr(v), int(w.numel()), int(t_step),
+                                                lr, beta1, beta2, eps, _stream()), "lp_adam_update_tensor")
+
+
+def lp_sgd_update_tensor(w: torch.Tensor, grad: torch.Tensor, lr: float) -> None:
+    _need(grad, torch.float32, "grad")
+    _need(w, w.dtype, "w")
+    _check(load_library().lp_sgd_update_tensor(_ptr(w), _LP_OF[w.dtype], _ptr(grad), int(w.numel()), lr, _stream()),
+           "lp_sgd_update_tensor")
 
 
 def lp_sgd_step(m: Model, grads: Grads, lr: float) -> None:

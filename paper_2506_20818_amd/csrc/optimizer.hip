@@ -91,6 +91,38 @@ dim3 grid_for(int64_t n_max, int count) {
 
 }  // namespace
 
+// one tensor at a time: parameters that live outside lp_model (the MLP edge predictor's)
+extern "C" int lp_adam_update_tensor(void *w, int32_t dtype, const float *grad, float *m, float *v, int64_t n, int64_t t_step, float lr,
+                                     float beta1, float beta2, float eps, void *stream) {
+    if (!w || !grad || !m || !v || n < 0) return LP_ERR_INVALID_ARG;
+    if (dtype != LP_F32 && dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (t_step < 1 || !std::isfinite(lr) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f))
+        return LP_ERR_INVALID_ARG;
+    if (n == 0) return LP_OK;
+    TensorTable t;
+    t.count = 1;
+    t.w[0] = w; t.g[0] = grad; t.m[0] = m; t.v[0] = v; t.n[0] = n; t.bf16[0] = dtype == LP_BF16 ? 1 : 0;
+    const float c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)t_step)));
+    const float c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)t_step)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    LpTimedScope timed(LP_KC_OTHER, st);
+    hipLaunchKernelGGL(adam_kernel, grid_for(n, 1), dim3(256), 0, st, t, lr, beta1, beta2, eps, c1, c2);
+    return lp_after_launch();
+}
+
+extern "C" int lp_sgd_update_tensor(void *w, int32_t dtype, const float *grad, int64_t n, float lr, void *stream) {
+    if (!w || !grad || n < 0 || !std::isfinite(lr)) return LP_ERR_INVALID_ARG;
+    if (dtype != LP_F32 && dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (n == 0) return LP_OK;
+    TensorTable t;
+    t.count = 1;
+    t.w[0] = w; t.g[0] = grad; t.m[0] = nullptr; t.v[0] = nullptr; t.n[0] = n; t.bf16[0] = dtype == LP_BF16 ? 1 : 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    LpTimedScope timed(LP_KC_OTHER, st);
+    hipLaunchKernelGGL(sgd_kernel, grid_for(n, 1), dim3(256), 0, st, t, lr);
+    return lp_after_launch();
+}
+
 extern "C" int lp_sgd_step(const lp_model *m, const lp_grads *g, float lr, void *stream) {
     TensorTable t;
     int64_t n_max;

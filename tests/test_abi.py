@@ -249,3 +249,60 @@ def test_blocks_bounds_and_argument_checks_on_the_host():
     assert bwd(wsb=128) == -3
     assert lib.lp_backward_blocks_workspace_bytes(C.byref(m), C.byref(b)) > 0
     assert lib.lp_forward_blocks_workspace_bytes(C.byref(_model([128, 256])), C.byref(b)) == 0
+
+
+def test_mlp_predictor_and_tensor_updates_reject_bad_arguments_on_the_host():
+    lib = B.load_library()
+    p = C.c_void_p(0x1000)
+
+    def mlp(dims=(256, 256, 256, 1), dtype=0, null_w=False):
+        s = B._MlpStruct()
+        s.n_layers, s.dtype = len(dims) - 1, dtype
+        for j, d in enumerate(dims):
+            s.dims[j] = d
+        for j in range(len(dims) - 1):
+            s.W[j] = None if null_w else 0x1000
+            s.bias[j] = 0x1000
+        return s
+
+    acts, grads = B._MlpActsStruct(), B._MlpGradsStruct()
+    acts.X = 0x1000
+    for j in range(3):
+        acts.U[j] = 0x1000
+        grads.dW[j] = grads.dbias[j] = 0x1000
+    sl = lambda m=mlp(), H=p, B_=4, npos=2, ws=p, wsb=1 << 30, loss=p: lib.lp_mlp_score_loss(
+        H, 10, B_, npos, p, p, C.byref(m), C.byref(acts), p, loss, p, ws, wsb, None)
+    assert sl(m=mlp(dims=(256, 256, 2))) == -1           # the last layer must have one output
+    assert sl(m=mlp(dims=(256, 250, 1))) == -4
+    assert sl(m=mlp(dtype=9)) == -4
+    assert sl(m=mlp(null_w=True)) == -1
+    assert sl(H=None) == -1
+    assert sl(npos=5) == -1
+    assert sl(loss=None) == -1
+    assert sl(ws=None) == -3
+    assert sl(wsb=16) == -3
+    bw = lambda m=mlp(), B_=4, ds=p, gr=grads, eg=p, ws=p, wsb=1 << 30: lib.lp_mlp_backward(
+        C.byref(m), C.byref(acts), B_, ds, C.byref(gr), eg, ws, wsb, None)
+    assert bw(ds=None) == -1
+    assert bw(eg=None) == -1
+    assert bw(gr=B._MlpGradsStruct()) == -1
+    assert bw(ws=None) == -3
+    assert bw(B_=-1) == -1
+    assert lib.lp_mlp_backward_workspace_bytes(C.byref(mlp()), 1000) > lib.lp_mlp_backward_workspace_bytes(C.byref(mlp()), 10) > 0
+    assert lib.lp_adam_update_tensor(None, 0, p, p, p, 10, 1, 1e-3, 0.9, 0.999, 1e-8, None) == -1
+    assert lib.lp_adam_update_tensor(p, 0, p, p, p, 10, 0, 1e-3, 0.9, 0.999, 1e-8, None) == -1
+    assert lib.lp_adam_update_tensor(p, 3, p, p, p, 10, 1, 1e-3, 0.9, 0.999, 1e-8, None) == -4
+    assert lib.lp_adam_update_tensor(p, 0, p, p, p, 0, 1, 1e-3, 0.9, 0.999, 1e-8, None) == 0
+    assert lib.lp_sgd_update_tensor(p, 0, None, 10, 0.1, None) == -1
+    assert lib.lp_sgd_update_tensor(p, 0, p, 0, 0.1, None) == 0
+    # lp_backward_edge_grads shares lp_backward's checks
+    g, acts3, gr3 = _csr(), B._ActsStruct(), B._GradsStruct()
+    for k in range(3):
+        acts3.A[k] = acts3.H[k] = 0x1000
+        gr3.dW_self[k] = gr3.dW_neigh[k] = gr3.dbias[k] = 0x1000
+    good = _model([128, 256, 256, 256])
+    eg = lambda B_=4, e=p, ws=p, wsb=1 << 40: lib.lp_backward_edge_grads(
+        C.byref(g), C.byref(good), p, C.byref(acts3), B_, p, p, e, C.byref(gr3), ws, wsb, None)
+    assert eg(e=None) == -1
+    assert eg(e=C.c_void_p(0x1004)) == -1
+    assert eg(ws=None) == -3

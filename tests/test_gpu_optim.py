@@ -101,3 +101,26 @@ def test_sgd_step_matches_oracle(bf16):
         for k in range(len(ref[key])):
             ref[key][k] = P.sgd_step(ref[key][k], g[key][k], float(np.float32(0.05)), storage="bf16" if (bf16 and key != "bias") else "f32")
     compare(model, ref, before, 1e-6, bf16)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_single_tensor_updates_match_oracle(bf16):
+    say("adam/sgd single tensor bf16=%s" % bf16)
+    rng = np.random.default_rng(21)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    w = dev_f32(rng.standard_normal((33, 8))).to(tdt)
+    ref = host(w.float()).astype(np.float64)
+    m, v = torch.zeros(33, 8, device=DEV), torch.zeros(33, 8, device=DEV)
+    rm, rv = np.zeros_like(ref), np.zeros_like(ref)
+    hp = dict(lr=float(np.float32(1e-2)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)), eps=float(np.float32(1e-8)))
+    for t in range(1, 4):
+        g = rng.standard_normal((33, 8)).astype(np.float32)
+        lp.lp_adam_update_tensor(w, dev_f32(g), m, v, t, lr=1e-2)
+        ref, rm, rv = P.adam_step(ref, g.astype(np.float64), rm, rv, t, storage="bf16" if bf16 else "f32", **hp)
+        got = host(w.float()).astype(np.float64)
+        assert np.all(np.abs(got - ref) <= np.abs(ref) * (2.0 ** -7 if bf16 else 2e-6) + 1e-7)
+        ref = got.copy()
+    g = rng.standard_normal((33, 8)).astype(np.float32)
+    lp.lp_sgd_update_tensor(w, dev_f32(g), 0.05)
+    ref = P.sgd_step(ref, g.astype(np.float64), float(np.float32(0.05)), storage="bf16" if bf16 else "f32")
+    assert np.all(np.abs(host(w.float()) - ref) <= np.abs(ref) * (2.0 ** -7 if bf16 else 2e-6) + 1e-7)
