@@ -322,20 +322,25 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
             *reinterpret_cast<v4i *>(Bs_ + (idx / KQ) * ROWB + ((idx % KQ) << 4)) = rbv[p];                            \
         }                                                                                                              \
     }
-#define LP_COMPUTE(stage, kk)                                                                                          \
+    // operands of one 32-byte group of the K step: two row blocks of the A tile, NB column blocks of the weight tile
+#define LP_LOAD_OPS(stage, kk, a_, b_)                                                                                 \
     {                                                                                                                  \
         const char *As_ = lds + (stage) * STAGE;                                                                       \
         const char *Bs_ = As_ + BMt * ROWB;                                                                            \
-        v4i a[2], b[NB];                                                                                               \
         _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            a[rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);       \
+            a_[rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);      \
         _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                              \
-            b[cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);       \
-        /* k-major order: consecutive MFMAs write different accumulators */                                            \
+            b_[cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + (kk) * 32 + 16 * h);      \
+    }
+    // k-major order: consecutive MFMAs write different accumulators
+#define LP_MFMA_OPS(a_, b_)                                                                                            \
+    {                                                                                                                  \
         _Pragma("unroll") for (int s_ = 0; s_ < NtElem<T>::STEPS; ++s_)                                                \
             _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                           \
-                _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) NtElem<T>::mfma_step(acc[rb][cb], b[cb], a[rb], s_); \
+                _Pragma("unroll") for (int cb = 0; cb < NB; ++cb) NtElem<T>::mfma_step(acc[rb][cb], b_[cb], a_[rb], s_); \
     }
+    // the LDS reads of the next group are issued before the MFMAs of the current one (two operand register sets)
+#define LP_ORDER() __builtin_amdgcn_sched_barrier(0)
 
     LP_FETCH_NEXT()
     LP_STASH(0)
@@ -343,14 +348,30 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     __syncthreads();
     int64_t cw = 0;  // output tile being accumulated
     int ct = 0;      // its K step
+    v4i a0[2], b0[NB], a1[2], b1[NB];
     for (int64_t u = 0; u < n_steps; ++u) {
         const int cur = (int)(u & 1);
-#pragma unroll
-        for (int kk = 0; kk < KSB / 64; ++kk) LP_COMPUTE(cur, kk)
+        LP_LOAD_OPS(cur, 0, a0, b0)
+        LP_LOAD_OPS(cur, 1, a1, b1)
+        LP_ORDER();
+        LP_MFMA_OPS(a0, b0)
+        if (KSB == 128) {
+            LP_ORDER();
+            LP_LOAD_OPS(cur, 2, a0, b0)
+            LP_ORDER();
+            LP_MFMA_OPS(a1, b1)
+        }
+        LP_ORDER();
         if (u + 1 < n_steps) LP_STASH(cur ^ 1)  // registers hold step u+1
         LP_FETCH_NEXT()                         // step u+2
-#pragma unroll
-        for (int kk = KSB / 64; kk < KSB / 32; ++kk) LP_COMPUTE(cur, kk)
+        LP_ORDER();
+        if (KSB == 128) {
+            LP_LOAD_OPS(cur, 3, a1, b1)
+            LP_ORDER();
+            LP_MFMA_OPS(a0, b0)
+            LP_ORDER();
+        }
+        LP_MFMA_OPS(a1, b1)
         __syncthreads();
         if (++ct < n_tiles) continue;
         ct = 0;
@@ -392,7 +413,9 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #undef LP_SET_PART
 #undef LP_FETCH_NEXT
 #undef LP_STASH
-#undef LP_COMPUTE
+#undef LP_LOAD_OPS
+#undef LP_MFMA_OPS
+#undef LP_ORDER
 }
 
 // ------------------------------------------------------------------------------------------------ NT, bfloat16
