@@ -219,7 +219,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--cpu-scale", type=float, default=0.25, help="fraction of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-scale", type=float, default=1.0, help="fraction of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
                     help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "

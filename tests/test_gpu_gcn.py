@@ -85,3 +85,38 @@ def test_gcn_step_collab_scale():
     neg = host(lp.lp_sample_neg(g, dev_i32(wl.pos_src), wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step))
     es, ed = O.batch_edges(wl.pos_src, wl.pos_dst, neg, wl.k_neg)
     check_step(ref, g, wl.W_neigh, wl.bias, wl.X, es, ed, wl.n_pos)
+
+
+@pytest.mark.parametrize("dims", [[24, 40, 8], [128, 512, 512, 512]])
+def test_gcn_step_bf16_storage(dims):
+    """bfloat16 storage of features, weights, activations and node-sized gradients (fp32 accumulation); bars as for
+    the GraphSAGE bf16 path: 2^-7 on activations and scores, 2e-2 on gradients."""
+    from lp_workloads import to_bf16_grid
+    rng = np.random.default_rng(400 + sum(dims))
+    n = 1400
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
+    rl, cl = G.add_self_pairs(n, r, c)
+    say("gcn bf16 dims=%s" % dims)
+    ref = O.build_csr(n, rl, cl, True)
+    g = lp.lp_build_csr(n, dev_i32(rl), dev_i32(cl), True)
+    W, b = toy_weights(rng, dims)
+    W = [to_bf16_grid(w) for w in W]
+    X = to_bf16_grid(rng.standard_normal((n, dims[0])).astype(np.float32))
+    B, n_pos = 2000, 800
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    model = gcn_model(W, b, bf16=True)
+    Xd = dev_f32(X).to(torch.bfloat16)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    a_ref = G.gcn_forward(ref, W, b, X, storage="bf16")
+    K = len(W)
+    for k in range(1, K + 1):
+        assert_close(host(acts.H[k - 1].float()), a_ref.H[k], 2.0 ** -7, "H^%d" % k)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[K], es, ed, n_pos)
+    g_ref = G.gcn_backward(ref, W, a_ref, es, ed, ds_ref, storage="bf16")
+    assert_close(host(s), s_ref, 2.0 ** -7, "scores")
+    for k in range(K):
+        assert_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], 2e-2, "dW^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), g_ref.dbias[k], 2e-2, "dbias^%d" % (k + 1))
+    assert_close(host(grads.dX.float()), g_ref.dX, 2e-2, "dX")

@@ -102,3 +102,29 @@ def test_whole_step_with_mlp_predictor(dims):
         assert_grad_close(host(grads.dW_neigh[k]), out["ref"].dW_neigh[k], out["lo"].dW_neigh[k], out["hi"].dW_neigh[k], "dW_neigh^%d" % (k + 1))
         assert_grad_close(host(grads.dbias[k]), out["ref"].dbias[k], out["lo"].dbias[k], out["hi"].dbias[k], "dbias^%d" % (k + 1))
     assert_grad_close(host(grads.dX), out["ref"].dX, out["lo"].dX, out["hi"].dX, "dX")
+
+
+def test_mlp_predictor_bf16_storage():
+    """bfloat16 storage of the embeddings, the products, the hidden layers and the predictor's weights (fp32
+    accumulation); bars as for the other bf16 paths: 2^-7 on scores, 2e-2 on gradients."""
+    from lp_workloads import to_bf16_grid
+    rng = np.random.default_rng(55)
+    n, B, n_pos, widths = 600, 2000, 900, [64, 256, 128]
+    say("mlp bf16 widths=%s" % widths)
+    H = to_bf16_grid((rng.standard_normal((n, widths[0])) * 0.7).astype(np.float32))
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    W, c = mlp_weights(rng, widths, scale=0.15)
+    W = [to_bf16_grid(w) for w in W]
+    bf = lambda a: dev_f32(a).to(torch.bfloat16)
+    p = lp.Mlp([bf(w) for w in W], [dev_f32(x) for x in c])
+    s, loss, ds, acts = lp.lp_mlp_score_loss(bf(H), dev_i32(es), dev_i32(ed), n_pos, p)
+    s_ref, a_ref = M.mlp_scores(H, es, ed, W, c, storage="bf16")
+    loss_ref, ds_ref = M.bce_mean(s_ref, n_pos)
+    assert_close(host(s), s_ref, 2.0 ** -7, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= 2.0 ** -7 * abs(loss_ref)
+    grads, eg = lp.lp_mlp_backward(p, acts, ds)
+    dW, dc, eg_ref, _ = M.mlp_backward(H, es, ed, W, a_ref, ds_ref, storage="bf16")
+    for j in range(len(W)):
+        assert_close(host(grads.dW[j]), dW[j], 2e-2, "dW_%d" % (j + 1))
+        assert_close(host(grads.dbias[j]), dc[j], 2e-2, "dc_%d" % (j + 1))
+    assert_close(host(eg.float())[:B], eg_ref, 2e-2, "edge_grad")
