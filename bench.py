@@ -221,6 +221,8 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--cpu-scale", type=float, default=1.0, help="fraction of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timing-level", type=int, default=1, choices=[1, 2],
+                    help="1: HIP events around the aggregation, GEMM, scatter, score and sampler launches; 2: around every launch")
     ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
                     help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "
                          "sampled_step: the mini-batch mode with sampled neighbourhoods")
@@ -308,7 +310,7 @@ def main():
     plain_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
 
     # timed region, with the library's per-launch HIP events switched on
-    lp.lp_timing_enable(True)
+    lp.lp_timing_enable(args.timing_level)
     lp.lp_timing_collect()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -393,8 +395,10 @@ def main():
         "roofline_spmm": lines["spmm"],
         "roofline_gemm_nt": lines["gemm_nt"],
         "roofline_gemm_tn": lines["gemm_tn"],
-        "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items()},
+        "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items() if k != "other" or args.timing_level > 1},
     }
+    if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
+        out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_scale)
     print(json.dumps(out), flush=True)

@@ -399,7 +399,9 @@ int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, co
 /* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each
  * kernel launch made by the calls above is bracketed by two HIP events on the
- * launch stream.  lp_timing_collect waits for the recorded events, writes the
+ * launch stream (lp_timing_enable(1): all classes but LP_KC_OTHER, whose small
+ * launches would pay more for the events than they take; lp_timing_enable(2):
+ * every launch; 0: off).  lp_timing_collect waits for the recorded events, writes the
  * summed milliseconds and launch counts per kernel class (arrays of at least
  * LP_KC_COUNT entries) and forgets them.  Off by default.  This is the only
  * process-wide state of the library; it is guarded by a mutex.

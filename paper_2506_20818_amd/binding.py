@@ -633,8 +633,9 @@ def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
 KERNEL_CLASSES = ["spmm", "gemm_nt", "gemm_tn", "scatter", "score", "sample", "other"]
 
 
-def lp_timing_enable(on: bool) -> None:
-    _check(load_library().lp_timing_enable(1 if on else 0), "lp_timing_enable")
+def lp_timing_enable(level) -> None:
+    """0/False: off; 1/True: the main kernel classes; 2: every launch."""
+    _check(load_library().lp_timing_enable(int(level)), "lp_timing_enable")
 
 
 def lp_timing_collect():

@@ -14,7 +14,7 @@ struct Span {
 };
 
 std::mutex g_mu;
-bool g_on = false;
+int g_level = 0;  // 0 off, 1 the main kernel classes, 2 every launch
 std::vector<Span> g_spans;
 std::vector<hipEvent_t> g_free;
 
@@ -33,7 +33,7 @@ hipEvent_t get_event() {
 
 LpTimedScope::LpTimedScope(int cls, hipStream_t st) : cls_(cls), st_(st), beg_(nullptr) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!g_on) return;
+    if (g_level == 0 || (g_level == 1 && cls_ == LP_KC_OTHER)) return;
     beg_ = get_event();
     if (beg_) (void)hipEventRecord(static_cast<hipEvent_t>(beg_), st_);
 }
@@ -52,7 +52,7 @@ LpTimedScope::~LpTimedScope() {
 
 extern "C" int lp_timing_enable(int on) {
     std::lock_guard<std::mutex> lock(g_mu);
-    g_on = on != 0;
+    g_level = on < 0 ? 0 : (on > 2 ? 2 : on);
     return LP_OK;
 }
 
