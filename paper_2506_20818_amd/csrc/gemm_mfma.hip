@@ -12,6 +12,7 @@
 //   copied to LDS as they are and read 4 bytes per lane (consecutive lanes, consecutive banks).  The node range
 //   is split over the grid; partial tiles are written out and summed in a fixed order by a second kernel.
 #include "lp_internal.h"
+#include <algorithm>
 
 namespace {
 
@@ -233,20 +234,26 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     constexpr int A_LOADS = BMt * KQ / TH;
     constexpr int B_LOADS = BN * KQ / TH;
     constexpr int STAGE = (BMt + BN) * ROWB;         // bytes per LDS stage
+    constexpr int EPB = MW == 4 ? 256 : 128;         // bytes of an output row segment per store pass of a wavefront
+    constexpr int EROW = EPB + 16;                   // its LDS pitch
+    constexpr int EPC = EPB / ES;                    // columns per pass
+    constexpr int CBP = EPC / 32;                    // 32-column accumulator blocks per pass
+    static_assert((TH / 64) * 32 * EROW <= STAGE, "the store staging of all wavefronts fits in one LDS stage");
+    static_assert(CBP >= 1 && NB % CBP == 0, "a pass covers whole accumulator blocks");
     __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+    __shared__ __attribute__((aligned(16))) char bias_lds[(TH / 64) * WN * 4];  // per wavefront: bias of its columns
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
     const int M_ = g.m_dev ? min(*g.m_dev, g.M) : g.M;  // rows actually present
     const int col_tiles = (g.N + BN - 1) / BN;
-    const int64_t row_tiles = ((int64_t)M_ + BMt - 1) / BMt;
+    const int row_tiles = M_ > 0 ? (M_ - 1) / BMt + 1 : 0;
     const int tiles0 = g.K[0] * ES / KSB, tiles1 = g.K[1] * ES / KSB;
     const int n_tiles = tiles0 + tiles1;
-    if ((int64_t)blockIdx.x >= row_tiles || n_tiles == 0) return;
-    const int64_t my_rows = (row_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
-    const int64_t n_work = my_rows * col_tiles;      // output tiles of this workgroup
-    const int64_t n_steps = n_work * n_tiles;
+    if ((int)blockIdx.x >= row_tiles || n_tiles == 0) return;
+    const int my_rows = (row_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int n_steps = my_rows * col_tiles * n_tiles;  // the launcher keeps this below 2^31
 
     v16f acc[2][NB];
 #pragma unroll
@@ -256,59 +263,77 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
 
-    // load cursor: output tile fw, K step ft
-    int64_t fw = 0;
-    int ft = 0;
-    int64_t m0f = 0;
-    int n0f = 0, n_endf = 0;
-    bool secondf = false;
+    // Load cursors (row tile, column tile, K step), one per operand.  Offsets are formed per load (clamped row *
+    // pitch + column bytes) instead of being kept in registers.  The loads themselves are unconditional (a cursor
+    // past its end repeats its last step): with a fixed number of loads per step the compiler can wait for the
+    // older ones by count and leave the younger ones in flight.  (Keeping two steps of A rows in flight was tried
+    // for the short bfloat16 steps and measured no faster.)
+    constexpr int RP = TH / KQ;                      // tile rows covered by one load of every thread
+    const int r0 = tid / KQ, c16 = (tid % KQ) << 4;
+    int rowA = blockIdx.x, colA = 0, ftA = 0;        // row tile, column tile, K step of the next A load
+    int rowB = blockIdx.x, colB = 0, ftB = 0;
     const char *abase = nullptr, *bbase = nullptr;
-    uint32_t aoff[A_LOADS], boff[B_LOADS];
+    uint32_t pitchA = 0, pitchB = 0;
+    int rmaxA = 0, rmaxB = 0;
     v4i ra[A_LOADS], rbv[B_LOADS];  // plain vector registers: a struct copy would go through private memory
 
-#define LP_SET_PART(part)                                                                                              \
+#define LP_FETCH_A()                                                                                                   \
+    if (rowA < row_tiles) {                                                                                            \
+        if (ftA == 0 || ftA == tiles0) {                                                                               \
+            const int part = (ftA == 0 && tiles0 > 0) ? 0 : 1;                                                         \
+            const int64_t m0f = (int64_t)rowA * BMt;                                                                   \
+            pitchA = (uint32_t)g.lda[part] * ES;                                                                       \
+            abase = static_cast<const char *>(g.A[part]) + m0f * (int64_t)pitchA;                                      \
+            rmaxA = (int)(M_ - 1 - m0f < BMt - 1 ? M_ - 1 - m0f : BMt - 1);                                            \
+        } else {                                                                                                       \
+            abase += KSB;                                                                                              \
+        }                                                                                                              \
+        if (++ftA == n_tiles) {                                                                                        \
+            ftA = 0;                                                                                                   \
+            if (++colA == col_tiles) {                                                                                 \
+                colA = 0;                                                                                              \
+                rowA += gridDim.x;                                                                                     \
+            }                                                                                                          \
+        }                                                                                                              \
+    }                                                                                                                  \
+    _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p)                                                                \
+        ra[p] = *reinterpret_cast<const v4i *>(abase + ((uint32_t)min(r0 + p * RP, rmaxA) * pitchA + c16));
+#define LP_FETCH_B()                                                                                                   \
+    if (rowB < row_tiles) {                                                                                            \
+        if (ftB == 0 || ftB == tiles0) {                                                                               \
+            const int part = (ftB == 0 && tiles0 > 0) ? 0 : 1;                                                         \
+            const int n0f = colB * BN;                                                                                 \
+            const bool secondf = n0f >= g.n_split;                                                                     \
+            const int n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                    \
+            pitchB = (uint32_t)g.ldb[part] * ES;                                                                       \
+            bbase = static_cast<const char *>(g.Bt[part][secondf ? 1 : 0]) +                                           \
+                    (int64_t)(secondf ? n0f - g.n_split : n0f) * (int64_t)pitchB;                                      \
+            rmaxB = n_endf - 1 - n0f < BN - 1 ? n_endf - 1 - n0f : BN - 1;                                             \
+        } else {                                                                                                       \
+            bbase += KSB;                                                                                              \
+        }                                                                                                              \
+        if (++ftB == n_tiles) {                                                                                        \
+            ftB = 0;                                                                                                   \
+            if (++colB == col_tiles) {                                                                                 \
+                colB = 0;                                                                                              \
+                rowB += gridDim.x;                                                                                     \
+            }                                                                                                          \
+        }                                                                                                              \
+    }                                                                                                                  \
+    _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p)                                                                \
+        rbv[p] = *reinterpret_cast<const v4i *>(bbase + ((uint32_t)min(r0 + p * RP, rmaxB) * pitchB + c16));
+    // Bias of the columns of this wavefront, for the output tile the NEXT step belongs to: requested every step
+    // (first in the order of requests, so it has arrived when the older loads have), parked in LDS one step later.
+    const char *bias_src = reinterpret_cast<const char *>(g.bias ? g.bias : static_cast<const float *>(tiles0 > 0 ? g.Bt[0][0] : g.Bt[1][0]));
+    char *bias_w = bias_lds + wave * (WN * 4);
+    v4f rbias;
+#define LP_FETCH_BIAS(col_tile)                                                                                        \
     {                                                                                                                  \
-        const char *A_ = static_cast<const char *>((part) ? g.A[1] : g.A[0]);                                          \
-        const int64_t lda_ = (int64_t)((part) ? g.lda[1] : g.lda[0]) * ES;                                             \
-        const int64_t ldb_ = (int64_t)((part) ? g.ldb[1] : g.ldb[0]) * ES;                                             \
-        const char *Bt_ = static_cast<const char *>(secondf ? ((part) ? g.Bt[1][1] : g.Bt[0][1])                       \
-                                                            : ((part) ? g.Bt[1][0] : g.Bt[0][0]));                     \
-        abase = A_ + m0f * lda_;                                                                                       \
-        bbase = Bt_ + (int64_t)(secondf ? n0f - g.n_split : n0f) * ldb_;                                               \
-        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                              \
-            int64_t r = idx / KQ;                                                                                      \
-            r = m0f + r < M_ ? r : M_ - 1 - m0f;                                                                     \
-            aoff[p] = (uint32_t)(r * lda_ + ((idx % KQ) << 4));                                                        \
-        }                                                                                                              \
-        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                              \
-            int64_t r = idx / KQ;                                                                                      \
-            r = n0f + r < n_endf ? r : n_endf - 1 - n0f;                                                               \
-            boff[p] = (uint32_t)(r * ldb_ + ((idx % KQ) << 4));                                                        \
-        }                                                                                                              \
+        const int nb_ = g.bias ? min((col_tile) * BN + wn * WN + 4 * (lane % (WN / 4)), g.N - 4) : 0;                  \
+        rbias = *reinterpret_cast<const v4f *>(bias_src + 4 * nb_);                                                    \
     }
-    // loads of the next K step in pipeline order (possibly the first step of the next output tile)
-#define LP_FETCH_NEXT()                                                                                                \
-    if (fw < n_work) {                                                                                                 \
-        if (ft == 0) {                                                                                                 \
-            m0f = ((int64_t)blockIdx.x + (fw / col_tiles) * gridDim.x) * BMt;                                          \
-            n0f = (int)(fw % col_tiles) * BN;                                                                          \
-            secondf = n0f >= g.n_split;                                                                                \
-            n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                              \
-            if (tiles0 > 0) LP_SET_PART(0) else LP_SET_PART(1)                                                         \
-        } else if (ft == tiles0) {                                                                                     \
-            LP_SET_PART(1)                                                                                             \
-        }                                                                                                              \
-        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) ra[p] = *reinterpret_cast<const v4i *>(abase + aoff[p]);   \
-        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) rbv[p] = *reinterpret_cast<const v4i *>(bbase + boff[p]);  \
-        abase += KSB;                                                                                                  \
-        bbase += KSB;                                                                                                  \
-        if (++ft == n_tiles) {                                                                                         \
-            ft = 0;                                                                                                    \
-            ++fw;                                                                                                      \
-        }                                                                                                              \
-    }
+#define LP_PUT_BIAS()                                                                                                  \
+    if (lane < WN / 4) *reinterpret_cast<v4f *>(bias_w + 16 * lane) = rbias;
 #define LP_STASH(stage)                                                                                                \
     {                                                                                                                  \
         char *As_ = lds + (stage) * STAGE;                                                                             \
@@ -342,77 +367,126 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     // the LDS reads of the next group are issued before the MFMAs of the current one (two operand register sets)
 #define LP_ORDER() __builtin_amdgcn_sched_barrier(0)
 
-    LP_FETCH_NEXT()
-    LP_STASH(0)
-    LP_FETCH_NEXT()
-    __syncthreads();
-    int64_t cw = 0;  // output tile being accumulated
-    int ct = 0;      // its K step
-    v4i a0[2], b0[NB], a1[2], b1[NB];
-    for (int64_t u = 0; u < n_steps; ++u) {
-        const int cur = (int)(u & 1);
-        LP_LOAD_OPS(cur, 0, a0, b0)
-        LP_LOAD_OPS(cur, 1, a1, b1)
-        LP_ORDER();
-        LP_MFMA_OPS(a0, b0)
-        if (KSB == 128) {
-            LP_ORDER();
-            LP_LOAD_OPS(cur, 2, a0, b0)
-            LP_ORDER();
-            LP_MFMA_OPS(a1, b1)
+    // One K step: MFMAs on LDS stage `cur`, while the registers of step u+1 go to the other stage and the loads of
+    // step u+2 are requested.
+#define LP_STEP(u_)                                                                                                    \
+    {                                                                                                                  \
+        const int cur = (u_) & 1;                                                                                      \
+        LP_LOAD_OPS(cur, 0, a0, b0)                                                                                    \
+        LP_LOAD_OPS(cur, 1, a1, b1)                                                                                    \
+        LP_ORDER();                                                                                                    \
+        LP_MFMA_OPS(a0, b0)                                                                                            \
+        if (KSB == 128) {                                                                                              \
+            LP_ORDER();                                                                                                \
+            LP_LOAD_OPS(cur, 2, a0, b0)                                                                                \
+            LP_ORDER();                                                                                                \
+            LP_MFMA_OPS(a1, b1)                                                                                        \
+        }                                                                                                              \
+        LP_ORDER();                                                                                                    \
+        LP_STASH(cur ^ 1)                                                                                              \
+        LP_PUT_BIAS()                                                                                                  \
+        LP_FETCH_BIAS((ct + 1 == n_tiles) ? (colC + 1 == col_tiles ? 0 : colC + 1) : colC)                             \
+        LP_FETCH_B()                                                                                                   \
+        LP_FETCH_A()                                                                                                   \
+        LP_ORDER();                                                                                                    \
+        if (KSB == 128) {                                                                                              \
+            LP_LOAD_OPS(cur, 3, a1, b1)                                                                                \
+            LP_ORDER();                                                                                                \
+            LP_MFMA_OPS(a0, b0)                                                                                        \
+            LP_ORDER();                                                                                                \
+        }                                                                                                              \
+        LP_MFMA_OPS(a1, b1)                                                                                            \
+        __syncthreads();                                                                                               \
+        if (++ct == n_tiles) {                                                                                         \
+            ct = 0;                                                                                                    \
+            store_tile(cur);                                                                                           \
+        }                                                                                                              \
+    }
+
+    int rowC = blockIdx.x, colC = 0;  // output tile being accumulated
+    int ct = 0;                       // its K step
+    // ---- an output tile is complete.  Every wavefront turns its accumulators into stored values, lays them out
+    // row-major in a private piece of the LDS stage that was just consumed, and reads them back so that one store
+    // instruction writes whole row segments of EPB bytes (LDS operations of one wavefront execute in order; the
+    // fences only keep the compiler from reordering them).  The closing barrier keeps the next step's tile copy out
+    // of that stage until every wavefront has left it.
+    auto store_tile = [&](int stage) __attribute__((always_inline)) {
+        const int64_t m0 = (int64_t)rowC * BMt + wm * 64;
+        const int n0 = colC * BN;
+        if (++colC == col_tiles) {
+            colC = 0;
+            rowC += gridDim.x;
         }
-        LP_ORDER();
-        if (u + 1 < n_steps) LP_STASH(cur ^ 1)  // registers hold step u+1
-        LP_FETCH_NEXT()                         // step u+2
-        LP_ORDER();
-        if (KSB == 128) {
-            LP_LOAD_OPS(cur, 3, a1, b1)
-            LP_ORDER();
-            LP_MFMA_OPS(a0, b0)
-            LP_ORDER();
-        }
-        LP_MFMA_OPS(a1, b1)
-        __syncthreads();
-        if (++ct < n_tiles) continue;
-        ct = 0;
-        // ---- this output tile is complete: store it (transposed accumulator blocks, see the head of this section)
-        const int64_t m0 = ((int64_t)blockIdx.x + (cw / col_tiles) * gridDim.x) * BMt;
-        const int n0 = (int)(cw % col_tiles) * BN;
-        ++cw;
         const bool second = n0 >= g.n_split;
         const bool scaled = g.rowscale && second;
-        T *__restrict__ Cb = static_cast<T *>(second ? g.C[1] : g.C[0]);
-        const int64_t ldc = second ? g.ldc[1] : g.ldc[0];
-        const int ncol0 = (second ? n0 - g.n_split : n0) + wn * WN + 4 * h;
+        char *__restrict__ Cb = static_cast<char *>(second ? g.C[1] : g.C[0]);
+        const int64_t pitchC = (int64_t)(second ? g.ldc[1] : g.ldc[0]) * ES;
+        const int nw0 = n0 + wn * WN;                      // first column of this wavefront
+        const int nshift = second ? g.n_split : 0;
+        float rs[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            const int64_t m = m0 + wm * 64 + rb * 32 + i32;
-            const bool m_ok = m < M_;
-            const float rs = (scaled && m_ok) ? g.rowscale[g.rowscale_index ? g.rowscale_index[m] : m] : 1.f;
-            T *__restrict__ Crow = Cb + (m_ok ? m : 0) * ldc + ncol0;
-#pragma unroll
-            for (int cb = 0; cb < NB; ++cb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n0 + wn * WN + cb * 32 + 8 * q + 4 * h;
-                    const bool n_ok = n < g.N;
-                    v4f bias = {0.f, 0.f, 0.f, 0.f};
-                    if (g.bias && n_ok) bias = *reinterpret_cast<const v4f *>(g.bias + n);
-                    float y[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float t = acc[rb][cb][4 * q + e] + bias[e];
-                        if (g.relu) t = fmaxf(t, 0.f);
-                        y[e] = t * rs;
-                        acc[rb][cb][4 * q + e] = 0.f;
-                    }
-                    if (m_ok && n_ok) NtElem<T>::store4(Crow + cb * 32 + 8 * q, y);
-                }
+            const int64_t m = m0 + rb * 32 + i32;
+            rs[rb] = (scaled && m < M_) ? g.rowscale[g.rowscale_index ? g.rowscale_index[m] : m] : 1.f;
         }
-    }
-#undef LP_SET_PART
-#undef LP_FETCH_NEXT
+        char *reg = lds + stage * STAGE + wave * (32 * EROW);
+        constexpr int LPR = EPB / 16;                      // lanes per row segment
+        constexpr int RPI = 64 / LPR;                      // rows per store instruction
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int pass = 0; pass < NB / CBP; ++pass) {
+#pragma unroll
+                for (int cbl = 0; cbl < CBP; ++cbl) {
+                    const int cb = pass * CBP + cbl;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        v4f bias = {0.f, 0.f, 0.f, 0.f};
+                        if (g.bias) bias = *reinterpret_cast<const v4f *>(bias_w + 16 * (cb * 8 + 2 * q + h));
+                        float y[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float t = acc[rb][cb][4 * q + e] + bias[e];
+                            if (g.relu) t = fmaxf(t, 0.f);
+                            y[e] = t * rs[rb];
+                            acc[rb][cb][4 * q + e] = 0.f;
+                        }
+                        NtElem<T>::store4(reinterpret_cast<T *>(reg + i32 * EROW) + cbl * 32 + 8 * q + 4 * h, y);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int j = 0; j < 32 / RPI; ++j) {
+                    const int row = j * RPI + lane / LPR, chunk = lane % LPR;
+                    const v4i v = *reinterpret_cast<const v4i *>(reg + row * EROW + 16 * chunk);
+                    const int64_t m = m0 + rb * 32 + row;
+                    const int n = nw0 + pass * EPC + chunk * (16 / ES);
+                    if (m < M_ && n < g.N) *reinterpret_cast<v4i *>(Cb + m * pitchC + (int64_t)(n - nshift) * ES) = v;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        __syncthreads();
+    };
+
+    v4i a0[2], b0[NB], a1[2], b1[NB];
+    LP_FETCH_BIAS(0)
+    LP_FETCH_A()
+    LP_FETCH_B()
+    LP_STASH(0)
+    LP_FETCH_B()
+    LP_FETCH_A()
+    __syncthreads();
+    for (int u = 0; u < n_steps; ++u) LP_STEP(u)
+#undef LP_STEP
+#undef LP_FETCH_A
+#undef LP_FETCH_B
 #undef LP_STASH
+#undef LP_FETCH_BIAS
+#undef LP_PUT_BIAS
 #undef LP_LOAD_OPS
 #undef LP_MFMA_OPS
 #undef LP_ORDER
@@ -916,8 +990,14 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     // output split
     const int es = lp_elem_bytes(a.dtype);
     const int fast_bn = a.N > 128 ? 256 : 128;
+    const int ve16 = 16 / es;
     const bool fast_ok = a.N > 64 && (a.K[0] * es % 64 == 0) && (a.K[1] * es % 64 == 0) && a.K[0] + a.K[1] > 0 &&
-                         (a.n_split >= a.N || a.n_split % fast_bn == 0);
+                         (a.n_split >= a.N || a.n_split % fast_bn == 0) &&
+                         // whole 16-byte pieces of output rows
+                         a.N % ve16 == 0 && a.ldc[0] % ve16 == 0 && lp_aligned16(a.C[0]) && (!a.bias || lp_aligned16(a.bias)) &&
+                         (a.n_split >= a.N || (a.ldc[1] % ve16 == 0 && lp_aligned16(a.C[1]))) &&
+                         // row offsets inside a tile are formed in 32 bits
+                         (int64_t)std::max(std::max(a.lda[0], a.lda[1]), std::max(a.ldb[0], a.ldb[1])) * es * 256 < ((int64_t)1 << 32);
     auto grid_for = [&](int bn) {
         const int64_t row_tiles8 = lp_ceil_div(lp_ceil_div(a.M, BM), 8) * 8;
         return dim3((unsigned)(row_tiles8 * lp_ceil_div(a.N, bn)));
@@ -930,7 +1010,10 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         const int64_t row_tiles = lp_ceil_div(a.M, bm);
         const int64_t slots = (big ? 1 : 2) * (int64_t)lp_compute_units();
         const dim3 pgrid((unsigned)(row_tiles < slots ? row_tiles : slots));
-#define LP_NT_FAST(T)                                                                                          \
+        const int64_t steps_per_wg = lp_ceil_div(row_tiles, (int64_t)pgrid.x) * lp_ceil_div(a.N, fast_bn) *
+                                     ((int64_t)(a.K[0] + a.K[1]) * es / 64);
+        if (steps_per_wg >= (int64_t)1 << 31) return LP_ERR_UNSUPPORTED;  // the kernels count K steps in 32 bits
+#define LP_NT_FAST(T)                                                                                             \
         if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 4, 128>), pgrid, dim3(512), 0, st, a);           \
         else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 2, 64>), pgrid, dim3(256), 0, st, a); \
         else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64>), pgrid, dim3(256), 0, st, a);
