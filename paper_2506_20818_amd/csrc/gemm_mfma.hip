@@ -215,8 +215,7 @@ template <> struct NtElem<lp_bf16_t> {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, w), __builtin_bit_cast(v8bf, x), acc, 0, 0, 0);
     }
     static __device__ __forceinline__ void store4(lp_bf16_t *p, const float (&y)[4]) {
-        *reinterpret_cast<uint2 *>(p) = make_uint2((uint32_t)lp_f32_to_bf16(y[0]) | ((uint32_t)lp_f32_to_bf16(y[1]) << 16),
-                                                   (uint32_t)lp_f32_to_bf16(y[2]) | ((uint32_t)lp_f32_to_bf16(y[3]) << 16));
+        *reinterpret_cast<uint2 *>(p) = make_uint2(lp_f32x2_to_bf16x2(y[0], y[1]), lp_f32x2_to_bf16x2(y[2], y[3]));
     }
 };
 
@@ -617,7 +616,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 for (int e = 0; e < 2; ++e) {
                     float t0 = acc[rb][cb][4 * q + 2 * e] + bias[2 * e], t1 = acc[rb][cb][4 * q + 2 * e + 1] + bias[2 * e + 1];
                     if (g.relu) { t0 = fmaxf(t0, 0.f); t1 = fmaxf(t1, 0.f); }
-                    packed[e] = (uint32_t)lp_f32_to_bf16(t0 * rs) | ((uint32_t)lp_f32_to_bf16(t1 * rs) << 16);
+                    packed[e] = lp_f32x2_to_bf16x2(t0 * rs, t1 * rs);
                 }
                 if (m_ok && n_ok) {
                     lp_bf16_t *__restrict__ C = static_cast<lp_bf16_t *>(second ? g.C[1] : g.C[0]);

@@ -170,12 +170,14 @@ typedef uint16_t lp_bf16_t;
 
 #if defined(__HIPCC__)
 __device__ __forceinline__ float lp_bf16_to_f32(lp_bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ lp_bf16_t lp_f32_to_bf16(float x) {  // round to nearest, ties to even
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (lp_bf16_t)0x7fc0;  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (lp_bf16_t)(u >> 16);
+// fp32 -> bfloat16, round to nearest, ties to even: the hardware pair conversion (v_cvt_pk_bf16_f32); `lo` lands in
+// the low half of the word
+__device__ __forceinline__ uint32_t lp_f32x2_to_bf16x2(float lo, float hi) {
+    typedef __bf16 lp_bf2 __attribute__((ext_vector_type(2)));
+    typedef float lp_f2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(lp_f2{lo, hi}, lp_bf2));
 }
+__device__ __forceinline__ lp_bf16_t lp_f32_to_bf16(float x) { return (lp_bf16_t)(lp_f32x2_to_bf16x2(x, 0.f) & 0xffffu); }
 
 // One 16-byte vector of a matrix row: 4 floats or 8 bfloat16 values, handled as fp32 in registers.
 template <typename T> struct LpVec;
@@ -203,7 +205,7 @@ template <> struct LpVec<lp_bf16_t> {
     static __device__ __forceinline__ void store(lp_bf16_t *p, const float (&v)[8]) {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)lp_f32_to_bf16(v[2 * i]) | ((uint32_t)lp_f32_to_bf16(v[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = lp_f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
         *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 };
