@@ -242,7 +242,7 @@ BlockBackwardWs carve_block_backward(void *ws, const lp_model *m, const lp_block
     for (int i = 0; i < 3; ++i) w.buf[i] = take(big);
     size_t tn = 0, cs = 0;
     for (int k = 1; k <= K; ++k) {
-        const size_t t = lp_gemm_tn_partials_bytes(b->cap[k] > 0 ? b->cap[k] : 1, m->dims[k - 1], m->dims[k]);
+        const size_t t = lp_weight_grads_partials_bytes(m->dtype, b->cap[k] > 0 ? b->cap[k] : 1, m->dims[k - 1], m->dims[k - 1], m->dims[k]);
         tn = t > tn ? t : tn;
         const size_t c = lp_colsum_partials_bytes(b->cap[k], m->dims[k]);
         cs = c > cs ? c : cs;
@@ -491,17 +491,15 @@ extern "C" int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const v
         const void *Hin = k > 1 ? saved->H[k - 2] : X_frontier;
         const int32_t rows = b->cap[k];
         const int32_t *rows_dev = b->n + k;
-        LP_TRY(lp_launch_colsum(dZ, dt, rows, Fo, out->dbias[k - 1], w.colsum_partials, st, rows_dev));
-        GemmTnArgs tn;
-        tn.dtype = dt;
-        tn.Kn = rows; tn.kn_dev = rows_dev;
-        tn.Mw = Fi; tn.Nw = Fo;
-        tn.B = dZ; tn.ldb = Fo;
-        tn.partials = w.tn_partials;
-        tn.At = Hin; tn.lda = Fi; tn.C = out->dW_self[k - 1];   // rows 0..n_k-1 of the wider frontier are the same nodes
-        LP_TRY(lp_launch_gemm_tn(tn, st));
-        tn.At = saved->A[k - 1]; tn.C = out->dW_neigh[k - 1];
-        LP_TRY(lp_launch_gemm_tn(tn, st));
+        WeightGradArgs wg;
+        wg.dtype = dt;
+        wg.Kn = rows; wg.kn_dev = rows_dev;
+        wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1];   // rows 0..n_k-1 of the wider frontier are the same nodes
+        wg.At[1] = saved->A[k - 1]; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW_neigh[k - 1];
+        wg.B = dZ; wg.Nw = Fo; wg.ldb = Fo;
+        wg.dbias = out->dbias[k - 1];
+        wg.partials = w.tn_partials; wg.colsum_partials = w.colsum_partials;
+        LP_TRY(lp_launch_weight_grads(wg, st));
         if (k == 1) break;
         GemmNtArgs ge;
         ge.dtype = dt;

@@ -888,6 +888,184 @@ TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
     return p;
 }
 
+// ------------------------------------------------------------------------------------------------ fused weight gradients
+// [At0 | At1]^T B and the column sums of B for fp32 storage.  256 x 256 output tile, eight wavefronts of 64 x 128,
+// 32 nodes per step, two LDS stages with one barrier per step; the reduction over nodes is split across the grid
+// and the partial tiles (and partial column sums, taken from the B tile in LDS and written by the workgroups of the
+// first tile row) are folded afterwards in a fixed order.  Loads are unconditional: a node beyond the end of the chunk reads
+// the last valid row and is replaced by zeros.
+constexpr int WG_BK = 32;
+constexpr int WG_LD = 256 + 4;
+constexpr int WG_THREADS = 512;
+
+template <bool INDEXED>  // rows of At taken through at_index
+__global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2))) void weight_grads_kernel(WeightGradArgs g, int chunk, int splits,
+                                                                                                         int tiles_n, int tiles) {
+    __shared__ __attribute__((aligned(16))) float lds[2][2][WG_BK * WG_LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    // the tiles of one node chunk get linear ids that are 8 apart: same XCD, so the chunk of B is fetched into one L2
+    const int L = blockIdx.x;
+    const int s = (L & 7) + 8 * ((L >> 3) / tiles);
+    const int t = (L >> 3) % tiles;
+    if (s >= splits) return;
+    const int m0 = (t / tiles_n) * 256, n0 = (t % tiles_n) * 256;
+    const int Mtot = g.Mw[0] + g.Mw[1];
+    int64_t Kn_ = g.Kn;
+    if (g.kn_dev) {
+        Kn_ = min((int64_t)*g.kn_dev, (int64_t)g.Kn);
+        chunk = (int)(((Kn_ + splits - 1) / splits + WG_BK - 1) / WG_BK * WG_BK);
+    }
+    const int64_t kbeg = (int64_t)s * chunk;
+    const int64_t kend = kbeg + chunk < Kn_ ? kbeg + chunk : Kn_;
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    const bool do_bias = g.dbias != nullptr && m0 == 0;
+    float bsum = 0.f;
+
+    if (kbeg < kend) {
+        // every thread loads four 16-byte pieces of each operand per step: tile rows 8p + wave, tile columns 4*lane ..
+        const int c = 4 * lane;
+        const int ma = m0 + c, nb = n0 + c;
+        // a thread whose columns lie outside the operands still loads (column 0 of At[1] / B) and drops the values
+        const bool a_ok = ma < Mtot, b_ok = nb < g.Nw;
+        const float *abase = static_cast<const float *>(g.At[1]);
+        int64_t pitch_a = g.lda[1];
+        if (ma < g.Mw[0]) { abase = static_cast<const float *>(g.At[0]) + ma; pitch_a = g.lda[0]; }
+        else if (a_ok) abase += ma - g.Mw[0];
+        const float *bbase = static_cast<const float *>(g.B) + (b_ok ? nb : 0);
+        const int64_t klast = Kn_ - 1;
+        v4f ra[4], rbv[4];
+        int64_t arow[4];
+        auto lookup = [&](int64_t k0) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int64_t k = min(k0 + 8 * p + wave, klast);
+                arow[p] = INDEXED ? (int64_t)g.at_index[k] : k;
+            }
+        };
+        auto fetch = [&](int64_t k0) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int64_t k = k0 + 8 * p + wave;
+                const bool live = k < kend;
+                const v4f va = *reinterpret_cast<const v4f *>(abase + arow[p] * pitch_a);
+                const v4f vb = *reinterpret_cast<const v4f *>(bbase + min(k, klast) * g.ldb);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ra[p][e] = (live && a_ok) ? va[e] : 0.f;
+                    rbv[p][e] = (live && b_ok) ? vb[e] : 0.f;
+                }
+            }
+        };
+        auto stash = [&](int stage) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                *reinterpret_cast<v4f *>(&lds[stage][0][(8 * p + wave) * WG_LD + c]) = ra[p];
+                *reinterpret_cast<v4f *>(&lds[stage][1][(8 * p + wave) * WG_LD + c]) = rbv[p];
+            }
+        };
+        auto compute = [&](int stage, int kp0) {
+            const float *As = lds[stage][0], *Bs = lds[stage][1];
+#pragma unroll
+            for (int kp = kp0; kp < kp0 + WG_BK / 4; ++kp) {
+                float a[2], b[4];
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) a[rb] = As[(kp * 2 + h) * WG_LD + wm * 64 + rb * 32 + i32];
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) b[cb] = Bs[(kp * 2 + h) * WG_LD + wn * 128 + cb * 32 + i32];
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = mfma32(a[rb], b[cb], acc[rb][cb]);
+                // column sums of the B tile: thread (column tid % 256, row parity tid / 256), every workgroup (no branch)
+                bsum += Bs[(kp * 2 + (tid >> 8)) * WG_LD + (tid & 255)];
+            }
+        };
+
+        lookup(kbeg);
+        fetch(kbeg);
+        lookup(kbeg + WG_BK);
+        stash(0);
+        fetch(kbeg + WG_BK);
+        lookup(kbeg + 2 * WG_BK);
+        __syncthreads();
+        int cur = 0;
+        for (int64_t k0 = kbeg; k0 < kend; k0 += WG_BK, cur ^= 1) {
+            compute(cur, 0);
+            stash(cur ^ 1);                 // registers hold step k0 + 32 (zeros past the end)
+            fetch(k0 + 2 * WG_BK);
+            lookup(k0 + 3 * WG_BK);
+            compute(cur, WG_BK / 4);
+            __syncthreads();
+        }
+    }
+
+    const int64_t ptot = (int64_t)Mtot * g.Nw + g.Nw;
+    float *__restrict__ P = g.partials + (int64_t)s * ptot;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const int n = n0 + wn * 128 + cb * 32 + i32;
+        if (n >= g.Nw) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < Mtot) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
+            }
+    }
+    if (do_bias) {  // even-row and odd-row sums of a column meet in LDS
+        __syncthreads();
+        lds[0][0][tid] = bsum;
+        __syncthreads();
+        if (tid < 256 && n0 + tid < g.Nw) P[(int64_t)Mtot * g.Nw + n0 + tid] = lds[0][0][tid] + lds[0][0][tid + 256];
+    }
+}
+
+// out = sum over the `rows` partial rows of P[rows, n0 + n1 + n2], columns routed to three outputs.  Same order of
+// additions as colsum_partial_kernel.
+__global__ __launch_bounds__(kThreads) void weight_grads_fold_kernel(const float *__restrict__ P, int rows, int64_t row_len, int64_t n0,
+                                                                      int64_t n1, int64_t n2, float *__restrict__ o0, float *__restrict__ o1,
+                                                                      float *__restrict__ o2) {
+    __shared__ float red[4][64][4];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t NV = row_len / 4;            // pitch of a partial row in 16-byte pieces
+    const int64_t NC = (n0 + n1 + n2) / 4;     // pieces that are summed
+    const int64_t cv = (int64_t)blockIdx.x * 64 + tx;
+    v4f a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;
+    if (cv < NC) {
+        int r = ty;
+        for (; r + 12 < rows; r += 16) {
+            const v4f x0 = *reinterpret_cast<const v4f *>(P + ((int64_t)r * NV + cv) * 4);
+            const v4f x1 = *reinterpret_cast<const v4f *>(P + ((int64_t)(r + 4) * NV + cv) * 4);
+            const v4f x2 = *reinterpret_cast<const v4f *>(P + ((int64_t)(r + 8) * NV + cv) * 4);
+            const v4f x3 = *reinterpret_cast<const v4f *>(P + ((int64_t)(r + 12) * NV + cv) * 4);
+            a0 += x0;
+            a1 += x1;
+            a0 += x2;
+            a1 += x3;
+        }
+        for (; r < rows; r += 4) a0 += *reinterpret_cast<const v4f *>(P + ((int64_t)r * NV + cv) * 4);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[ty][tx][e] = a0[e] + a1[e];
+    __syncthreads();
+    if (ty == 0 && cv < NC) {
+        const int64_t col = cv * 4;
+        float *dst = col < n0 ? o0 + col : (col < n0 + n1 ? o1 + (col - n0) : o2 + (col - n0 - n1));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e] = (red[0][tx][e] + red[1][tx][e]) + (red[2][tx][e] + red[3][tx][e]);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ small helpers
 template <typename T>
 __global__ void transpose_kernel(const T *__restrict__ in, int rows, int cols, T *__restrict__ out) {
@@ -1068,6 +1246,71 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t st) {
     // fold the partial tiles: a column sum of the [splits, Mw*Nw] matrix
     const int64_t n = (int64_t)a.Mw * a.Nw;
     return lp_launch_colsum(a.partials, LP_F32, p.splits, n, a.C, a.partials + lp_align_up(sizeof(float) * (size_t)p.splits * n) / sizeof(float), st);
+}
+
+namespace {
+struct WgPlan {
+    bool fused = false;
+    int tiles_m = 0, tiles_n = 0, tiles = 0, splits = 0, chunk = 0;
+};
+WgPlan plan_weight_grads(int32_t dtype, int32_t Kn, int32_t Mw0, int32_t Mw1, int32_t Nw) {
+    WgPlan p;
+    const int Mtot = Mw0 + Mw1;
+    // fused path: fp32, 16-byte pieces never straddle the two operands, tiles reasonably full
+    p.fused = dtype == LP_F32 && Kn > 0 && Mw1 > 0 && (Mw0 % 4) == 0 && (Mw1 % 4) == 0 && (Nw % 4) == 0 && Mtot >= 192 && Nw >= 192 &&
+              (Mtot % 256 == 0 || Mtot % 256 >= 128) && (Nw % 256 == 0 || Nw % 256 >= 128);
+    if (!p.fused) return p;
+    p.tiles_m = (int)lp_ceil_div(Mtot, 256);
+    p.tiles_n = (int)lp_ceil_div(Nw, 256);
+    p.tiles = p.tiles_m * p.tiles_n;
+    int64_t want = lp_ceil_div(lp_compute_units(), p.tiles);   // one workgroup per compute unit
+    const int64_t max_by_len = lp_ceil_div(Kn, 8 * WG_BK);     // at least 256 nodes per workgroup
+    int64_t s = want < max_by_len ? want : max_by_len;
+    if (s < 1) s = 1;
+    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), WG_BK) * WG_BK);
+    p.splits = (int)lp_ceil_div(Kn, p.chunk);
+    return p;
+}
+}  // namespace
+
+size_t lp_weight_grads_partials_bytes(int32_t dtype, int32_t Kn, int32_t Mw0, int32_t Mw1, int32_t Nw) {
+    if (Kn <= 0 || Nw <= 0) return 0;
+    const WgPlan p = plan_weight_grads(dtype, Kn, Mw0, Mw1, Nw);
+    if (p.fused) return lp_align_up(sizeof(float) * (size_t)p.splits * ((size_t)(Mw0 + Mw1) * Nw + Nw));
+    const size_t a = Mw0 > 0 ? lp_gemm_tn_partials_bytes(Kn, Mw0, Nw) : 0, b = Mw1 > 0 ? lp_gemm_tn_partials_bytes(Kn, Mw1, Nw) : 0;
+    return a > b ? a : b;
+}
+
+int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t st) {
+    if (a.Nw <= 0) return LP_OK;
+    const WgPlan p = plan_weight_grads(a.dtype, a.Kn, a.Mw[0], a.Mw[1], a.Nw);
+    const bool aligned = lp_aligned16(a.At[0]) && lp_aligned16(a.At[1]) && lp_aligned16(a.B) && (a.lda[0] % 4) == 0 && (a.lda[1] % 4) == 0 &&
+                         (a.ldb % 4) == 0 && lp_aligned16(a.C[0]) && lp_aligned16(a.C[1]) && (!a.dbias || lp_aligned16(a.dbias));
+    if (p.fused && aligned && (a.Mw[0] == 0 || (a.At[0] && a.C[0])) && a.At[1] && a.B && a.C[1] && a.partials) {
+        LpTimedScope timed(LP_KC_GEMM_TN, st);
+        const unsigned grid = (unsigned)(p.tiles * lp_ceil_div(p.splits, 8) * 8);
+        if (a.at_index) hipLaunchKernelGGL(weight_grads_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        else hipLaunchKernelGGL(weight_grads_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        LP_TRY(lp_after_launch());
+        const int64_t n0 = (int64_t)a.Mw[0] * a.Nw, n1 = (int64_t)a.Mw[1] * a.Nw, n2 = a.dbias ? a.Nw : 0;
+        hipLaunchKernelGGL(weight_grads_fold_kernel, dim3((unsigned)lp_ceil_div((n0 + n1 + n2) / 4, 64)), dim3(kThreads), 0, st, a.partials,
+                           p.splits, n0 + n1 + a.Nw, n0, n1, n2, a.C[0], a.C[1], a.dbias);
+        return lp_after_launch();
+    }
+    if (a.dbias) LP_TRY(lp_launch_colsum(a.B, a.dtype, a.Kn, a.Nw, a.dbias, a.colsum_partials, st, a.kn_dev));
+    for (int s = 0; s < 2; ++s) {
+        if (a.Mw[s] <= 0) continue;
+        GemmTnArgs tn;
+        tn.dtype = a.dtype;
+        tn.Kn = a.Kn; tn.kn_dev = a.kn_dev; tn.at_index = a.at_index;
+        tn.Mw = a.Mw[s]; tn.Nw = a.Nw;
+        tn.At = a.At[s]; tn.lda = a.lda[s];
+        tn.B = a.B; tn.ldb = a.ldb;
+        tn.C = a.C[s];
+        tn.partials = a.partials;
+        LP_TRY(lp_launch_gemm_tn(tn, st));
+    }
+    return LP_OK;
 }
 
 int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, int dtype, hipStream_t st) {

@@ -121,6 +121,29 @@ struct GemmTnArgs {
 size_t lp_gemm_tn_partials_bytes(int32_t Kn, int32_t Mw, int32_t Nw);
 int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t stream);
 
+// Weight and bias gradients of one layer in one pass over the nodes:
+//   C[0] = At[0]^T B,  C[1] = At[1]^T B,  dbias = column sums of B,
+// At[s]: [Kn, Mw[s]] (Mw[0] may be 0), B: [Kn, Nw]; at_index / kn_dev as in GemmTnArgs.  fp32 layers of the usual
+// widths take a fused kernel (B is read once, 256 x 256 tiles); everything else goes through lp_launch_gemm_tn and
+// lp_launch_colsum.  Sums are taken in a fixed order.
+struct WeightGradArgs {
+    int32_t dtype = LP_F32;
+    int32_t Kn = 0;
+    const int32_t *kn_dev = nullptr;
+    const int32_t *at_index = nullptr;
+    const void *At[2] = {nullptr, nullptr};
+    int32_t Mw[2] = {0, 0};
+    int32_t lda[2] = {0, 0};
+    const void *B = nullptr;
+    int32_t Nw = 0, ldb = 0;
+    float *C[2] = {nullptr, nullptr};    // [Mw[s], Nw] contiguous
+    float *dbias = nullptr;              // [Nw] or null
+    float *partials = nullptr;           // lp_weight_grads_partials_bytes()
+    float *colsum_partials = nullptr;    // lp_colsum_partials_bytes(Kn, Nw); used by the unfused path
+};
+size_t lp_weight_grads_partials_bytes(int32_t dtype, int32_t Kn, int32_t Mw0, int32_t Mw1, int32_t Nw);
+int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t stream);
+
 // out[c, r] = in[r, c] for a small [rows, cols] matrix (weights) of 4-byte or 2-byte elements.
 int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, int dtype, hipStream_t stream);
 // out[n] = sum_m in[m, n] for a contiguous [M, N] matrix stored as `dtype` (N a multiple of its vector width);

@@ -107,7 +107,7 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
     for (int i = 0; i < 3; ++i) w.buf[i] = take(big);
     size_t tn = 0, cs = 0;
     for (int k = 0; k < m->n_layers; ++k) {
-        size_t t = lp_gemm_tn_partials_bytes(n_nodes, m->dims[k], m->dims[k + 1]);
+        size_t t = lp_weight_grads_partials_bytes(m->dtype, n_nodes, m->layer_type == LP_LAYER_GCN ? 0 : m->dims[k], m->dims[k], m->dims[k + 1]);
         tn = t > tn ? t : tn;
         size_t c = lp_colsum_partials_bytes(n_nodes, m->dims[k + 1]);
         cs = c > cs ? c : cs;
@@ -285,20 +285,15 @@ static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, cons
         const int32_t rows = listed ? cap : N;    // host-side bound; the exact count is read on the device
         const int32_t *rows_dev = listed ? w.n_touched : nullptr;
         const int32_t *row_of = listed ? w.touched : nullptr;
-        LP_TRY(lp_launch_colsum(dZ, dt, rows, Fo, out->dbias[k - 1], w.colsum_partials, st, rows_dev));
-        GemmTnArgs tn;
-        tn.dtype = dt;
-        tn.Kn = rows; tn.kn_dev = rows_dev; tn.at_index = row_of;
-        tn.Mw = Fi; tn.Nw = Fo;
-        tn.B = dZ; tn.ldb = Fo;
-        tn.partials = w.tn_partials;
-        tn.lda = Fi;
-        if (!gcn) {
-            tn.At = Hin; tn.C = out->dW_self[k - 1];
-            LP_TRY(lp_launch_gemm_tn(tn, st));
-        }
-        tn.At = Ak; tn.C = out->dW_neigh[k - 1];
-        LP_TRY(lp_launch_gemm_tn(tn, st));
+        WeightGradArgs wg;
+        wg.dtype = dt;
+        wg.Kn = rows; wg.kn_dev = rows_dev; wg.at_index = row_of;
+        if (!gcn) { wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1]; }
+        wg.At[1] = Ak; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW_neigh[k - 1];
+        wg.B = dZ; wg.Nw = Fo; wg.ldb = Fo;
+        wg.dbias = out->dbias[k - 1];
+        wg.partials = w.tn_partials; wg.colsum_partials = w.colsum_partials;
+        LP_TRY(lp_launch_weight_grads(wg, st));
         if (k == 1 && !out->dX) break;
         GemmNtArgs ge;
         ge.dtype = dt;

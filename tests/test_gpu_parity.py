@@ -252,7 +252,8 @@ def check_grads(grads, ref, K, lo=None, hi=None):
         assert_grad_close(host(grads.dX), ref.dX, lo.dX, hi.dX, "dX")
 
 
-@pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8]])
+@pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8],
+                                  [192, 200, 232]])   # the last: fused weight-gradient tiles that are partly empty
 @pytest.mark.parametrize("sym", [True, False])
 def test_backward_parity(dims, sym):
     rng = np.random.default_rng(1000 + sum(dims) + sym)
