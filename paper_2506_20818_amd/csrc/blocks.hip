@@ -70,43 +70,57 @@ __global__ void set_scalar_kernel(int32_t *dst, const int32_t *a, const uint32_t
     if (blockIdx.x == 0 && threadIdx.x == 0) *dst = (a ? *a : 0) + (int32_t)*b;
 }
 
-// one thread per node of the frontier: its sample, in draw order, as global ids
+// G lanes per node of the frontier (G >= fan): its sample, in draw order, as global ids.  The partial Fisher-Yates
+// shuffle runs over the virtual array a[p] = p; the positions written so far are remembered one per lane (in the order
+// they were written), so "the current value at position r" is a ballot over the group and the latest matching lane.
+// Lane q of a group computes Philox block q (the words of swaps 4q .. 4q+3) once, before the swaps.
+template <int G>
 __global__ __launch_bounds__(256) void sample_rows_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
                                                           const int32_t *__restrict__ nodes, const int32_t *__restrict__ n_rows_dev,
                                                           int32_t fan, uint32_t hop, uint32_t seed_lo, uint32_t seed_hi,
                                                           uint32_t step_lo, uint32_t step_hi, const int32_t *__restrict__ ptr,
                                                           int32_t *__restrict__ col_global, int32_t *__restrict__ row_of_entry,
                                                           const int32_t *__restrict__ index, int32_t *__restrict__ mark) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= *n_rows_dev) return;
-    const int32_t v = nodes[i];
-    const int32_t lo = rowptr[v], d = rowptr[v + 1] - lo;
-    const int32_t base = ptr[i];
-    auto emit = [&](int t, int32_t position) {
-        const int32_t u = colidx[lo + position];
-        col_global[base + t] = u;
-        row_of_entry[base + t] = (int32_t)i;
-        if (index[u] < 0) mark[u] = 1;  // joins the next frontier; every writer stores the same value
-    };
-    if (d <= fan) {
-        for (int t = 0; t < d; ++t) emit(t, t);
-        return;
+    const int lane = threadIdx.x & 63, sub = lane % G, gbase = lane - sub;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const bool live = i < *n_rows_dev;
+    int32_t v = 0, lo = 0, d = 0, base = 0;
+    if (live) {
+        v = nodes[i];
+        lo = rowptr[v];
+        d = rowptr[v + 1] - lo;
+        base = ptr[i];
     }
-    // partial Fisher-Yates over the virtual array a[p] = p; only the positions written so far are remembered
-    int32_t mpos[LP_MAX_FANOUT], mval[LP_MAX_FANOUT];
-    int nm = 0;
-    LpU4 w = {0u, 0u, 0u, 0u};
-    for (int t = 0; t < fan; ++t) {
-        if ((t & 3) == 0) w = lp_philox4x32_10(LpU4{(uint32_t)v, (hop << 16) + (uint32_t)(t >> 2), step_lo, step_hi}, seed_lo, seed_hi);
-        const uint32_t word = (t & 3) == 0 ? w.x : (t & 3) == 1 ? w.y : (t & 3) == 2 ? w.z : w.w;
-        const int32_t r = t + (int32_t)(((uint64_t)word * (uint32_t)(d - t)) >> 32);
-        int32_t val_r = r, val_t = t;
-        for (int j = nm - 1; j >= 0; --j)
-            if (mpos[j] == r) { val_r = mval[j]; break; }
-        for (int j = nm - 1; j >= 0; --j)
-            if (mpos[j] == t) { val_t = mval[j]; break; }
-        if (r != t) { mpos[nm] = r; mval[nm] = val_t; ++nm; }
-        emit(t, val_r);
+    const bool drawn = d > fan;          // same for all lanes of a group
+    int32_t position = sub;              // a node with d <= fan takes all its neighbours in list order
+    if (__any(drawn)) {
+        LpU4 w = {0u, 0u, 0u, 0u};
+        if (drawn && 4 * sub < fan) w = lp_philox4x32_10(LpU4{(uint32_t)v, (hop << 16) + (uint32_t)sub, step_lo, step_hi}, seed_lo, seed_hi);
+        const uint64_t gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull);
+        int32_t mpos = -1, mval = 0;     // remembered write number `sub` of this group
+        int nm = 0;                      // writes remembered so far
+        for (int t = 0; t < fan; ++t) {  // every lane of the wavefront runs the same trip count
+            const uint32_t mine = (t & 3) == 0 ? w.x : (t & 3) == 1 ? w.y : (t & 3) == 2 ? w.z : w.w;
+            const uint32_t word = (uint32_t)__shfl((int)mine, gbase + (t >> 2));
+            const int32_t r = t + (int32_t)(((uint64_t)word * (uint32_t)(drawn ? d - t : 1)) >> 32);
+            const uint64_t hit_r = (__ballot(sub < nm && mpos == r) >> gbase) & gmask;
+            const uint64_t hit_t = (__ballot(sub < nm && mpos == t) >> gbase) & gmask;
+            const int32_t from_r = __shfl(mval, gbase + (hit_r ? 63 - __clzll((long long)hit_r) : 0));
+            const int32_t from_t = __shfl(mval, gbase + (hit_t ? 63 - __clzll((long long)hit_t) : 0));
+            const int32_t val_r = hit_r ? from_r : r, val_t = hit_t ? from_t : t;
+            if (r != t) {
+                if (sub == nm) { mpos = r; mval = val_t; }
+                ++nm;
+            }
+            if (drawn && sub == t) position = val_r;
+        }
+    }
+    const int32_t take = d < fan ? d : fan;
+    if (live && sub < take) {
+        const int32_t u = colidx[lo + position];
+        col_global[base + sub] = u;
+        row_of_entry[base + sub] = (int32_t)i;
+        if (index[u] < 0) mark[u] = 1;  // joins the next frontier; every writer stores the same value
     }
 }
 
@@ -341,9 +355,18 @@ extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src
         }
         LP_TRY(lp_launch_zero(reinterpret_cast<float *>(w.mark), N, st));
         if (cap_k > 0)
-            hipLaunchKernelGGL(sample_rows_kernel, dim3((unsigned)lp_ceil_div(cap_k, 256)), dim3(256), 0, st, g->rowptr, g->colidx, out->nodes,
-                               n_k, fan, hop, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32), ptr,
-                               w.col_global, w.row_of_entry, out->index, w.mark);
+        {
+            const int G = fan <= 16 ? 16 : 64;
+            const dim3 sgrid((unsigned)lp_ceil_div((int64_t)cap_k * G, 256));
+            if (G == 16)
+                hipLaunchKernelGGL(sample_rows_kernel<16>, sgrid, dim3(256), 0, st, g->rowptr, g->colidx, out->nodes, n_k, fan, hop, (uint32_t)seed,
+                                   (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32), ptr, w.col_global, w.row_of_entry, out->index,
+                                   w.mark);
+            else
+                hipLaunchKernelGGL(sample_rows_kernel<64>, sgrid, dim3(256), 0, st, g->rowptr, g->colidx, out->nodes, n_k, fan, hop, (uint32_t)seed,
+                                   (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32), ptr, w.col_global, w.row_of_entry, out->index,
+                                   w.mark);
+        }
         {   // the drawn nodes that are new join the node list, ascending
             const int32_t *mark = w.mark;
             int32_t *nodes = out->nodes, *index = out->index;

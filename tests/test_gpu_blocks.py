@@ -65,7 +65,8 @@ def run_case(csr_ref, g, Ws, Wn, b, X, es, ed, n_pos, fanout, seed, step):
 
 
 @pytest.mark.parametrize("dims,fanout", [([8, 16, 4], [3, 2]), ([12, 20, 16, 8], [25, 10, 5]), ([128, 256, 256, 256], [25, 10, 5]),
-                                         ([64, 64], [64]), ([36, 68, 32], [1, 1])])
+                                         ([64, 64], [64]), ([36, 68, 32], [1, 1]),
+                                         ([8, 16, 4], [16, 17])])   # both sides of the 16-lane / 64-lane draw kernels
 @pytest.mark.parametrize("sym", [True, False])
 def test_sampled_step_small_graphs(dims, fanout, sym):
     rng = np.random.default_rng(sum(dims) + sum(fanout) + sym)
