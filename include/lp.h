@@ -354,6 +354,11 @@ int lp_adam_step(const lp_model *m, const lp_grads *g, const lp_opt_state *s, in
  * lp_backward_blocks: weight and bias gradients of the batch loss through the
  * blocks (dscore from lp_score_loss); out->dX is ignored.  Fixed summation
  * order: repeated calls give the same bits.
+ *
+ * lp_backward_blocks_edge_grads: the same with dL/dH^K seeded from edge_grad
+ * (device [n_edges, F_K], storage type, from lp_mlp_backward on the frontier
+ * positions: Eq. 2 with the MLP scorer): row e_src_pos[e] receives
+ * edge_grad_e * h_v, row e_dst_pos[e] receives edge_grad_e * h_u.
  */
 int lp_blocks_bounds(int32_t n_nodes, int64_t nnz, int64_t B, int32_t K, const int32_t *fanout, int32_t *cap,
                      int64_t *cap_entries);
@@ -366,6 +371,8 @@ int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, const void *X,
 size_t lp_backward_blocks_workspace_bytes(const lp_model *m, const lp_blocks *b);
 int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved, const float *dscore,
                        lp_grads *out, void *ws, size_t ws_bytes, void *stream);
+int lp_backward_blocks_edge_grads(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved,
+                                  const void *edge_grad, lp_grads *out, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * MLP edge predictor (Eq. 2 with the MLP the paper's experiments use, see

@@ -126,10 +126,16 @@ def forward_blocks(b: Blocks, W_self, W_neigh, bias, X) -> BlockActs:
     return BlockActs(H, A, Z)
 
 
-def backward_blocks(b: Blocks, W_self, W_neigh, acts: BlockActs, dscore, relu_margin: float = 0.0) -> O.Grads:
-    """Chain rule through scorer, layers and sampled aggregation; dX is not formed."""
+def backward_blocks(b: Blocks, W_self, W_neigh, acts: BlockActs, dscore, relu_margin: float = 0.0, seed_grad=None) -> O.Grads:
+    """Chain rule through scorer, layers and sampled aggregation; dX is not formed.
+
+    ``seed_grad``: dL/dH^K on frontier K given directly by a scorer other than the dot product (dscore is then unused).
+    """
     K = len(W_self)
-    G = O.edge_grad_scatter(acts.H[K], b.e_src_pos, b.e_dst_pos, np.asarray(dscore, np.float64))
+    if seed_grad is not None:
+        G = np.asarray(seed_grad, np.float64)
+    else:
+        G = O.edge_grad_scatter(acts.H[K], b.e_src_pos, b.e_dst_pos, np.asarray(dscore, np.float64))
     dWs, dWn, db = [None] * K, [None] * K, [None] * K
     for k in range(K, 0, -1):
         nk = int(b.n[k])

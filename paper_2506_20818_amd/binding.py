@@ -112,6 +112,8 @@ EXPORTS = {
     "lp_backward_blocks_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.POINTER(_BlocksStruct)]),
     "lp_backward_blocks": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                                      C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_backward_blocks_edge_grads": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
+                                     C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_mlp_score_loss_workspace_bytes": (C.c_size_t, [C.POINTER(_MlpStruct), C.c_int64]),
     "lp_mlp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(_MlpStruct),
                                     C.POINTER(_MlpActsStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -444,6 +446,20 @@ def lp_backward_blocks(b: Blocks, m: Model, acts: BlockActs, dscore: torch.Tenso
         ws = _ws(lib.lp_backward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)), dev)
     _check(lib.lp_backward_blocks(C.byref(b.c), C.byref(m.c), _ptr(acts.X_frontier), C.byref(acts.c), _ptr(dscore),
                                   C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward_blocks")
+    return grads
+
+
+def lp_backward_blocks_edge_grads(b: Blocks, m: Model, acts: BlockActs, edge_grad: torch.Tensor, grads: Optional[Grads] = None,
+                                  ws: Optional[torch.Tensor] = None) -> Grads:
+    lib = load_library()
+    _need(edge_grad, m.torch_dtype, "edge_grad")
+    dev = edge_grad.device
+    if grads is None:
+        grads = Grads(1, m.dims, dev, False, m.torch_dtype)
+    if ws is None:
+        ws = _ws(lib.lp_backward_blocks_workspace_bytes(C.byref(m.c), C.byref(b.c)), dev)
+    _check(lib.lp_backward_blocks_edge_grads(C.byref(b.c), C.byref(m.c), _ptr(acts.X_frontier), C.byref(acts.c), _ptr(edge_grad),
+                                             C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward_blocks_edge_grads")
     return grads
 
 

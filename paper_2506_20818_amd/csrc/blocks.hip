@@ -469,14 +469,18 @@ extern "C" size_t lp_backward_blocks_workspace_bytes(const lp_model *m, const lp
     return carve_block_backward(nullptr, m, b).bytes;
 }
 
-extern "C" int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved,
-                                  const float *dscore, lp_grads *out, void *ws, size_t ws_bytes, void *stream) {
+namespace {
+// dL/dH^K is seeded either from dscore (dot-product scorer) or from edge_grad (per-edge gradient rows of another
+// scorer); exactly one of the two is given.
+int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved, const float *dscore,
+                         const void *edge_grad, lp_grads *out, void *ws, size_t ws_bytes, void *stream) {
     LP_TRY(check_blocks(b, true));
     LP_TRY(check_block_model(m, b));
     if (!X_frontier || !lp_aligned16(X_frontier) || !saved || !out) return LP_ERR_INVALID_ARG;
     const int K = m->n_layers;
     const int64_t B = b->n_edges;
-    if (B < 0 || (B > 0 && !dscore)) return LP_ERR_INVALID_ARG;
+    if (B < 0 || (B > 0 && !dscore && !edge_grad)) return LP_ERR_INVALID_ARG;
+    if (edge_grad && !lp_aligned16(edge_grad)) return LP_ERR_INVALID_ARG;
     for (int k = 0; k < K; ++k) {
         if (!saved->A[k] || !saved->H[k]) return LP_ERR_INVALID_ARG;
         if (!out->dW_self[k] || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
@@ -503,7 +507,9 @@ extern "C" int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const v
         SpmmArgs sc;
         sc.dtype = dt;
         sc.n_rows = b->cap[K]; sc.n_rows_dev = b->n + K; sc.F = m->dims[K];
-        sc.rowptr = w.bptr; sc.colidx = w.bcol; sc.w = w.bw;
+        sc.rowptr = w.bptr; sc.colidx = w.bcol;
+        if (dscore) sc.w = w.bw;
+        else { sc.entry_rows = edge_grad; sc.entry_row_index = reinterpret_cast<const int32_t *>(w.bw); }
         sc.n_entries = 2 * B; sc.long_queue = w.long_queue;
         sc.in = saved->H[K - 1]; sc.out = dZ;
         sc.timing_class = LP_KC_SCATTER;
@@ -548,4 +554,17 @@ extern "C" int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const v
         LP_TRY(lp_launch_spmm(sp, st));
     }
     return LP_OK;
+}
+}  // namespace
+
+extern "C" int lp_backward_blocks(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved,
+                                  const float *dscore, lp_grads *out, void *ws, size_t ws_bytes, void *stream) {
+    if (b && b->n_edges > 0 && !dscore) return LP_ERR_INVALID_ARG;
+    return backward_blocks_impl(b, m, X_frontier, saved, dscore, nullptr, out, ws, ws_bytes, stream);
+}
+
+extern "C" int lp_backward_blocks_edge_grads(const lp_blocks *b, const lp_model *m, const void *X_frontier, const lp_acts *saved,
+                                             const void *edge_grad, lp_grads *out, void *ws, size_t ws_bytes, void *stream) {
+    if (b && b->n_edges > 0 && !edge_grad) return LP_ERR_INVALID_ARG;
+    return backward_blocks_impl(b, m, X_frontier, saved, nullptr, edge_grad, out, ws, ws_bytes, stream);
 }

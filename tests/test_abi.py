@@ -248,6 +248,12 @@ def test_blocks_bounds_and_argument_checks_on_the_host():
     assert bwd(ws=None) == -3
     assert bwd(wsb=128) == -3
     assert lib.lp_backward_blocks_workspace_bytes(C.byref(m), C.byref(b)) > 0
+    bwd_eg = lambda eg=p, gr=grads, ws=p, wsb=1 << 40: lib.lp_backward_blocks_edge_grads(
+        C.byref(b), C.byref(m), p, C.byref(acts), eg, C.byref(gr), ws, wsb, None)
+    assert bwd_eg(eg=None) == -1
+    assert bwd_eg(eg=C.c_void_p(0x1004)) == -1            # not 16-byte aligned
+    assert bwd_eg(gr=B._GradsStruct()) == -1
+    assert bwd_eg(ws=None) == -3
     assert lib.lp_forward_blocks_workspace_bytes(C.byref(_model([128, 256])), C.byref(b)) == 0
 
 

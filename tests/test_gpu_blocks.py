@@ -127,3 +127,47 @@ def test_sampled_step_collab_scale_batch():
     es, ed = O.batch_edges(pos_src, pos_dst, neg, 1)
     blocks, ref = run_case(ref_csr, g, wl.W_self, wl.W_neigh, wl.bias, wl.X, es, ed, n_pos, [25, 10, 5], seed=2024, step=9)
     say("frontiers %s, block entries %s" % (ref.n.tolist(), [int(p[-1]) for p in ref.ptr]))
+
+
+@pytest.mark.parametrize("dims,fanout", [([12, 20, 8], [4, 3]), ([128, 256, 256, 256], [25, 10, 5])])
+def test_sampled_step_with_mlp_predictor(dims, fanout):
+    """Sampled blocks + the MLP scorer: lp_mlp_score_loss / lp_mlp_backward on frontier positions, then
+    lp_backward_blocks_edge_grads; against blocks_oracle + mlp_oracle."""
+    from oracle import mlp_oracle as M
+    from test_gpu_mlp import mlp_weights
+    rng = np.random.default_rng(1300 + sum(dims))
+    n = 1200
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3300, 500)
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 400, 200
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    es[:60] = 3                                      # the hub end point is scored many times
+    W, cc = mlp_weights(rng, [dims[-1], 32, 16], scale=0.4)
+    K = len(fanout)
+    say("sampled step with MLP predictor dims=%s fanout=%s" % (dims, fanout))
+    bref = Bk.sample_blocks(ref, es, ed, fanout, 11, 2)
+    blocks = lp.lp_sample_blocks(g, dev_i32(es), dev_i32(ed), fanout, 11, 2)
+    check_blocks(blocks, bref, K)
+    model = make_model(Ws, Wn, b)
+    p = lp.Mlp([dev_f32(w) for w in W], [dev_f32(x) for x in cc])
+    acts = lp.lp_sage_forward_blocks(blocks, model, dev_f32(X))
+    s, loss, ds, macts = lp.lp_mlp_score_loss(acts.H[-1], blocks.e_src_pos, blocks.e_dst_pos, n_pos, p)
+    mgrads, eg = lp.lp_mlp_backward(p, macts, ds)
+    grads = lp.lp_backward_blocks_edge_grads(blocks, model, acts, eg)
+    torch.cuda.synchronize()
+    a_ref = Bk.forward_blocks(bref, Ws, Wn, b, X)
+    s_ref, ma_ref = M.mlp_scores(a_ref.H[K], bref.e_src_pos, bref.e_dst_pos, W, cc)
+    loss_ref, ds_ref = M.bce_mean(s_ref, n_pos)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * max(1.0, abs(loss_ref))
+    out = {}
+    for name, margin in (("ref", 0.0), ("lo", 5e-6), ("hi", -5e-6)):
+        _, _, _, G_ref = M.mlp_backward(a_ref.H[K], bref.e_src_pos, bref.e_dst_pos, W, ma_ref, ds_ref, relu_margin=margin)
+        out[name] = Bk.backward_blocks(bref, Ws, Wn, a_ref, None, relu_margin=margin, seed_grad=G_ref)
+    for k in range(K):
+        assert_grad_close(host(grads.dW_self[k]), out["ref"].dW_self[k], out["lo"].dW_self[k], out["hi"].dW_self[k], "dW_self^%d" % (k + 1))
+        assert_grad_close(host(grads.dW_neigh[k]), out["ref"].dW_neigh[k], out["lo"].dW_neigh[k], out["hi"].dW_neigh[k], "dW_neigh^%d" % (k + 1))
+        assert_grad_close(host(grads.dbias[k]), out["ref"].dbias[k], out["lo"].dbias[k], out["hi"].dbias[k], "dbias^%d" % (k + 1))

@@ -158,3 +158,44 @@ def test_sampled_gradients_match_central_finite_differences(dims):
                 arrs[k][idx] = old
                 fd = (lp_ - lm_) / (2 * h)
                 assert abs(fd - grad[k][idx]) < 1e-7 + 1e-5 * abs(fd), (name, k, idx, fd, grad[k][idx])
+
+
+def test_sampled_gradients_with_mlp_scorer_match_central_finite_differences():
+    """The seed_grad path: the MLP scorer's gradient on frontier K, pushed through the sampled blocks, against central
+    differences of the loss of the whole chain (blocks forward -> MLP scores -> BCE mean)."""
+    from oracle import mlp_oracle as M
+    rng = np.random.default_rng(41)
+    n, dims = 50, [4, 6, 5]
+    csr = graph(rng, n, 200, hub=20)
+    K = len(dims) - 1
+    Ws, Wn, b = model(rng, dims)
+    X = rng.standard_normal((n, dims[0]))
+    es, ed = rng.integers(0, n, 10).astype(np.int32), rng.integers(0, n, 10).astype(np.int32)
+    blocks = Bk.sample_blocks(csr, es, ed, [3, 2], seed=9, step=1)
+    W = [rng.standard_normal((dims[-1], 4)) * 0.5, rng.standard_normal((4, 1)) * 0.5]
+    c = [rng.standard_normal(4) * 0.2, rng.standard_normal(1) * 0.2]
+
+    def loss_of(Ws_, Wn_, b_):
+        a = Bk.forward_blocks(blocks, Ws_, Wn_, b_, X)
+        s, _ = M.mlp_scores(a.H[K], blocks.e_src_pos, blocks.e_dst_pos, W, c)
+        return M.bce_mean(s, 6)[0]
+
+    acts = Bk.forward_blocks(blocks, Ws, Wn, b, X)
+    s, macts = M.mlp_scores(acts.H[K], blocks.e_src_pos, blocks.e_dst_pos, W, c)
+    _, ds = M.bce_mean(s, 6)
+    _, _, _, G = M.mlp_backward(acts.H[K], blocks.e_src_pos, blocks.e_dst_pos, W, macts, ds)
+    g = Bk.backward_blocks(blocks, Ws, Wn, acts, None, seed_grad=G)
+    h = 1e-6
+    for k in range(K):
+        for name, arrs, grad in (("Ws", Ws, g.dW_self), ("Wn", Wn, g.dW_neigh), ("b", b, g.dbias)):
+            it = np.nditer(arrs[k], flags=["multi_index"])
+            for _ in it:
+                idx = it.multi_index
+                old = arrs[k][idx]
+                arrs[k][idx] = old + h
+                lp_ = loss_of(Ws, Wn, b)
+                arrs[k][idx] = old - h
+                lm_ = loss_of(Ws, Wn, b)
+                arrs[k][idx] = old
+                fd = (lp_ - lm_) / (2 * h)
+                assert abs(fd - grad[k][idx]) < 1e-7 + 1e-5 * abs(fd), (name, k, idx, fd, grad[k][idx])
