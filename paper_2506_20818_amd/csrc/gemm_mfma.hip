@@ -1182,7 +1182,9 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (fast_ok) {
         // persistent workgroups filling every compute unit; the widest tile (256 x 256, eight wavefronts, 128-byte
         // K step, one workgroup per compute unit) when K allows
-        const bool big = fast_bn == 256 && (a.K[0] * es % 128 == 0) && (a.K[1] * es % 128 == 0) && a.M >= 4096;
+        // (with fewer 256-row tiles than compute units, 128-row tiles spread the same work over twice as many of them)
+        const bool big = fast_bn == 256 && (a.K[0] * es % 128 == 0) && (a.K[1] * es % 128 == 0) &&
+                         lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units();
         const int bm = big ? 256 : 128;
         const int64_t row_tiles = lp_ceil_div(a.M, bm);
         const int64_t slots = (big ? 1 : 2) * (int64_t)lp_compute_units();
