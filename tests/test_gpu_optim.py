@@ -124,3 +124,53 @@ def test_single_tensor_updates_match_oracle(bf16):
     lp.lp_sgd_update_tensor(w, dev_f32(g), 0.05)
     ref = P.sgd_step(ref, g.astype(np.float64), float(np.float32(0.05)), storage="bf16" if bf16 else "f32")
     assert np.all(np.abs(host(w.float()) - ref) <= np.abs(ref) * (2.0 ** -7 if bf16 else 2e-6) + 1e-7)
+
+
+def test_training_loop_follows_the_oracle_for_several_steps():
+    """Algorithm 1's per-worker loop on a small graph: negatives (new Philox step each iteration), forward, loss,
+    backward, Adam update, five times, on the GPU and in the oracle (its own Adam on its own gradients).  The loss
+    trajectories stay together, the loss goes down, and the accumulated weight change agrees per tensor."""
+    from oracle import lp_oracle as O
+    from gpu_util import HipStep, dev_i32, make_model
+    rng = np.random.default_rng(2024)
+    n, dims = 900, [16, 32, 24]
+    K = len(dims) - 1
+    src, dst = rng.integers(0, n, 3000).astype(np.int32), rng.integers(0, n, 3000).astype(np.int32)
+    ref_csr = O.build_csr(n, src, dst, True)
+    g = lp.lp_build_csr(n, dev_i32(src), dev_i32(dst), True)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    Ws = [(rng.standard_normal((dims[k], dims[k + 1])) * 0.3).astype(np.float32) for k in range(K)]
+    Wn = [(rng.standard_normal((dims[k], dims[k + 1])) * 0.3).astype(np.float32) for k in range(K)]
+    b = [(rng.standard_normal(dims[k + 1]) * 0.1).astype(np.float32) for k in range(K)]
+    pick = rng.choice(src.size, 256, replace=False)
+    pos_src, pos_dst = src[pick], dst[pick]
+    model = make_model(Ws, Wn, b)
+    state = lp.AdamState(model)
+    Xd = dev_f32(X)
+    ref = {"W_self": [w.astype(np.float64) for w in Ws], "W_neigh": [w.astype(np.float64) for w in Wn], "bias": [x.astype(np.float64) for x in b]}
+    start = {k: [x.copy() for x in v] for k, v in ref.items()}
+    mom = {k: [np.zeros_like(x) for x in v] for k, v in ref.items()}
+    vel = {k: [np.zeros_like(x) for x in v] for k, v in ref.items()}
+    hp = dict(lr=float(np.float32(1e-2)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)), eps=float(np.float32(1e-8)))
+    losses_gpu, losses_ref = [], []
+    for t in range(1, 6):
+        say("training loop iteration %d" % t)
+        got = HipStep(g, model, Xd, dev_i32(pos_src), dev_i32(pos_dst), 2, n, 99, t, want_dX=False)
+        lp.lp_adam_step(model, got.grads, state, t, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8)
+        exp = O.train_step(ref_csr, ref["W_self"], ref["W_neigh"], ref["bias"], X, pos_src, pos_dst, 2, n, 99, t)
+        assert np.array_equal(host(got.e_dst), exp.e_dst)                     # same negatives at every step
+        losses_gpu.append(float(host(got.loss)[0]))
+        losses_ref.append(float(exp.loss))
+        gr = {"W_self": exp.grads.dW_self, "W_neigh": exp.grads.dW_neigh, "bias": exp.grads.dbias}
+        for key in ref:
+            for k in range(K):
+                ref[key][k], mom[key][k], vel[key][k] = P.adam_step(ref[key][k], gr[key][k], mom[key][k], vel[key][k], t, **hp)
+    torch.cuda.synchronize()
+    assert np.allclose(losses_gpu, losses_ref, rtol=1e-3, atol=0), (losses_gpu, losses_ref)
+    assert losses_ref[-1] < losses_ref[0] and losses_gpu[-1] < losses_gpu[0]
+    for key in ("W_self", "W_neigh", "bias"):
+        for k, tns in enumerate(getattr(model, key)):
+            moved_gpu = host(tns.float()).astype(np.float64) - start[key][k]
+            moved_ref = ref[key][k] - start[key][k]
+            rel = np.linalg.norm(moved_gpu - moved_ref) / np.linalg.norm(moved_ref)
+            assert rel < 2e-2, "%s[%d]: accumulated update differs by %.3e (relative L2)" % (key, k, rel)
