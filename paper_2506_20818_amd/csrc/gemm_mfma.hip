@@ -1030,6 +1030,164 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
     }
 }
 
+// The same for bfloat16 storage.  The MFMA (v_mfma_f32_32x32x16_bf16) takes eight consecutive nodes per lane while
+// memory is node-major, so a loader thread fetches an 8 x 8 block (eight nodes, sixteen bytes of each), transposes it
+// in registers and writes eight 16-byte pieces to an LDS tile laid out [column][node] (pitch 64 + 8 nodes).  256 x 256
+// output tile, eight wavefronts of 64 x 128, 64 nodes per step, two LDS stages, one barrier per step; wavefronts 0-3
+// load the [At0 | At1] tile, wavefronts 4-7 the B tile.  The column sums of B are not taken here.
+template <bool INDEXED>
+__global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2))) void weight_grads_bf16_kernel(WeightGradArgs g, int chunk,
+                                                                                                              int splits, int tiles_n, int tiles) {
+    constexpr int STAGE = 512 * T_LD;  // elements per LDS stage: 256 columns of each operand
+    __shared__ __attribute__((aligned(16))) lp_bf16_t lds[2 * STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int L = blockIdx.x;
+    const int s = (L & 7) + 8 * ((L >> 3) / tiles);
+    const int t = (L >> 3) % tiles;
+    if (s >= splits) return;
+    const int m0 = (t / tiles_n) * 256, n0 = (t % tiles_n) * 256;
+    const int Mtot = g.Mw[0] + g.Mw[1];
+    int64_t Kn_ = g.Kn;
+    if (g.kn_dev) {
+        Kn_ = min((int64_t)*g.kn_dev, (int64_t)g.Kn);
+        chunk = (int)(((Kn_ + splits - 1) / splits + TK - 1) / TK * TK);
+    }
+    const int64_t kbeg = (int64_t)s * chunk;
+    const int64_t kend = kbeg + chunk < Kn_ ? kbeg + chunk : Kn_;
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    // column sums of B: the workgroups of the first tile row add up what their B loaders pass on, per thread for
+    // its eight columns and its node chunk (fp32 sums of the transposed node pairs)
+    const bool do_bias = g.dbias != nullptr && m0 == 0;
+    float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    if (kbeg < kend) {
+        // loader task: node chunk q (8 nodes) and column chunk c (8 columns) of one operand tile
+        const bool loads_a = tid < 256;
+        const int task = tid & 255;
+        const int q = task & 7, c = task >> 3;
+        const int col = (loads_a ? m0 : n0) + 8 * c;
+        const bool col_ok = col < (loads_a ? Mtot : g.Nw);
+        // a thread whose columns lie outside the operand still loads (column 0) and drops the values
+        const lp_bf16_t *src;
+        int64_t pitch;
+        if (!loads_a) { src = static_cast<const lp_bf16_t *>(g.B) + (col_ok ? col : 0); pitch = g.ldb; }
+        else if (col < g.Mw[0]) { src = static_cast<const lp_bf16_t *>(g.At[0]) + col; pitch = g.lda[0]; }
+        else { src = static_cast<const lp_bf16_t *>(g.At[1]) + (col_ok ? col - g.Mw[0] : 0); pitch = g.lda[1]; }
+        const bool indexed = INDEXED && loads_a;
+        const int dst_off = (loads_a ? 0 : 256 * T_LD) + (8 * c) * T_LD + 8 * q;
+        const int64_t klast = Kn_ - 1;
+        v4i rows[8];
+        int64_t srow[8];
+        auto lookup = [&](int64_t k0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int64_t k = min(k0 + 8 * q + e, klast);
+                srow[e] = indexed ? (int64_t)g.at_index[k] : k;
+            }
+        };
+        auto fetch = [&](int64_t k0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool live = col_ok && k0 + 8 * q + e < kend;
+                const v4i v = *reinterpret_cast<const v4i *>(src + srow[e] * pitch);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) rows[e][d] = live ? v[d] : 0;
+            }
+        };
+        auto stash = [&](int stage) {
+            lp_bf16_t *dst = lds + stage * STAGE + dst_off;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {  // column j of the block: nodes 0..7, two per 32-bit word
+                v4i o;
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+                    o[d] = (int)__builtin_amdgcn_perm((uint32_t)rows[2 * d + 1][j >> 1], (uint32_t)rows[2 * d][j >> 1],
+                                                      (j & 1) ? 0x07060302u : 0x05040100u);
+                *reinterpret_cast<v4i *>(dst + j * T_LD) = o;
+                if (do_bias && !loads_a) {
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+                        bsum[j] += __uint_as_float((uint32_t)o[d] << 16) + __uint_as_float((uint32_t)o[d] & 0xffff0000u);
+                }
+            }
+        };
+        auto compute = [&](int stage, int kk0) {
+            const lp_bf16_t *As = lds + stage * STAGE, *Bs = As + 256 * T_LD;
+#pragma unroll
+            for (int kk = kk0; kk < kk0 + TK / 32; ++kk) {
+                v4i a[2], b[4];
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) a[rb] = *reinterpret_cast<const v4i *>(&As[(wm * 64 + rb * 32 + i32) * T_LD + kk * 16 + 8 * h]);
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) b[cb] = *reinterpret_cast<const v4i *>(&Bs[(wn * 128 + cb * 32 + i32) * T_LD + kk * 16 + 8 * h]);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[rb]), __builtin_bit_cast(v8bf, b[cb]),
+                                                                              acc[rb][cb], 0, 0, 0);
+            }
+        };
+
+        lookup(kbeg);
+        fetch(kbeg);
+        lookup(kbeg + TK);
+        stash(0);
+        fetch(kbeg + TK);
+        lookup(kbeg + 2 * TK);
+        __syncthreads();
+        int cur = 0;
+        for (int64_t k0 = kbeg; k0 < kend; k0 += TK, cur ^= 1) {
+            compute(cur, 0);
+            stash(cur ^ 1);                 // registers hold step k0 + 64 (zeros past the end)
+            fetch(k0 + 2 * TK);
+            lookup(k0 + 3 * TK);
+            compute(cur, TK / 32);
+            __syncthreads();
+        }
+    }
+
+    const int64_t ptot = (int64_t)Mtot * g.Nw + g.Nw;
+    float *__restrict__ P = g.partials + (int64_t)s * ptot;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const int n = n0 + wn * 128 + cb * 32 + i32;
+        if (n >= g.Nw) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < Mtot) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
+            }
+    }
+    if (do_bias) {  // the eight node chunks of a column meet in LDS and are added in a fixed order
+        float *red = reinterpret_cast<float *>(lds);
+        __syncthreads();
+        if (tid >= 256) {
+            const int task = tid & 255;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) red[(task & 7) * 256 + 8 * (task >> 3) + j] = bsum[j];
+        }
+        __syncthreads();
+        if (tid < 256 && n0 + tid < g.Nw) {
+            float sum = 0.f;
+#pragma unroll
+            for (int qq = 0; qq < 8; ++qq) sum += red[qq * 256 + tid];
+            P[(int64_t)Mtot * g.Nw + n0 + tid] = sum;
+        }
+    }
+}
+
 // out = sum over the `rows` partial rows of P[rows, n0 + n1 + n2], columns routed to three outputs.  Same order of
 // additions as colsum_partial_kernel.
 __global__ __launch_bounds__(kThreads) void weight_grads_fold_kernel(const float *__restrict__ P, int rows, int64_t row_len, int64_t n0,
@@ -1259,17 +1417,19 @@ WgPlan plan_weight_grads(int32_t dtype, int32_t Kn, int32_t Mw0, int32_t Mw1, in
     WgPlan p;
     const int Mtot = Mw0 + Mw1;
     // fused path: fp32, 16-byte pieces never straddle the two operands, tiles reasonably full
-    p.fused = dtype == LP_F32 && Kn > 0 && Mw1 > 0 && (Mw0 % 4) == 0 && (Mw1 % 4) == 0 && (Nw % 4) == 0 && Mtot >= 192 && Nw >= 192 &&
-              (Mtot % 256 == 0 || Mtot % 256 >= 128) && (Nw % 256 == 0 || Nw % 256 >= 128);
+    const int ve = lp_vec_elems(dtype);
+    p.fused = (dtype == LP_F32 || dtype == LP_BF16) && Kn > 0 && Mw1 > 0 && (Mw0 % ve) == 0 && (Mw1 % ve) == 0 && (Nw % ve) == 0 &&
+              Mtot >= 192 && Nw >= 192 && (Mtot % 256 == 0 || Mtot % 256 >= 128) && (Nw % 256 == 0 || Nw % 256 >= 128);
     if (!p.fused) return p;
+    const int step = dtype == LP_BF16 ? TK : WG_BK;   // nodes per step
     p.tiles_m = (int)lp_ceil_div(Mtot, 256);
     p.tiles_n = (int)lp_ceil_div(Nw, 256);
     p.tiles = p.tiles_m * p.tiles_n;
     int64_t want = lp_ceil_div(lp_compute_units(), p.tiles);   // one workgroup per compute unit
-    const int64_t max_by_len = lp_ceil_div(Kn, 8 * WG_BK);     // at least 256 nodes per workgroup
+    const int64_t max_by_len = lp_ceil_div(Kn, 256);           // at least 256 nodes per workgroup
     int64_t s = want < max_by_len ? want : max_by_len;
     if (s < 1) s = 1;
-    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), WG_BK) * WG_BK);
+    p.chunk = (int)(lp_ceil_div(lp_ceil_div(Kn, s), step) * step);
     p.splits = (int)lp_ceil_div(Kn, p.chunk);
     return p;
 }
@@ -1286,13 +1446,20 @@ size_t lp_weight_grads_partials_bytes(int32_t dtype, int32_t Kn, int32_t Mw0, in
 int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t st) {
     if (a.Nw <= 0) return LP_OK;
     const WgPlan p = plan_weight_grads(a.dtype, a.Kn, a.Mw[0], a.Mw[1], a.Nw);
-    const bool aligned = lp_aligned16(a.At[0]) && lp_aligned16(a.At[1]) && lp_aligned16(a.B) && (a.lda[0] % 4) == 0 && (a.lda[1] % 4) == 0 &&
-                         (a.ldb % 4) == 0 && lp_aligned16(a.C[0]) && lp_aligned16(a.C[1]) && (!a.dbias || lp_aligned16(a.dbias));
+    const int ve = lp_vec_elems(a.dtype);
+    const bool aligned = lp_aligned16(a.At[0]) && lp_aligned16(a.At[1]) && lp_aligned16(a.B) && (a.lda[0] % ve) == 0 && (a.lda[1] % ve) == 0 &&
+                         (a.ldb % ve) == 0 && lp_aligned16(a.C[0]) && lp_aligned16(a.C[1]) && (!a.dbias || lp_aligned16(a.dbias));
     if (p.fused && aligned && (a.Mw[0] == 0 || (a.At[0] && a.C[0])) && a.At[1] && a.B && a.C[1] && a.partials) {
+        const bool bf16 = a.dtype == LP_BF16;
         LpTimedScope timed(LP_KC_GEMM_TN, st);
         const unsigned grid = (unsigned)(p.tiles * lp_ceil_div(p.splits, 8) * 8);
-        if (a.at_index) hipLaunchKernelGGL(weight_grads_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
-        else hipLaunchKernelGGL(weight_grads_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        if (bf16) {
+            if (a.at_index) hipLaunchKernelGGL(weight_grads_bf16_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+            else hipLaunchKernelGGL(weight_grads_bf16_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        } else {
+            if (a.at_index) hipLaunchKernelGGL(weight_grads_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+            else hipLaunchKernelGGL(weight_grads_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        }
         LP_TRY(lp_after_launch());
         const int64_t n0 = (int64_t)a.Mw[0] * a.Nw, n1 = (int64_t)a.Mw[1] * a.Nw, n2 = a.dbias ? a.Nw : 0;
         hipLaunchKernelGGL(weight_grads_fold_kernel, dim3((unsigned)lp_ceil_div((n0 + n1 + n2) / 4, 64)), dim3(kThreads), 0, st, a.partials,

@@ -82,7 +82,8 @@ def check_grads(grads, ref, K):
         assert_close(hostf(grads.dX), ref.dX, TOL_GRAD, "dX")
 
 
-@pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24]])
+@pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24],
+                                  [192, 200, 232]])   # the last: fused weight-gradient tiles that are partly empty
 @pytest.mark.parametrize("sym", [True, False])
 def test_backward_parity_bf16(dims, sym):
     rng = np.random.default_rng(2000 + sum(dims) + sym)
