@@ -218,7 +218,7 @@ MlpBackwardWs carve_backward(void *ws, const lp_mlp *p, int64_t B) {
     for (int i = 0; i < 2; ++i) w.buf[i] = take((size_t)lp_elem_bytes(p->dtype) * rows * (size_t)wmax);
     size_t tn = 0, cs = lp_colsum_partials_bytes((int64_t)rows, wmax + 4);
     for (int j = 1; j < p->n_layers; ++j) {
-        const size_t t = lp_gemm_tn_partials_bytes((int32_t)rows, p->dims[j - 1], p->dims[j]);
+        const size_t t = lp_weight_grads_partials_bytes(p->dtype, (int32_t)rows, 0, p->dims[j - 1], p->dims[j]);
         tn = t > tn ? t : tn;
     }
     w.tn_partials = reinterpret_cast<float *>(take(tn));
@@ -345,15 +345,14 @@ extern "C" int lp_mlp_backward(const lp_mlp *p, const lp_mlp_acts *saved, int64_
     for (int j = L - 1; j >= 1; --j) {
         const int Fi = p->dims[j - 1], Fo = p->dims[j];
         const void *Uin = j > 1 ? saved->U[j - 2] : saved->X;
-        LP_TRY(lp_launch_colsum(dZ, dt, B, Fo, out->dbias[j - 1], w.colsum_partials, st));
-        GemmTnArgs tn;
-        tn.dtype = dt;
-        tn.Kn = (int32_t)B; tn.Mw = Fi; tn.Nw = Fo;
-        tn.At = Uin; tn.lda = Fi;
-        tn.B = dZ; tn.ldb = Fo;
-        tn.C = out->dW[j - 1];
-        tn.partials = w.tn_partials;
-        LP_TRY(lp_launch_gemm_tn(tn, st));
+        WeightGradArgs wg;   // dW_j = U_{j-1}^T dZ and db_j = column sums of dZ in one pass
+        wg.dtype = dt;
+        wg.Kn = (int32_t)B;
+        wg.At[1] = Uin; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW[j - 1];
+        wg.B = dZ; wg.Nw = Fo; wg.ldb = Fo;
+        wg.dbias = out->dbias[j - 1];
+        wg.partials = w.tn_partials; wg.colsum_partials = w.colsum_partials;
+        LP_TRY(lp_launch_weight_grads(wg, st));
         void *dst = j > 1 ? other : edge_grad;
         GemmNtArgs ge;
         ge.dtype = dt;
