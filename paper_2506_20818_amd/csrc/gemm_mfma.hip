@@ -891,17 +891,22 @@ TnPlan plan_tn(int32_t Kn, int32_t Mw, int32_t Nw) {
 // ------------------------------------------------------------------------------------------------ fused weight gradients
 // [At0 | At1]^T B and the column sums of B for fp32 storage.  256 x 256 output tile, eight wavefronts of 64 x 128,
 // 32 nodes per step, two LDS stages with one barrier per step; the reduction over nodes is split across the grid
-// and the partial tiles (and partial column sums, taken from the B tile in LDS and written by the workgroups of the
-// first tile row) are folded afterwards in a fixed order.  Loads are unconditional: a node beyond the end of the chunk reads
-// the last valid row and is replaced by zeros.
+// and the partial tiles (and partial column sums, written by the workgroups of the first tile row) are folded
+// afterwards in a fixed order.
+// A loader thread fetches a 4 x 4 block of each operand (four nodes, sixteen bytes of each) and writes it transposed
+// (a renaming of registers) into an LDS tile laid out [column][node], pitch 32 nodes + 16 bytes: the layout of the NT
+// kernel's stage, so that one 16-byte LDS read per operand block feeds four MFMAs (lane half h supplies nodes
+// 4h .. 4h+3 of a group of eight).  The B loaders also add up their blocks for the column sums.
+// Loads are unconditional: a node beyond the end of the chunk reads the last valid row and is replaced by zeros.
 constexpr int WG_BK = 32;
-constexpr int WG_LD = 256 + 4;
+constexpr int WG_ROWB = WG_BK * 4 + 16;   // bytes per LDS row (one column of an operand tile)
 constexpr int WG_THREADS = 512;
 
 template <bool INDEXED>  // rows of At taken through at_index
 __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2))) void weight_grads_kernel(WeightGradArgs g, int chunk, int splits,
                                                                                                          int tiles_n, int tiles) {
-    __shared__ __attribute__((aligned(16))) float lds[2][2][WG_BK * WG_LD];
+    constexpr int STAGE = 512 * WG_ROWB;  // 256 columns of each operand
+    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i32 = lane & 31, h = lane >> 5;
@@ -928,11 +933,11 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
     const bool do_bias = g.dbias != nullptr && m0 == 0;
-    float bsum = 0.f;
+    const int ng = tid & 7, cg = tid >> 3;     // loader task: nodes 4 ng .. + 3, tile columns 4 cg .. + 3 of both operands
+    v4f bsum = {0.f, 0.f, 0.f, 0.f};           // column sums of this thread's B columns over its nodes
 
     if (kbeg < kend) {
-        // every thread loads four 16-byte pieces of each operand per step: tile rows 8p + wave, tile columns 4*lane ..
-        const int c = 4 * lane;
+        const int c = 4 * cg;
         const int ma = m0 + c, nb = n0 + c;
         // a thread whose columns lie outside the operands still loads (column 0 of At[1] / B) and drops the values
         const bool a_ok = ma < Mtot, b_ok = nb < g.Nw;
@@ -946,47 +951,50 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
         int64_t arow[4];
         auto lookup = [&](int64_t k0) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int64_t k = min(k0 + 8 * p + wave, klast);
-                arow[p] = INDEXED ? (int64_t)g.at_index[k] : k;
+            for (int i = 0; i < 4; ++i) {
+                const int64_t k = min(k0 + 4 * ng + i, klast);
+                arow[i] = INDEXED ? (int64_t)g.at_index[k] : k;
             }
         };
         auto fetch = [&](int64_t k0) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int64_t k = k0 + 8 * p + wave;
+            for (int i = 0; i < 4; ++i) {
+                const int64_t k = k0 + 4 * ng + i;
                 const bool live = k < kend;
-                const v4f va = *reinterpret_cast<const v4f *>(abase + arow[p] * pitch_a);
+                const v4f va = *reinterpret_cast<const v4f *>(abase + arow[i] * pitch_a);
                 const v4f vb = *reinterpret_cast<const v4f *>(bbase + min(k, klast) * g.ldb);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    ra[p][e] = (live && a_ok) ? va[e] : 0.f;
-                    rbv[p][e] = (live && b_ok) ? vb[e] : 0.f;
+                    ra[i][e] = (live && a_ok) ? va[e] : 0.f;
+                    rbv[i][e] = (live && b_ok) ? vb[e] : 0.f;
                 }
             }
         };
         auto stash = [&](int stage) {
+            char *As = lds + stage * STAGE, *Bs = As + 256 * WG_ROWB;
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                *reinterpret_cast<v4f *>(&lds[stage][0][(8 * p + wave) * WG_LD + c]) = ra[p];
-                *reinterpret_cast<v4f *>(&lds[stage][1][(8 * p + wave) * WG_LD + c]) = rbv[p];
+            for (int j = 0; j < 4; ++j) {   // column j of the block: its four nodes
+                *reinterpret_cast<v4f *>(As + (c + j) * WG_ROWB + 16 * ng) = v4f{ra[0][j], ra[1][j], ra[2][j], ra[3][j]};
+                *reinterpret_cast<v4f *>(Bs + (c + j) * WG_ROWB + 16 * ng) = v4f{rbv[0][j], rbv[1][j], rbv[2][j], rbv[3][j]};
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bsum += rbv[i];
         };
-        auto compute = [&](int stage, int kp0) {
-            const float *As = lds[stage][0], *Bs = lds[stage][1];
+        auto compute = [&](int stage, int kk0) {
+            const char *As = lds + stage * STAGE, *Bs = As + 256 * WG_ROWB;
 #pragma unroll
-            for (int kp = kp0; kp < kp0 + WG_BK / 4; ++kp) {
-                float a[2], b[4];
+            for (int kk = kk0; kk < kk0 + 2; ++kk) {   // a group of eight nodes: 32 bytes of every row
+                v4f a[2], b[4];
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) a[rb] = As[(kp * 2 + h) * WG_LD + wm * 64 + rb * 32 + i32];
+                for (int rb = 0; rb < 2; ++rb) a[rb] = *reinterpret_cast<const v4f *>(As + (wm * 64 + rb * 32 + i32) * WG_ROWB + kk * 32 + 16 * h);
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb) b[cb] = Bs[(kp * 2 + h) * WG_LD + wn * 128 + cb * 32 + i32];
+                for (int cb = 0; cb < 4; ++cb) b[cb] = *reinterpret_cast<const v4f *>(Bs + (wn * 128 + cb * 32 + i32) * WG_ROWB + kk * 32 + 16 * h);
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
+                for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = mfma32(a[rb], b[cb], acc[rb][cb]);
-                // column sums of the B tile: thread (column tid % 256, row parity tid / 256), every workgroup (no branch)
-                bsum += Bs[(kp * 2 + (tid >> 8)) * WG_LD + (tid & 255)];
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = mfma32(a[rb][e], b[cb][e], acc[rb][cb]);
             }
         };
 
@@ -1003,7 +1011,7 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
             stash(cur ^ 1);                 // registers hold step k0 + 32 (zeros past the end)
             fetch(k0 + 2 * WG_BK);
             lookup(k0 + 3 * WG_BK);
-            compute(cur, WG_BK / 4);
+            compute(cur, 2);
             __syncthreads();
         }
     }
@@ -1022,11 +1030,17 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
                 if (m < Mtot) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
             }
     }
-    if (do_bias) {  // even-row and odd-row sums of a column meet in LDS
+    if (do_bias) {  // the eight node groups of a column meet in LDS and are added in a fixed order
+        float *red = reinterpret_cast<float *>(lds);
         __syncthreads();
-        lds[0][0][tid] = bsum;
+        *reinterpret_cast<v4f *>(red + ng * 256 + 4 * cg) = bsum;
         __syncthreads();
-        if (tid < 256 && n0 + tid < g.Nw) P[(int64_t)Mtot * g.Nw + n0 + tid] = lds[0][0][tid] + lds[0][0][tid + 256];
+        if (tid < 256 && n0 + tid < g.Nw) {
+            float sum = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sum += red[q * 256 + tid];
+            P[(int64_t)Mtot * g.Nw + n0 + tid] = sum;
+        }
     }
 }
 
