@@ -369,6 +369,13 @@ def main():
         t = traffic.get(cls + "_bytes_per_launch")
         lines[cls]["traffic"] = int(t) if t else None
     dominant = max(lines, key=lambda c: per_step[c][0])
+    # the two small steps of the metric's second half: scoring gathers two embedding rows per edge and writes a score
+    # and a gradient scalar; the sampler is latency bound, so it is reported as samples per second
+    es = 2 if bf16 else 4
+    score_line = hbm_line("score", Bn * (2.0 * wl.dims[-1] * es + 16.0))
+    sample_ms = per_step["sample"][0]
+    sample_line = {"bound": "latency", "kernel": "sample", "achieved": round(n_pos * k_neg / (sample_ms * 1e-3) / 1e9, 3) if sample_ms > 0 else 0.0,
+                   "unit": "Gsamples/s", "launches_per_step": per_step["sample"][1], "avg_launch_ms": round(sample_ms / max(per_step["sample"][1], 1), 4)}
 
     out = {
         "metric": "train-step edges/sec (pos+neg) on 1 MI355X; SpMM achieved HBM GB/s",
@@ -395,6 +402,8 @@ def main():
         "roofline_spmm": lines["spmm"],
         "roofline_gemm_nt": lines["gemm_nt"],
         "roofline_gemm_tn": lines["gemm_tn"],
+        "roofline_score": score_line,
+        "sampler": sample_line,
         "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items() if k != "other" or args.timing_level > 1},
     }
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference

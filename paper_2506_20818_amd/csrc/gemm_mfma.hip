@@ -262,75 +262,72 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
 
-    // Load cursors (row tile, column tile, K step), one per operand.  Offsets are formed per load (clamped row *
-    // pitch + column bytes) instead of being kept in registers.  The loads themselves are unconditional (a cursor
+    // Load cursor: the K steps of one part of one output tile form a segment, inside which both operand pointers
+    // just advance by KSB; what a new segment needs (pointers, pitches, row clamps, the next tile's bias) is worked
+    // out only when the count of steps left in the segment reaches zero.  Offsets are formed per load (clamped row
+    // * pitch + column bytes) instead of being kept in registers.  The loads themselves are unconditional (a cursor
     // past its end repeats its last step): with a fixed number of loads per step the compiler can wait for the
     // older ones by count and leave the younger ones in flight.  (Keeping two steps of A rows in flight was tried
     // for the short bfloat16 steps and measured no faster.)
     constexpr int RP = TH / KQ;                      // tile rows covered by one load of every thread
     const int r0 = tid / KQ, c16 = (tid % KQ) << 4;
-    int rowA = blockIdx.x, colA = 0, ftA = 0;        // row tile, column tile, K step of the next A load
-    int rowB = blockIdx.x, colB = 0, ftB = 0;
+    int rowF = blockIdx.x, colF = 0, partF = 0;      // the segment that begins next: row tile, column tile, K part
+    int seg_left = 0;                                // K steps left in the current segment
+    int kstep = KSB;                                 // pointer advance per step; 0 once the cursor is past its end
     const char *abase = nullptr, *bbase = nullptr;
     uint32_t pitchA = 0, pitchB = 0;
     int rmaxA = 0, rmaxB = 0;
     v4i ra[A_LOADS], rbv[B_LOADS];  // plain vector registers: a struct copy would go through private memory
-
-#define LP_FETCH_A()                                                                                                   \
-    if (rowA < row_tiles) {                                                                                            \
-        if (ftA == 0 || ftA == tiles0) {                                                                               \
-            const int part = (ftA == 0 && tiles0 > 0) ? 0 : 1;                                                         \
-            const int64_t m0f = (int64_t)rowA * BMt;                                                                   \
-            pitchA = (uint32_t)g.lda[part] * ES;                                                                       \
-            abase = static_cast<const char *>(g.A[part]) + m0f * (int64_t)pitchA;                                      \
-            rmaxA = (int)(M_ - 1 - m0f < BMt - 1 ? M_ - 1 - m0f : BMt - 1);                                            \
-        } else {                                                                                                       \
-            abase += KSB;                                                                                              \
-        }                                                                                                              \
-        if (++ftA == n_tiles) {                                                                                        \
-            ftA = 0;                                                                                                   \
-            if (++colA == col_tiles) {                                                                                 \
-                colA = 0;                                                                                              \
-                rowA += gridDim.x;                                                                                     \
-            }                                                                                                          \
-        }                                                                                                              \
-    }                                                                                                                  \
-    _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p)                                                                \
-        ra[p] = *reinterpret_cast<const v4i *>(abase + ((uint32_t)min(r0 + p * RP, rmaxA) * pitchA + c16));
-#define LP_FETCH_B()                                                                                                   \
-    if (rowB < row_tiles) {                                                                                            \
-        if (ftB == 0 || ftB == tiles0) {                                                                               \
-            const int part = (ftB == 0 && tiles0 > 0) ? 0 : 1;                                                         \
-            const int n0f = colB * BN;                                                                                 \
-            const bool secondf = n0f >= g.n_split;                                                                     \
-            const int n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                    \
-            pitchB = (uint32_t)g.ldb[part] * ES;                                                                       \
-            bbase = static_cast<const char *>(g.Bt[part][secondf ? 1 : 0]) +                                           \
-                    (int64_t)(secondf ? n0f - g.n_split : n0f) * (int64_t)pitchB;                                      \
-            rmaxB = n_endf - 1 - n0f < BN - 1 ? n_endf - 1 - n0f : BN - 1;                                             \
-        } else {                                                                                                       \
-            bbase += KSB;                                                                                              \
-        }                                                                                                              \
-        if (++ftB == n_tiles) {                                                                                        \
-            ftB = 0;                                                                                                   \
-            if (++colB == col_tiles) {                                                                                 \
-                colB = 0;                                                                                              \
-                rowB += gridDim.x;                                                                                     \
-            }                                                                                                          \
-        }                                                                                                              \
-    }                                                                                                                  \
-    _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p)                                                                \
-        rbv[p] = *reinterpret_cast<const v4i *>(bbase + ((uint32_t)min(r0 + p * RP, rmaxB) * pitchB + c16));
-    // Bias of the columns of this wavefront, for the output tile the NEXT step belongs to: requested every step
-    // (first in the order of requests, so it has arrived when the older loads have), parked in LDS one step later.
+    // Bias of this wavefront's columns: requested when the first segment of a tile begins (two steps before that
+    // tile's first MFMA), parked in LDS when the tile before it has been stored.
     const char *bias_src = reinterpret_cast<const char *>(g.bias ? g.bias : static_cast<const float *>(tiles0 > 0 ? g.Bt[0][0] : g.Bt[1][0]));
     char *bias_w = bias_lds + wave * (WN * 4);
-    v4f rbias;
-#define LP_FETCH_BIAS(col_tile)                                                                                        \
-    {                                                                                                                  \
-        const int nb_ = g.bias ? min((col_tile) * BN + wn * WN + 4 * (lane % (WN / 4)), g.N - 4) : 0;                  \
-        rbias = *reinterpret_cast<const v4f *>(bias_src + 4 * nb_);                                                    \
+    v4f rbias = {0.f, 0.f, 0.f, 0.f};
+
+#define LP_BEGIN_SEGMENT()                                                                                             \
+    if (rowF >= row_tiles) {   /* nothing left: keep repeating the last step */                                        \
+        abase -= KSB;                                                                                                  \
+        bbase -= KSB;                                                                                                  \
+        kstep = 0;                                                                                                     \
+        seg_left = 0x7fffffff;                                                                                         \
+    } else {                                                                                                           \
+        const int part = (partF == 0 && tiles0 > 0) ? 0 : 1;                                                           \
+        const int64_t m0f = (int64_t)rowF * BMt;                                                                       \
+        pitchA = (uint32_t)g.lda[part] * ES;                                                                           \
+        abase = static_cast<const char *>(g.A[part]) + m0f * (int64_t)pitchA;                                          \
+        rmaxA = (int)(M_ - 1 - m0f < BMt - 1 ? M_ - 1 - m0f : BMt - 1);                                                \
+        const int n0f = colF * BN;                                                                                     \
+        const bool secondf = n0f >= g.n_split;                                                                         \
+        const int n_endf = secondf ? g.N : (g.n_split < g.N ? g.n_split : g.N);                                        \
+        pitchB = (uint32_t)g.ldb[part] * ES;                                                                           \
+        bbase = static_cast<const char *>(g.Bt[part][secondf ? 1 : 0]) +                                               \
+                (int64_t)(secondf ? n0f - g.n_split : n0f) * (int64_t)pitchB;                                          \
+        rmaxB = n_endf - 1 - n0f < BN - 1 ? n_endf - 1 - n0f : BN - 1;                                                 \
+        seg_left = part == 0 ? tiles0 : tiles1;                                                                        \
+        if (partF == 0) {   /* first segment of a tile */                                                              \
+            const int nb_ = g.bias ? min(n0f + wn * WN + 4 * (lane % (WN / 4)), g.N - 4) : 0;                          \
+            rbias = *reinterpret_cast<const v4f *>(bias_src + 4 * nb_);                                                \
+        }                                                                                                              \
+        if (part == 0 && tiles1 > 0) {                                                                                 \
+            partF = 1;                                                                                                 \
+        } else {                                                                                                       \
+            partF = 0;                                                                                                 \
+            if (++colF == col_tiles) {                                                                                 \
+                colF = 0;                                                                                              \
+                rowF += gridDim.x;                                                                                     \
+            }                                                                                                          \
+        }                                                                                                              \
     }
+    // loads of the next K step in pipeline order (possibly the first step of the next output tile)
+#define LP_FETCH()                                                                                                     \
+    if (seg_left == 0) LP_BEGIN_SEGMENT()                                                                              \
+    _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p)                                                                \
+        rbv[p] = *reinterpret_cast<const v4i *>(bbase + ((uint32_t)min(r0 + p * RP, rmaxB) * pitchB + c16));           \
+    _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p)                                                                \
+        ra[p] = *reinterpret_cast<const v4i *>(abase + ((uint32_t)min(r0 + p * RP, rmaxA) * pitchA + c16));            \
+    abase += kstep;                                                                                                    \
+    bbase += kstep;                                                                                                    \
+    --seg_left;
 #define LP_PUT_BIAS()                                                                                                  \
     if (lane < WN / 4) *reinterpret_cast<v4f *>(bias_w + 16 * lane) = rbias;
 #define LP_STASH(stage)                                                                                                \
@@ -383,10 +380,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         }                                                                                                              \
         LP_ORDER();                                                                                                    \
         LP_STASH(cur ^ 1)                                                                                              \
-        LP_PUT_BIAS()                                                                                                  \
-        LP_FETCH_BIAS((ct + 1 == n_tiles) ? (colC + 1 == col_tiles ? 0 : colC + 1) : colC)                             \
-        LP_FETCH_B()                                                                                                   \
-        LP_FETCH_A()                                                                                                   \
+        LP_FETCH()                                                                                                     \
         LP_ORDER();                                                                                                    \
         if (KSB == 128) {                                                                                              \
             LP_LOAD_OPS(cur, 3, a1, b1)                                                                                \
@@ -468,23 +462,21 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
+        LP_PUT_BIAS()   // the next tile's bias (requested two steps ago) replaces the one just used
         __syncthreads();
     };
 
     v4i a0[2], b0[NB], a1[2], b1[NB];
-    LP_FETCH_BIAS(0)
-    LP_FETCH_A()
-    LP_FETCH_B()
+    LP_FETCH()
+    LP_PUT_BIAS()       // first tile
     LP_STASH(0)
-    LP_FETCH_B()
-    LP_FETCH_A()
+    LP_FETCH()
     __syncthreads();
     for (int u = 0; u < n_steps; ++u) LP_STEP(u)
 #undef LP_STEP
-#undef LP_FETCH_A
-#undef LP_FETCH_B
+#undef LP_FETCH
+#undef LP_BEGIN_SEGMENT
 #undef LP_STASH
-#undef LP_FETCH_BIAS
 #undef LP_PUT_BIAS
 #undef LP_LOAD_OPS
 #undef LP_MFMA_OPS
@@ -1340,7 +1332,8 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     const int es = lp_elem_bytes(a.dtype);
     const int fast_bn = a.N > 128 ? 256 : 128;
     const int ve16 = 16 / es;
-    const bool fast_ok = a.N > 64 && (a.K[0] * es % 64 == 0) && (a.K[1] * es % 64 == 0) && a.K[0] + a.K[1] > 0 &&
+    // (at least two K steps per output tile: the bias of a tile is requested while the tile before it is finishing)
+    const bool fast_ok = a.N > 64 && (a.K[0] * es % 64 == 0) && (a.K[1] * es % 64 == 0) && (int64_t)(a.K[0] + a.K[1]) * es >= 128 &&
                          (a.n_split >= a.N || a.n_split % fast_bn == 0) &&
                          // whole 16-byte pieces of output rows
                          a.N % ve16 == 0 && a.ldc[0] % ve16 == 0 && lp_aligned16(a.C[0]) && (!a.bias || lp_aligned16(a.bias)) &&
@@ -1355,7 +1348,7 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         // persistent workgroups filling every compute unit; the widest tile (256 x 256, eight wavefronts, 128-byte
         // K step, one workgroup per compute unit) when K allows
         // (with fewer 256-row tiles than compute units, 128-row tiles spread the same work over twice as many of them)
-        const bool big = fast_bn == 256 && (a.K[0] * es % 128 == 0) && (a.K[1] * es % 128 == 0) &&
+        const bool big = fast_bn == 256 && (a.K[0] * es % 128 == 0) && (a.K[1] * es % 128 == 0) && (int64_t)(a.K[0] + a.K[1]) * es >= 256 &&
                          lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units();
         const int bm = big ? 256 : 128;
         const int64_t row_tiles = lp_ceil_div(a.M, bm);
