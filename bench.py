@@ -355,6 +355,30 @@ def main():
     torch.cuda.synchronize()
     plain_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
 
+    # the same step recorded once as a HIP graph and replayed (the library allocates nothing and clears its scratch
+    # with kernels, so a step can be captured); every replay draws the negatives of the recorded step id, which is why
+    # this figure is informational and `value` comes from the eager steps
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(1500)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step(1500)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+    except RuntimeError as exc:   # capture unsupported in this environment: report that, do not fail the benchmark
+        sys.stderr.write("graph replay not measured: %s\n" % exc)
+
     # timed region, with the library's per-launch HIP events switched on
     lp.lp_timing_enable(args.timing_level)
     lp.lp_timing_collect()
@@ -432,6 +456,7 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "ms_per_step_without_events": round(plain_ms, 4),
+        "ms_per_step_graph_replay": round(graph_ms, 4) if graph_ms is not None else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

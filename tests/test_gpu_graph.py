@@ -1,0 +1,86 @@
+"""The training step under HIP graph capture: the library allocates nothing, clears its scratch with kernels and keeps
+no state between calls, so a step recorded once can be replayed.  Every replay must reproduce the eager result bit
+for bit, also when other eager work and synchronisations run between the replays."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2506_20818_amd as lp
+from paper_2506_20818_amd import binding as B
+from lp_workloads import make_workload
+from gpu_util import DEV, dev_f32, dev_i32, make_model
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+class StepBuffers:
+    """All outputs and workspaces of one step, allocated up front (graph capture must not allocate)."""
+
+    def __init__(self, g, model, n_pos, k_neg, want_dX):
+        Bn = n_pos * (1 + k_neg)
+        u8 = lambda n: torch.empty(max(int(n), 16), dtype=torch.uint8, device=DEV)
+        self.e_src = torch.zeros(Bn, dtype=torch.int32, device=DEV)
+        self.e_dst = torch.zeros(Bn, dtype=torch.int32, device=DEV)
+        self.acts = lp.Acts(g.n_nodes, model.dims, DEV, model.torch_dtype)
+        self.grads = lp.Grads(g.n_nodes, model.dims, DEV, want_dX, model.torch_dtype)
+        self.scores = torch.zeros(Bn, dtype=torch.float32, device=DEV)
+        self.dscore = torch.zeros(Bn, dtype=torch.float32, device=DEV)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        self.ws_f = u8(B.forward_workspace_bytes(model, g.n_nodes))
+        self.ws_b = u8(B.backward_workspace_bytes(model, g.n_nodes, Bn))
+        self.ws_l = u8(1 << 16)
+
+    def tensors(self, K):
+        out = [self.e_dst, self.scores, self.loss, self.dscore] + [self.acts.H[k] for k in range(K)]
+        out += [self.grads.dW_self[k] for k in range(K)] + [self.grads.dW_neigh[k] for k in range(K)] + [self.grads.dbias[k] for k in range(K)]
+        return out
+
+
+def run_step(g, model, X, pos_src, pos_dst, k_neg, n_space, seed, step, buf):
+    n_pos = int(pos_src.numel())
+    buf.e_src[:n_pos].copy_(pos_src)
+    buf.e_dst[:n_pos].copy_(pos_dst)
+    lp.lp_sample_neg(g, pos_src, k_neg, n_space, seed, step, neg_dst=buf.e_dst[n_pos:], neg_src=buf.e_src[n_pos:])
+    lp.lp_sage_forward(g, model, X, buf.acts, buf.ws_f)
+    lp.lp_score_loss(buf.acts.H[-1], buf.e_src, buf.e_dst, n_pos, buf.scores, buf.loss, buf.dscore, buf.ws_l)
+    lp.lp_backward(g, model, X, buf.acts, buf.e_src, buf.e_dst, buf.dscore, buf.grads, buf.ws_b)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_captured_step_replays_bit_exactly(name):
+    wl = make_workload(name)
+    say("graph capture of the training step, %s" % name)
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    model = make_model(wl.W_self, wl.W_neigh, wl.bias)
+    X = dev_f32(wl.X)
+    pos_src, pos_dst = dev_i32(wl.pos_src), dev_i32(wl.pos_dst)
+    K = len(wl.dims) - 1
+    eager = StepBuffers(g, model, wl.n_pos, wl.k_neg, False)
+    other = StepBuffers(g, model, wl.n_pos, wl.k_neg, False)
+    cap = StepBuffers(g, model, wl.n_pos, wl.k_neg, False)
+    run_step(g, model, X, pos_src, pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed, 7, eager)
+    torch.cuda.synchronize()
+    expected = [t.clone() for t in eager.tensors(K)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # one eager pass on the capture stream first
+        run_step(g, model, X, pos_src, pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed, 7, cap)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_step(g, model, X, pos_src, pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed, 7, cap)
+    for replay in range(3):
+        for t in cap.tensors(K):
+            t.zero_()
+        run_step(g, model, X, pos_src, pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed, 100 + replay, other)   # eager work in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, exp) in enumerate(zip(cap.tensors(K), expected)):
+            assert torch.equal(got, exp), "replay %d: output %d differs from the eager step" % (replay, i)
