@@ -1,5 +1,7 @@
-// Device-wide exclusive prefix sums over a functor (reduce, spine, apply: three launches), for 32- or 64-bit
-// unsigned values.  Integer sums are associative, so the result does not depend on how the work is split.
+// Device-wide exclusive prefix sums over a functor, for 32- or 64-bit unsigned values: block sums, then every block
+// adds up the sums of the blocks before it and applies (two launches; with more than kDirectBlocks blocks a
+// one-block pass over the block sums comes in between).  Integer sums are associative, so the result does not
+// depend on how the work is split.
 // Everything here has internal linkage: each translation unit that includes this header gets its own kernels.
 #pragma once
 
@@ -78,9 +80,11 @@ __global__ __launch_bounds__(kThreads) void scan_spine_kernel(V *block_sums, int
     if (threadIdx.x == 0 && total_out) *total_out = carry;
 }
 
-// sink(i, exclusive_prefix_of_i, f(i)) is called for every i < n
-template <class V, class F, class S>
-__global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64_t n, const V *block_sums) {
+// sink(i, exclusive_prefix_of_i, f(i)) is called for every i < n.  DIRECT: block_sums holds the plain block sums and
+// the block adds up those before it itself (the last block also writes the grand total); otherwise block_sums holds
+// their exclusive prefix.
+template <class V, class F, class S, bool DIRECT>
+__global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64_t n, const V *block_sums, V *total_out) {
     __shared__ V lds4[4];
     const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
     V v[kItems];
@@ -90,8 +94,18 @@ __global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64
         v[i] = (base + i < n) ? f(base + i) : 0u;
         s += v[i];
     }
+    V before;
+    if (DIRECT) {
+        V mine = 0;
+        for (int64_t i = threadIdx.x; i < (int64_t)blockIdx.x; i += kThreads) mine += block_sums[i];
+        block_exclusive_scan(mine, lds4, before);
+        __syncthreads();
+    } else {
+        before = block_sums[blockIdx.x];
+    }
     V total;
-    V run = block_sums[blockIdx.x] + block_exclusive_scan(s, lds4, total);
+    V run = before + block_exclusive_scan(s, lds4, total);
+    if (DIRECT && total_out && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *total_out = before + total;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         if (base + i < n) sink(base + i, run, v[i]);
@@ -99,12 +113,18 @@ __global__ __launch_bounds__(kThreads) void scan_apply_kernel(F f, S sink, int64
     }
 }
 
+constexpr int64_t kDirectBlocks = 4096;  // up to here every block reads the sums of all blocks before it
+
 template <class V, class F, class S>
 int device_exclusive_scan(F f, S sink, int64_t n, V *block_sums, V *total_out, hipStream_t st) {
     const int64_t nb = lp_ceil_div(n > 0 ? n : 1, kTile);
     hipLaunchKernelGGL((scan_reduce_kernel<V, F>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, n, block_sums);
-    hipLaunchKernelGGL((scan_spine_kernel<V>), dim3(1), dim3(kThreads), 0, st, block_sums, nb, total_out);
-    hipLaunchKernelGGL((scan_apply_kernel<V, F, S>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, sink, n, block_sums);
+    if (nb <= kDirectBlocks) {
+        hipLaunchKernelGGL((scan_apply_kernel<V, F, S, true>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, sink, n, block_sums, total_out);
+    } else {
+        hipLaunchKernelGGL((scan_spine_kernel<V>), dim3(1), dim3(kThreads), 0, st, block_sums, nb, total_out);
+        hipLaunchKernelGGL((scan_apply_kernel<V, F, S, false>), dim3((unsigned)nb), dim3(kThreads), 0, st, f, sink, n, block_sums, total_out);
+    }
     return lp_after_launch();
 }
 
