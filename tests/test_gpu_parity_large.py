@@ -4,7 +4,8 @@ C3 (one worker's view of a partitioned 1 M-node graph, 3 negatives per positive)
 element.  C4 (2.9 M nodes, 29 M directed entries): CSR and negatives bit-exact in full; the floating-point calls
 are checked at full size on outputs the oracle can compute one by one - sampled rows of the aggregation and of
 the layer output, every score, and the weight gradients of a one-layer model (whose loss gradient only touches
-the batch endpoints, so the oracle needs those rows alone).
+the batch endpoints, so the oracle needs those rows alone).  C5 (bf16 storage, one worker's view of C4's graph):
+CSR bit-exact and one full-size layer with its scores and weight gradients on the rows the batch touches.
 """
 import numpy as np
 import pytest
@@ -116,3 +117,47 @@ def test_C4_score_and_one_layer_backward(c4):
         if vs.size:
             dX_ref[i] += (T_t[pos_of[vs]] / deg[vs, None]).sum(0)
     assert_close(host(grads.dX[torch.from_numpy(rows).to(DEV)]), dX_ref, TOL_GRAD, "dX rows")
+
+
+def test_C5_bf16_one_layer_full_size():
+    """C5 (one worker's view of C4's graph, cross edges kept w.p. 0.2; bf16 storage, hidden 512) at full size: CSR bit
+    exact; one 128 -> 512 layer, its scores and its weight gradients against the oracle on the rows the batch
+    touches (bf16 bars: 2^-7 on activations and scores, 2e-2 on gradients)."""
+    from lp_workloads import to_bf16_grid
+    from test_gpu_parity_bf16 import TOL_ACT as BF_ACT, TOL_GRAD as BF_GRAD, bf16_model, dev_bf16, hostf
+    wl = make_workload("C5_keep0.2", with_features=False)
+    say("C5_keep0.2: N=%d E=%d, bf16 one layer 128->512" % (wl.n_nodes, wl.src.size))
+    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    check_csr(g, ref)
+    rng = np.random.default_rng(55)
+    N, Fi, Fo = wl.n_nodes, 128, 512
+    X = to_bf16_grid(init_features(N, Fi, 905))
+    Ws = to_bf16_grid((rng.standard_normal((Fi, Fo)) / np.sqrt(2 * Fi) * Fo ** -0.25).astype(np.float32))
+    Wn = to_bf16_grid((rng.standard_normal((Fi, Fo)) / np.sqrt(2 * Fi) * Fo ** -0.25).astype(np.float32))
+    b = rng.uniform(-0.1, 0.1, Fo).astype(np.float32)
+    neg, _ = O.sample_neg(ref, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+    es, ed = O.batch_edges(wl.pos_src, wl.pos_dst, neg, wl.k_neg)
+    model = bf16_model([Ws], [Wn], [b])
+    Xd = dev_bf16(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), wl.n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds)
+    torch.cuda.synchronize()
+
+    touched = np.unique(np.concatenate([es, ed]))
+    pos_of = np.full(N, -1, np.int64)
+    pos_of[touched] = np.arange(touched.size)
+    a_t = to_bf16_grid(O.mean_aggregate(ref, X, touched).astype(np.float32)).astype(np.float64)   # A is stored as bf16
+    x_t = X[touched].astype(np.float64)
+    h_t = to_bf16_grid((x_t @ Ws.astype(np.float64) + a_t @ Wn.astype(np.float64) + b).astype(np.float32)).astype(np.float64)
+    ridx = torch.from_numpy(touched).to(DEV)
+    assert_close(hostf(acts.A[0][ridx]), a_t, BF_ACT, "A^1 rows")
+    assert_close(hostf(acts.H[0][ridx]), h_t, BF_ACT, "H^1 rows")
+    s_ref, loss_ref, ds_ref = O.score_loss(h_t, pos_of[es], pos_of[ed], wl.n_pos)
+    assert_close(host(s), s_ref, BF_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= BF_ACT * abs(loss_ref)
+    dZ_t = to_bf16_grid(O.edge_grad_scatter(h_t, pos_of[es], pos_of[ed], ds_ref).astype(np.float32)).astype(np.float64)
+    assert_close(host(grads.dbias[0]), dZ_t.sum(0), BF_GRAD, "dbias")
+    assert_close(host(grads.dW_self[0]), x_t.T @ dZ_t, BF_GRAD, "dW_self")
+    assert_close(host(grads.dW_neigh[0]), a_t.T @ dZ_t, BF_GRAD, "dW_neigh")
