@@ -321,6 +321,23 @@ int lp_adam_step(const lp_model *m, const lp_grads *g, const lp_opt_state *s, in
                  float beta2, float eps, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * lp_hits_at_k - the accuracy metric of the paper's experiments
+ * ("Hyperparameters": Hits@100, the metric of the Open Graph Benchmark's link
+ * prediction tasks).  The K-th largest of the n_neg negative-edge scores is the
+ * threshold; *hits (device int64) receives the number of the n_pos positive
+ * scores that are strictly greater; Hits@K = *hits / n_pos.  With n_neg < K
+ * the threshold is -infinity and every positive is a hit.  threshold: optional
+ * device float that receives the threshold.  Scores are device fp32 arrays
+ * (e.g. the `scores` output of lp_score_loss or lp_mlp_score_loss on the test
+ * edges); they must not contain NaN.  Integer result: bit-exact.
+ * Errors: LP_ERR_INVALID_ARG (K < 1, negative counts, NULL arrays or hits),
+ * LP_ERR_OUT_OF_RANGE (n_neg >= 2^31), LP_ERR_WORKSPACE.
+ */
+size_t lp_hits_at_k_workspace_bytes(int64_t n_neg);
+int lp_hits_at_k(const float *pos_scores, int64_t n_pos, const float *neg_scores, int64_t n_neg, int64_t K, int64_t *hits,
+                 float *threshold, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * Sampled-neighbourhood training step (the paper's mini-batch mode: Sec. II-B,
  * last paragraph; Fig. 1b; "Hyperparameters": 25, 10, 5 neighbours for the
  * first, second, third hop).

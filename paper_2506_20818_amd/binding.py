@@ -114,6 +114,9 @@ EXPORTS = {
                                      C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_backward_blocks_edge_grads": (C.c_int, [C.POINTER(_BlocksStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                                      C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_hits_at_k_workspace_bytes": (C.c_size_t, [C.c_int64]),
+    "lp_hits_at_k": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                               C.c_void_p]),
     "lp_mlp_score_loss_workspace_bytes": (C.c_size_t, [C.POINTER(_MlpStruct), C.c_int64]),
     "lp_mlp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(_MlpStruct),
                                     C.POINTER(_MlpActsStruct), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -461,6 +464,21 @@ def lp_backward_blocks_edge_grads(b: Blocks, m: Model, acts: BlockActs, edge_gra
     _check(lib.lp_backward_blocks_edge_grads(C.byref(b.c), C.byref(m.c), _ptr(acts.X_frontier), C.byref(acts.c), _ptr(edge_grad),
                                              C.byref(grads.c), _ptr(ws), ws.numel(), _stream()), "lp_backward_blocks_edge_grads")
     return grads
+
+
+def lp_hits_at_k(pos_scores: torch.Tensor, neg_scores: torch.Tensor, K: int, ws: Optional[torch.Tensor] = None):
+    """Returns (hits, threshold) as device tensors (int64 [1], float32 [1]); Hits@K = hits / pos_scores.numel()."""
+    lib = load_library()
+    _need(pos_scores, torch.float32, "pos_scores")
+    _need(neg_scores, torch.float32, "neg_scores")
+    dev = pos_scores.device
+    hits = torch.zeros(1, dtype=torch.int64, device=dev)
+    thr = torch.zeros(1, dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = _ws(lib.lp_hits_at_k_workspace_bytes(int(neg_scores.numel())), dev)
+    _check(lib.lp_hits_at_k(_ptr(pos_scores), int(pos_scores.numel()), _ptr(neg_scores), int(neg_scores.numel()), int(K), _ptr(hits),
+                            _ptr(thr), _ptr(ws), ws.numel(), _stream()), "lp_hits_at_k")
+    return hits, thr
 
 
 def forward_blocks_workspace_bytes(m: Model, b: Blocks) -> int:

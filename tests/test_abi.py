@@ -312,3 +312,20 @@ def test_mlp_predictor_and_tensor_updates_reject_bad_arguments_on_the_host():
     assert eg(e=None) == -1
     assert eg(e=C.c_void_p(0x1004)) == -1
     assert eg(ws=None) == -3
+
+
+def test_hits_at_k_rejects_bad_arguments_on_the_host():
+    lib = B.load_library()
+    p = C.c_void_p(0x1000)
+    call = lambda pos=p, n_pos=10, neg=p, n_neg=20, K=5, hits=p, ws=p, wsb=1 << 30: lib.lp_hits_at_k(
+        pos, n_pos, neg, n_neg, K, hits, None, ws, wsb, None)
+    assert call(K=0) == -1
+    assert call(n_pos=-1) == -1
+    assert call(pos=None) == -1
+    assert call(neg=None) == -1
+    assert call(hits=None) == -1
+    assert call(n_neg=1 << 31) == -2
+    assert call(ws=None) == -3
+    assert call(wsb=64) == -3
+    assert lib.lp_hits_at_k_workspace_bytes(1000) > 16000
+    assert lib.lp_hits_at_k_workspace_bytes(-1) == 0
