@@ -18,8 +18,17 @@ Reading taken here (the paper leaves the mechanics to its graph library):
     position t with position t + floor(word * (d - t) / 2^32), where word is word (t mod 4) of Philox4x32-10 with
     counter (v, hop * 2^16 + t div 4, step_lo, step_hi) and key (seed_lo, seed_hi); the sample is positions
     0..f-1 after f swaps, in that order.  A node with d <= f takes all its neighbours in list order.
+  * a fan-out of 0 stands for "all neighbours" (a full-neighbourhood mini-batch): no draw, the whole list in order.
 With a fan-out at least as large as every degree the computational graph is the exact K-hop neighbourhood, and
 embeddings, loss and weight gradients coincide with the full-graph step: that is the main pin of this file.
+
+GCN layers on the blocks ("Hyperparameters" names a 3-layer GCN trained in mini-batches; the neighbour sampling is
+stated for GraphSAGE only).  Reading: the Kipf-Welling propagation of the full visible graph, restricted to the
+computational graph, with the degrees d^ of the FULL graph in the normalisation,
+    a_v = (d^_v / |S(v)|) * sum_{u in S(v)} h_u / sqrt(d^_v d^_u),    z_v = a_v W + b,
+where the factor d^_v / |S(v)| makes a drawn subset an unbiased estimate of the full sum and is 1 for a
+full-neighbourhood block, for which the layer equals the full-graph GCN exactly on the computational graph.  The
+self-pair is an ordinary entry of the caller's CSR (as in the full-graph GCN), so there is no separate self path.
 """
 from __future__ import annotations
 
@@ -46,7 +55,7 @@ class Blocks:
 def sample_row(neigh: np.ndarray, f: int, v: int, hop: int, seed: int, step: int) -> np.ndarray:
     """S(v): the draw described in the header, one node, Python integers."""
     d = int(neigh.size)
-    if d <= f:
+    if f == 0 or d <= f:
         return neigh.copy()
     a = list(range(d))
     words = None
@@ -156,3 +165,62 @@ def backward_blocks(b: Blocks, W_self, W_neigh, acts: BlockActs, dscore, relu_ma
                 np.add.at(Gn, col[lo:hi], T[i])       # a sampled node can only occur once per row, add.at is for safety
         G = Gn
     return O.Grads(dWs, dWn, db, None)
+
+
+# ---------------------------------------------------------------------------------------------- GCN layers on blocks
+def gcn_block_aggregate(ptr: np.ndarray, col: np.ndarray, inv_deg_pos: np.ndarray, H: np.ndarray) -> np.ndarray:
+    """a_i = (d_i / |row i|) * sum over the entries p of row i of H[col[p]] / sqrt(d_i d_col[p]); d = full-graph degrees
+    of the nodes at the frontier positions (inv_deg_pos = 1 / d, 0 for a node without entries)."""
+    out = np.zeros((ptr.size - 1, H.shape[1]))
+    c = np.sqrt(inv_deg_pos)
+    for i in range(ptr.size - 1):
+        lo, hi = ptr[i], ptr[i + 1]
+        if hi > lo:
+            d_i = 1.0 / inv_deg_pos[i]
+            out[i] = (d_i / float(hi - lo)) * c[i] * (c[col[lo:hi]][:, None] * H[col[lo:hi]]).sum(axis=0)
+    return out
+
+
+def forward_blocks_gcn(b: Blocks, inv_deg: np.ndarray, W, bias, X) -> BlockActs:
+    """inv_deg: the full graph's 1 / d^ per node (O.inverse_degrees of the CSR that holds the self-pairs)."""
+    K = len(W)
+    ipos = np.asarray(inv_deg, np.float64)[b.nodes[:b.n[0]]]
+    H = [np.asarray(X, np.float64)[b.nodes[:b.n[0]]]]
+    A, Z = [None], [None]
+    for k in range(1, K + 1):
+        a = gcn_block_aggregate(b.ptr[k - 1], b.col[k - 1], ipos, H[k - 1])
+        z = a @ np.asarray(W[k - 1], np.float64) + np.asarray(bias[k - 1], np.float64)
+        A.append(a)
+        Z.append(z)
+        H.append(np.maximum(z, 0.0) if k < K else z)
+    return BlockActs(H, A, Z)
+
+
+def backward_blocks_gcn(b: Blocks, inv_deg: np.ndarray, W, acts: BlockActs, dscore, relu_margin: float = 0.0,
+                        seed_grad=None) -> O.Grads:
+    """Weight and bias gradients through the GCN blocks (dW is reported as dW_neigh, as in the full-graph GCN)."""
+    K = len(W)
+    ipos = np.asarray(inv_deg, np.float64)[b.nodes[:b.n[0]]]
+    c = np.sqrt(ipos)
+    if seed_grad is not None:
+        G = np.asarray(seed_grad, np.float64)
+    else:
+        G = O.edge_grad_scatter(acts.H[K], b.e_src_pos, b.e_dst_pos, np.asarray(dscore, np.float64))
+    dW, db = [None] * K, [None] * K
+    for k in range(K, 0, -1):
+        nk = int(b.n[k])
+        dZ = G if k == K else G * (acts.Z[k] > relu_margin)
+        db[k - 1] = dZ.sum(axis=0)
+        dW[k - 1] = acts.A[k].T @ dZ
+        if k == 1:
+            break
+        ptr, col = b.ptr[k - 1], b.col[k - 1]
+        T = dZ @ np.asarray(W[k - 1], np.float64).T
+        Gn = np.zeros((int(b.n[k - 1]), acts.H[k - 1].shape[1]))
+        for i in range(nk):
+            lo, hi = ptr[i], ptr[i + 1]
+            if hi > lo:
+                w_i = (1.0 / ipos[i]) / float(hi - lo) * c[i]
+                np.add.at(Gn, col[lo:hi], (w_i * c[col[lo:hi]])[:, None] * T[i])
+        G = Gn
+    return O.Grads([None] * K, dW, db, None)

@@ -199,3 +199,97 @@ def test_sampled_gradients_with_mlp_scorer_match_central_finite_differences():
                 arrs[k][idx] = old
                 fd = (lp_ - lm_) / (2 * h)
                 assert abs(fd - grad[k][idx]) < 1e-7 + 1e-5 * abs(fd), (name, k, idx, fd, grad[k][idx])
+
+
+def gcn_setup(rng, n, e, dims, hub=None):
+    from oracle import gcn_oracle as Gc
+    r = rng.integers(0, n, e).astype(np.int32)
+    c = rng.integers(0, n, e).astype(np.int32)
+    if hub:
+        r = np.concatenate([r, np.full(hub, 1, np.int32)])
+        c = np.concatenate([c, rng.choice(n, hub, replace=False).astype(np.int32)])
+    r2, c2 = Gc.add_self_pairs(n, r, c)
+    csr = O.build_csr(n, r2, c2, True)
+    K = len(dims) - 1
+    W = [rng.standard_normal((dims[k], dims[k + 1])) * 0.4 for k in range(K)]
+    b = [rng.standard_normal(dims[k + 1]) * 0.2 for k in range(K)]
+    return csr, W, b
+
+
+def test_full_neighbourhood_gcn_blocks_reproduce_the_full_graph_gcn():
+    """Fan-out 0 = all neighbours: the GCN layers on the blocks must equal the (separately pinned) full-graph GCN on
+    every node of the computational graph, and the weight gradients must coincide."""
+    from oracle import gcn_oracle as Gc
+    rng = np.random.default_rng(3)
+    n, dims = 250, [5, 9, 7, 4]
+    csr, W, b = gcn_setup(rng, n, 600, dims, hub=50)
+    X = rng.standard_normal((n, dims[0]))
+    es, ed = rng.integers(0, n, 30).astype(np.int32), rng.integers(0, n, 30).astype(np.int32)
+    blocks = Bk.sample_blocks(csr, es, ed, [0, 0, 0], seed=1, step=1)
+    for k in range(1, 4):       # every row of every block holds the node's whole list, in order
+        for i in range(0, int(blocks.n[k]), 7):
+            v = blocks.nodes[i]
+            row = blocks.nodes[blocks.col[k - 1][blocks.ptr[k - 1][i]:blocks.ptr[k - 1][i + 1]]]
+            assert np.array_equal(row, csr.colidx[csr.rowptr[v]:csr.rowptr[v + 1]])
+    inv = O.inverse_degrees(csr)
+    acts = Bk.forward_blocks_gcn(blocks, inv, W, b, X)
+    full = Gc.gcn_forward(csr, W, b, X)
+    for k in (1, 2, 3):
+        np.testing.assert_allclose(acts.H[k], full.H[k][blocks.nodes[:blocks.n[k]]], rtol=1e-11, atol=1e-13)
+    s, loss, ds = O.score_loss(acts.H[3], blocks.e_src_pos, blocks.e_dst_pos, 20)
+    s_f, loss_f, ds_f = O.score_loss(full.H[3], es, ed, 20)
+    np.testing.assert_allclose(s, s_f, rtol=1e-11, atol=1e-13)
+    g = Bk.backward_blocks_gcn(blocks, inv, W, acts, ds)
+    g_f = Gc.gcn_backward(csr, W, full, es, ed, ds_f)
+    for k in range(3):
+        np.testing.assert_allclose(g.dW_neigh[k], g_f.dW_neigh[k], rtol=1e-9, atol=1e-13)
+        np.testing.assert_allclose(g.dbias[k], g_f.dbias[k], rtol=1e-9, atol=1e-13)
+    # the same fan-out convention for the GraphSAGE layers: equal to the full-graph step as well
+    Ws, Wn, bb = model(rng, dims)
+    a2 = Bk.forward_blocks(blocks, Ws, Wn, bb, X)
+    np.testing.assert_allclose(a2.H[3], O.sage_forward(csr, Ws, Wn, bb, X).H[3][blocks.nodes[:blocks.n[3]]], rtol=1e-11, atol=1e-13)
+
+
+def test_sampled_gcn_is_unbiased_and_its_gradients_match_finite_differences():
+    rng = np.random.default_rng(8)
+    n, dims = 60, [4, 6, 3]
+    csr, W, b = gcn_setup(rng, n, 260, dims, hub=25)
+    K = 2
+    X = rng.standard_normal((n, dims[0]))
+    inv = O.inverse_degrees(csr)
+    es, ed = rng.integers(0, n, 12).astype(np.int32), rng.integers(0, n, 12).astype(np.int32)
+    # one layer, many independent draws: the mean of the sampled aggregate tends to the full aggregate
+    from oracle import gcn_oracle as Gc
+    exact = Gc.normalised_aggregate(csr, X)
+    acc, reps = 0.0, 400
+    for s in range(reps):
+        blk = Bk.sample_blocks(csr, es[:4], ed[:4], [3], seed=100 + s, step=0)
+        a = Bk.gcn_block_aggregate(blk.ptr[0], blk.col[0], inv[blk.nodes[:blk.n[0]]], X[blk.nodes[:blk.n[0]]])
+        acc = acc + a
+        seeds = blk.nodes[:blk.n[1]]
+    err = np.abs(acc / reps - exact[seeds]).max()
+    assert err < 0.25, err                                  # Monte-Carlo error ~ 1/sqrt(400) of an O(1) quantity
+    blocks = Bk.sample_blocks(csr, es, ed, [4, 3], seed=3, step=4)
+    assert any(np.diff(p).max() < np.diff(csr.rowptr).max() for p in blocks.ptr)
+
+    def loss_of(W_, b_):
+        a = Bk.forward_blocks_gcn(blocks, inv, W_, b_, X)
+        return O.score_loss(a.H[K], blocks.e_src_pos, blocks.e_dst_pos, 7)[1]
+
+    acts = Bk.forward_blocks_gcn(blocks, inv, W, b, X)
+    _, _, ds = O.score_loss(acts.H[K], blocks.e_src_pos, blocks.e_dst_pos, 7)
+    g = Bk.backward_blocks_gcn(blocks, inv, W, acts, ds)
+    h = 1e-6
+    for k in range(K):
+        for name, arrs, grad in (("W", W, g.dW_neigh), ("b", b, g.dbias)):
+            it = np.nditer(arrs[k], flags=["multi_index"])
+            for _ in it:
+                idx = it.multi_index
+                old = arrs[k][idx]
+                arrs[k][idx] = old + h
+                lp_ = loss_of(W, b)
+                arrs[k][idx] = old - h
+                lm_ = loss_of(W, b)
+                arrs[k][idx] = old
+                fd = (lp_ - lm_) / (2 * h)
+                assert abs(fd - grad[k][idx]) < 1e-7 + 1e-5 * abs(fd), (name, k, idx, fd, grad[k][idx])
