@@ -45,6 +45,7 @@ extern "C" {
 #define LP_MAX_LAYERS 8
 #define LP_MAX_MLP_LAYERS 4 /* linear layers of the MLP edge predictor */
 #define LP_MAX_FANOUT 64 /* most neighbours one node may draw per hop in lp_sample_blocks */
+#define LP_FANOUT_ALL 0  /* fan-out value that stands for "all neighbours" (no draw) */
 
 enum {
     LP_OK = 0,
@@ -138,6 +139,7 @@ typedef struct lp_blocks {
     int32_t *t_ptr[LP_MAX_LAYERS];          /* device [cap[k-1]+1]: transposed block, rows = positions in frontier k-1 */
     int32_t *t_col[LP_MAX_LAYERS];          /* device [cap_entries[k-1]]: positions in frontier k, by entry index */
     int32_t *e_src_pos, *e_dst_pos;         /* device [B]: the scored edges in positions of frontier K (-1: id out of range) */
+    float *node_inv_deg;                    /* device [cap[0]]: inv_deg (of the graph sampled from) of nodes[i] */
 } lp_blocks;
 
 /* MLP edge predictor: x_e = h_u * h_v (element-wise), u^j = relu(u^(j-1) W[j-1] + bias[j-1]) for j < L,
@@ -344,7 +346,9 @@ int lp_hits_at_k(const float *pos_scores, int64_t n_pos, const float *neg_scores
  *
  * lp_blocks_bounds: pure host arithmetic; cap [K+1] and cap_entries [K] for a
  * graph of n_nodes / nnz entries, B scored edges and fan-outs fanout[0..K-1]
- * (fanout[0] = first hop = layer K; each in 1..LP_MAX_FANOUT).
+ * (fanout[0] = first hop = layer K; each in 1..LP_MAX_FANOUT, or LP_FANOUT_ALL
+ * for a full-neighbourhood hop: every node of the frontier takes its whole
+ * list, in list order).
  *
  * lp_sample_blocks: fills `out` (whose arrays and cap fields the caller set up
  * from the bounds) for the batch e_src/e_dst (device [B]; ids outside the graph
@@ -366,7 +370,13 @@ int lp_hits_at_k(const float *pos_scores, int64_t n_pos, const float *neg_scores
  * saved->A[k-1]: device [cap[k], F_{k-1}], saved->H[k-1]: device [cap[k], F_k];
  * row i belongs to nodes[i].  The embeddings of the batch end points are the
  * first n[K] rows of saved->H[K-1]; score them with lp_score_loss(H, cap[K],
- * ..., e_src_pos, e_dst_pos, ...).
+ * ..., e_src_pos, e_dst_pos, ...).  With layer_type = LP_LAYER_GCN the layer is
+ * the graph convolution of the full graph restricted to the blocks, with the
+ * full graph's degrees in the normalisation:
+ *   a_v = (d_v / |S(v)|) sum_{u in S(v)} h_u / sqrt(d_v d_u),  z_v = a_v W_neigh + b
+ * (d = row lengths of the CSR the blocks were sampled from, which holds the
+ * self-pairs; the factor d_v / |S(v)| is 1 for a full-neighbourhood hop, for
+ * which the result equals lp_sage_forward's GCN on the computational graph).
  *
  * lp_backward_blocks: weight and bias gradients of the batch loss through the
  * blocks (dscore from lp_score_loss); out->dX is ignored.  Fixed summation

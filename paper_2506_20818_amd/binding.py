@@ -76,7 +76,8 @@ class _BlocksStruct(C.Structure):
                 ("n", C.c_void_p), ("nodes", C.c_void_p), ("index", C.c_void_p),
                 ("ptr", C.c_void_p * LP_MAX_LAYERS), ("col", C.c_void_p * LP_MAX_LAYERS),
                 ("inv_cnt", C.c_void_p * LP_MAX_LAYERS), ("t_ptr", C.c_void_p * LP_MAX_LAYERS),
-                ("t_col", C.c_void_p * LP_MAX_LAYERS), ("e_src_pos", C.c_void_p), ("e_dst_pos", C.c_void_p)]
+                ("t_col", C.c_void_p * LP_MAX_LAYERS), ("e_src_pos", C.c_void_p), ("e_dst_pos", C.c_void_p),
+                ("node_inv_deg", C.c_void_p)]
 
 
 class _OptStateStruct(C.Structure):
@@ -385,6 +386,7 @@ class Blocks:
         self.t_ptr = [i32(self.cap[k - 1] + 1) for k in range(1, K + 1)]
         self.t_col = [i32(self.cap_entries[k - 1]) for k in range(1, K + 1)]
         self.e_src_pos, self.e_dst_pos = i32(self.B), i32(self.B)
+        self.node_inv_deg = torch.empty(max(self.cap[0], 1), dtype=torch.float32, device=dev)
         s = _BlocksStruct()
         s.n_layers, s.n_graph_nodes, s.n_edges = K, g.n_nodes, self.B
         for k in range(K + 1):
@@ -395,6 +397,7 @@ class Blocks:
             s.t_ptr[k], s.t_col[k] = self.t_ptr[k].data_ptr(), self.t_col[k].data_ptr()
         s.n, s.nodes, s.index = self.n.data_ptr(), self.nodes.data_ptr(), self.index.data_ptr()
         s.e_src_pos, s.e_dst_pos = self.e_src_pos.data_ptr(), self.e_dst_pos.data_ptr()
+        s.node_inv_deg = self.node_inv_deg.data_ptr()
         self.c = s
         self.sample_ws = _ws(lib.lp_sample_blocks_workspace_bytes(g.n_nodes, g.nnz, self.B, K, self.fan_c), dev)
 

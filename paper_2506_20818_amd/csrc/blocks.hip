@@ -31,12 +31,12 @@ int compute_bounds(int32_t n_nodes, int64_t nnz, int64_t B, int32_t K, const int
     if (n_nodes <= 0 || nnz < 0 || B < 0 || K < 1 || K > LP_MAX_LAYERS || !fanout) return LP_ERR_INVALID_ARG;
     if (B >= ((int64_t)1 << 30) || nnz >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
     for (int h = 0; h < K; ++h)
-        if (fanout[h] < 1 || fanout[h] > LP_MAX_FANOUT) return LP_ERR_UNSUPPORTED;
+        if (fanout[h] != LP_FANOUT_ALL && (fanout[h] < 1 || fanout[h] > LP_MAX_FANOUT)) return LP_ERR_UNSUPPORTED;
     int64_t c = 2 * B < n_nodes ? 2 * B : n_nodes;
     b.cap[K] = (int32_t)c;
     b.max_entries = 1;
     for (int k = K; k >= 1; --k) {
-        const int64_t f = fanout[K - k];
+        const int64_t f = fanout[K - k] == LP_FANOUT_ALL ? nnz + 1 : fanout[K - k];   // all neighbours: only nnz and N bound it
         int64_t e = c * f < nnz ? c * f : nnz;
         b.cap_entries[k - 1] = e;
         b.max_entries = e > b.max_entries ? e : b.max_entries;
@@ -124,6 +124,31 @@ __global__ __launch_bounds__(256) void sample_rows_kernel(const int32_t *__restr
     }
 }
 
+// Full-neighbourhood hop: a 64-lane group per node of the frontier copies the node's whole list, in list order.
+__global__ __launch_bounds__(256) void take_all_rows_kernel(const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+                                                            const int32_t *__restrict__ nodes, const int32_t *__restrict__ n_rows_dev,
+                                                            const int32_t *__restrict__ ptr, int32_t *__restrict__ col_global,
+                                                            int32_t *__restrict__ row_of_entry, const int32_t *__restrict__ index,
+                                                            int32_t *__restrict__ mark) {
+    const int lane = threadIdx.x & 63;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (i >= *n_rows_dev) return;
+    const int32_t v = nodes[i];
+    const int32_t lo = rowptr[v], d = rowptr[v + 1] - lo, base = ptr[i];
+    for (int32_t t = lane; t < d; t += 64) {
+        const int32_t u = colidx[lo + t];
+        col_global[base + t] = u;
+        row_of_entry[base + t] = (int32_t)i;
+        if (index[u] < 0) mark[u] = 1;  // joins the next frontier; every writer stores the same value
+    }
+}
+
+__global__ void node_inv_deg_kernel(const int32_t *__restrict__ nodes, const int32_t *__restrict__ n_dev, const float *__restrict__ inv_deg,
+                                    float *__restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < *n_dev) out[i] = inv_deg[nodes[i]];
+}
+
 __global__ void translate_kernel(const int32_t *__restrict__ col_global, const int32_t *__restrict__ ptr,
                                  const int32_t *__restrict__ n_rows_dev, int64_t cap_entries, const int32_t *__restrict__ index,
                                  int32_t *__restrict__ col, uint64_t *__restrict__ keys, uint32_t park_row) {
@@ -191,7 +216,7 @@ SampleWs carve_sample(void *ws, int32_t n_nodes, const Bounds &b) {
 
 int check_blocks(const lp_blocks *b, bool need_transposed) {
     if (!b || b->n_layers < 1 || b->n_layers > LP_MAX_LAYERS || b->n_graph_nodes <= 0) return LP_ERR_INVALID_ARG;
-    if (!b->n || !b->nodes || !b->index || !b->e_src_pos || !b->e_dst_pos) return LP_ERR_INVALID_ARG;
+    if (!b->n || !b->nodes || !b->index || !b->e_src_pos || !b->e_dst_pos || !b->node_inv_deg) return LP_ERR_INVALID_ARG;
     for (int k = 0; k <= b->n_layers; ++k)
         if (b->cap[k] < 0 || (k < b->n_layers && b->cap[k] < b->cap[k + 1])) return LP_ERR_INVALID_ARG;
     for (int k = 0; k < b->n_layers; ++k) {
@@ -205,14 +230,15 @@ int check_blocks(const lp_blocks *b, bool need_transposed) {
 int check_block_model(const lp_model *m, const lp_blocks *b) {
     if (!m || m->n_layers != b->n_layers) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
-    if (m->layer_type != LP_LAYER_SAGE_MEAN) return LP_ERR_UNSUPPORTED;  // sampled blocks: GraphSAGE-mean layers only
+    if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
+    const bool gcn = m->layer_type == LP_LAYER_GCN;   // a single weight matrix (W_neigh) per layer
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
         if ((m->dims[k] % lp_vec_elems(m->dtype)) || m->dims[k] > 1024) return LP_ERR_UNSUPPORTED;
     }
     for (int k = 0; k < m->n_layers; ++k) {
-        if (!m->W_self[k] || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
-        if (!lp_aligned16(m->W_self[k]) || !lp_aligned16(m->W_neigh[k])) return LP_ERR_INVALID_ARG;
+        if ((!gcn && !m->W_self[k]) || !m->W_neigh[k] || !m->bias[k]) return LP_ERR_INVALID_ARG;
+        if ((!gcn && !lp_aligned16(m->W_self[k])) || !lp_aligned16(m->W_neigh[k])) return LP_ERR_INVALID_ARG;
     }
     return LP_OK;
 }
@@ -256,7 +282,8 @@ BlockBackwardWs carve_block_backward(void *ws, const lp_model *m, const lp_block
     for (int i = 0; i < 3; ++i) w.buf[i] = take(big);
     size_t tn = 0, cs = 0;
     for (int k = 1; k <= K; ++k) {
-        const size_t t = lp_weight_grads_partials_bytes(m->dtype, b->cap[k] > 0 ? b->cap[k] : 1, m->dims[k - 1], m->dims[k - 1], m->dims[k]);
+        const size_t t = lp_weight_grads_partials_bytes(m->dtype, b->cap[k] > 0 ? b->cap[k] : 1,
+                                                        m->layer_type == LP_LAYER_GCN ? 0 : m->dims[k - 1], m->dims[k - 1], m->dims[k]);
         tn = t > tn ? t : tn;
         const size_t c = lp_colsum_partials_bytes(b->cap[k], m->dims[k]);
         cs = c > cs ? c : cs;
@@ -296,7 +323,7 @@ extern "C" size_t lp_sample_blocks_workspace_bytes(int32_t n_nodes, int64_t nnz,
 extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src, const int32_t *e_dst, int32_t K,
                                 const int32_t *fanout, uint64_t seed, uint64_t step, lp_blocks *out, void *ws, size_t ws_bytes,
                                 void *stream) {
-    if (!g || g->n_nodes <= 0 || g->nnz < 0 || !g->rowptr || (g->nnz > 0 && !g->colidx) || !out) return LP_ERR_INVALID_ARG;
+    if (!g || g->n_nodes <= 0 || g->nnz < 0 || !g->rowptr || (g->nnz > 0 && !g->colidx) || !g->inv_deg || !out) return LP_ERR_INVALID_ARG;
     Bounds bd;
     LP_TRY(compute_bounds(g->n_nodes, g->nnz, B, K, fanout, bd));
     if (B > 0 && (!e_src || !e_dst)) return LP_ERR_INVALID_ARG;
@@ -332,7 +359,8 @@ extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src
     LP_TRY(lp_after_launch());
 
     for (int k = K; k >= 1; --k) {
-        const int32_t fan = fanout[K - k];
+        const bool take_all = fanout[K - k] == LP_FANOUT_ALL;
+        const int32_t fan = take_all ? 0x7fffffff : fanout[K - k];
         const uint32_t hop = (uint32_t)(K + 1 - k);
         const int32_t cap_k = out->cap[k] < bd.cap[k] ? out->cap[k] : bd.cap[k];
         const int64_t cap_e = bd.cap_entries[k - 1];
@@ -354,8 +382,12 @@ extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src
             LP_TRY(device_exclusive_scan<uint32_t>(count, store, (int64_t)cap_k + 1, w.sums, static_cast<uint32_t *>(nullptr), st));
         }
         LP_TRY(lp_launch_zero(reinterpret_cast<float *>(w.mark), N, st));
-        if (cap_k > 0)
-        {
+        if (cap_k <= 0) {
+            // nothing to draw from
+        } else if (take_all) {
+            hipLaunchKernelGGL(take_all_rows_kernel, dim3((unsigned)lp_ceil_div((int64_t)cap_k * 64, 256)), dim3(256), 0, st, g->rowptr, g->colidx,
+                               out->nodes, n_k, ptr, w.col_global, w.row_of_entry, out->index, w.mark);
+        } else {
             const int G = fan <= 16 ? 16 : 64;
             const dim3 sgrid((unsigned)lp_ceil_div((int64_t)cap_k * G, 256));
             if (G == 16)
@@ -395,6 +427,12 @@ extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src
         }
         LP_TRY(lp_after_launch());
     }
+    // 1/|N(v)| of every node of the computational graph (the GCN layers normalise with the full graph's degrees)
+    if (out->cap[0] > 0) {
+        hipLaunchKernelGGL(node_inv_deg_kernel, dim3((unsigned)lp_ceil_div(out->cap[0], 256)), dim3(256), 0, st, out->nodes, out->n, g->inv_deg,
+                           out->node_inv_deg);
+        LP_TRY(lp_after_launch());
+    }
     return LP_OK;
 }
 
@@ -430,6 +468,7 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
         LP_TRY(lp_after_launch());
     }
     const void *Hprev = X_frontier;
+    const bool gcn = m->layer_type == LP_LAYER_GCN;
     for (int k = 1; k <= K; ++k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
         SpmmArgs sp;
@@ -437,14 +476,18 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
         sp.n_rows = b->cap[k]; sp.n_rows_dev = b->n + k;
         sp.F = Fi;
         sp.rowptr = b->ptr[k - 1]; sp.colidx = b->col[k - 1];
-        sp.inv_deg = b->inv_cnt[k - 1];
+        if (gcn) {   // (d_v / |S(v)|) sum h_u / sqrt(d_v d_u), d = degrees of the graph the blocks were sampled from
+            sp.inv_deg = b->node_inv_deg; sp.sym_norm = true; sp.sym_row_cnt = b->inv_cnt[k - 1];
+        } else {
+            sp.inv_deg = b->inv_cnt[k - 1];
+        }
         sp.n_entries = b->cap_entries[k - 1];
         sp.in = Hprev; sp.out = saved->A[k - 1];
         LP_TRY(lp_launch_spmm(sp, st));
         const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
         void *WsT = wt, *WnT = wt + wbytes;
         wt += 2 * wbytes;
-        LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
+        if (!gcn) LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
         LP_TRY(lp_launch_transpose(m->W_neigh[k - 1], Fi, Fo, WnT, dt, st));
         GemmNtArgs ge;
         ge.dtype = dt;
@@ -452,7 +495,7 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
         ge.N = Fo; ge.n_split = Fo;
         ge.A[0] = Hprev; ge.A[1] = saved->A[k - 1];   // a frontier is a prefix of the one before: row i is node i in both
         ge.lda[0] = ge.lda[1] = Fi;
-        ge.K[0] = ge.K[1] = Fi;
+        ge.K[0] = gcn ? 0 : Fi; ge.K[1] = Fi;
         ge.Bt[0][0] = WsT; ge.Bt[1][0] = WnT;
         ge.ldb[0] = ge.ldb[1] = Fi;
         ge.bias = static_cast<const float *>(m->bias[k - 1]);
@@ -479,11 +522,12 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
     if (!X_frontier || !lp_aligned16(X_frontier) || !saved || !out) return LP_ERR_INVALID_ARG;
     const int K = m->n_layers;
     const int64_t B = b->n_edges;
+    const bool gcn = m->layer_type == LP_LAYER_GCN;   // one weight matrix per layer: its gradient goes to dW_neigh
     if (B < 0 || (B > 0 && !dscore && !edge_grad)) return LP_ERR_INVALID_ARG;
     if (edge_grad && !lp_aligned16(edge_grad)) return LP_ERR_INVALID_ARG;
     for (int k = 0; k < K; ++k) {
         if (!saved->A[k] || !saved->H[k]) return LP_ERR_INVALID_ARG;
-        if (!out->dW_self[k] || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
+        if ((!gcn && !out->dW_self[k]) || !out->dW_neigh[k] || !out->dbias[k]) return LP_ERR_INVALID_ARG;
     }
     if (!ws || ws_bytes < lp_backward_blocks_workspace_bytes(m, b)) return LP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -491,7 +535,7 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
     if (B == 0 || b->cap[K] == 0) {  // an empty batch has a zero loss: every gradient is zero
         for (int k = 0; k < K; ++k) {
             const int64_t nw = (int64_t)m->dims[k] * m->dims[k + 1];
-            LP_TRY(lp_launch_zero(out->dW_self[k], nw, st));
+            if (!gcn) LP_TRY(lp_launch_zero(out->dW_self[k], nw, st));
             LP_TRY(lp_launch_zero(out->dW_neigh[k], nw, st));
             LP_TRY(lp_launch_zero(out->dbias[k], m->dims[k + 1], st));
         }
@@ -523,7 +567,7 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
         WeightGradArgs wg;
         wg.dtype = dt;
         wg.Kn = rows; wg.kn_dev = rows_dev;
-        wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1];   // rows 0..n_k-1 of the wider frontier are the same nodes
+        if (!gcn) { wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1]; }   // rows 0..n_k-1 of the wider frontier are the same nodes
         wg.At[1] = saved->A[k - 1]; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW_neigh[k - 1];
         wg.B = dZ; wg.Nw = Fo; wg.ldb = Fo;
         wg.dbias = out->dbias[k - 1];
@@ -533,14 +577,20 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
         GemmNtArgs ge;
         ge.dtype = dt;
         ge.M = rows; ge.m_dev = rows_dev;
-        ge.N = 2 * Fi; ge.n_split = Fi;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
-        ge.Bt[0][0] = m->W_self[k - 1];
-        ge.Bt[0][1] = m->W_neigh[k - 1];
         ge.ldb[0] = Fo;
-        ge.rowscale = b->inv_cnt[k - 1];
-        ge.C[0] = Q; ge.C[1] = R;
-        ge.ldc[0] = ge.ldc[1] = Fi;
+        if (gcn) {   // dZ W^T -> R; the normalisation is applied by the aggregation that follows
+            ge.N = Fi; ge.n_split = Fi;
+            ge.Bt[0][0] = m->W_neigh[k - 1];
+            ge.C[0] = R; ge.ldc[0] = Fi;
+        } else {
+            ge.N = 2 * Fi; ge.n_split = Fi;
+            ge.Bt[0][0] = m->W_self[k - 1];
+            ge.Bt[0][1] = m->W_neigh[k - 1];
+            ge.rowscale = b->inv_cnt[k - 1];
+            ge.C[0] = Q; ge.C[1] = R;
+            ge.ldc[0] = ge.ldc[1] = Fi;
+        }
         LP_TRY(lp_launch_gemm_nt(ge, st));
         // gradient on frontier k-1: the self path for its first n_k rows plus the transposed block, gated by the ReLU
         SpmmArgs sp;
@@ -548,7 +598,12 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
         sp.n_rows = b->cap[k - 1]; sp.n_rows_dev = b->n + (k - 1); sp.F = Fi;
         sp.rowptr = b->t_ptr[k - 1]; sp.colidx = b->t_col[k - 1];
         sp.n_entries = b->cap_entries[k - 1]; sp.long_queue = w.long_queue;   // a popular node can be drawn by thousands of rows
-        sp.in = R; sp.addend = Q; sp.addend_rows_dev = rows_dev;
+        sp.in = R;
+        if (gcn) {   // entry (u <- v) weighs (1/|S(v)|) / sqrt(1/d_v), row u is scaled by sqrt(1/d_u); no separate self path
+            sp.inv_deg = b->node_inv_deg; sp.sym_norm = true; sp.sym_col_cnt = b->inv_cnt[k - 1];
+        } else {
+            sp.addend = Q; sp.addend_rows_dev = rows_dev;
+        }
         sp.gate = Hin;
         sp.out = dZ;   // dZ of layer k is finished: its buffer takes the gradient of layer k-1
         LP_TRY(lp_launch_spmm(sp, st));

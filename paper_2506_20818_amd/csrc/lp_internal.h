@@ -59,6 +59,11 @@ struct SpmmArgs {
     const int32_t *entry_row_index = nullptr;  // element-wise by its row entry_row_index[p] (instead of a scalar weight)
     bool sym_norm = false;               // symmetric normalisation: entry p weighs sqrt(inv_deg[colidx[p]]), row v is
                                          // scaled by sqrt(inv_deg[v]) (inv_deg required, w unused)
+    // with sym_norm, for a sampled subset of the neighbours (inverse counts 1/|S| of the sampled rows): a row v with
+    // sym_row_cnt is scaled by sym_row_cnt[v] / sqrt(inv_deg[v]) instead; an entry with column c and sym_col_cnt
+    // weighs sym_col_cnt[c] / sqrt(inv_deg[c]) instead (the transposed pass)
+    const float *sym_row_cnt = nullptr;
+    const float *sym_col_cnt = nullptr;
     const void *in = nullptr;
     const void *addend = nullptr;        // optional [n_rows, F]
     const int32_t *in_index = nullptr;   // optional [number of nodes]: row of `in` / `addend` that holds a node, or < 0

@@ -40,7 +40,14 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
         const int cnt = min(64, hi - base);
         int32_t mine = lane < cnt ? a.colidx[base + lane] : 0;
         float mine_w = 1.f;
-        if (W == 1) mine_w = lane < cnt ? (a.sym_norm ? sqrtf(a.inv_deg[mine]) : a.w[base + lane]) : 0.f;
+        if (W == 1) {
+            mine_w = 0.f;
+            if (lane < cnt) {
+                if (!a.sym_norm) mine_w = a.w[base + lane];
+                else if (a.sym_col_cnt) mine_w = a.sym_col_cnt[mine] / sqrtf(a.inv_deg[mine]);   // the column has this entry: inv_deg > 0
+                else mine_w = sqrtf(a.inv_deg[mine]);
+            }
+        }
         int32_t mine_row = 0;
         if (W == 2) mine_row = lane < cnt ? a.entry_row_index[base + lane] : 0;
         if (a.in_index) mine = lane < cnt ? a.in_index[mine] : -1;  // row of `in` that holds the neighbour, < 0: a zero row
@@ -94,6 +101,16 @@ __device__ __forceinline__ void fold_groups(float (&acc)[C][VE]) {
             for (int e = 0; e < VE; ++e) acc[c][e] += __shfl_xor(acc[c][e], d, 64);
 }
 
+// What the sum of row v is multiplied by: 1/deg (mean), sqrt(1/deg) (symmetric normalisation), or, for a sampled
+// subset of the neighbours, (1/|S|) / sqrt(1/deg).
+__device__ __forceinline__ float row_scale(const SpmmArgs &a, int32_t v) {
+    if (!a.inv_deg) return 1.0f;
+    const float id = a.inv_deg[v];
+    if (!a.sym_norm) return id;
+    if (a.sym_row_cnt) return id > 0.f ? a.sym_row_cnt[v] / sqrtf(id) : 0.f;
+    return sqrtf(id);
+}
+
 // Scale, optional addend, optional gate, store: 16 bytes of output row v starting at vector column colv.
 template <typename T>
 __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int FV, int colv, float scale,
@@ -145,7 +162,7 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     accumulate_blocks<T, G, C, W, 4>(a, static_cast<const T *>(a.in), lo, hi, 64, lane, acc);
     fold_groups<G, C, VE>(acc);
     if (sub != 0 || fl >= FV) return;
-    const float scale = a.inv_deg ? (a.sym_norm ? sqrtf(a.inv_deg[v]) : a.inv_deg[v]) : 1.0f;
+    const float scale = row_scale(a, v);
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int colv = fl + 64 * c;
@@ -174,7 +191,7 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
             for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
         accumulate_blocks<T, G, C, W, U>(a, static_cast<const T *>(a.in), lo + 64 * wave, hi, 64 * kLongWaves, lane, acc);
         fold_groups<G, C, VE>(acc);
-        const float scale = a.inv_deg ? (a.sym_norm ? sqrtf(a.inv_deg[v]) : a.inv_deg[v]) : 1.0f;
+        const float scale = row_scale(a, v);
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             if (sub == 0) {

@@ -196,7 +196,7 @@ def _blocks(K=3, n_graph=1000, n_edges=64, fan=(25, 10, 5), nnz=5000):
     for k in range(K):
         b.cap_entries[k] = cap_e[k]
         b.ptr[k] = b.col[k] = b.inv_cnt[k] = b.t_ptr[k] = b.t_col[k] = 0x1000
-    b.n = b.nodes = b.index = b.e_src_pos = b.e_dst_pos = 0x1000
+    b.n = b.nodes = b.index = b.e_src_pos = b.e_dst_pos = b.node_inv_deg = 0x1000
     return b, fan_c
 
 
@@ -209,7 +209,9 @@ def test_blocks_bounds_and_argument_checks_on_the_host():
     assert list(cap) == [1000, 1000, 416, 16] and list(cap_e) == [5000, 4160, 400]      # min(N, c(1+f)), min(nnz, c f)
     assert lib.lp_blocks_bounds(1000, 5000, 8, 0, fan, cap, cap_e) == -1
     assert lib.lp_blocks_bounds(0, 5000, 8, 3, fan, cap, cap_e) == -1
-    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(25, 0, 5), cap, cap_e) == -4
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(25, -1, 5), cap, cap_e) == -4
+    assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(0, 10, 5), cap, cap_e) == 0          # 0: all neighbours
+    assert list(cap) == [1000, 1000, 1000, 16] and list(cap_e) == [5000, 5000, 5000]
     assert lib.lp_blocks_bounds(1000, 5000, 8, 3, (C.c_int32 * 3)(25, 65, 5), cap, cap_e) == -4
     assert lib.lp_blocks_bounds(1000, 5000, 1 << 30, 3, fan, cap, cap_e) == -2
     assert lib.lp_sample_blocks_workspace_bytes(1000, 5000, 8, 3, fan) > 0

@@ -171,3 +171,78 @@ def test_sampled_step_with_mlp_predictor(dims, fanout):
         assert_grad_close(host(grads.dW_self[k]), out["ref"].dW_self[k], out["lo"].dW_self[k], out["hi"].dW_self[k], "dW_self^%d" % (k + 1))
         assert_grad_close(host(grads.dW_neigh[k]), out["ref"].dW_neigh[k], out["lo"].dW_neigh[k], out["hi"].dW_neigh[k], "dW_neigh^%d" % (k + 1))
         assert_grad_close(host(grads.dbias[k]), out["ref"].dbias[k], out["lo"].dbias[k], out["hi"].dbias[k], "dbias^%d" % (k + 1))
+
+
+# ------------------------------------------------------------------ full-neighbourhood hops and GCN layers on the blocks
+def test_full_neighbourhood_blocks_sage():
+    """Fan-out 0 = all neighbours (hub rows of several hundred entries included): blocks bit-exact, step within the
+    usual bars; by construction this equals the full-graph step on the computational graph."""
+    rng = np.random.default_rng(31)
+    n, dims = 1100, [16, 40, 24]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 2600, 400)
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    es, ed = rng.integers(0, n, 150).astype(np.int32), rng.integers(0, n, 150).astype(np.int32)
+    es[:20] = 3
+    say("full-neighbourhood blocks (fan-out 0), GraphSAGE")
+    run_case(ref, g, Ws, Wn, b, X, es, ed, 70, [0, 0], seed=5, step=9)
+    run_case(ref, g, Ws, Wn, b, X, es, ed, 70, [4, 0], seed=5, step=9)       # mixed: drawn first hop, full second hop
+
+
+def gcn_case(dims, fanout, bf16=False):
+    from oracle import gcn_oracle as Gc
+    rng = np.random.default_rng(700 + sum(dims) + sum(fanout))
+    n = 1000
+    r, c = graph_with_hub_and_empty_rows(rng, n, 2500, 300)
+    r2, c2 = Gc.add_self_pairs(n, r, c)
+    ref = O.build_csr(n, r2, c2, True)
+    g = lp.lp_build_csr(n, dev_i32(r2), dev_i32(c2), True)
+    K = len(dims) - 1
+    W = [(rng.standard_normal((dims[k], dims[k + 1])) * 0.3).astype(np.float32) for k in range(K)]
+    b = [(rng.standard_normal(dims[k + 1]) * 0.2).astype(np.float32) for k in range(K)]
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 200, 90
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    es[:30] = 3
+    say("GCN on blocks dims=%s fanout=%s" % (dims, fanout))
+    bref = Bk.sample_blocks(ref, es, ed, fanout, 21, 4)
+    blocks = lp.lp_sample_blocks(g, dev_i32(es), dev_i32(ed), fanout, 21, 4)
+    check_blocks(blocks, bref, K)
+    inv = O.inverse_degrees(ref)
+    assert np.array_equal(host(blocks.node_inv_deg)[:bref.n[0]], inv[bref.nodes[:bref.n[0]]].astype(np.float32))
+    model = lp.Model(None, [dev_f32(w) for w in W], [dev_f32(x) for x in b], layer_type=lp.LP_LAYER_GCN)
+    acts = lp.lp_sage_forward_blocks(blocks, model, dev_f32(X))
+    a_ref = Bk.forward_blocks_gcn(bref, inv, W, b, X)
+    for k in range(1, K + 1):
+        assert_close(host(acts.A[k - 1])[:bref.n[k]], a_ref.A[k], TOL_ACT, "A^%d" % k)
+        assert_close(host(acts.H[k - 1])[:bref.n[k]], a_ref.H[k], TOL_ACT, "H^%d" % k)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], blocks.e_src_pos, blocks.e_dst_pos, n_pos)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[K], bref.e_src_pos, bref.e_dst_pos, n_pos)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    grads = lp.lp_backward_blocks(blocks, model, acts, ds)
+    g_ref = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref)
+    lo = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref, relu_margin=5e-6)
+    hi = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref, relu_margin=-5e-6)
+    for k in range(K):
+        assert_grad_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], lo.dW_neigh[k], hi.dW_neigh[k], "dW^%d" % (k + 1))
+        assert_grad_close(host(grads.dbias[k]), g_ref.dbias[k], lo.dbias[k], hi.dbias[k], "dbias^%d" % (k + 1))
+    return ref, g, W, b, X, es, ed, n_pos, acts, bref
+
+
+@pytest.mark.parametrize("dims,fanout", [([12, 20, 8], [0, 0]), ([12, 20, 8], [5, 3]), ([128, 256, 256, 256], [0, 0, 0]),
+                                         ([128, 256, 256, 256], [25, 10, 5])])
+def test_gcn_layers_on_blocks(dims, fanout):
+    gcn_case(dims, fanout)
+
+
+def test_gcn_full_neighbourhood_blocks_equal_the_full_graph_gcn_on_the_gpu():
+    """Both GPU paths against each other as well: with all neighbours taken, the embeddings of the batch end points
+    from the blocks must agree with lp_sage_forward's GCN on the whole graph (to fp32 summation-order noise)."""
+    dims = [16, 32, 16]
+    ref, g, W, b, X, es, ed, n_pos, acts, bref = gcn_case(dims, [0, 0])
+    model = lp.Model(None, [dev_f32(w) for w in W], [dev_f32(x) for x in b], layer_type=lp.LP_LAYER_GCN)
+    full = lp.lp_sage_forward(g, model, dev_f32(X))
+    seeds = torch.from_numpy(bref.nodes[:bref.n[2]].astype(np.int64)).to("cuda:0")
+    assert_close(host(acts.H[-1])[:bref.n[2]], host(full.H[-1][seeds]).astype(np.float64), 1e-5, "blocks vs full graph")
