@@ -41,18 +41,19 @@ def spmm_bytes_listed(n, nnz, F, n_t, nnz_t, eb=4):
     return nnz * 8 + nnz_t * eb * F + (n + 1) * 4 + n * 4 + 2 * n * eb * F + n_t * eb * F
 
 
-def step_counts(n, nnz, dims, n_t, nnz_t, eb=4):
+def step_counts(n, nnz, dims, n_t, nnz_t, eb=4, paths=2):
     """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer's backward products run over the
-    n_t endpoint rows only (every other row of dL/dH^K is exactly zero)."""
+    n_t endpoint rows only (every other row of dL/dH^K is exactly zero).  paths: weight matrices per layer (2 for
+    GraphSAGE's self and neighbour paths, 1 for GCN)."""
     K = len(dims) - 1
     sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K + 1))
     sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K))
     if K >= 2:
         sp += spmm_bytes_listed(n, nnz, dims[K - 1], n_t, nnz_t, eb)
     rows = lambda k: n_t if k == K else n
-    nt = sum(2.0 * n * dims[k] * 2 * dims[k - 1] for k in range(1, K + 1))                # forward
-    nt += sum(2.0 * rows(k) * 2 * dims[k - 1] * dims[k] for k in range(2, K + 1))         # input gradients
-    tn = sum(2.0 * 2 * rows(k) * dims[k - 1] * dims[k] for k in range(1, K + 1))          # dW_self, dW_neigh
+    nt = sum(2.0 * n * dims[k] * paths * dims[k - 1] for k in range(1, K + 1))            # forward
+    nt += sum(2.0 * rows(k) * paths * dims[k - 1] * dims[k] for k in range(2, K + 1))     # input gradients
+    tn = sum(2.0 * paths * rows(k) * dims[k - 1] * dims[k] for k in range(1, K + 1))      # dW_self, dW_neigh
     return sp, nt, tn
 
 
@@ -272,6 +273,10 @@ def main():
     ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
                     help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "
                          "sampled_step: the mini-batch mode with sampled neighbourhoods")
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
+                    help="--task train_step: GraphSAGE-mean layers (the headline) or GCN layers (self-pairs added to the graph)")
+    ap.add_argument("--predictor", default="dot", choices=["dot", "mlp"],
+                    help="--task train_step: dot-product scorer (the headline) or the 3-layer MLP edge predictor")
     ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
     ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
     ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
@@ -301,7 +306,12 @@ def main():
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
     f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
 
-    rows, cols = i32(wl.src), i32(wl.dst)
+    gcn, use_mlp = args.model == "gcn", args.predictor == "mlp"
+    src_np, dst_np = wl.src, wl.dst
+    if gcn:   # the GCN propagation runs over the graph with every self-pair present
+        loop = np.arange(wl.n_nodes, dtype=np.int32)
+        src_np, dst_np = np.concatenate([wl.src, loop]), np.concatenate([wl.dst, loop])
+    rows, cols = i32(src_np), i32(dst_np)
     lp.lp_build_csr(wl.n_nodes, rows, cols, True)                     # warm-up of the setup path
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -312,10 +322,21 @@ def main():
     bf16 = wl.dtype == "bf16"
     tdt = torch.bfloat16 if bf16 else torch.float32
     st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32      # storage type of features and weights
-    model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+    if gcn:
+        model = lp.Model(None, [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias], layer_type=lp.LP_LAYER_GCN)
+    else:
+        model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
     X = st(wl.X)
     n_pos, k_neg, Bn = wl.n_pos, wl.k_neg, wl.batch_edges
     pos_src = i32(wl.pos_src)
+    mlp = None
+    if use_mlp:   # "Hyperparameters": a 3-layer MLP edge predictor, hidden width 256 (here: the embedding width)
+        rng = np.random.default_rng(777)
+        F = wl.dims[-1]
+        md = [F, F, F, 1]
+        mlp = lp.Mlp([st((rng.standard_normal((md[j], md[j + 1])) / np.sqrt(md[j])).astype(np.float32)) for j in range(3)],
+                     [f32(rng.uniform(-0.1, 0.1, md[j + 1]).astype(np.float32)) for j in range(3)])
+        macts, mgrads = lp.MlpActs(mlp, Bn, dev), lp.MlpGrads(mlp, dev)
     e_src = torch.empty(Bn, dtype=torch.int32, device=dev)
     e_dst = torch.empty(Bn, dtype=torch.int32, device=dev)
     e_src[:n_pos] = pos_src
@@ -333,8 +354,14 @@ def main():
     def step(i):
         lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
         lp.lp_sage_forward(g, model, X, acts, ws_f)
-        lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
-        lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)
+        if mlp is None:
+            lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
+            lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)
+        else:   # the binding allocates scores, edge gradients and workspaces per call (torch's caching allocator)
+            s_, l_, ds_, _ = lp.lp_mlp_score_loss(acts.H[-1], e_src, e_dst, n_pos, mlp, macts)
+            _, eg = lp.lp_mlp_backward(mlp, macts, ds_, mgrads)
+            lp.lp_backward_edge_grads(g, model, X, acts, e_src, e_dst, eg, grads, ws_b)
+            loss.copy_(l_)
 
     if args.copy_calibration_mib > 0:
         a = torch.zeros(args.copy_calibration_mib << 18, dtype=torch.float32, device=dev)
@@ -405,7 +432,11 @@ def main():
     n_t, nnz_t = n_t_sum / max(args.steps, 1), nnz_t_sum / max(args.steps, 1)
 
     n, nnz = wl.n_nodes, g.nnz
-    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, n_t, nnz_t, 2 if bf16 else 4)
+    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, n_t, nnz_t, 2 if bf16 else 4, 1 if gcn else 2)
+    if use_mlp:   # hidden layers of the predictor on Bn edge rows: forward, input gradients and weight gradients
+        F = wl.dims[-1]
+        nt_flops += 2 * 2.0 * Bn * F * F + 2 * 2.0 * Bn * F * F
+        tn_flops += 2 * 2.0 * Bn * F * F
     per_step = {k: (ms / max(args.steps, 1), cnt // max(args.steps, 1)) for k, (ms, cnt) in classes.items()}
 
     def hbm_line(cls, bytes_per_step):
@@ -426,7 +457,7 @@ def main():
     # same script, scaled by what a plain copy of known size reads); null when no summary covers the workload.
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not gcn and not use_mlp:
         with open(tpath) as fh:
             traffic = json.load(fh)
 
@@ -442,7 +473,10 @@ def main():
     # the two small steps of the metric's second half: scoring gathers two embedding rows per edge and writes a score
     # and a gradient scalar; the sampler is latency bound, so it is reported as samples per second
     es = 2 if bf16 else 4
-    score_line = hbm_line("score", Bn * (2.0 * wl.dims[-1] * es + 16.0))
+    score_bytes = Bn * (2.0 * wl.dims[-1] * es + 16.0)
+    if use_mlp:   # the element-wise product of the two rows is written out, and the output layer reads the last hidden row
+        score_bytes += Bn * 2.0 * wl.dims[-1] * es
+    score_line = hbm_line("score", score_bytes)
     sample_ms = per_step["sample"][0]
     sample_line = {"bound": "latency", "kernel": "sample", "achieved": round(n_pos * k_neg / (sample_ms * 1e-3) / 1e9, 3) if sample_ms > 0 else 0.0,
                    "unit": "Gsamples/s", "launches_per_step": per_step["sample"][1], "avg_launch_ms": round(sample_ms / max(per_step["sample"][1], 1), 4)}
@@ -462,9 +496,11 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, GraphSAGE-mean %s, "
+        "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, %s %s, %s, "
                                "%d positives + %d uniform negatives per step, full-neighbour aggregation"
-                               % (args.workload, n, nnz, "->".join(map(str, wl.dims)), n_pos, n_pos * k_neg),
+                               % (args.workload, n, nnz, "GCN (self-pairs in the graph)" if gcn else "GraphSAGE-mean",
+                                  "->".join(map(str, wl.dims)), "3-layer MLP edge predictor" if use_mlp else "dot-product scorer",
+                                  n_pos, n_pos * k_neg),
                    "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg,
                    "batch_endpoint_nodes": round(n_t, 1)},
         "loss": round(loss_val, 6),
@@ -479,7 +515,7 @@ def main():
     }
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
         out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not gcn and not use_mlp:   # the oracle leg times the headline step only
         out["cpu_baseline"] = cpu_baseline(args.cpu_scale)
     print(json.dumps(out), flush=True)
 

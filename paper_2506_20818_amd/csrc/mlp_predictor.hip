@@ -253,8 +253,8 @@ extern "C" int lp_mlp_score_loss(const void *HK, int32_t n_nodes, int64_t B, int
     const int dt = p->dtype;
     float *partial = static_cast<float *>(ws);
     char *wt = static_cast<char *>(ws) + lp_align_up(sizeof(float) * kMaxLossBlocks);
-    LpTimedScope timed(LP_KC_SCORE, st);
     if (B > 0) {
+        LpTimedScope timed(LP_KC_SCORE, st);
         const int FV = p->dims[0] / lp_vec_elems(dt);
         const unsigned grid = (unsigned)lp_ceil_div(B * FV, 256);
         if (dt == LP_BF16)
@@ -285,6 +285,7 @@ extern "C" int lp_mlp_score_loss(const void *HK, int32_t n_nodes, int64_t B, int
     const int F = p->dims[L - 1];
     const int G = group_lanes(F, lp_vec_elems(dt));
     const int nb = loss_blocks(B, G);
+    LpTimedScope timed(LP_KC_SCORE, st);   // opened after the products, which time themselves
     if (dt == LP_BF16) launch_out_loss<lp_bf16_t>(G, nb, st, Uprev, p->W[L - 1], p->bias[L - 1], n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
     else launch_out_loss<float>(G, nb, st, Uprev, p->W[L - 1], p->bias[L - 1], n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
     hipLaunchKernelGGL(mean_finish_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, B, loss);
