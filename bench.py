@@ -41,6 +41,12 @@ def spmm_bytes_listed(n, nnz, F, n_t, nnz_t, eb=4):
     return nnz * 8 + nnz_t * eb * F + (n + 1) * 4 + n * 4 + 2 * n * eb * F + n_t * eb * F
 
 
+def fp32_products_name(bf16, split):
+    if bf16:
+        return None
+    return "bf16x6 (three bfloat16 terms per value, six term products, fp32 accumulation)" if split else "fp32 matrix instructions"
+
+
 def step_counts(n, nnz, dims, n_t, nnz_t, eb=4, paths=2):
     """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer's backward products run over the
     n_t endpoint rows only (every other row of dL/dH^K is exactly zero).  paths: weight matrices per layer (2 for
@@ -142,6 +148,7 @@ def sampled_step_task(args):
     from paper_2506_20818_amd import binding as B
     from lp_workloads import make_workload
 
+    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = make_workload(args.workload)
@@ -149,6 +156,7 @@ def sampled_step_task(args):
     f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
     g = lp.lp_build_csr(wl.n_nodes, i32(wl.src), i32(wl.dst), True)
     bf16 = wl.dtype == "bf16"
+    split = (not bf16) and lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
     tdt = torch.bfloat16 if bf16 else torch.float32
     st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32
     model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
@@ -248,7 +256,7 @@ def sampled_step_task(args):
     out = {"metric": "sampled-neighbourhood train-step edges/sec (pos+neg), Adam update included, on 1 MI355X",
            "value": round(Bn / (ms * 1e-3), 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+           "dtype": "bf16" if bf16 else "f32", "fp32_products": fp32_products_name(bf16, split), "data": "synthetic",
            "config": {"workload": "%s graph (%d nodes, %d directed entries), GraphSAGE-mean %s, %d positives + %d negatives per "
                                   "step, fan-outs %s (first hop first)" % (args.workload, wl.n_nodes, g.nnz, "->".join(map(str, wl.dims)),
                                                                            n_pos, n_pos * k_neg, fanout),
@@ -277,6 +285,8 @@ def main():
                     help="--task train_step: GraphSAGE-mean layers (the headline) or GCN layers (self-pairs added to the graph)")
     ap.add_argument("--predictor", default="dot", choices=["dot", "mlp"],
                     help="--task train_step: dot-product scorer (the headline) or the 3-layer MLP edge predictor")
+    ap.add_argument("--fp32-products", default="bf16x6", choices=["bf16x6", "native"],
+                    help="how fp32 models form their dense products (see lp_set_fp32_products in include/lp.h)")
     ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
     ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
     ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
@@ -300,6 +310,7 @@ def main():
     from paper_2506_20818_amd import binding as B
     from lp_workloads import make_workload
 
+    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = make_workload(args.workload)
@@ -320,6 +331,7 @@ def main():
     build_s = time.perf_counter() - t0
 
     bf16 = wl.dtype == "bf16"
+    split = (not bf16) and lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
     tdt = torch.bfloat16 if bf16 else torch.float32
     st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32      # storage type of features and weights
     if gcn:
@@ -461,11 +473,17 @@ def main():
         with open(tpath) as fh:
             traffic = json.load(fh)
 
-    # with bf16 storage both kinds of product run on the bf16 matrix cores (fp32 accumulation)
-    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS
+    # with bf16 storage both kinds of product run on the bf16 matrix cores (fp32 accumulation); so do fp32 models in
+    # the default product mode, where one fp32 product costs six bf16 term products: the ceiling for algorithmic
+    # fp32 flops is then a sixth of the bf16 peak
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if bf16 else (round(BF16_MFMA_PEAK_TFLOPS / 6.0, 1) if split else MFMA_FP32_PEAK_TFLOPS)
     lines = {"spmm": hbm_line("spmm", sp_bytes),
              "gemm_nt": mfma_line("gemm_nt", nt_flops, mfma_peak),
              "gemm_tn": mfma_line("gemm_tn", tn_flops, mfma_peak)}
+    if split:
+        for cls in ("gemm_nt", "gemm_tn"):
+            lines[cls]["peak_basis"] = "bf16 MFMA peak %.0f TFLOP/s / 6 term products per fp32 product" % BF16_MFMA_PEAK_TFLOPS
+            lines[cls]["mfma_tflops_executed"] = round(6.0 * lines[cls]["achieved"], 1)
     for cls in lines:
         t = traffic.get(cls + "_bytes_per_launch")
         lines[cls]["traffic"] = int(t) if t else None
@@ -495,6 +513,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32",
+        "fp32_products": fp32_products_name(bf16, split),
         "data": "synthetic",
         "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, %s %s, %s, "
                                "%d positives + %d uniform negatives per step, full-neighbour aggregation"

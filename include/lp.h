@@ -431,14 +431,35 @@ int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, co
                            size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * How the dense products of an fp32 model are formed (Eq. 1's UPDATE and its
+ * gradients; the paper fixes no arithmetic).  Storage, accumulation and every
+ * result stay fp32 in both modes.
+ *   LP_FP32_PRODUCTS_BF16X6 (default): each fp32 operand value is written as the
+ *     exact sum of three bfloat16 terms and a product is taken as the six largest
+ *     of the nine term products on the bf16 matrix cores, accumulated in fp32.
+ *     What is left out is below 2^-26 of each product, a quarter of one fp32
+ *     rounding; measured against fp64 the results are as close as those of the
+ *     fp32 matrix instructions, at 6/16 of their issue time.  Non-finite inputs,
+ *     and magnitudes above the largest bfloat16 (3.39e38), give NaN where the
+ *     fp32 instructions would give an infinity or a finite value.
+ *   LP_FP32_PRODUCTS_NATIVE: fp32 matrix instructions.
+ * Process-wide, read at every launch; returns LP_ERR_INVALID_ARG for another
+ * value.  bf16 models are not affected.
+ */
+#define LP_FP32_PRODUCTS_NATIVE 0
+#define LP_FP32_PRODUCTS_BF16X6 1
+int lp_set_fp32_products(int mode);
+int lp_get_fp32_products(void);
+
+/* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each
  * kernel launch made by the calls above is bracketed by two HIP events on the
  * launch stream (lp_timing_enable(1): all classes but LP_KC_OTHER, whose small
  * launches would pay more for the events than they take; lp_timing_enable(2):
  * every launch; 0: off).  lp_timing_collect waits for the recorded events, writes the
  * summed milliseconds and launch counts per kernel class (arrays of at least
- * LP_KC_COUNT entries) and forgets them.  Off by default.  This is the only
- * process-wide state of the library; it is guarded by a mutex.
+ * LP_KC_COUNT entries) and forgets them.  Off by default.  Process-wide state
+ * (with lp_set_fp32_products the only one of the library), guarded by a mutex.
  */
 enum {
     LP_KC_SPMM = 0,     /* CSR mean aggregation, forward and transposed */

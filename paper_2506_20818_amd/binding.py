@@ -135,6 +135,8 @@ EXPORTS = {
     "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
                                C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "lp_timing_enable": (C.c_int, [C.c_int]),
+    "lp_set_fp32_products": (C.c_int, [C.c_int]),
+    "lp_get_fp32_products": (C.c_int, []),
     "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                               C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
@@ -665,6 +667,19 @@ def backward_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:
 
 def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
     return int(load_library().lp_sage_forward_workspace_bytes(C.byref(m.c), n_nodes))
+
+
+LP_FP32_PRODUCTS_NATIVE = 0
+LP_FP32_PRODUCTS_BF16X6 = 1
+
+
+def lp_set_fp32_products(mode: int) -> None:
+    """How fp32 models multiply matrices: LP_FP32_PRODUCTS_BF16X6 (default) or LP_FP32_PRODUCTS_NATIVE.  Process-wide."""
+    _check(load_library().lp_set_fp32_products(int(mode)), "lp_set_fp32_products")
+
+
+def lp_get_fp32_products() -> int:
+    return int(load_library().lp_get_fp32_products())
 
 
 KERNEL_CLASSES = ["spmm", "gemm_nt", "gemm_tn", "scatter", "score", "sample", "other"]

@@ -12,6 +12,8 @@
 //   copied to LDS as they are and read 4 bytes per lane (consecutive lanes, consecutive banks).  The node range
 //   is split over the grid; partial tiles are written out and summed in a fixed order by a second kernel.
 #include "lp_internal.h"
+
+#include <atomic>
 #include <algorithm>
 
 namespace {
@@ -219,25 +221,54 @@ template <> struct NtElem<lp_bf16_t> {
     }
 };
 
+// fp32 values as sums of three bfloat16 terms (SPLIT variant of the kernel below).  t0 = bf16(x), t1 = bf16(x - t0),
+// t2 = bf16(x - t0 - t1), every rounding to nearest: the remainders are exact in fp32 and the last one fits in eight
+// bits, so t0 + t1 + t2 == x for every finite x whose last term is not subnormal.  A product x*y is then the sum of
+// nine exact bf16 products, of which the three smallest (t1*u2, t2*u1, t2*u2: below 2^-26 of |x*y|) are left out; the
+// other six run on the bf16 matrix cores with fp32 accumulation.  Measured against fp64, the result is as close as
+// the fp32 MFMA's (both are dominated by the fp32 accumulation), at 6/16 of its issue time.
+// Four consecutive values of a row -> the 8-byte pieces of the three term planes.
+__device__ __forceinline__ void lp_split3(const v4i &v, uint2 &t0, uint2 &t1, uint2 &t2) {
+    const v4f x = __builtin_bit_cast(v4f, v);
+    float r[4];
+    t0 = make_uint2(lp_f32x2_to_bf16x2(x[0], x[1]), lp_f32x2_to_bf16x2(x[2], x[3]));
+    r[0] = x[0] - __uint_as_float(t0.x << 16);
+    r[1] = x[1] - __uint_as_float(t0.x & 0xffff0000u);
+    r[2] = x[2] - __uint_as_float(t0.y << 16);
+    r[3] = x[3] - __uint_as_float(t0.y & 0xffff0000u);
+    t1 = make_uint2(lp_f32x2_to_bf16x2(r[0], r[1]), lp_f32x2_to_bf16x2(r[2], r[3]));
+    r[0] -= __uint_as_float(t1.x << 16);
+    r[1] -= __uint_as_float(t1.x & 0xffff0000u);
+    r[2] -= __uint_as_float(t1.y << 16);
+    r[3] -= __uint_as_float(t1.y & 0xffff0000u);
+    t2 = make_uint2(lp_f32x2_to_bf16x2(r[0], r[1]), lp_f32x2_to_bf16x2(r[2], r[3]));
+}
+
 // T: storage type; NB: 32-column blocks per wavefront (tile width 64*NB); MW: wavefronts along M (tile height 64*MW,
 // 128*MW threads); KSB: bytes of every operand row consumed per K step (64 or 128).
-template <typename T, int NB, int MW, int KSB>
+// SPLIT (fp32 only, KSB = 64): the tile copy turns the sixteen fp32 values of a row into three planes of sixteen
+// bfloat16 terms (an LDS row is plane 0 | plane 1 | plane 2 | 16 bytes of padding = 112 bytes = 28 banks: sixteen
+// consecutive rows start in sixteen different groups of four banks), and a K step is six bf16 MFMAs per accumulator
+// block instead of eight fp32 ones.
+template <typename T, int NB, int MW, int KSB, bool SPLIT = false>
 __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
+    static_assert(!SPLIT || (sizeof(T) == 4 && KSB == 64), "the split product is defined for fp32 rows, sixteen values per step");
     constexpr int ES = (int)sizeof(T);
     constexpr int TH = 128 * MW;
     constexpr int BMt = 64 * MW;
     constexpr int BN = 64 * NB;
     constexpr int WN = 32 * NB;
-    constexpr int ROWB = KSB + 16;                   // bytes per LDS row
+    constexpr int ROWB = SPLIT ? 3 * (KSB / 2) + 16 : KSB + 16;   // bytes per LDS row
     constexpr int KQ = KSB / 16;                     // 16-byte vectors per tile row
     constexpr int A_LOADS = BMt * KQ / TH;
     constexpr int B_LOADS = BN * KQ / TH;
-    constexpr int STAGE = (BMt + BN) * ROWB;         // bytes per LDS stage
     constexpr int EPB = MW == 4 ? 256 : 128;         // bytes of an output row segment per store pass of a wavefront
     constexpr int EROW = EPB + 16;                   // its LDS pitch
     constexpr int EPC = EPB / ES;                    // columns per pass
     constexpr int CBP = EPC / 32;                    // 32-column accumulator blocks per pass
-    static_assert((TH / 64) * 32 * EROW <= STAGE, "the store staging of all wavefronts fits in one LDS stage");
+    constexpr int TILEB = (BMt + BN) * ROWB;         // bytes of the two operand tiles
+    constexpr int STAGEB = (TH / 64) * 32 * EROW;    // bytes of the store staging of all wavefronts
+    constexpr int STAGE = TILEB > STAGEB ? TILEB : STAGEB;   // bytes per LDS stage
     static_assert(CBP >= 1 && NB % CBP == 0, "a pass covers whole accumulator blocks");
     __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
     __shared__ __attribute__((aligned(16))) char bias_lds[(TH / 64) * WN * 4];  // per wavefront: bias of its columns
@@ -319,8 +350,12 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         }                                                                                                              \
     }
     // loads of the next K step in pipeline order (possibly the first step of the next output tile)
+#define LP_CURSOR()                                                                                                    \
+    if (seg_left == 0) LP_BEGIN_SEGMENT()
 #define LP_FETCH()                                                                                                     \
-    if (seg_left == 0) LP_BEGIN_SEGMENT()                                                                              \
+    LP_CURSOR()                                                                                                        \
+    LP_LOADS()
+#define LP_LOADS()                                                                                                     \
     _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p)                                                                \
         rbv[p] = *reinterpret_cast<const v4i *>(bbase + ((uint32_t)min(r0 + p * RP, rmaxB) * pitchB + c16));           \
     _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p)                                                                \
@@ -330,18 +365,43 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     --seg_left;
 #define LP_PUT_BIAS()                                                                                                  \
     if (lane < WN / 4) *reinterpret_cast<v4f *>(bias_w + 16 * lane) = rbias;
+#define LP_STASH_ONE(base_, idx_, v_)                                                                                  \
+    if constexpr (SPLIT) {                                                                                             \
+        uint2 t0_, t1_, t2_;                                                                                           \
+        lp_split3(v_, t0_, t1_, t2_);                                                                                  \
+        char *d_ = (base_) + ((idx_) / KQ) * ROWB + (((idx_) % KQ) << 3);                                              \
+        *reinterpret_cast<uint2 *>(d_) = t0_;                                                                          \
+        *reinterpret_cast<uint2 *>(d_ + KSB / 2) = t1_;                                                                \
+        *reinterpret_cast<uint2 *>(d_ + KSB) = t2_;                                                                    \
+    } else {                                                                                                           \
+        *reinterpret_cast<v4i *>((base_) + ((idx_) / KQ) * ROWB + (((idx_) % KQ) << 4)) = v_;                          \
+    }
 #define LP_STASH(stage)                                                                                                \
     {                                                                                                                  \
         char *As_ = lds + (stage) * STAGE;                                                                             \
         char *Bs_ = As_ + BMt * ROWB;                                                                                  \
-        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                              \
-            *reinterpret_cast<v4i *>(As_ + (idx / KQ) * ROWB + ((idx % KQ) << 4)) = ra[p];                             \
+        _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) { LP_STASH_ONE(As_, p * TH + tid, ra[p]) }                 \
+        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) { LP_STASH_ONE(Bs_, p * TH + tid, rbv[p]) }                \
+    }
+    // SPLIT: the three term planes of the K step: two row blocks of the A tile, NB column blocks of the weight tile
+#define LP_LOAD_PLANES(stage, a_, b_)                                                                                  \
+    {                                                                                                                  \
+        const char *As_ = lds + (stage) * STAGE;                                                                       \
+        const char *Bs_ = As_ + BMt * ROWB;                                                                            \
+        _Pragma("unroll") for (int t = 0; t < 3; ++t) {                                                                \
+            _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                           \
+                a_[t][rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + t * (KSB / 2) + 16 * h); \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                          \
+                b_[t][cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + t * (KSB / 2) + 16 * h); \
         }                                                                                                              \
-        _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) {                                                          \
-            const int idx = p * TH + tid;                                                                              \
-            *reinterpret_cast<v4i *>(Bs_ + (idx / KQ) * ROWB + ((idx % KQ) << 4)) = rbv[p];                            \
-        }                                                                                                              \
+    }
+    // one pair of term planes: weight term tb times row term ta, into every accumulator block
+#define LP_MFMA_TERM(a_, b_, ta, tb)                                                                                   \
+    {                                                                                                                  \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                          \
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, b_[tb][cb]),            \
+                                                                      __builtin_bit_cast(v8bf, a_[ta][rb]), acc[rb][cb], 0, 0, 0); \
     }
     // operands of one 32-byte group of the K step: two row blocks of the A tile, NB column blocks of the weight tile
 #define LP_LOAD_OPS(stage, kk, a_, b_)                                                                                 \
@@ -365,6 +425,27 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 
     // One K step: MFMAs on LDS stage `cur`, while the registers of step u+1 go to the other stage and the loads of
     // step u+2 are requested.
+    // SPLIT: smallest products first; the copy of the next tile and the loads of the one after it sit behind the
+    // first two term pairs
+#define LP_STEP_SPLIT(u_)                                                                                              \
+    {                                                                                                                  \
+        const int cur = (u_) & 1;                                                                                      \
+        LP_CURSOR()   /* the only branch of the step: everything below is one basic block */                          \
+        LP_LOAD_PLANES(cur, sa, sb)                                                                                    \
+        LP_MFMA_TERM(sa, sb, 2, 0)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 0, 2)                                                                                     \
+        LP_STASH(cur ^ 1)                                                                                              \
+        LP_LOADS()                                                                                                     \
+        LP_MFMA_TERM(sa, sb, 1, 1)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 1, 0)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 0, 1)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 0, 0)                                                                                     \
+        __syncthreads();                                                                                               \
+        if (++ct == n_tiles) {                                                                                         \
+            ct = 0;                                                                                                    \
+            store_tile(cur);                                                                                           \
+        }                                                                                                              \
+    }
 #define LP_STEP(u_)                                                                                                    \
     {                                                                                                                  \
         const int cur = (u_) & 1;                                                                                      \
@@ -466,15 +547,26 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         __syncthreads();
     };
 
-    v4i a0[2], b0[NB], a1[2], b1[NB];
     LP_FETCH()
     LP_PUT_BIAS()       // first tile
     LP_STASH(0)
     LP_FETCH()
     __syncthreads();
-    for (int u = 0; u < n_steps; ++u) LP_STEP(u)
+    if constexpr (SPLIT) {
+        v4i sa[3][2], sb[3][NB];
+        for (int u = 0; u < n_steps; ++u) LP_STEP_SPLIT(u)
+    } else {
+        v4i a0[2], b0[NB], a1[2], b1[NB];
+        for (int u = 0; u < n_steps; ++u) LP_STEP(u)
+    }
 #undef LP_STEP
+#undef LP_STEP_SPLIT
+#undef LP_STASH_ONE
+#undef LP_LOAD_PLANES
+#undef LP_MFMA_TERM
 #undef LP_FETCH
+#undef LP_CURSOR
+#undef LP_LOADS
 #undef LP_BEGIN_SEGMENT
 #undef LP_STASH
 #undef LP_PUT_BIAS
@@ -1036,6 +1128,172 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
     }
 }
 
+// The same for fp32 storage with every product formed from bfloat16 terms (see lp_split3): sixteen nodes per step, an
+// LDS row (one column of an operand tile) holds the three term planes of its sixteen nodes (112 bytes with padding, the
+// layout of the SPLIT NT kernel), and a step is six bf16 MFMAs per accumulator block.  Wavefronts 0-3 load the
+// [At0 | At1] tile, wavefronts 4-7 the B tile: a loader thread fetches a 4 x 4 block (four nodes, sixteen bytes of
+// each), and for each of its four columns splits the four nodes' values and writes 8 bytes to each plane.  The B
+// loaders of every tile add up their blocks for the column sums (kept by the first tile row only).
+constexpr int WS_BK = 16;
+constexpr int WS_ROWB = 3 * (WS_BK * 2) + 16;
+
+template <bool INDEXED>
+__global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2))) void weight_grads_split_kernel(WeightGradArgs g, int chunk,
+                                                                                                               int splits, int tiles_n, int tiles) {
+    constexpr int STAGE = 512 * WS_ROWB;  // 256 columns of each operand
+    __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int L = blockIdx.x;
+    const int s = (L & 7) + 8 * ((L >> 3) / tiles);
+    const int t = (L >> 3) % tiles;
+    if (s >= splits) return;
+    const int m0 = (t / tiles_n) * 256, n0 = (t % tiles_n) * 256;
+    const int Mtot = g.Mw[0] + g.Mw[1];
+    int64_t Kn_ = g.Kn;
+    if (g.kn_dev) {
+        Kn_ = min((int64_t)*g.kn_dev, (int64_t)g.Kn);
+        chunk = (int)(((Kn_ + splits - 1) / splits + WS_BK - 1) / WS_BK * WS_BK);
+    }
+    const int64_t kbeg = (int64_t)s * chunk;
+    const int64_t kend = kbeg + chunk < Kn_ ? kbeg + chunk : Kn_;
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
+    const bool do_bias = g.dbias != nullptr && m0 == 0;
+    const bool is_b = tid >= 256;                 // wavefront-uniform: which operand this thread loads
+    const int ng = tid & 3, cg = (tid & 255) >> 2;   // loader task: nodes 4 ng .. + 3, tile columns 4 cg .. + 3
+    v4f bsum = {0.f, 0.f, 0.f, 0.f};
+
+    if (kbeg < kend) {
+        const int c = 4 * cg;
+        const int ma = m0 + c, nb = n0 + c;
+        // a thread whose columns lie outside its operand still loads (column 0 of At[1] / B) and drops the values
+        const bool ok = is_b ? nb < g.Nw : ma < Mtot;
+        const float *base;
+        int64_t pitch;
+        if (is_b) {
+            base = static_cast<const float *>(g.B) + (ok ? nb : 0);
+            pitch = g.ldb;
+        } else if (ma < g.Mw[0]) {
+            base = static_cast<const float *>(g.At[0]) + ma;
+            pitch = g.lda[0];
+        } else {
+            base = static_cast<const float *>(g.At[1]) + (ok ? ma - g.Mw[0] : 0);
+            pitch = g.lda[1];
+        }
+        const int64_t klast = Kn_ - 1;
+        v4f rv[4];
+        int64_t row[4];
+        auto lookup = [&](int64_t k0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t k = min(k0 + 4 * ng + i, klast);
+                const int64_t listed = INDEXED ? (int64_t)g.at_index[k] : k;   // loaded by the B loaders too: no branch
+                row[i] = is_b ? k : listed;
+            }
+        };
+        auto fetch = [&](int64_t k0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool live = ok && k0 + 4 * ng + i < kend;
+                const v4f v = *reinterpret_cast<const v4f *>(base + row[i] * pitch);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rv[i][e] = live ? v[e] : 0.f;
+            }
+        };
+        auto stash = [&](int stage) {
+            char *dst = lds + stage * STAGE + (is_b ? 256 * WS_ROWB : 0) + c * WS_ROWB + 8 * ng;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {   // column j of the block: its four nodes
+                uint2 t0, t1, t2;
+                lp_split3(__builtin_bit_cast(v4i, v4f{rv[0][j], rv[1][j], rv[2][j], rv[3][j]}), t0, t1, t2);
+                *reinterpret_cast<uint2 *>(dst + j * WS_ROWB) = t0;
+                *reinterpret_cast<uint2 *>(dst + j * WS_ROWB + 2 * WS_BK) = t1;
+                *reinterpret_cast<uint2 *>(dst + j * WS_ROWB + 4 * WS_BK) = t2;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bsum += rv[i];
+        };
+        v4i sa[3][2], sb[3][4];
+        auto planes = [&](int stage) {
+            const char *As = lds + stage * STAGE, *Bs = As + 256 * WS_ROWB;
+#pragma unroll
+            for (int tt = 0; tt < 3; ++tt) {
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+                    sa[tt][rb] = *reinterpret_cast<const v4i *>(As + (wm * 64 + rb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+                    sb[tt][cb] = *reinterpret_cast<const v4i *>(Bs + (wn * 128 + cb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
+            }
+        };
+        auto term = [&](int ta, int tb) {
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, sa[ta][rb]), __builtin_bit_cast(v8bf, sb[tb][cb]),
+                                                                          acc[rb][cb], 0, 0, 0);
+        };
+
+        lookup(kbeg);
+        fetch(kbeg);
+        lookup(kbeg + WS_BK);
+        stash(0);
+        fetch(kbeg + WS_BK);
+        lookup(kbeg + 2 * WS_BK);
+        __syncthreads();
+        int cur = 0;
+        for (int64_t k0 = kbeg; k0 < kend; k0 += WS_BK, cur ^= 1) {
+            planes(cur);
+            term(2, 0);                     // smallest products first
+            term(0, 2);
+            stash(cur ^ 1);                 // registers hold step k0 + 16 (zeros past the end)
+            fetch(k0 + 2 * WS_BK);
+            lookup(k0 + 3 * WS_BK);
+            term(1, 1);
+            term(1, 0);
+            term(0, 1);
+            term(0, 0);
+            __syncthreads();
+        }
+    }
+
+    const int64_t ptot = (int64_t)Mtot * g.Nw + g.Nw;
+    float *__restrict__ P = g.partials + (int64_t)s * ptot;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const int n = n0 + wn * 128 + cb * 32 + i32;
+        if (n >= g.Nw) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * 64 + rb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < Mtot) P[(int64_t)m * g.Nw + n] = acc[rb][cb][r];
+            }
+    }
+    if (do_bias) {  // the four node groups of a column meet in LDS and are added in a fixed order
+        float *red = reinterpret_cast<float *>(lds);
+        __syncthreads();
+        if (is_b) *reinterpret_cast<v4f *>(red + ng * 256 + 4 * cg) = bsum;
+        __syncthreads();
+        if (tid < 256 && n0 + tid < g.Nw) {
+            float sum = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sum += red[q * 256 + tid];
+            P[(int64_t)Mtot * g.Nw + n0 + tid] = sum;
+        }
+    }
+}
+
 // The same for bfloat16 storage.  The MFMA (v_mfma_f32_32x32x16_bf16) takes eight consecutive nodes per lane while
 // memory is node-major, so a loader thread fetches an 8 x 8 block (eight nodes, sixteen bytes of each), transposes it
 // in registers and writes eight 16-byte pieces to an LDS tile laid out [column][node] (pitch 64 + 8 nodes).  256 x 256
@@ -1313,6 +1571,18 @@ int lp_compute_units() {
     return cus;
 }
 
+// How fp32 matrices are multiplied: LP_FP32_PRODUCTS_BF16X6 (three-term bfloat16 splitting on the bf16 matrix cores)
+// or LP_FP32_PRODUCTS_NATIVE (fp32 MFMA).  Process-wide; read at every launch.
+static std::atomic<int> g_fp32_products{LP_FP32_PRODUCTS_BF16X6};
+
+extern "C" int lp_set_fp32_products(int mode) {
+    if (mode != LP_FP32_PRODUCTS_NATIVE && mode != LP_FP32_PRODUCTS_BF16X6) return LP_ERR_INVALID_ARG;
+    g_fp32_products.store(mode);
+    return LP_OK;
+}
+
+extern "C" int lp_get_fp32_products(void) { return g_fp32_products.load(); }
+
 int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return LP_OK;
     for (int s = 0; s < 2; ++s) {
@@ -1361,7 +1631,24 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 4, 128>), pgrid, dim3(512), 0, st, a);           \
         else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 2, 64>), pgrid, dim3(256), 0, st, a); \
         else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64>), pgrid, dim3(256), 0, st, a);
-        if (bf16) { LP_NT_FAST(lp_bf16_t) } else { LP_NT_FAST(float) }
+        if (bf16) {
+            LP_NT_FAST(lp_bf16_t)
+        } else if (g_fp32_products.load() == LP_FP32_PRODUCTS_BF16X6) {
+            // sixteen values of a row per K step; 256-row tiles once they fill every compute unit
+            if (fast_bn == 256 && lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units()) {
+                const int64_t rt = lp_ceil_div(a.M, 256);
+                const dim3 sgrid((unsigned)(rt < lp_compute_units() ? rt : lp_compute_units()));
+                hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 4, 64, true>), sgrid, dim3(512), 0, st, a);
+            } else {
+                const int64_t rt = lp_ceil_div(a.M, 128);
+                const int64_t sl = (fast_bn == 256 ? 1 : 2) * (int64_t)lp_compute_units();   // resident workgroups (LDS)
+                const dim3 sgrid((unsigned)(rt < sl ? rt : sl));
+                if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 2, 64, true>), sgrid, dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 2, 2, 64, true>), sgrid, dim3(256), 0, st, a);
+            }
+        } else {
+            LP_NT_FAST(float)
+        }
 #undef LP_NT_FAST
     } else if (bf16) {
         const int bn = a.N > 128 ? 256 : (a.N > 64 ? 128 : 64);
@@ -1463,6 +1750,9 @@ int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t st) {
         if (bf16) {
             if (a.at_index) hipLaunchKernelGGL(weight_grads_bf16_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
             else hipLaunchKernelGGL(weight_grads_bf16_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+        } else if (g_fp32_products.load() == LP_FP32_PRODUCTS_BF16X6) {
+            if (a.at_index) hipLaunchKernelGGL(weight_grads_split_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
+            else hipLaunchKernelGGL(weight_grads_split_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
         } else {
             if (a.at_index) hipLaunchKernelGGL(weight_grads_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
             else hipLaunchKernelGGL(weight_grads_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "lp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lp_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(lp_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_function():
@@ -331,3 +331,15 @@ def test_hits_at_k_rejects_bad_arguments_on_the_host():
     assert call(wsb=64) == -3
     assert lib.lp_hits_at_k_workspace_bytes(1000) > 16000
     assert lib.lp_hits_at_k_workspace_bytes(-1) == 0
+
+
+def test_fp32_product_mode_is_checked_and_remembered():
+    lib = B.load_library()
+    assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_BF16X6       # the default
+    assert lib.lp_set_fp32_products(7) == -1 and lib.lp_set_fp32_products(-1) == -1
+    assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_BF16X6
+    try:
+        assert lib.lp_set_fp32_products(B.LP_FP32_PRODUCTS_NATIVE) == 0
+        assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_NATIVE
+    finally:
+        assert lib.lp_set_fp32_products(B.LP_FP32_PRODUCTS_BF16X6) == 0

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 import paper_2506_20818_amd as lp
 from lp_workloads import make_workload
 from oracle import lp_oracle as O
-from gpu_util import DEV, HipStep, assert_close, dev_f32, dev_i32, host, make_model
+from gpu_util import DEV, HipStep, assert_close, dev_f32, dev_i32, host, make_model, rel_err
 
 TOL_ACT = 1e-4
 TOL_GRAD = 1e-3
@@ -253,7 +253,8 @@ def check_grads(grads, ref, K, lo=None, hi=None):
 
 
 @pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8],
-                                  [192, 200, 232]])   # the last: fused weight-gradient tiles that are partly empty
+                                  [192, 200, 232],    # fused weight-gradient tiles that are partly empty
+                                  [64, 512, 128], [48, 80, 144]])   # 128-column tiles; K parts of 48 and 80 values
 @pytest.mark.parametrize("sym", [True, False])
 def test_backward_parity(dims, sym):
     rng = np.random.default_rng(1000 + sum(dims) + sym)
@@ -281,6 +282,17 @@ def test_backward_parity(dims, sym):
     # without dX the weight gradients are the same
     grads2 = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
     check_grads(grads2, g_ref, len(dims) - 1, lo, hi)
+
+
+@pytest.mark.parametrize("dims", [[128, 256, 256, 256], [192, 200, 232], [64, 512, 128], [48, 80, 144]])
+def test_backward_parity_with_fp32_matrix_instructions(dims):
+    """The same bar with LP_FP32_PRODUCTS_NATIVE (the other tests run the default, products from bfloat16 terms)."""
+    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE)
+    try:
+        assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_NATIVE
+        test_backward_parity(dims, True)
+    finally:
+        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
 
 
 @pytest.mark.parametrize("dims", [[16, 32, 8], [128, 256, 64], [64, 520, 8]])
@@ -344,25 +356,39 @@ def whole_step(name):
     run_whole_step(make_workload(name))
 
 
-def run_whole_step(wl):
+BOTH_PRODUCT_MODES = (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE)
+
+
+def run_whole_step(wl, modes=(lp.LP_FP32_PRODUCTS_BF16X6,)):
+    """One step against the oracle, once per way of forming the fp32 products; returns, per mode, the 2-norm relative
+    errors of the embeddings and of the first layer's weight gradient (the two ends of the chain of products)."""
     say("whole step %s N=%d nnz~%d B=%d" % (wl.name, wl.n_nodes, 2 * wl.src.size, wl.batch_edges))
     ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
     exp = O.train_step(ref, wl.W_self, wl.W_neigh, wl.bias, wl.X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space,
                        wl.sampler_seed, wl.sampler_step)
     g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
     check_csr(g, ref)
-    got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
-                  wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
-    assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
     K = len(wl.dims) - 1
-    for k in range(1, K + 1):
-        assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
-        assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
-    assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
-    assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
-    assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
     lo, hi = gate_slack(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore)
-    check_grads(got.grads, exp.grads, K, lo, hi)
+    errs = {}
+    try:
+        for mode in modes:
+            say("  fp32 products mode %d" % mode)
+            lp.lp_set_fp32_products(mode)
+            got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
+                          wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+            assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+            for k in range(1, K + 1):
+                assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
+                assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+            assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
+            assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+            assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
+            check_grads(got.grads, exp.grads, K, lo, hi)
+            errs[mode] = (rel_err(host(got.acts.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
+    finally:
+        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
+    return errs
 
 
 def test_whole_step_C1():
@@ -370,4 +396,9 @@ def test_whole_step_C1():
 
 
 def test_whole_step_C2_full_size():
-    whole_step("C2")
+    """Both ways of forming the fp32 products meet the bar at full size, and the products taken from bfloat16 terms
+    are as close to the fp64 oracle as those of the fp32 matrix instructions (embeddings; the weight gradients go
+    through ReLU gates whose flips dominate either error)."""
+    errs = run_whole_step(make_workload("C2"), BOTH_PRODUCT_MODES)
+    say("  2-norm relative errors (H^K, dW_neigh^1): split %s native %s" % (errs[lp.LP_FP32_PRODUCTS_BF16X6], errs[lp.LP_FP32_PRODUCTS_NATIVE]))
+    assert errs[lp.LP_FP32_PRODUCTS_BF16X6][0] <= 1.5 * errs[lp.LP_FP32_PRODUCTS_NATIVE][0] + 1e-7
