@@ -439,9 +439,11 @@ int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, co
  *     of the nine term products on the bf16 matrix cores, accumulated in fp32.
  *     What is left out is below 2^-26 of each product, a quarter of one fp32
  *     rounding; measured against fp64 the results are as close as those of the
- *     fp32 matrix instructions, at 6/16 of their issue time.  Non-finite inputs,
- *     and magnitudes above the largest bfloat16 (3.39e38), give NaN where the
- *     fp32 instructions would give an infinity or a finite value.
+ *     fp32 matrix instructions, at 6/16 of their issue time.  Range: non-finite
+ *     inputs, and magnitudes above the largest bfloat16 (3.39e38), give NaN where
+ *     the fp32 instructions would give an infinity or a finite value; term
+ *     products below the smallest normal fp32 (1.2e-38) are flushed to zero, so
+ *     products smaller than about 1e-33 lose the accuracy of their small terms.
  *   LP_FP32_PRODUCTS_NATIVE: fp32 matrix instructions.
  * Process-wide, read at every launch; returns LP_ERR_INVALID_ARG for another
  * value.  bf16 models are not affected.

@@ -164,6 +164,42 @@ def test_forward_parity_widths_hub_and_empty_rows(dims, sym):
     assert iso.size >= 50 and np.all(host(acts.A[0])[iso] == 0)
 
 
+@pytest.mark.parametrize("x_scale,w_scale", [(1e-10, 1.0), (1e15, 1e-3), (1.0, 1e12), (1e-6, 1e-6)])
+def test_products_from_bfloat16_terms_across_magnitudes(x_scale, w_scale):
+    """The three-term splitting is relative: features and weights far from 1 (products from about 1e-28 up to 1e27)
+    meet the same relative bar, forward and backward, with values whose exponents differ inside one row.  (Term
+    products below the smallest normal fp32, 1.2e-38, are flushed by the matrix instructions, so full accuracy
+    needs products above about 1e-33: the documented limit of this mode.)"""
+    rng = np.random.default_rng(77)
+    dims = [64, 256, 128]
+    n = 900
+    r, c = random_pairs(rng, n, 4000)
+    say("split products x_scale=%g w_scale=%g" % (x_scale, w_scale))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims)
+    Ws[0], Wn[0] = (Ws[0] * w_scale).astype(np.float32), (Wn[0] * w_scale).astype(np.float32)
+    b = [(bb * x_scale * w_scale).astype(np.float32) for bb in b]
+    spread = np.exp2(rng.integers(-12, 13, (n, dims[0]))).astype(np.float32)       # exponents differ inside a row
+    X = (rng.standard_normal((n, dims[0])) * spread * x_scale).astype(np.float32)
+    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+    assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
+    acts = lp.lp_sage_forward(g, model, Xd)
+    exp = O.sage_forward(ref, Ws, Wn, b, X)
+    for k in range(1, len(dims)):
+        assert_close(host(acts.H[k - 1]), exp.H[k], TOL_ACT, "H^%d" % k)
+    # backward from a given dL/ds (the loss itself would saturate at these magnitudes)
+    B = 1200
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    ds = (rng.standard_normal(B) / B).astype(np.float32)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), dev_f32(ds), want_dX=True)
+    g_ref = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64))
+    margin = GATE_MARGIN * x_scale * w_scale          # the near-tie band scales with the pre-activations
+    lo = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), relu_margin=margin)
+    hi = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), relu_margin=-margin)
+    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
+
+
 def test_forward_without_row_order_and_single_node():
     say("forward natural row order / one-node graph")
     rng = np.random.default_rng(5)
