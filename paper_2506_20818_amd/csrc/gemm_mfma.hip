@@ -383,15 +383,17 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         _Pragma("unroll") for (int p = 0; p < A_LOADS; ++p) { LP_STASH_ONE(As_, p * TH + tid, ra[p]) }                 \
         _Pragma("unroll") for (int p = 0; p < B_LOADS; ++p) { LP_STASH_ONE(Bs_, p * TH + tid, rbv[p]) }                \
     }
-    // SPLIT: term plane t of the K step in a stage: two row blocks of the A tile, NB column blocks of the weight tile
-#define LP_LOAD_PLANE(stage, a_, b_, t)                                                                                \
+    // SPLIT: the three term planes of the K step: two row blocks of the A tile, NB column blocks of the weight tile
+#define LP_LOAD_PLANES(stage, a_, b_)                                                                                  \
     {                                                                                                                  \
         const char *As_ = lds + (stage) * STAGE;                                                                       \
         const char *Bs_ = As_ + BMt * ROWB;                                                                            \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                               \
-            a_[t][rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + (t) * (KSB / 2) + 16 * h); \
-        _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                              \
-            b_[t][cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + (t) * (KSB / 2) + 16 * h); \
+        _Pragma("unroll") for (int t = 0; t < 3; ++t) {                                                                \
+            _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                           \
+                a_[t][rb] = *reinterpret_cast<const v4i *>(As_ + (wm * 64 + rb * 32 + i32) * ROWB + t * (KSB / 2) + 16 * h); \
+            _Pragma("unroll") for (int cb = 0; cb < NB; ++cb)                                                          \
+                b_[t][cb] = *reinterpret_cast<const v4i *>(Bs_ + (wn * WN + cb * 32 + i32) * ROWB + t * (KSB / 2) + 16 * h); \
+        }                                                                                                              \
     }
     // one pair of term planes: weight term tb times row term ta, into every accumulator block
 #define LP_MFMA_TERM(a_, b_, ta, tb)                                                                                   \
@@ -423,34 +425,22 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 
     // One K step: MFMAs on LDS stage `cur`, while the registers of step u+1 go to the other stage and the loads of
     // step u+2 are requested.
-    // SPLIT: the step's barrier sits in the middle.  Plane 1 of both operands (the middle terms) was read from this
-    // stage behind the barrier of the step before; planes 0 and 2 are read now, under the first term pair.  The
-    // three pairs that involve plane 1 come first, then the copy of the next tile into the other stage and the loads
-    // of the tile after it, then the barrier (every wavefront has read all of this stage and written its share of
-    // the other one), then plane 1 of the NEXT step into the registers that just became free, under the three
-    // remaining pairs: no wavefront waits for LDS with an idle matrix pipe.
+    // SPLIT: smallest products first; the copy of the next tile and the loads of the one after it sit behind the
+    // first two term pairs
 #define LP_STEP_SPLIT(u_)                                                                                              \
     {                                                                                                                  \
         const int cur = (u_) & 1;                                                                                      \
         LP_CURSOR()   /* the only branch of the step: everything below is one basic block */                          \
-        LP_LOAD_PLANE(cur, sa, sb, 0)                                                                                  \
-        LP_LOAD_PLANE(cur, sa, sb, 2)                                                                                  \
-        LP_ORDER();                                                                                                    \
-        LP_MFMA_TERM(sa, sb, 1, 1)                                                                                     \
-        LP_ORDER();                                                                                                    \
-        LP_MFMA_TERM(sa, sb, 1, 0)                                                                                     \
-        LP_MFMA_TERM(sa, sb, 0, 1)                                                                                     \
-        LP_STASH(cur ^ 1)                                                                                              \
-        LP_LOADS()                                                                                                     \
-        LP_ORDER();                                                                                                    \
-        __syncthreads();                                                                                               \
-        LP_ORDER();                                                                                                    \
-        LP_LOAD_PLANE(cur ^ 1, sa, sb, 1)                                                                              \
-        LP_ORDER();                                                                                                    \
+        LP_LOAD_PLANES(cur, sa, sb)                                                                                    \
         LP_MFMA_TERM(sa, sb, 2, 0)                                                                                     \
         LP_MFMA_TERM(sa, sb, 0, 2)                                                                                     \
+        LP_STASH(cur ^ 1)                                                                                              \
+        LP_LOADS()                                                                                                     \
+        LP_MFMA_TERM(sa, sb, 1, 1)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 1, 0)                                                                                     \
+        LP_MFMA_TERM(sa, sb, 0, 1)                                                                                     \
         LP_MFMA_TERM(sa, sb, 0, 0)                                                                                     \
-        LP_ORDER();                                                                                                    \
+        __syncthreads();                                                                                               \
         if (++ct == n_tiles) {                                                                                         \
             ct = 0;                                                                                                    \
             store_tile(cur);                                                                                           \
@@ -564,7 +554,6 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     __syncthreads();
     if constexpr (SPLIT) {
         v4i sa[3][2], sb[3][NB];
-        LP_LOAD_PLANE(0, sa, sb, 1)
         for (int u = 0; u < n_steps; ++u) LP_STEP_SPLIT(u)
     } else {
         v4i a0[2], b0[NB], a1[2], b1[NB];
@@ -573,7 +562,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #undef LP_STEP
 #undef LP_STEP_SPLIT
 #undef LP_STASH_ONE
-#undef LP_LOAD_PLANE
+#undef LP_LOAD_PLANES
 #undef LP_MFMA_TERM
 #undef LP_FETCH
 #undef LP_CURSOR
