@@ -218,6 +218,11 @@ template <> struct LpVec<float> {
     static __device__ __forceinline__ void store(float *p, const float (&v)[4]) {
         *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
     }
+    // streaming store: the line is not kept in the caches for this kernel's own later reads
+    static __device__ __forceinline__ void store_streaming(float *p, const float (&v)[4]) {
+        typedef float lp_v4f __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(lp_v4f{v[0], v[1], v[2], v[3]}, reinterpret_cast<lp_v4f *>(p));
+    }
 };
 template <> struct LpVec<lp_bf16_t> {
     static constexpr int N = 8;
@@ -235,6 +240,13 @@ template <> struct LpVec<lp_bf16_t> {
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = lp_f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
         *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    static __device__ __forceinline__ void store_streaming(lp_bf16_t *p, const float (&v)[8]) {
+        typedef uint32_t lp_v4u __attribute__((ext_vector_type(4)));
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = lp_f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
+        __builtin_nontemporal_store(lp_v4u{w[0], w[1], w[2], w[3]}, reinterpret_cast<lp_v4u *>(p));
     }
 };
 #endif

@@ -136,7 +136,7 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
 #pragma unroll
         for (int e = 0; e < VE; ++e) y[e] = gt[e] > 0.f ? y[e] : 0.f;
     }
-    LpVec<T>::store(static_cast<T *>(a.out) + o, y);
+    LpVec<T>::store_streaming(static_cast<T *>(a.out) + o, y);   // written once, read by a later kernel: leave the caches to the gathered rows
 }
 
 template <typename T, int G, int C, int W>
