@@ -351,7 +351,7 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
     }
     // loads of the next K step in pipeline order (possibly the first step of the next output tile)
 #define LP_CURSOR()                                                                                                    \
-    if (seg_left == 0) LP_BEGIN_SEGMENT()
+    if (seg_left == 0) { LP_BEGIN_SEGMENT() }
 #define LP_FETCH()                                                                                                     \
     LP_CURSOR()                                                                                                        \
     LP_LOADS()
