@@ -208,6 +208,29 @@ def sampled_step_task(args):
     lp.lp_timing_enable(False)
     ms = dt * 1e3 / max(args.steps, 1)
 
+    # The same step recorded once as a HIP graph and replayed (every replay repeats the recorded batch id and Adam
+    # step count, so this is a timing of the launch overhead, not a training loop): informational.
+    graph_ms = None
+    try:
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            step(1500)
+        torch.cuda.current_stream().wait_stream(cap)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            step(1500)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+    except RuntimeError as exc:
+        sys.stderr.write("graph replay not measured: %s\n" % exc)
+
     # The same steps with the next batch's negatives and computational graph built on a second stream while the
     # current batch trains (they depend on the graph and the batch only, not on the weights): what a training loop
     # with a prefetching sampler sees.  Two sets of batch buffers; events order producer and consumer.
@@ -255,7 +278,8 @@ def sampled_step_task(args):
     entries = [int(blocks.ptr[k][frontiers[k + 1]].item()) for k in range(len(fanout))]
     out = {"metric": "sampled-neighbourhood train-step edges/sec (pos+neg), Adam update included, on 1 MI355X",
            "value": round(Bn / (ms * 1e-3), 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "ms_per_step": round(ms, 4), "ms_per_step_graph_replay": round(graph_ms, 4) if graph_ms is not None else None,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if bf16 else "f32", "fp32_products": fp32_products_name(bf16, split), "data": "synthetic",
            "config": {"workload": "%s graph (%d nodes, %d directed entries), GraphSAGE-mean %s, %d positives + %d negatives per "
                                   "step, fan-outs %s (first hop first)" % (args.workload, wl.n_nodes, g.nnz, "->".join(map(str, wl.dims)),

@@ -84,3 +84,74 @@ def test_captured_step_replays_bit_exactly(name):
         torch.cuda.synchronize()
         for i, (got, exp) in enumerate(zip(cap.tensors(K), expected)):
             assert torch.equal(got, exp), "replay %d: output %d differs from the eager step" % (replay, i)
+
+
+def run_sampled_step(g, model, X, pos_src, pos_dst, k_neg, n_space, seed, step, fanout, buf):
+    n_pos = int(pos_src.numel())
+    buf["e_src"][:n_pos].copy_(pos_src)
+    buf["e_dst"][:n_pos].copy_(pos_dst)
+    lp.lp_sample_neg(g, pos_src, k_neg, n_space, seed, step, neg_dst=buf["e_dst"][n_pos:], neg_src=buf["e_src"][n_pos:])
+    lp.lp_sample_blocks(g, buf["e_src"], buf["e_dst"], fanout, seed + 1, step, buf["blocks"])
+    lp.lp_sage_forward_blocks(buf["blocks"], model, X, buf["acts"], buf["ws_f"])
+    lp.lp_score_loss(buf["acts"].H[-1], buf["blocks"].e_src_pos, buf["blocks"].e_dst_pos, n_pos, buf["scores"], buf["loss"],
+                     buf["dscore"], buf["ws_l"])
+    lp.lp_backward_blocks(buf["blocks"], model, buf["acts"], buf["dscore"], buf["grads"], buf["ws_b"])
+
+
+def sampled_buffers(g, model, Bn, fanout, dims):
+    u8 = lambda n: torch.empty(max(int(n), 16), dtype=torch.uint8, device=DEV)
+    blocks = lp.Blocks(g, Bn, fanout)
+    return {"e_src": torch.zeros(Bn, dtype=torch.int32, device=DEV), "e_dst": torch.zeros(Bn, dtype=torch.int32, device=DEV),
+            "blocks": blocks, "acts": lp.BlockActs(blocks, dims, DEV, model.torch_dtype),
+            "grads": lp.Grads(1, dims, DEV, dtype=model.torch_dtype),
+            "scores": torch.zeros(Bn, dtype=torch.float32, device=DEV), "dscore": torch.zeros(Bn, dtype=torch.float32, device=DEV),
+            "loss": torch.zeros(1, dtype=torch.float32, device=DEV),
+            "ws_f": u8(B.forward_blocks_workspace_bytes(model, blocks)), "ws_b": u8(B.backward_blocks_workspace_bytes(model, blocks)),
+            "ws_l": u8(1 << 16)}
+
+
+def sampled_outputs(buf, K):
+    out = [buf["e_dst"], buf["blocks"].n, buf["blocks"].nodes, buf["scores"], buf["loss"], buf["dscore"]]
+    out += [buf["grads"].dW_self[k] for k in range(K)] + [buf["grads"].dW_neigh[k] for k in range(K)] + [buf["grads"].dbias[k] for k in range(K)]
+    return out
+
+
+def test_captured_sampled_step_replays_bit_exactly():
+    """The mini-batch mode (negatives, sampled blocks with device-side frontier sizes, forward, loss, backward) recorded
+    as one HIP graph: grids are sized by host-side bounds and every count stays on the device, so the recording does not
+    depend on the batch; three replays with eager work of other batches in between equal the eager step bit for bit."""
+    wl = make_workload("C2")
+    say("graph capture of the sampled-neighbourhood step, C2 graph")
+    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    model = make_model(wl.W_self, wl.W_neigh, wl.bias)
+    X = dev_f32(wl.X)
+    n_pos, fanout = 4096, [25, 10, 5]
+    pos_src, pos_dst = dev_i32(wl.pos_src[:n_pos]), dev_i32(wl.pos_dst[:n_pos])
+    Bn, K = n_pos * (1 + wl.k_neg), len(wl.dims) - 1
+    eager, other, cap = (sampled_buffers(g, model, Bn, fanout, wl.dims) for _ in range(3))
+    args = (g, model, X, pos_src, pos_dst, wl.k_neg, wl.n_space, wl.sampler_seed)
+    run_sampled_step(*args, 7, fanout, eager)
+    torch.cuda.synchronize()
+    n_front = int(eager["blocks"].n[0].item())
+    expected = [t.clone() for t in sampled_outputs(eager, K)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_sampled_step(*args, 7, fanout, cap)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_sampled_step(*args, 7, fanout, cap)
+    for replay in range(3):
+        for t in sampled_outputs(cap, K):
+            t.zero_()
+        run_sampled_step(*args, 200 + replay, fanout, other)      # eager work of another batch in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, exp) in enumerate(zip(sampled_outputs(cap, K), expected)):
+            if i == 2:      # frontier node list: entries past the realised frontier size are unspecified
+                got, exp = got[:n_front], exp[:n_front]
+            assert torch.equal(got, exp), "replay %d: output %d differs from the eager step" % (replay, i)
