@@ -1,7 +1,7 @@
 // lp_build_csr: canonical CSR (+ transpose, inverse degrees, degree-ordered row lists) of a pair list.
 //
 // Pipeline, all on the device:
-//   pack (row, col) into one 64-bit key  ->  least-significant-digit radix sort, 8 bits per pass, only over
+//   pack (row, col) into one 64-bit key  ->  least-significant-digit radix sort, 8 or 9 bits per pass, only over
 //   the bits a node id can occupy  ->  flag first occurrences, prefix-sum, compact (repeated pairs collapse)
 //   ->  row pointers by binary search of each row's first key  ->  the same on swapped keys for the transpose.
 // The graph definition this realises: Sec. II-A (edge set over node pairs) and Sec. IV-A (neighbour sets,
@@ -14,31 +14,40 @@ namespace {
 using namespace lp_scan;
 constexpr int kWaveChunk = 64 * kItems;   // keys per wavefront
 
-// ------------------------------------------------------------------ radix sort of 64-bit keys, one 8-bit digit per pass
+// ------------------------------------------------------------------ radix sort of 64-bit keys, one digit of 8 or 9 bits per pass
+// (nine when that saves a pass: node ids below 2^18 sort in two passes instead of three)
+template <int BITS>
 __global__ __launch_bounds__(kThreads) void rs_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, int shift,
                                                            uint32_t *__restrict__ hist, int64_t nb) {
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
+    constexpr int BINS = 1 << BITS;
+    __shared__ uint32_t h[BINS];
+#pragma unroll
+    for (int j = threadIdx.x; j < BINS; j += kThreads) h[j] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * kTile;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         int64_t idx = base + i * kThreads + threadIdx.x;
-        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & 255u], 1u);
+        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & (uint32_t)(BINS - 1)], 1u);
     }
     __syncthreads();
-    hist[(int64_t)threadIdx.x * nb + blockIdx.x] = h[threadIdx.x];  // digit-major, so one scan orders everything
+#pragma unroll
+    for (int j = threadIdx.x; j < BINS; j += kThreads) hist[(int64_t)j * nb + blockIdx.x] = h[j];  // digit-major, so one scan orders everything
 }
 
 // Stable scatter.  Keys of a block are taken in index order: wavefront w owns keys [w*512, w*512+512) of the
-// tile and walks them 64 at a time; inside such a group the rank among equal digits comes from eight ballots.
+// tile and walks them 64 at a time; inside such a group the rank among equal digits comes from one ballot per bit.
+template <int BITS>
 __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
                                                               int64_t n, int shift, const uint32_t *__restrict__ gbase,
                                                               int64_t nb) {
-    __shared__ uint32_t cnt[4][256];
+    constexpr int BINS = 1 << BITS;
+    __shared__ uint32_t cnt[4][BINS];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) cnt[i][tid] = 0;
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = tid; j < BINS; j += kThreads) cnt[i][j] = 0;
     __syncthreads();
     const int64_t wbase = (int64_t)blockIdx.x * kTile + (int64_t)w * kWaveChunk;
     uint64_t k[kItems];
@@ -48,15 +57,16 @@ __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__
         int64_t idx = wbase + r * 64 + lane;
         valid[r] = idx < n;
         k[r] = valid[r] ? in[idx] : 0ull;
-        if (valid[r]) atomicAdd(&cnt[w][(k[r] >> shift) & 255u], 1u);
+        if (valid[r]) atomicAdd(&cnt[w][(k[r] >> shift) & (uint32_t)(BINS - 1)], 1u);
     }
     __syncthreads();
-    {
-        uint32_t run = gbase[(int64_t)tid * nb + blockIdx.x];
+#pragma unroll
+    for (int j = tid; j < BINS; j += kThreads) {
+        uint32_t run = gbase[(int64_t)j * nb + blockIdx.x];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            uint32_t c = cnt[i][tid];
-            cnt[i][tid] = run;
+            uint32_t c = cnt[i][j];
+            cnt[i][j] = run;
             run += c;
         }
     }
@@ -64,10 +74,10 @@ __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__
     volatile uint32_t *my = cnt[w];
 #pragma unroll
     for (int r = 0; r < kItems; ++r) {
-        const uint32_t d = (uint32_t)(k[r] >> shift) & 255u;
+        const uint32_t d = (uint32_t)(k[r] >> shift) & (uint32_t)(BINS - 1);
         unsigned long long peers = __ballot(valid[r]);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
+        for (int b = 0; b < BITS; ++b) {
             const bool bit = (d >> b) & 1u;
             unsigned long long bb = __ballot(valid[r] && bit);
             peers &= bit ? bb : ~bb;
@@ -83,30 +93,34 @@ __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__
     }
 }
 
-// Sorts keys on bits [0, n_bits).  `a` holds the input, `b` is a buffer of the same size; returns the buffer
-// that holds the result.  hist: 256 * ceil(n / kTile) + ceil(that / kTile) uint32.
+// Sorts keys on bits [first_bit, first_bit + n_bits).  `a` holds the input, `b` is a buffer of the same size; returns the
+// buffer that holds the result.  hist: radix_hist_words(n) uint32.
 uint64_t *radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t st,
                      int *status) {
     *status = LP_OK;
     if (n <= 1) return a;
     const int64_t nb = lp_ceil_div(n, kTile);
-    uint32_t *spine = hist + 256 * nb;
-    for (int shift = first_bit; shift < first_bit + n_bits; shift += 8) {
-        hipLaunchKernelGGL(rs_hist_kernel, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
+    const int digit = (n_bits + 8) / 9 < (n_bits + 7) / 8 ? 9 : 8;   // bits per pass
+    const int64_t bins = (int64_t)1 << digit;
+    uint32_t *spine = hist + bins * nb;
+    for (int shift = first_bit; shift < first_bit + n_bits; shift += digit) {
+        if (digit == 9) hipLaunchKernelGGL(rs_hist_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
+        else hipLaunchKernelGGL(rs_hist_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
         auto load = [hist] __device__(int64_t i) { return hist[i]; };
         auto store = [hist] __device__(int64_t i, uint32_t ex, uint32_t) { hist[i] = ex; };
-        int s = device_exclusive_scan<uint32_t>(load, store, 256 * nb, spine, nullptr, st);
+        int s = device_exclusive_scan<uint32_t>(load, store, bins * nb, spine, nullptr, st);
         if (s != LP_OK) { *status = s; return a; }
-        hipLaunchKernelGGL(rs_scatter_kernel, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
+        if (digit == 9) hipLaunchKernelGGL(rs_scatter_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
+        else hipLaunchKernelGGL(rs_scatter_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
         uint64_t *t = a; a = b; b = t;
     }
     *status = lp_after_launch();
     return a;
 }
 
-size_t radix_hist_words(int64_t n) {
+size_t radix_hist_words(int64_t n) {   // enough for either digit width
     const int64_t nb = lp_ceil_div(n > 0 ? n : 1, kTile);
-    return (size_t)(256 * nb + lp_ceil_div(256 * nb, kTile) + 8);
+    return (size_t)(512 * nb + lp_ceil_div(512 * nb, kTile) + 8);
 }
 
 // ------------------------------------------------------------------ CSR specific kernels
