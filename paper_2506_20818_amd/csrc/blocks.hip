@@ -149,19 +149,18 @@ __global__ void node_inv_deg_kernel(const int32_t *__restrict__ nodes, const int
     if (i < *n_dev) out[i] = inv_deg[nodes[i]];
 }
 
+// Local column of every entry, its sort key (column, position), and the entry count as a device scalar: the sort and
+// the row offsets of the transposed block run over the entries actually drawn, not over the capacity.
 __global__ void translate_kernel(const int32_t *__restrict__ col_global, const int32_t *__restrict__ ptr,
                                  const int32_t *__restrict__ n_rows_dev, int64_t cap_entries, const int32_t *__restrict__ index,
-                                 int32_t *__restrict__ col, uint64_t *__restrict__ keys, uint32_t park_row) {
+                                 int32_t *__restrict__ col, uint64_t *__restrict__ keys, uint32_t *__restrict__ n_entries_out) {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= cap_entries) return;
     const int32_t n_entries = ptr[*n_rows_dev];
-    if (p < n_entries) {
-        const int32_t c = index[col_global[p]];
-        col[p] = c;
-        keys[p] = ((uint64_t)(uint32_t)c << 32) | (uint32_t)p;
-    } else {
-        keys[p] = ((uint64_t)park_row << 32) | (uint32_t)p;  // unused slots sort behind the last row
-    }
+    if (p == 0) *n_entries_out = (uint32_t)n_entries;
+    if (p >= cap_entries || p >= n_entries) return;
+    const int32_t c = index[col_global[p]];
+    col[p] = c;
+    keys[p] = ((uint64_t)(uint32_t)c << 32) | (uint32_t)p;
 }
 
 __global__ void transposed_cols_kernel(const uint64_t *__restrict__ sorted, const int32_t *__restrict__ ptr,
@@ -415,12 +414,14 @@ extern "C" int lp_sample_blocks(const lp_csr *g, int64_t B, const int32_t *e_src
         }
         if (cap_e > 0) {
             const unsigned ge = (unsigned)lp_ceil_div(cap_e, 256);
+            uint32_t *n_entries = w.total + 8;   // its own word of the scalar area
             hipLaunchKernelGGL(translate_kernel, dim3(ge), dim3(256), 0, st, w.col_global, ptr, n_k, cap_e, out->index, out->col[k - 1],
-                               w.keys_a, (uint32_t)out->cap[k - 1]);
+                               w.keys_a, n_entries);
             int status;
-            const uint64_t *sorted = lp_radix_sort(w.keys_a, w.keys_b, cap_e, 32, lp_bits_for((int64_t)out->cap[k - 1] + 1), w.hist, st, &status);
+            const uint64_t *sorted = lp_radix_sort(w.keys_a, w.keys_b, cap_e, 32, lp_bits_for((int64_t)out->cap[k - 1] + 1), w.hist, st, &status,
+                                                   n_entries);
             LP_TRY(status);
-            LP_TRY(lp_launch_row_offsets(sorted, cap_e, nullptr, out->cap[k - 1], 32, out->t_ptr[k - 1], st));
+            LP_TRY(lp_launch_row_offsets(sorted, cap_e, n_entries, out->cap[k - 1], 32, out->t_ptr[k - 1], st));
             hipLaunchKernelGGL(transposed_cols_kernel, dim3(ge), dim3(256), 0, st, sorted, ptr, n_k, cap_e, w.row_of_entry, out->t_col[k - 1]);
         } else {
             LP_TRY(lp_launch_zero(reinterpret_cast<float *>(out->t_ptr[k - 1]), (int64_t)out->cap[k - 1] + 1, st));

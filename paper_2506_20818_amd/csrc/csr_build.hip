@@ -17,10 +17,11 @@ constexpr int kWaveChunk = 64 * kItems;   // keys per wavefront
 // ------------------------------------------------------------------ radix sort of 64-bit keys, one digit of 8 or 9 bits per pass
 // (nine when that saves a pass: node ids below 2^18 sort in two passes instead of three)
 template <int BITS>
-__global__ __launch_bounds__(kThreads) void rs_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, int shift,
-                                                           uint32_t *__restrict__ hist, int64_t nb) {
+__global__ __launch_bounds__(kThreads) void rs_hist_kernel(const uint64_t *__restrict__ keys, int64_t n, const uint32_t *__restrict__ n_dev,
+                                                           int shift, uint32_t *__restrict__ hist, int64_t nb) {
     constexpr int BINS = 1 << BITS;
     __shared__ uint32_t h[BINS];
+    if (n_dev) n = min(n, (int64_t)*n_dev);   // keys actually present (blocks past them still write their zero counts)
 #pragma unroll
     for (int j = threadIdx.x; j < BINS; j += kThreads) h[j] = 0;
     __syncthreads();
@@ -39,11 +40,13 @@ __global__ __launch_bounds__(kThreads) void rs_hist_kernel(const uint64_t *__res
 // tile and walks them 64 at a time; inside such a group the rank among equal digits comes from one ballot per bit.
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
-                                                              int64_t n, int shift, const uint32_t *__restrict__ gbase,
-                                                              int64_t nb) {
+                                                              int64_t n, const uint32_t *__restrict__ n_dev, int shift,
+                                                              const uint32_t *__restrict__ gbase, int64_t nb) {
     constexpr int BINS = 1 << BITS;
     __shared__ uint32_t cnt[4][BINS];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    if (n_dev) n = min(n, (int64_t)*n_dev);
+    if ((int64_t)blockIdx.x * kTile >= n) return;   // the whole workgroup: nothing of this tile is present
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -94,9 +97,10 @@ __global__ __launch_bounds__(kThreads) void rs_scatter_kernel(const uint64_t *__
 }
 
 // Sorts keys on bits [first_bit, first_bit + n_bits).  `a` holds the input, `b` is a buffer of the same size; returns the
-// buffer that holds the result.  hist: radix_hist_words(n) uint32.
+// buffer that holds the result.  hist: radix_hist_words(n) uint32.  With n_dev (a device count, at most n) only the
+// first *n_dev keys are sorted; what lies behind them in the returned buffer is unspecified.
 uint64_t *radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t st,
-                     int *status) {
+                     int *status, const uint32_t *n_dev = nullptr) {
     *status = LP_OK;
     if (n <= 1) return a;
     const int64_t nb = lp_ceil_div(n, kTile);
@@ -104,14 +108,14 @@ uint64_t *radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_b
     const int64_t bins = (int64_t)1 << digit;
     uint32_t *spine = hist + bins * nb;
     for (int shift = first_bit; shift < first_bit + n_bits; shift += digit) {
-        if (digit == 9) hipLaunchKernelGGL(rs_hist_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
-        else hipLaunchKernelGGL(rs_hist_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, shift, hist, nb);
+        if (digit == 9) hipLaunchKernelGGL(rs_hist_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, n_dev, shift, hist, nb);
+        else hipLaunchKernelGGL(rs_hist_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, n, n_dev, shift, hist, nb);
         auto load = [hist] __device__(int64_t i) { return hist[i]; };
         auto store = [hist] __device__(int64_t i, uint32_t ex, uint32_t) { hist[i] = ex; };
         int s = device_exclusive_scan<uint32_t>(load, store, bins * nb, spine, nullptr, st);
         if (s != LP_OK) { *status = s; return a; }
-        if (digit == 9) hipLaunchKernelGGL(rs_scatter_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
-        else hipLaunchKernelGGL(rs_scatter_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, shift, hist, nb);
+        if (digit == 9) hipLaunchKernelGGL(rs_scatter_kernel<9>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, n_dev, shift, hist, nb);
+        else hipLaunchKernelGGL(rs_scatter_kernel<8>, dim3((unsigned)nb), dim3(kThreads), 0, st, a, b, n, n_dev, shift, hist, nb);
         uint64_t *t = a; a = b; b = t;
     }
     *status = lp_after_launch();
@@ -235,8 +239,8 @@ int lp_bits_for(int64_t n_values) {
 size_t lp_radix_sort_hist_words(int64_t n) { return radix_hist_words(n); }
 
 uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t st,
-                        int *status) {
-    return radix_sort(a, b, n, first_bit, n_bits, hist, st, status);
+                        int *status, const uint32_t *n_dev) {
+    return radix_sort(a, b, n, first_bit, n_bits, hist, st, status, n_dev);
 }
 
 int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,

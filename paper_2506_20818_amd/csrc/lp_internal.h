@@ -160,12 +160,13 @@ int lp_launch_colsum(const void *in, int dtype, int64_t M, int64_t N, float *out
 int lp_launch_zero(float *p, int64_t n, hipStream_t stream);
 
 // ---------------------------------------------------------------- sorting (csr_build.hip)
-// Stable least-significant-digit radix sort of 64-bit keys on bits [first_bit, first_bit + n_bits), 8 bits per
+// Stable least-significant-digit radix sort of 64-bit keys on bits [first_bit, first_bit + n_bits), 8 or 9 bits per
 // pass.  `a` holds the input, `b` is a second buffer of n keys, `hist` has lp_radix_sort_hist_words(n) words.
-// Returns the buffer that holds the sorted keys (a or b).
+// Returns the buffer that holds the sorted keys (a or b).  With n_dev (a device count, at most n) only the first
+// *n_dev keys are sorted and what lies behind them in the returned buffer is unspecified.
 size_t lp_radix_sort_hist_words(int64_t n);
 uint64_t *lp_radix_sort(uint64_t *a, uint64_t *b, int64_t n, int first_bit, int n_bits, uint32_t *hist, hipStream_t stream,
-                        int *status);
+                        int *status, const uint32_t *n_dev = nullptr);
 // offsets[r] = number of sorted keys below (r << shift), r = 0..n_rows; the key count is *n_dev when n_dev is
 // given, else n_host.
 int lp_launch_row_offsets(const uint64_t *sorted, int64_t n_host, const uint32_t *n_dev, int32_t n_rows, int shift,
