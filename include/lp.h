@@ -444,6 +444,9 @@ int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, co
  *     the fp32 instructions would give an infinity or a finite value; term
  *     products below the smallest normal fp32 (1.2e-38) are flushed to zero, so
  *     products smaller than about 1e-33 lose the accuracy of their small terms.
+ *     Products whose shape the bf16-term kernels do not take (an inner dimension
+ *     that is not a multiple of 16, outputs narrower than 65 columns, fused weight
+ *     gradients below 192 x 192) use the fp32 matrix instructions in this mode too.
  *   LP_FP32_PRODUCTS_NATIVE: fp32 matrix instructions.
  * Process-wide, read at every launch; returns LP_ERR_INVALID_ARG for another
  * value.  bf16 models are not affected.
