@@ -1266,38 +1266,52 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
         };
         auto fetch = [&](int64_t k0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bool live = ok && k0 + 4 * ng + i < kend;
-                const v4f v = *reinterpret_cast<const v4f *>(base + row[i] * pitch);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) rv[i][e] = live ? v[e] : 0.f;
-            }
+            for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const v4f *>(base + row[i] * pitch);   // used as loaded: see stash_half
+            (void)k0;
         };
-        auto stash = [&](int stage) {
+        // columns j0, j0 + 1 of the block (four nodes each, fetched for the step that starts at node k0) into a stage;
+        // nodes beyond the end of the chunk and columns outside the operand count as zeros (decided here, not at the
+        // load, so that nothing waits for the loads before this point); the second half also adds up the block
+        auto stash_half = [&](int stage, int j0, int64_t k0) {
             char *dst = lds + stage * STAGE + (is_b ? 256 * WS_ROWB : 0) + c * WS_ROWB + 8 * ng;
+            bool live[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {   // column j of the block: its four nodes
+            for (int i = 0; i < 4; ++i) live[i] = ok && k0 + 4 * ng + i < kend;
+            if (j0 == 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rv[i][e] = live[i] ? rv[i][e] : 0.f;
+            }
+#pragma unroll
+            for (int j = j0; j < j0 + 2; ++j) {
                 uint2 t0, t1, t2;
                 lp_split3(__builtin_bit_cast(v4i, v4f{rv[0][j], rv[1][j], rv[2][j], rv[3][j]}), t0, t1, t2);
                 *reinterpret_cast<uint2 *>(dst + j * WS_ROWB) = t0;
                 *reinterpret_cast<uint2 *>(dst + j * WS_ROWB + 2 * WS_BK) = t1;
                 *reinterpret_cast<uint2 *>(dst + j * WS_ROWB + 4 * WS_BK) = t2;
             }
+            if (j0 == 2) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) bsum += rv[i];
+                for (int i = 0; i < 4; ++i) bsum += rv[i];
+            }
+        };
+        auto stash = [&](int stage, int64_t k0) {
+            stash_half(stage, 0, k0);
+            stash_half(stage, 2, k0);
         };
         v4i sa[3][2], sb[3][4];
-        auto planes = [&](int stage) {
-            const char *As = lds + stage * STAGE, *Bs = As + 256 * WS_ROWB;
+        auto plane_a = [&](int stage, int tt) {
+            const char *As = lds + stage * STAGE;
 #pragma unroll
-            for (int tt = 0; tt < 3; ++tt) {
+            for (int rb = 0; rb < 2; ++rb)
+                sa[tt][rb] = *reinterpret_cast<const v4i *>(As + (wm * 64 + rb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
+        };
+        auto plane_b = [&](int stage, int tt) {
+            const char *Bs = lds + stage * STAGE + 256 * WS_ROWB;
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-                    sa[tt][rb] = *reinterpret_cast<const v4i *>(As + (wm * 64 + rb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb)
-                    sb[tt][cb] = *reinterpret_cast<const v4i *>(Bs + (wn * 128 + cb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
-            }
+            for (int cb = 0; cb < 4; ++cb)
+                sb[tt][cb] = *reinterpret_cast<const v4i *>(Bs + (wn * 128 + cb * 32 + i32) * WS_ROWB + tt * (2 * WS_BK) + 16 * h);
         };
         auto term = [&](int ta, int tb) {
 #pragma unroll
@@ -1311,22 +1325,35 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
         lookup(kbeg);
         fetch(kbeg);
         lookup(kbeg + WS_BK);
-        stash(0);
+        stash(0, kbeg);
         fetch(kbeg + WS_BK);
         lookup(kbeg + 2 * WS_BK);
         __syncthreads();
         int cur = 0;
+        // One step, in the order of the SPLIT NT kernel's: term planes read one term pair ahead of their use, the tile
+        // copy (registers hold step k0 + 16, zeros past the end) in two halves under the second and third pair, then
+        // the loads of step k0 + 32, which so have most of a step to arrive.
         for (int64_t k0 = kbeg; k0 < kend; k0 += WS_BK, cur ^= 1) {
-            planes(cur);
-            term(2, 0);                     // smallest products first
+            plane_a(cur, 2);
+            plane_b(cur, 0);
+            plane_a(cur, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            term(2, 0);
+            plane_b(cur, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            term(0, 0);
+            plane_a(cur, 1);
+            stash_half(cur ^ 1, 0, k0 + WS_BK);
+            __builtin_amdgcn_sched_barrier(0);
             term(0, 2);
-            stash(cur ^ 1);                 // registers hold step k0 + 16 (zeros past the end)
+            plane_b(cur, 1);
+            stash_half(cur ^ 1, 2, k0 + WS_BK);
             fetch(k0 + 2 * WS_BK);
             lookup(k0 + 3 * WS_BK);
-            term(1, 1);
+            __builtin_amdgcn_sched_barrier(0);
             term(1, 0);
             term(0, 1);
-            term(0, 0);
+            term(1, 1);
             __syncthreads();
         }
     }
