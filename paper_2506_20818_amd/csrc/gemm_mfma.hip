@@ -506,6 +506,37 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
             store_tile(cur);                                                                                           \
         }                                                                                                              \
     }
+    // Four-group step (KSB = 128) with the tile copy spread over the groups, a quarter of the fetched vectors under
+    // each, every vector reloaded right after its copy (the order that paid in the SPLIT step)
+#define LP_STEP_SPREAD(u_)                                                                                             \
+    {                                                                                                                  \
+        const int cur = (u_) & 1;                                                                                      \
+        LP_CURSOR()                                                                                                    \
+        LP_LOAD_OPS(cur, 0, a0, b0)                                                                                    \
+        LP_LOAD_OPS(cur, 1, a1, b1)                                                                                    \
+        LP_ORDER();                                                                                                    \
+        LP_MFMA_OPS(a0, b0)                                                                                            \
+        lp_unrolled<NV / 4>([&](auto q_) { LP_MOVE_ONE(cur ^ 1, decltype(q_)::value) });                               \
+        LP_ORDER();                                                                                                    \
+        LP_LOAD_OPS(cur, 2, a0, b0)                                                                                    \
+        LP_ORDER();                                                                                                    \
+        LP_MFMA_OPS(a1, b1)                                                                                            \
+        lp_unrolled<NV / 2 - NV / 4>([&](auto q_) { LP_MOVE_ONE(cur ^ 1, NV / 4 + decltype(q_)::value) });             \
+        LP_ORDER();                                                                                                    \
+        LP_LOAD_OPS(cur, 3, a1, b1)                                                                                    \
+        LP_ORDER();                                                                                                    \
+        LP_MFMA_OPS(a0, b0)                                                                                            \
+        lp_unrolled<3 * NV / 4 - NV / 2>([&](auto q_) { LP_MOVE_ONE(cur ^ 1, NV / 2 + decltype(q_)::value) });         \
+        LP_ORDER();                                                                                                    \
+        LP_MFMA_OPS(a1, b1)                                                                                            \
+        lp_unrolled<NV - 3 * NV / 4>([&](auto q_) { LP_MOVE_ONE(cur ^ 1, 3 * NV / 4 + decltype(q_)::value) });         \
+        LP_ADVANCE()                                                                                                   \
+        __syncthreads();                                                                                               \
+        if (++ct == n_tiles) {                                                                                         \
+            ct = 0;                                                                                                    \
+            store_tile(cur);                                                                                           \
+        }                                                                                                              \
+    }
 #define LP_STEP(u_)                                                                                                    \
     {                                                                                                                  \
         const int cur = (u_) & 1;                                                                                      \
@@ -616,12 +647,17 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         constexpr int NV = A_LOADS + B_LOADS;   // vectors a thread fetches per step
         v4i sa[3][2], sb[3][NB];
         for (int u = 0; u < n_steps; ++u) LP_STEP_SPLIT(u)
+    } else if constexpr (KSB == 128) {
+        constexpr int NV = A_LOADS + B_LOADS;
+        v4i a0[2], b0[NB], a1[2], b1[NB];
+        for (int u = 0; u < n_steps; ++u) LP_STEP_SPREAD(u)
     } else {
         v4i a0[2], b0[NB], a1[2], b1[NB];
         for (int u = 0; u < n_steps; ++u) LP_STEP(u)
     }
 #undef LP_STEP
 #undef LP_STEP_SPLIT
+#undef LP_STEP_SPREAD
 #undef LP_STASH_ONE
 #undef LP_MOVE_ONE
 #undef LP_ADVANCE
