@@ -210,3 +210,34 @@ def test_hidden_512_persistent_tiles(storage, n):
         assert_close(host(s), s_ref, TOL_ACT, "scores")
         lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
         check_grads(grads, g_ref, 2, lo, hi)
+
+
+@pytest.mark.parametrize("n,dims", [(65535, [48, 256]), (65537, [48, 256]), (65536 + 255, [64, 192, 320]), (131072 + 1, [32, 272])])
+def test_row_counts_around_the_256_row_tile_switch(n, dims):
+    """Node counts just below and above 256 rows x 256 compute units (where the persistent NT kernels change from
+    128-row to 256-row tiles), K parts of 48, 64 and 192 values (3, 4 and 12 steps per part), output widths that
+    leave the second column tile three quarters empty (320) or almost empty (272): forward and backward, every
+    element against the oracle."""
+    from test_gpu_parity import check_grads, gate_slack, random_pairs, toy_model
+    rng = np.random.default_rng(n + sum(dims))
+    r, c = random_pairs(rng, n, 3 * n)
+    say("tile switch: n=%d dims=%s" % (n, dims))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 5000, 2000
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    K = len(dims) - 1
+    for k in range(1, K + 1):
+        assert_close(host(acts.H[k - 1]), a_ref.H[k], TOL_ACT, "H^%d" % k)
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    check_grads(grads, g_ref, K, lo, hi)
