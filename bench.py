@@ -456,6 +456,23 @@ def main():
     loss_val = float(loss.item())
     ms_per_step = dt * 1e3 / max(args.steps, 1)
 
+    # for reference, the same steps with the other way of forming the fp32 products (outside the timed region)
+    other_products = None
+    if not bf16:
+        was = lp.lp_get_fp32_products()
+        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if split else lp.LP_FP32_PRODUCTS_BF16X6)
+        for i in range(3):
+            step(3000 + i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(2000 + i)      # the batches of the timed region: the last loss is comparable with "loss"
+        torch.cuda.synchronize()
+        oms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+        lp.lp_set_fp32_products(was)
+        other_products = {"fp32_products": fp32_products_name(False, not split), "ms_per_step_without_events": round(oms, 4),
+                          "value": round(Bn / (oms * 1e-3), 1), "loss": round(float(loss.item()), 6)}
+
     # accounting only (outside the timed region): how many nodes are an endpoint of a scored edge in the timed steps,
     # and how many CSR entries point at one of them
     deg = (g.rowptr[1:] - g.rowptr[:-1]).to(torch.int64)
@@ -555,6 +572,7 @@ def main():
         "roofline_score": score_line,
         "sampler": sample_line,
         "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items() if k != "other" or args.timing_level > 1},
+        "with_other_fp32_products": other_products,
     }
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
         out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
