@@ -470,6 +470,7 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
     }
     const void *Hprev = X_frontier;
     const bool gcn = m->layer_type == LP_LAYER_GCN;
+    LP_TRY(lp_launch_transpose_weights(m, wt, st));   // every W^T, in one launch
     for (int k = 1; k <= K; ++k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
         SpmmArgs sp;
@@ -488,8 +489,6 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
         const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
         void *WsT = wt, *WnT = wt + wbytes;
         wt += 2 * wbytes;
-        if (!gcn) LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
-        LP_TRY(lp_launch_transpose(m->W_neigh[k - 1], Fi, Fo, WnT, dt, st));
         GemmNtArgs ge;
         ge.dtype = dt;
         ge.M = b->cap[k]; ge.m_dev = b->n + k;

@@ -1629,6 +1629,23 @@ __global__ void transpose_kernel(const T *__restrict__ in, int rows, int cols, T
         if (orow0 + i < cols && ocol < rows) out[(int64_t)(orow0 + i) * rows + ocol] = tile[threadIdx.x][i];
 }
 
+template <typename T>
+__global__ void transpose_batch_kernel(TransposeBatch b) {
+    __shared__ T tile[32][33];
+    const int z = blockIdx.z;
+    const int rows = b.rows[z], cols = b.cols[z];
+    const int c = blockIdx.x * 32 + threadIdx.x, r0 = blockIdx.y * 32;
+    if (blockIdx.x * 32 >= cols || r0 >= rows) return;   // the grid covers the largest matrix of the batch
+    const T *__restrict__ in = static_cast<const T *>(b.in[z]);
+    T *__restrict__ out = static_cast<T *>(b.out[z]);
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (r0 + i < rows && c < cols) tile[i][threadIdx.x] = in[(int64_t)(r0 + i) * cols + c];
+    __syncthreads();
+    const int orow0 = blockIdx.x * 32, ocol = r0 + threadIdx.x;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (orow0 + i < cols && ocol < rows) out[(int64_t)(orow0 + i) * rows + ocol] = tile[threadIdx.x][i];
+}
+
 constexpr int kColsumRows = 256;  // rows folded by one workgroup
 
 // partials[chunk, c] = sum of in[r, c] over the rows r of the chunk, rows taken in a fixed order, summed in fp32.
@@ -1918,6 +1935,41 @@ int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, i
         hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(32, 8), 0, st, static_cast<const float *>(in), rows, cols,
                            static_cast<float *>(out));
     return lp_after_launch();
+}
+
+int lp_launch_transpose_batch(const TransposeBatch &b, int dtype, hipStream_t st) {
+    if (b.n <= 0) return LP_OK;
+    if (b.n > 16) return LP_ERR_INVALID_ARG;
+    int32_t max_rows = 0, max_cols = 0;
+    for (int i = 0; i < b.n; ++i) {
+        if (!b.in[i] || !b.out[i] || b.rows[i] <= 0 || b.cols[i] <= 0) return LP_ERR_INVALID_ARG;
+        max_rows = std::max(max_rows, b.rows[i]);
+        max_cols = std::max(max_cols, b.cols[i]);
+    }
+    LpTimedScope timed(LP_KC_OTHER, st);
+    const dim3 grid((unsigned)lp_ceil_div(max_cols, 32), (unsigned)lp_ceil_div(max_rows, 32), (unsigned)b.n);
+    if (dtype == LP_BF16) hipLaunchKernelGGL((transpose_batch_kernel<lp_bf16_t>), grid, dim3(32, 8), 0, st, b);
+    else hipLaunchKernelGGL((transpose_batch_kernel<float>), grid, dim3(32, 8), 0, st, b);
+    return lp_after_launch();
+}
+
+int lp_launch_transpose_weights(const lp_model *m, void *wt, hipStream_t st) {
+    TransposeBatch b;
+    char *p = static_cast<char *>(wt);
+    const size_t eb = (size_t)lp_elem_bytes(m->dtype);
+    for (int k = 1; k <= m->n_layers; ++k) {
+        const int Fi = m->dims[k - 1], Fo = m->dims[k];
+        const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
+        const void *src[2] = {m->W_self[k - 1], m->W_neigh[k - 1]};
+        for (int s = 0; s < 2; ++s) {
+            if (src[s]) {
+                b.in[b.n] = src[s]; b.out[b.n] = p + s * wbytes; b.rows[b.n] = Fi; b.cols[b.n] = Fo;
+                ++b.n;
+            }
+        }
+        p += 2 * wbytes;
+    }
+    return lp_launch_transpose_batch(b, m->dtype, st);
 }
 
 size_t lp_colsum_partials_bytes(int64_t M, int64_t N) {

@@ -151,6 +151,17 @@ int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t stream);
 
 // out[c, r] = in[r, c] for a small [rows, cols] matrix (weights) of 4-byte or 2-byte elements.
 int lp_launch_transpose(const void *in, int32_t rows, int32_t cols, void *out, int dtype, hipStream_t stream);
+// the same for up to 16 matrices of one storage type in a single launch (out[i] = in[i]^T)
+struct TransposeBatch {
+    int n = 0;
+    const void *in[16];
+    void *out[16];
+    int32_t rows[16], cols[16];
+};
+int lp_launch_transpose_batch(const TransposeBatch &b, int dtype, hipStream_t stream);
+// all weight matrices of a model transposed into consecutive areas of `wt` (layer k: W_self^T, then W_neigh^T, each
+// lp_align_up(F_{k-1} F_k, 64) elements; a NULL W_self leaves its area unwritten): one launch
+int lp_launch_transpose_weights(const lp_model *m, void *wt, hipStream_t stream);
 // out[n] = sum_m in[m, n] for a contiguous [M, N] matrix stored as `dtype` (N a multiple of its vector width);
 // fp32 sums in a fixed order; partials: lp_colsum_partials_bytes()
 size_t lp_colsum_partials_bytes(int64_t M, int64_t N);

@@ -167,6 +167,8 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
     const int K = m->n_layers;
     const bool gcn = m->layer_type == LP_LAYER_GCN;
     const void *Hprev = X;
+    // the NT products want the reduction index contiguous: every W^T ([Fo, Fi]) is written up front, in one launch
+    LP_TRY(lp_launch_transpose_weights(m, wt, st));
     for (int k = 1; k <= K; ++k) {
         const int Fi = m->dims[k - 1], Fo = m->dims[k];
         void *A = saved->A[k - 1];
@@ -185,12 +187,9 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         sp.in = Hprev;
         sp.out = A;
         LP_TRY(lp_launch_spmm(sp, st));
-        // the NT product wants the reduction index contiguous: W^T is [Fo, Fi]
         const size_t wbytes = lp_align_up((size_t)Fi * Fo, 64) * eb;
         void *WsT = wt, *WnT = wt + wbytes;
         wt += 2 * wbytes;
-        if (!gcn) LP_TRY(lp_launch_transpose(m->W_self[k - 1], Fi, Fo, WsT, dt, st));
-        LP_TRY(lp_launch_transpose(m->W_neigh[k - 1], Fi, Fo, WnT, dt, st));
         GemmNtArgs ge;
         ge.dtype = dt;
         ge.M = g->n_nodes;
