@@ -3,8 +3,11 @@
 
 A step is one pass of the whole hot path over one minibatch: lp_sample_neg -> lp_sage_forward (full-neighbour,
 all visible nodes) -> lp_score_loss -> lp_backward, with every input already resident in HBM.  The workload is
-the Collab-scale Chung-Lu configuration ("C2"): 235 000 nodes, ~2.4 M directed CSR entries, 128 -> 256 -> 256 ->
-256 GraphSAGE-mean in fp32, 65 536 positives + 65 536 negatives per step.  Prints ONE JSON line.
+by default the largest single-GPU configuration ("C4", the one the aggregation's HBM target is judged on): a power-law
+graph with the paper's largest edge count, 2.9 M nodes, ~29 M directed CSR entries (feature matrices of 1.5-3 GB, far
+beyond the 256 MB Infinity Cache), 128 -> 256 -> 256 -> 256 GraphSAGE-mean in fp32, 131 072 positives + 131 072
+negatives per step; --workload selects the other configurations (C1, C2, C3, C5_keep1, C5_keep0.5, C5_keep0.2).
+Prints ONE JSON line.
 
 The per-kernel numbers in "roofline" come from HIP events recorded by the library around each launch inside the
 timed region (lp_timing_enable); "cpu_baseline" times the CPU oracle, as it stands, on a stated fraction of the
@@ -25,6 +28,10 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix
+INFINITY_CACHE_BYTES = 256 << 20   # MI355X last-level cache in front of HBM
+
+# fraction of each workload that the CPU oracle is timed on by default (about 10-30 s of host work)
+CPU_SCALE = {"C1": 1.0, "C2": 1.0, "C3": 0.5, "C4": 0.2, "C5_keep1": 0.1, "C5_keep0.5": 0.1, "C5_keep0.2": 0.15}
 
 
 def spmm_bytes(n, nnz, F, backward, eb=4):
@@ -63,25 +70,33 @@ def step_counts(n, nnz, dims, n_t, nnz_t, eb=4, paths=2):
     return sp, nt, tn
 
 
-def cpu_baseline(scale):
-    """Time the CPU oracle on a `scale` fraction of the workload (nodes, edges and batch all scaled)."""
-    from lp_workloads import make_workload
+def cpu_baseline(workload, scale):
+    """Time the CPU oracle, as it stands, on a `scale` fraction of `workload` (nodes, edges and batch all scaled by
+    the same factor through the workload's own generator)."""
+    from lp_workloads import make_workload, to_bf16_grid
     from oracle import lp_oracle as O
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    wl = make_workload("C2", scale=scale)
+    wl = make_workload(workload, scale=scale)
+    storage = "bf16" if wl.dtype == "bf16" else "f32"
+    if storage == "bf16":
+        wl.X = to_bf16_grid(wl.X)
+        wl.W_self, wl.W_neigh = [to_bf16_grid(w) for w in wl.W_self], [to_bf16_grid(w) for w in wl.W_neigh]
     g = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
     t0 = time.perf_counter()
     O.train_step(g, wl.W_self, wl.W_neigh, wl.bias, wl.X, wl.pos_src, wl.pos_dst, wl.k_neg, wl.n_space,
-                 wl.sampler_seed, wl.sampler_step)
+                 wl.sampler_seed, wl.sampler_step, storage=storage)
     dt = time.perf_counter() - t0
     return {"value": wl.batch_edges / dt, "unit": "edges/s", "cores": int(cores), "kind": "oracle",
-            "seconds": round(dt, 3),
-            "sample": "one full oracle step (numpy fp64) on the C2 generator at scale %.3g: %d nodes, %d directed "
-                      "entries, %d scored edges" % (scale, wl.n_nodes, g.nnz, wl.batch_edges)}
+            "seconds": round(dt, 3), "scale": scale,
+            "sample": "one full oracle step (numpy fp64%s) on the %s generator at scale %.3g: %d nodes, %d directed "
+                      "entries, %d scored edges; the dense products run on %d BLAS threads, the aggregation and its "
+                      "adjoint are single-threaded loops over the rows"
+                      % (", stored matrices rounded to bf16" if storage == "bf16" else "", workload, scale, wl.n_nodes,
+                         g.nnz, wl.batch_edges, int(cores))}
 
 
 def sparsify_task(args):
@@ -297,8 +312,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C2")
-    ap.add_argument("--cpu-scale", type=float, default=1.0, help="fraction of the workload the CPU oracle is timed on")
+    ap.add_argument("--workload", default=None, help="default: C4 (train_step), C2 (sampled_step), C3 (sparsify)")
+    ap.add_argument("--cpu-scale", type=float, default=None,
+                    help="fraction of the workload the CPU oracle is timed on (default: per workload, 10-30 s of host work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--timing-level", type=int, default=1, choices=[1, 2],
                     help="1: HIP events around the aggregation, GEMM, scatter, score and sampler launches; 2: around every launch")
@@ -325,7 +341,9 @@ def main():
     if args.task == "sparsify":
         return sparsify_task(args)
     if args.task == "sampled_step":
+        args.workload = args.workload or "C2"
         return sampled_step_task(args)
+    args.workload = args.workload or "C4"
 
     import numpy as np
     import torch
@@ -492,12 +510,18 @@ def main():
         tn_flops += 2 * 2.0 * Bn * F * F
     per_step = {k: (ms / max(args.steps, 1), cnt // max(args.steps, 1)) for k, (ms, cnt) in classes.items()}
 
+    es = 2 if bf16 else 4
+    # whether the matrix the widest aggregation gathers from fits the Infinity Cache: if it does, "achieved" is
+    # cache-assisted and must not be read as an HBM rate
+    cache_resident = bool(n * max(wl.dims[:-1]) * es <= INFINITY_CACHE_BYTES)
+
     def hbm_line(cls, bytes_per_step):
         ms, cnt = per_step[cls]
         gbs = bytes_per_step / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         return {"bound": "hbm", "kernel": cls, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "launches_per_step": cnt,
-                "avg_launch_ms": round(ms / max(cnt, 1), 4), "algorithmic_bytes_per_launch": int(bytes_per_step / max(cnt, 1))}
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "frac_counters": None, "cache_resident": cache_resident,
+                "launches_per_step": cnt, "avg_launch_ms": round(ms / max(cnt, 1), 4),
+                "algorithmic_bytes_per_launch": int(bytes_per_step / max(cnt, 1))}
 
     def mfma_line(cls, flops_per_step, peak=MFMA_FP32_PEAK_TFLOPS):
         ms, cnt = per_step[cls]
@@ -506,11 +530,13 @@ def main():
                 "frac": round(tf / peak, 4), "traffic": None, "launches_per_step": cnt,
                 "avg_launch_ms": round(ms / max(cnt, 1), 4), "flops_per_launch": int(flops_per_step / max(cnt, 1))}
 
-    # HBM bytes per launch from the committed rocprofv3 --pmc summaries (FETCH_SIZE and WRITE_SIZE runs of this
-    # same script, scaled by what a plain copy of known size reads); null when no summary covers the workload.
+    # HBM bytes per launch are NOT measured in this run (counter collection needs rocprofv3 around the process): they
+    # are copied from the committed summary of two rocprofv3 --pmc runs of this same script (FETCH_SIZE, WRITE_SIZE,
+    # each scaled by what a plain copy of known size reads), named in "traffic_source"; null when no summary covers
+    # the workload and model variant.
     traffic = {}
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
-    if os.path.exists(tpath) and not gcn and not use_mlp:
+    if os.path.exists(tpath) and not gcn and not use_mlp and (bf16 or split):
         with open(tpath) as fh:
             traffic = json.load(fh)
 
@@ -525,20 +551,32 @@ def main():
         for cls in ("gemm_nt", "gemm_tn"):
             lines[cls]["peak_basis"] = "bf16 MFMA peak %.0f TFLOP/s / 6 term products per fp32 product" % BF16_MFMA_PEAK_TFLOPS
             lines[cls]["mfma_tflops_executed"] = round(6.0 * lines[cls]["achieved"], 1)
-    for cls in lines:
-        t = traffic.get(cls + "_bytes_per_launch")
-        lines[cls]["traffic"] = int(t) if t else None
-    dominant = max(lines, key=lambda c: per_step[c][0])
     # the two small steps of the metric's second half: scoring gathers two embedding rows per edge and writes a score
     # and a gradient scalar; the sampler is latency bound, so it is reported as samples per second
-    es = 2 if bf16 else 4
     score_bytes = Bn * (2.0 * wl.dims[-1] * es + 16.0)
     if use_mlp:   # the element-wise product of the two rows is written out, and the output layer reads the last hidden row
         score_bytes += Bn * 2.0 * wl.dims[-1] * es
-    score_line = hbm_line("score", score_bytes)
+    lines["score"] = hbm_line("score", score_bytes)
+    lines["score"]["cache_resident"] = bool(n * wl.dims[-1] * es <= INFINITY_CACHE_BYTES)
     sample_ms = per_step["sample"][0]
     sample_line = {"bound": "latency", "kernel": "sample", "achieved": round(n_pos * k_neg / (sample_ms * 1e-3) / 1e9, 3) if sample_ms > 0 else 0.0,
-                   "unit": "Gsamples/s", "launches_per_step": per_step["sample"][1], "avg_launch_ms": round(sample_ms / max(per_step["sample"][1], 1), 4)}
+                   "unit": "Gsamples/s", "launches_per_step": per_step["sample"][1], "avg_launch_ms": round(sample_ms / max(per_step["sample"][1], 1), 4),
+                   "traffic": None, "counter_gbs": None}
+    for cls in lines:
+        t = traffic.get(cls + "_bytes_per_launch")
+        lines[cls]["traffic"] = int(t) if t else None
+        if t:
+            lines[cls]["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % args.workload)
+            if lines[cls]["bound"] == "hbm" and lines[cls]["avg_launch_ms"] > 0:   # counter bytes / time / peak
+                lines[cls]["frac_counters"] = round(t / (lines[cls]["avg_launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    t = traffic.get("sample_bytes_per_launch")
+    if t:
+        sample_line["traffic"] = int(t)
+        sample_line["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % args.workload)
+        if sample_line["avg_launch_ms"] > 0:
+            sample_line["counter_gbs"] = round(t / (sample_line["avg_launch_ms"] * 1e-3) / 1e9, 1)
+    score_line = lines.pop("score")
+    dominant = max(lines, key=lambda c: per_step[c][0])
 
     out = {
         "metric": "train-step edges/sec (pos+neg) on 1 MI355X; SpMM achieved HBM GB/s",
@@ -577,7 +615,7 @@ def main():
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
         out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
     if not args.no_cpu_baseline and not gcn and not use_mlp:   # the oracle leg times the headline step only
-        out["cpu_baseline"] = cpu_baseline(args.cpu_scale)
+        out["cpu_baseline"] = cpu_baseline(args.workload, args.cpu_scale if args.cpu_scale else CPU_SCALE.get(args.workload, 0.1))
     print(json.dumps(out), flush=True)
 
 

@@ -69,8 +69,24 @@ def _chung_lu_weights(n_nodes: int, m: int, gamma: float, w_max: float):
     return raw * (2.0 * m / raw.sum())
 
 
+_EDGE_CACHE: Dict[tuple, tuple] = {}
+
+
 def chung_lu_edges(n_nodes: int, m: int, gamma: float, seed: int, perm_seed: int,
                    w_max: Optional[float] = None):
+    """Chung-Lu style power-law graph (the last few results are remembered per process: several workloads are
+    views of the same graph, and drawing 15 M edges takes half a minute).  Callers get fresh copies."""
+    key = (n_nodes, m, gamma, seed, perm_seed, w_max)
+    if key not in _EDGE_CACHE:
+        if len(_EDGE_CACHE) >= 2:
+            _EDGE_CACHE.pop(next(iter(_EDGE_CACHE)))
+        _EDGE_CACHE[key] = _chung_lu_edges(n_nodes, m, gamma, seed, perm_seed, w_max)
+    u, v = _EDGE_CACHE[key]
+    return u.copy(), v.copy()
+
+
+def _chung_lu_edges(n_nodes: int, m: int, gamma: float, seed: int, perm_seed: int,
+                    w_max: Optional[float] = None):
     """Chung-Lu style power-law graph.
 
     ``m`` endpoint pairs are drawn i.i.d. proportionally to the expected-degree

@@ -12,7 +12,7 @@ from lp_workloads import make_workload
 from oracle import blocks_oracle as Bk
 from oracle import lp_oracle as O
 from gpu_util import assert_close, dev_f32, dev_i32, host, make_model
-from test_gpu_parity import TOL_ACT, assert_grad_close, graph_with_hub_and_empty_rows, toy_model
+from test_gpu_parity import TOL_ACT, TOL_GRAD, graph_with_hub_and_empty_rows, toy_model
 
 
 def say(msg):
@@ -55,12 +55,10 @@ def run_case(csr_ref, g, Ws, Wn, b, X, es, ed, n_pos, fanout, seed, step):
     assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
     grads = lp.lp_backward_blocks(blocks, model, acts, ds)
     g_ref = Bk.backward_blocks(ref, Ws, Wn, a_ref, ds_ref)
-    lo = Bk.backward_blocks(ref, Ws, Wn, a_ref, ds_ref, relu_margin=5e-6)      # near-ties of the ReLU gate, as in the
-    hi = Bk.backward_blocks(ref, Ws, Wn, a_ref, ds_ref, relu_margin=-5e-6)     # full-graph gradient tests
     for k in range(K):
-        assert_grad_close(host(grads.dW_self[k]), g_ref.dW_self[k], lo.dW_self[k], hi.dW_self[k], "dW_self^%d" % (k + 1))
-        assert_grad_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], lo.dW_neigh[k], hi.dW_neigh[k], "dW_neigh^%d" % (k + 1))
-        assert_grad_close(host(grads.dbias[k]), g_ref.dbias[k], lo.dbias[k], hi.dbias[k], "dbias^%d" % (k + 1))
+        assert_close(host(grads.dW_self[k]), g_ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), g_ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
     return blocks, ref
 
 
@@ -163,14 +161,12 @@ def test_sampled_step_with_mlp_predictor(dims, fanout):
     loss_ref, ds_ref = M.bce_mean(s_ref, n_pos)
     assert_close(host(s), s_ref, TOL_ACT, "scores")
     assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * max(1.0, abs(loss_ref))
-    out = {}
-    for name, margin in (("ref", 0.0), ("lo", 5e-6), ("hi", -5e-6)):
-        _, _, _, G_ref = M.mlp_backward(a_ref.H[K], bref.e_src_pos, bref.e_dst_pos, W, ma_ref, ds_ref, relu_margin=margin)
-        out[name] = Bk.backward_blocks(bref, Ws, Wn, a_ref, None, relu_margin=margin, seed_grad=G_ref)
+    _, _, _, G_ref = M.mlp_backward(a_ref.H[K], bref.e_src_pos, bref.e_dst_pos, W, ma_ref, ds_ref)
+    out = {"ref": Bk.backward_blocks(bref, Ws, Wn, a_ref, None, seed_grad=G_ref)}
     for k in range(K):
-        assert_grad_close(host(grads.dW_self[k]), out["ref"].dW_self[k], out["lo"].dW_self[k], out["hi"].dW_self[k], "dW_self^%d" % (k + 1))
-        assert_grad_close(host(grads.dW_neigh[k]), out["ref"].dW_neigh[k], out["lo"].dW_neigh[k], out["hi"].dW_neigh[k], "dW_neigh^%d" % (k + 1))
-        assert_grad_close(host(grads.dbias[k]), out["ref"].dbias[k], out["lo"].dbias[k], out["hi"].dbias[k], "dbias^%d" % (k + 1))
+        assert_close(host(grads.dW_self[k]), out["ref"].dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), out["ref"].dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), out["ref"].dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
 
 
 # ------------------------------------------------------------------ full-neighbourhood hops and GCN layers on the blocks
@@ -223,11 +219,9 @@ def gcn_case(dims, fanout, bf16=False):
     assert_close(host(s), s_ref, TOL_ACT, "scores")
     grads = lp.lp_backward_blocks(blocks, model, acts, ds)
     g_ref = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref)
-    lo = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref, relu_margin=5e-6)
-    hi = Bk.backward_blocks_gcn(bref, inv, W, a_ref, ds_ref, relu_margin=-5e-6)
     for k in range(K):
-        assert_grad_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], lo.dW_neigh[k], hi.dW_neigh[k], "dW^%d" % (k + 1))
-        assert_grad_close(host(grads.dbias[k]), g_ref.dbias[k], lo.dbias[k], hi.dbias[k], "dbias^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), g_ref.dW_neigh[k], TOL_GRAD, "dW^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), g_ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
     return ref, g, W, b, X, es, ed, n_pos, acts, bref
 
 

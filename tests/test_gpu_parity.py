@@ -2,8 +2,11 @@
 
 Bars: CSR arrays and sampled negatives bit-exact; activations, scores and loss within 1e-4 relative;
 gradients within 1e-3 relative (per tensor, max-norm and 2-norm), all in fp32 on the GPU vs fp64 in the oracle.
-Gradient entries that hinge on a hidden unit within 5e-6 of the ReLU kink (where fp32 and fp64 may take
-different branches, both valid) get the oracle-computed width of that ambiguity as extra slack.
+Weight and bias gradients are held to that bar as they are.  Only the input gradient dX gets an allowance for ReLU
+near-ties: where the kernel's fp32 pre-activation and the oracle's fp64 one fall on different sides of zero (both
+branches are valid there), the entries of dX that hinge on such units get the oracle-computed width of that
+ambiguity as slack; the range of |z| is measured from the units that actually differ, the band may cover at most
+0.1 % of dX, and every test prints how many units differed and how much the band covers.
 """
 import numpy as np
 import pytest
@@ -194,10 +197,8 @@ def test_products_from_bfloat16_terms_across_magnitudes(x_scale, w_scale):
     ds = (rng.standard_normal(B) / B).astype(np.float32)
     grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), dev_f32(ds), want_dX=True)
     g_ref = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64))
-    margin = GATE_MARGIN * x_scale * w_scale          # the near-tie band scales with the pre-activations
-    lo = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), relu_margin=margin)
-    hi = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), relu_margin=-margin)
-    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
+    K = len(dims) - 1
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), hidden_of(acts, K)))
 
 
 def test_forward_without_row_order_and_single_node():
@@ -253,39 +254,79 @@ def test_score_loss_zero_embeddings_and_empty_batch():
 
 
 # ------------------------------------------------------------------------------------------------ backward
-GATE_MARGIN = 5e-6      # |z| below this is a near-tie of the ReLU gate for fp32 arithmetic on O(1) activations
+DX_BAND_CAP = 1e-3      # the near-tie band of dX may cover at most 0.1 % of its entries
 
 
-def gate_slack(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref):
-    """Gradient entries that depend on hidden units sitting within GATE_MARGIN of the ReLU kink: the kernel
-    takes relu'(z) = [z > 0] on its fp32 z, the oracle on its fp64 z, and for such units either branch is a
-    correct answer.  Returns |g(+margin) - g(-margin)| per tensor, computed by the oracle alone."""
-    lo = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=GATE_MARGIN)
-    hi = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=-GATE_MARGIN)
-    return lo, hi
+def dx_band(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, hidden_gpu, storage="f32"):
+    """Near-ties of the ReLU gate, for the input gradient only.  The kernel takes relu'(z) = [z > 0] on its own
+    (fp32-accumulated) pre-activation, the oracle on its fp64 one; a hidden unit whose |z| lies below the
+    accumulated rounding error may take either branch, and either is a correct answer.  The width of that range is
+    MEASURED here, not assumed: hidden_gpu[k-1] is the kernel's stored H^k (k = 1..K-1) and the margin is the largest
+    |z| of the oracle over the units where the two sides decided differently (0 when they agree everywhere, and
+    then there is no band).  Returns None, or a function that computes, per entry of dX, the oracle's
+    |dX(all such units off) - dX(all on)|.  Weight and bias gradients get no such allowance."""
+    K = len(Ws)
+    margin, flips, units = 0.0, 0, 0
+    for k in range(1, K):
+        z = acts_ref.Z[k]
+        differ = (np.asarray(hidden_gpu[k - 1]) > 0) != (z > 0)
+        flips += int(differ.sum())
+        units += z.size
+        if differ.any():
+            margin = max(margin, float(np.abs(z[differ]).max()))
+    say("  ReLU gate: %d of %d hidden units decided differently, largest |z| among them %.3e" % (flips, units, margin))
+    if flips == 0:
+        return None
+    margin = margin * (1.0 + 1e-9) + 1e-300
+
+    def width():          # two more oracle backward passes: computed only if the plain bar is missed
+        lo = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=margin, storage=storage)
+        hi = O.backward(ref_csr, Ws, Wn, acts_ref, es, ed, ds_ref, relu_margin=-margin, storage=storage)
+        return np.abs(hi.dX - lo.dX)
+    return width
 
 
-def assert_grad_close(got, ref, lo, hi, what):
+def assert_dx_close(got, ref, band, tol, what="dX", cap_on="covered"):
+    """dX against the oracle.  The plain per-tensor bar is tried first; only if it fails is the near-tie band of
+    dx_band used, and then (a) everything outside the band must meet the bar and (b) the band must stay small:
+    with cap_on="covered" the entries whose band is wider than the tolerance, with cap_on="rescued" the entries
+    that miss the plain bar and are excused by the band, may be at most DX_BAND_CAP of all entries.  (bf16
+    storage uses the second form: there the stored activations differ by whole bf16 steps, the measured range of
+    |z| is about 1e-2, so the band is wide by nature while the entries that actually move stay few.)"""
     got = np.asarray(got, np.float64)
     assert np.all(np.isfinite(got)), what
-    excess = np.maximum(np.abs(got - ref) - 2.0 * np.abs(hi - lo), 0.0)     # outside the near-tie band
+    e_max, e_l2 = rel_err(got, ref)
+    if e_max <= tol and e_l2 <= tol:
+        say("  %s meets the bar without any band (max-norm rel %.2e, 2-norm rel %.2e)" % (what, e_max, e_l2))
+        return
+    assert band is not None, "%s: max-norm rel %.3e, 2-norm rel %.3e > %.1e and no gate decision differs" % (what, e_max, e_l2, tol)
+    band = band()
+    diff = np.abs(got - ref)
+    excess = np.maximum(diff - band, 0.0)                     # outside the near-tie band
     m, l2 = np.abs(ref).max(), np.sqrt((ref * ref).sum())
-    e_max = excess.max() / m if m > 0 else excess.max()
-    e_l2 = np.sqrt((excess * excess).sum()) / l2 if l2 > 0 else np.sqrt((excess * excess).sum())
-    assert e_max <= TOL_GRAD and e_l2 <= TOL_GRAD, "%s: max-norm rel %.3e, 2-norm rel %.3e" % (what, e_max, e_l2)
-    # the band itself must be rare: it may not swallow the comparison
-    assert (np.abs(hi - lo) > TOL_GRAD * m).mean() < 0.02 if m > 0 else True, what + ": near-tie band too wide"
+    x_max = excess.max() / m if m > 0 else excess.max()
+    x_l2 = np.sqrt((excess * excess).sum()) / l2 if l2 > 0 else np.sqrt((excess * excess).sum())
+    covered = float((band > tol * m).mean())
+    rescued = float((diff > tol * m).mean())
+    say("  %s: plain errors %.2e / %.2e; near-tie band wider than the tolerance on %.4f %% of the entries, "
+        "%.4f %% of the entries miss the plain bar and lie inside it" % (what, e_max, e_l2, 100.0 * covered, 100.0 * rescued))
+    assert x_max <= tol and x_l2 <= tol, "%s outside the band: max-norm rel %.3e, 2-norm rel %.3e" % (what, x_max, x_l2)
+    share = covered if cap_on == "covered" else rescued
+    assert share <= DX_BAND_CAP, what + ": near-tie band (%s) takes %.4f %% of the entries" % (cap_on, 100.0 * share)
 
 
-def check_grads(grads, ref, K, lo=None, hi=None):
-    lo = ref if lo is None else lo
-    hi = ref if hi is None else hi
+def check_grads(grads, ref, K, dx_band_width=None):
+    """Weight and bias gradients of every layer at the plain bar; dX (when computed) with the measured near-tie band."""
     for k in range(K):
-        assert_grad_close(host(grads.dW_self[k]), ref.dW_self[k], lo.dW_self[k], hi.dW_self[k], "dW_self^%d" % (k + 1))
-        assert_grad_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], lo.dW_neigh[k], hi.dW_neigh[k], "dW_neigh^%d" % (k + 1))
-        assert_grad_close(host(grads.dbias[k]), ref.dbias[k], lo.dbias[k], hi.dbias[k], "dbias^%d" % (k + 1))
+        assert_close(host(grads.dW_self[k]), ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
+        assert_close(host(grads.dbias[k]), ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
     if grads.dX is not None:
-        assert_grad_close(host(grads.dX), ref.dX, lo.dX, hi.dX, "dX")
+        assert_dx_close(host(grads.dX), ref.dX, dx_band_width, TOL_GRAD)
+
+
+def hidden_of(acts, K, to_host=host):
+    return [to_host(acts.H[k - 1]) for k in range(1, K)]
 
 
 @pytest.mark.parametrize("dims", [[4, 8], [12, 20, 4], [64, 64, 64], [128, 256, 256, 256], [100, 132, 68], [64, 512, 8],
@@ -312,12 +353,12 @@ def test_backward_parity(dims, sym):
     a_ref = O.sage_forward(ref, Ws, Wn, b, X)
     s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
     g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
-    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
+    K = len(dims) - 1
     assert_close(host(s), s_ref, TOL_ACT, "scores")
-    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K)))
     # without dX the weight gradients are the same
     grads2 = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
-    check_grads(grads2, g_ref, len(dims) - 1, lo, hi)
+    check_grads(grads2, g_ref, K)
 
 
 @pytest.mark.parametrize("dims", [[128, 256, 256, 256], [192, 200, 232], [64, 512, 128], [48, 80, 144]])
@@ -364,8 +405,8 @@ def test_hub_rows_served_by_a_whole_workgroup(dims):
     grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
     s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
     g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref)
-    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
-    check_grads(grads, g_ref, len(dims) - 1, lo, hi)
+    K = len(dims) - 1
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K)))
     # same bits when repeated: the hub sums do not depend on which workgroup serves which row
     again = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
     assert np.array_equal(host(again.dX), host(grads.dX)) and np.array_equal(host(again.dW_neigh[0]), host(grads.dW_neigh[0]))
@@ -405,7 +446,6 @@ def run_whole_step(wl, modes=(lp.LP_FP32_PRODUCTS_BF16X6,)):
     g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
     check_csr(g, ref)
     K = len(wl.dims) - 1
-    lo, hi = gate_slack(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore)
     errs = {}
     try:
         for mode in modes:
@@ -420,7 +460,8 @@ def run_whole_step(wl, modes=(lp.LP_FP32_PRODUCTS_BF16X6,)):
             assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
             assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
             assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
-            check_grads(got.grads, exp.grads, K, lo, hi)
+            check_grads(got.grads, exp.grads, K, dx_band(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore,
+                                                         hidden_of(got.acts, K)))
             errs[mode] = (rel_err(host(got.acts.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
     finally:
         lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)

@@ -16,7 +16,7 @@ import paper_2506_20818_amd as lp
 from lp_workloads import make_workload, to_bf16_grid
 from oracle import lp_oracle as O
 from gpu_util import DEV, assert_close, dev_f32, dev_i32, host
-from test_gpu_parity import graph_with_hub_and_empty_rows, random_pairs, say, toy_model
+from test_gpu_parity import assert_dx_close, dx_band, graph_with_hub_and_empty_rows, hidden_of, random_pairs, say, toy_model
 
 TOL_ACT = 2.0 ** -7
 TOL_GRAD = 2e-2
@@ -73,13 +73,13 @@ def test_score_loss_parity_bf16(F):
     assert_close(host(ds), ds_ref, 1e-4, "dscore")
 
 
-def check_grads(grads, ref, K):
+def check_grads(grads, ref, K, dx_band_width=None):
     for k in range(K):
         assert_close(host(grads.dW_self[k]), ref.dW_self[k], TOL_GRAD, "dW_self^%d" % (k + 1))
         assert_close(host(grads.dW_neigh[k]), ref.dW_neigh[k], TOL_GRAD, "dW_neigh^%d" % (k + 1))
         assert_close(host(grads.dbias[k]), ref.dbias[k], TOL_GRAD, "dbias^%d" % (k + 1))
     if grads.dX is not None:
-        assert_close(hostf(grads.dX), ref.dX, TOL_GRAD, "dX")
+        assert_dx_close(hostf(grads.dX), ref.dX, dx_band_width, TOL_GRAD, cap_on="rescued")
 
 
 @pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24],
@@ -108,7 +108,8 @@ def test_backward_parity_bf16(dims, sym):
     g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="bf16")
     assert_close(host(s), s_ref, TOL_ACT, "scores")
     assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
-    check_grads(grads, g_ref, len(dims) - 1)
+    K = len(dims) - 1
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K, hostf), storage="bf16"))
 
 
 def whole_step_bf16(name, scale=1.0):
@@ -147,5 +148,5 @@ def test_whole_step_C1_bf16():
 
 def test_whole_step_C5_shape_one_eighth_scale():
     # one worker's share of the partitioned graph at hidden 512 and 4 negatives per positive, on the generator
-    # scaled to 1/8 so that the fp64 oracle finishes in about a minute
+    # scaled to 1/8, every element of every saved matrix (the larger scales live in test_gpu_parity_large.py)
     whole_step_bf16("C5_keep0.2", scale=0.125)

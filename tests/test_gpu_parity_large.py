@@ -1,11 +1,13 @@
 """GPU parity at the larger benchmark shapes.
 
 C3 (one worker's view of a partitioned 1 M-node graph, 3 negatives per positive): the whole step, element by
-element.  C4 (2.9 M nodes, 29 M directed entries): CSR and negatives bit-exact in full; the floating-point calls
-are checked at full size on outputs the oracle can compute one by one - sampled rows of the aggregation and of
-the layer output, every score, and the weight gradients of a one-layer model (whose loss gradient only touches
-the batch endpoints, so the oracle needs those rows alone).  C5 (bf16 storage, one worker's view of C4's graph):
-CSR bit-exact and one full-size layer with its scores and weight gradients on the rows the batch touches.
+element.  C4 (2.9 M nodes, 29 M directed entries), the configuration the benchmark times: CSR and negatives
+bit-exact in full, and the whole three-layer step against a full fp64 oracle step of the same size (every weight and
+bias gradient of every layer, every score and loss-gradient scalar, the loss, and the rows of every A^k and H^k on
+a sample of random, hub and empty rows), in both ways of forming the fp32 products; plus one-layer pieces whose
+input gradient is checked on sampled rows.  C5 (bf16 storage, hidden 512, one worker's view of C4's graph, cross
+edges kept w.p. 1.0, 0.5 and 0.2): CSR bit-exact at full size for every setting; the whole step at full size for
+keep 1.0 (the largest view, with the longest hub rows) and on the generator scaled to a quarter for the other two.
 """
 import numpy as np
 import pytest
@@ -14,10 +16,10 @@ import torch
 pytestmark = pytest.mark.gpu
 
 import paper_2506_20818_amd as lp
-from lp_workloads import init_features, make_workload
+from lp_workloads import CONFIGS, init_features, make_workload
 from oracle import lp_oracle as O
-from gpu_util import DEV, assert_close, dev_f32, dev_i32, host, make_model
-from test_gpu_parity import TOL_ACT, TOL_GRAD, check_csr, run_sampler, say, whole_step
+from gpu_util import DEV, HipStep, assert_close, dev_f32, dev_i32, host, make_model
+from test_gpu_parity import TOL_ACT, TOL_GRAD, check_csr, check_grads, run_sampler, say, whole_step
 
 
 def test_whole_step_C3_worker_view():
@@ -45,6 +47,55 @@ def sample_rows(ref, rng, n_random=1500, n_hubs=20):
     hubs = np.argsort(deg)[-n_hubs:]
     empty = np.flatnonzero(deg == 0)[:20]
     return np.unique(np.concatenate([rng.integers(0, ref.n_nodes, n_random), hubs, empty]))
+
+
+def oracle_step_in_stages(ref, Ws, Wn, bias, X, wl, storage="f32"):
+    """O.train_step written out call by call, so that a long run names the stage it is in."""
+    say("  oracle: negatives")
+    neg, _ = O.sample_neg(ref, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+    es, ed = O.batch_edges(wl.pos_src, wl.pos_dst, neg, wl.k_neg)
+    say("  oracle: forward (fp64, %d nodes)" % ref.n_nodes)
+    acts = O.sage_forward(ref, Ws, Wn, bias, X, storage)
+    s, loss, ds = O.score_loss(acts.H[-1], es, ed, wl.pos_src.size)
+    say("  oracle: backward")
+    grads = O.backward(ref, Ws, Wn, acts, es, ed, ds, storage=storage)
+    say("  oracle: done")
+    return O.StepResult(neg, es, ed, acts, s, loss, ds, grads)
+
+
+@pytest.mark.timeout(900)
+def test_whole_step_C4_full_size(c4):
+    """The configuration the benchmark times, all three layers, at full size and in the launch configuration of the
+    benchmark (same entry points, same workspaces, no dX): this is where the gated transposed aggregation over 2.9 M
+    rows with 15 000-entry hub columns, the fused weight gradients with 2.9 M reduction rows and their fold, and
+    the rotation of the backward buffers across layers are checked."""
+    wl, ref, g = c4
+    say("C4 whole step, full size: N=%d nnz=%d B=%d dims=%s" % (wl.n_nodes, ref.nnz, wl.batch_edges, wl.dims))
+    X = init_features(wl.n_nodes, wl.dims[0], CONFIGS["C4"]["seeds"]["x"])
+    exp = oracle_step_in_stages(ref, wl.W_self, wl.W_neigh, wl.bias, X, wl)
+    K = len(wl.dims) - 1
+    rng = np.random.default_rng(404)
+    rows = sample_rows(ref, rng, n_random=3000, n_hubs=40)
+    ridx = torch.from_numpy(rows).to(DEV)
+    Xd = dev_f32(X)
+    try:
+        for mode in (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE):
+            say("  fp32 products mode %d" % mode)
+            lp.lp_set_fp32_products(mode)
+            got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
+                          wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step, want_dX=False)
+            assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+            for k in range(1, K + 1):
+                assert_close(host(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], TOL_ACT, "A^%d rows" % k)
+                assert_close(host(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], TOL_ACT, "H^%d rows" % k)
+            assert bool(torch.isfinite(got.acts.H[-1]).all())
+            assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
+            assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+            assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
+            check_grads(got.grads, exp.grads, K)
+            del got
+    finally:
+        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
 
 
 @pytest.mark.parametrize("F", [128, 256])
@@ -119,48 +170,52 @@ def test_C4_score_and_one_layer_backward(c4):
     assert_close(host(grads.dX[torch.from_numpy(rows).to(DEV)]), dX_ref, TOL_GRAD, "dX rows")
 
 
-def test_C5_bf16_one_layer_full_size():
-    """C5 (one worker's view of C4's graph, cross edges kept w.p. 0.2; bf16 storage, hidden 512) at full size: CSR bit
-    exact; one 128 -> 512 layer, its scores and its weight gradients against the oracle on the rows the batch
-    touches (bf16 bars: 2^-7 on activations and scores, 2e-2 on gradients)."""
+def whole_step_bf16_sampled_rows(wl, ref, g):
+    """A bf16 whole step against the oracle (bf16 bars: 2^-7 on activations, scores and loss, 2e-2 on gradients):
+    every gradient, score and the loss; A^k and H^k on sampled, hub and empty rows."""
     from lp_workloads import to_bf16_grid
-    from test_gpu_parity_bf16 import TOL_ACT as BF_ACT, TOL_GRAD as BF_GRAD, bf16_model, dev_bf16, hostf
-    wl = make_workload("C5_keep0.2", with_features=False)
-    say("C5_keep0.2: N=%d E=%d, bf16 one layer 128->512" % (wl.n_nodes, wl.src.size))
-    ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
-    g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
-    check_csr(g, ref)
-    rng = np.random.default_rng(55)
-    N, Fi, Fo = wl.n_nodes, 128, 512
-    X = to_bf16_grid(init_features(N, Fi, 905))
-    Ws = to_bf16_grid((rng.standard_normal((Fi, Fo)) / np.sqrt(2 * Fi) * Fo ** -0.25).astype(np.float32))
-    Wn = to_bf16_grid((rng.standard_normal((Fi, Fo)) / np.sqrt(2 * Fi) * Fo ** -0.25).astype(np.float32))
-    b = rng.uniform(-0.1, 0.1, Fo).astype(np.float32)
-    neg, _ = O.sample_neg(ref, wl.pos_src, wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
-    es, ed = O.batch_edges(wl.pos_src, wl.pos_dst, neg, wl.k_neg)
-    model = bf16_model([Ws], [Wn], [b])
-    Xd = dev_bf16(X)
-    acts = lp.lp_sage_forward(g, model, Xd)
-    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), wl.n_pos)
-    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds)
-    torch.cuda.synchronize()
+    from test_gpu_parity_bf16 import TOL_ACT as BF_ACT, bf16_model, check_grads as bf_check_grads, dev_bf16, hostf
+    Ws, Wn = [to_bf16_grid(w) for w in wl.W_self], [to_bf16_grid(w) for w in wl.W_neigh]
+    X = to_bf16_grid(wl.X)
+    exp = oracle_step_in_stages(ref, Ws, Wn, wl.bias, X, wl, storage="bf16")
+    K = len(wl.dims) - 1
+    model, Xd = bf16_model(Ws, Wn, wl.bias), dev_bf16(X)
+    got = HipStep(g, model, Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst), wl.k_neg, wl.n_space, wl.sampler_seed,
+                  wl.sampler_step, want_dX=False)
+    assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+    rows = sample_rows(ref, np.random.default_rng(505), n_random=3000, n_hubs=40)
+    ridx = torch.from_numpy(rows).to(DEV)
+    for k in range(1, K + 1):
+        assert_close(hostf(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], BF_ACT, "A^%d rows" % k)
+        assert_close(hostf(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], BF_ACT, "H^%d rows" % k)
+    assert bool(torch.isfinite(got.acts.H[-1].float()).all())
+    assert_close(host(got.scores), exp.scores, BF_ACT, "scores")
+    assert abs(float(host(got.loss)[0]) - exp.loss) <= BF_ACT * abs(exp.loss)
+    bf_check_grads(got.grads, exp.grads, K)
 
-    touched = np.unique(np.concatenate([es, ed]))
-    pos_of = np.full(N, -1, np.int64)
-    pos_of[touched] = np.arange(touched.size)
-    a_t = to_bf16_grid(O.mean_aggregate(ref, X, touched).astype(np.float32)).astype(np.float64)   # A is stored as bf16
-    x_t = X[touched].astype(np.float64)
-    h_t = to_bf16_grid((x_t @ Ws.astype(np.float64) + a_t @ Wn.astype(np.float64) + b).astype(np.float32)).astype(np.float64)
-    ridx = torch.from_numpy(touched).to(DEV)
-    assert_close(hostf(acts.A[0][ridx]), a_t, BF_ACT, "A^1 rows")
-    assert_close(hostf(acts.H[0][ridx]), h_t, BF_ACT, "H^1 rows")
-    s_ref, loss_ref, ds_ref = O.score_loss(h_t, pos_of[es], pos_of[ed], wl.n_pos)
-    assert_close(host(s), s_ref, BF_ACT, "scores")
-    assert abs(float(host(loss)[0]) - loss_ref) <= BF_ACT * abs(loss_ref)
-    dZ_t = to_bf16_grid(O.edge_grad_scatter(h_t, pos_of[es], pos_of[ed], ds_ref).astype(np.float32)).astype(np.float64)
-    assert_close(host(grads.dbias[0]), dZ_t.sum(0), BF_GRAD, "dbias")
-    assert_close(host(grads.dW_self[0]), x_t.T @ dZ_t, BF_GRAD, "dW_self")
-    assert_close(host(grads.dW_neigh[0]), a_t.T @ dZ_t, BF_GRAD, "dW_neigh")
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("keep,scale", [("1", 1.0), ("0.5", 0.25), ("0.2", 0.25)])
+def test_whole_step_C5_bf16(keep, scale):
+    """One worker's share of C4's graph under a 4-way partition, cross edges kept w.p. `keep`, bf16 storage, hidden
+    512, four negatives per positive.  CSR bit-exact at full size for every setting; the whole step at `scale`."""
+    name = "C5_keep" + keep
+    full = make_workload(name, with_features=False)
+    say("%s: N=%d E=%d, CSR at full size" % (name, full.n_nodes, full.src.size))
+    ref = O.build_csr(full.n_nodes, full.src, full.dst, True)
+    g = lp.lp_build_csr(full.n_nodes, dev_i32(full.src), dev_i32(full.dst), True)
+    check_csr(g, ref)
+    if scale == 1.0:
+        wl = full
+        wl.X = init_features(wl.n_nodes, wl.dims[0], CONFIGS[name]["seeds"]["x"])
+    else:
+        del ref, g
+        wl = make_workload(name, scale=scale)
+        ref = O.build_csr(wl.n_nodes, wl.src, wl.dst, True)
+        g = lp.lp_build_csr(wl.n_nodes, dev_i32(wl.src), dev_i32(wl.dst), True)
+    say("%s whole step at scale %g: N=%d nnz=%d B=%d dims=%s max degree %d" % (
+        name, scale, wl.n_nodes, ref.nnz, wl.batch_edges, wl.dims, int(np.diff(ref.rowptr).max())))
+    whole_step_bf16_sampled_rows(wl, ref, g)
 
 
 @pytest.mark.parametrize("storage,n", [("f32", 40000), ("bf16", 40000)])
@@ -168,7 +223,7 @@ def test_hidden_512_persistent_tiles(storage, n):
     """Hidden width 512 on 40 000 nodes (enough 128-row tiles for one persistent workgroup per CU): layer transforms
     with two column tiles and the input-gradient transform of layer 2 with two outputs of 512 columns, with fp32
     products from bfloat16 terms and with bf16 storage; forward and backward against the oracle on every element."""
-    from test_gpu_parity import check_grads, gate_slack, random_pairs, toy_model
+    from test_gpu_parity import check_grads, dx_band, hidden_of, random_pairs, toy_model
     rng = np.random.default_rng(4242)
     dims = [64, 512, 512]
     r, c = random_pairs(rng, n, 120000)
@@ -186,16 +241,14 @@ def test_hidden_512_persistent_tiles(storage, n):
         model, Xd = bf16_model(Ws, Wn, b), dev_bf16(X)
         acts = lp.lp_sage_forward(g, model, Xd)
         s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
-        # (no dX here: with 2.5 M entries, single ReLU-gate flips between bf16 and fp64 pre-activations put a few of
-        # them outside the max-norm bar; the layer-2 input-gradient transform still runs)
-        grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
+        grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
         a_ref = O.sage_forward(ref, Ws, Wn, b, X, storage="bf16")
         s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
         g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="bf16")
         for k in (1, 2):
             assert_close(hostf(acts.H[k - 1]), a_ref.H[k], BF_ACT, "H^%d" % k)
         assert_close(host(s), s_ref, BF_ACT, "scores")
-        bf_check_grads(grads, g_ref, 2)
+        bf_check_grads(grads, g_ref, 2, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, 2, hostf), storage="bf16"))
     else:
         assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
         model, Xd = make_model(Ws, Wn, b), dev_f32(X)
@@ -208,8 +261,7 @@ def test_hidden_512_persistent_tiles(storage, n):
         for k in (1, 2):
             assert_close(host(acts.H[k - 1]), a_ref.H[k], TOL_ACT, "H^%d" % k)
         assert_close(host(s), s_ref, TOL_ACT, "scores")
-        lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
-        check_grads(grads, g_ref, 2, lo, hi)
+        check_grads(grads, g_ref, 2, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, 2)))
 
 
 @pytest.mark.parametrize("n,dims", [(65535, [48, 256]), (65537, [48, 256]), (65536 + 255, [64, 192, 320]), (131072 + 1, [32, 272])])
@@ -218,7 +270,7 @@ def test_row_counts_around_the_256_row_tile_switch(n, dims):
     128-row to 256-row tiles), K parts of 48, 64 and 192 values (3, 4 and 12 steps per part), output widths that
     leave the second column tile three quarters empty (320) or almost empty (272): forward and backward, every
     element against the oracle."""
-    from test_gpu_parity import check_grads, gate_slack, random_pairs, toy_model
+    from test_gpu_parity import check_grads, dx_band, hidden_of, random_pairs, toy_model
     rng = np.random.default_rng(n + sum(dims))
     r, c = random_pairs(rng, n, 3 * n)
     say("tile switch: n=%d dims=%s" % (n, dims))
@@ -239,5 +291,4 @@ def test_row_counts_around_the_256_row_tile_switch(n, dims):
     for k in range(1, K + 1):
         assert_close(host(acts.H[k - 1]), a_ref.H[k], TOL_ACT, "H^%d" % k)
     assert_close(host(s), s_ref, TOL_ACT, "scores")
-    lo, hi = gate_slack(ref, Ws, Wn, a_ref, es, ed, ds_ref)
-    check_grads(grads, g_ref, K, lo, hi)
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K)))
