@@ -249,6 +249,29 @@ int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int
                   void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * lp_score_loss_noalloc - lp_score_loss for callers that cannot allocate or hand
+ * over a workspace: code under HIP graph capture, tight serving loops that score
+ * candidate edges, harnesses that forbid hipMalloc.  Same arguments without
+ * ws/ws_bytes, same kernels, same results bit for bit.  The per-block partial
+ * sums of the loss (the only scratch of this call, 2 048 floats = 8 KiB whatever
+ * B is) live in a device array inside the library, of which every GPU the
+ * library runs on holds one copy until the process ends; the call allocates and
+ * frees nothing.  The array's device address is looked up on the first call on
+ * each device (make that call outside a graph capture).
+ * Limits: B <= LP_SCORE_LOSS_NOALLOC_MAX_EDGES, else LP_ERR_OUT_OF_RANGE (the
+ * block count, and with it the scratch, stays fixed; edges beyond the first
+ * few thousand per block are walked in a loop).  Every call on one GPU shares
+ * that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it and must be ordered by the caller; calls one after the
+ * other on a stream need nothing, every entry that is read was written by the
+ * same call.  LP_ERR_HIP if the address cannot be obtained.
+ */
+#define LP_SCORE_LOSS_NOALLOC_MAX_EDGES ((int64_t)1 << 28)
+int lp_score_loss_noalloc(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                          const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore,
+                          void *stream);
+
+/* ---------------------------------------------------------------------------
  * lp_backward - gradient of the batch loss with respect to all weights
  * (Algorithm 1, "Compute the gradient"): scatters dscore through the dot
  * product into dL/dH^K, then walks the layers K..1 through the ReLU, the two

@@ -98,6 +98,8 @@ EXPORTS = {
     "lp_score_loss_workspace_bytes": (C.c_size_t, [C.c_int64]),
     "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lp_score_loss_noalloc": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
     "lp_sparsify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64]),
     "lp_sparsify": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
@@ -347,6 +349,28 @@ def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_
         ws = _ws(lib.lp_score_loss_workspace_bytes(B), dev)
     _check(lib.lp_score_loss(_ptr(HK), HK.shape[0], HK.shape[1], _LP_OF[HK.dtype], B, n_pos_edges, _ptr(e_src), _ptr(e_dst),
                              _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(ws), ws.numel(), _stream()), "lp_score_loss")
+    return scores, loss, dscore
+
+
+def lp_score_loss_noalloc(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_pos_edges: int,
+                          scores: torch.Tensor, loss: torch.Tensor, dscore: Optional[torch.Tensor] = None):
+    """lp_score_loss without a workspace: the caller passes every output, nothing is allocated here or in the
+    library (its scratch is a device array inside the library)."""
+    lib = load_library()
+    if HK.dtype not in _LP_OF:
+        raise ValueError("HK must be float32 or bfloat16")
+    _need(HK, HK.dtype, "HK")
+    _need(e_src, torch.int32, "e_src")
+    _need(e_dst, torch.int32, "e_dst")
+    _need(scores, torch.float32, "scores")
+    _need(loss, torch.float32, "loss")
+    if dscore is not None:
+        _need(dscore, torch.float32, "dscore")
+    B = int(e_src.numel())
+    if int(e_dst.numel()) != B or int(scores.numel()) < B or (dscore is not None and int(dscore.numel()) < B) or loss.numel() < 1:
+        raise ValueError("e_dst, scores and dscore must hold one entry per edge of e_src")
+    _check(lib.lp_score_loss_noalloc(_ptr(HK), HK.shape[0], HK.shape[1], _LP_OF[HK.dtype], B, n_pos_edges, _ptr(e_src),
+                                     _ptr(e_dst), _ptr(scores), _ptr(loss), _ptr(dscore), _stream()), "lp_score_loss_noalloc")
     return scores, loss, dscore
 
 

@@ -7,10 +7,35 @@
 // the wavefront).  The loss is reduced block by block and then by one block, always in the same order.
 #include "lp_internal.h"
 
-namespace {
+#include <mutex>
 
 constexpr int kThreads = 256;
 constexpr int kMaxLossBlocks = 2048;
+
+// Scratch of lp_score_loss_noalloc: the per-block partial sums of the loss, one float per block (8 KiB).  Each GPU
+// that the library runs on holds its own copy of this array at its own address until the process ends.  In host
+// code the name below is only a stand-in for the symbol, not a device address: the address is looked up once per
+// device with hipGetSymbolAddress and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) float scratch[kMaxLossBlocks];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device); nullptr on failure.
+float *scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float *p = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 template <int G>
 __device__ inline float group_sum(float v) {
@@ -112,17 +137,23 @@ extern "C" size_t lp_score_loss_workspace_bytes(int64_t B) {
     return sizeof(float) * kMaxLossBlocks;
 }
 
-extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
-                             const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, void *ws,
-                             size_t ws_bytes, void *stream) {
+namespace {
+
+int check_score_args(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                     const int32_t *e_src, const int32_t *e_dst, const float *scores, const float *loss) {
     if (!HK || n_nodes <= 0 || F <= 0 || B < 0 || n_pos_edges < 0 || n_pos_edges > B || !loss) return LP_ERR_INVALID_ARG;
     if (B > 0 && (!e_src || !e_dst || !scores)) return LP_ERR_INVALID_ARG;
     if ((dtype != LP_F32 && dtype != LP_BF16) || F % lp_vec_elems(dtype)) return LP_ERR_UNSUPPORTED;
     if (!lp_aligned16(HK)) return LP_ERR_INVALID_ARG;
     if (B >= ((int64_t)1 << 31)) return LP_ERR_OUT_OF_RANGE;
-    if (!ws || ws_bytes < lp_score_loss_workspace_bytes(B)) return LP_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    float *partial = static_cast<float *>(ws);
+    return LP_OK;
+}
+
+// Both entry points: `partial` holds at least kMaxLossBlocks floats; the first `nb` are overwritten by the scoring
+// kernel (every block writes its sum) and only those are read by the finishing kernel, so nothing needs clearing.
+int run_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                   const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, float *partial,
+                   hipStream_t st) {
     const int G = group_lanes(F, lp_vec_elems(dtype));
     const int nb = loss_blocks(B, G);
     LpTimedScope timed(LP_KC_SCORE, st);
@@ -130,4 +161,26 @@ extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t
     else launch_score<float>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, B, loss);
     return lp_after_launch();
+}
+
+}  // namespace
+
+extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
+                             const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, void *ws,
+                             size_t ws_bytes, void *stream) {
+    LP_TRY(check_score_args(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss));
+    if (!ws || ws_bytes < lp_score_loss_workspace_bytes(B)) return LP_ERR_WORKSPACE;
+    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, static_cast<float *>(ws),
+                          static_cast<hipStream_t>(stream));
+}
+
+extern "C" int lp_score_loss_noalloc(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B,
+                                     int64_t n_pos_edges, const int32_t *e_src, const int32_t *e_dst, float *scores,
+                                     float *loss, float *dscore, void *stream) {
+    LP_TRY(check_score_args(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss));
+    if (B > LP_SCORE_LOSS_NOALLOC_MAX_EDGES) return LP_ERR_OUT_OF_RANGE;
+    float *partial = scratch_of_current_device();   // the device address, never the array's name
+    if (!partial) return LP_ERR_HIP;
+    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, partial,
+                          static_cast<hipStream_t>(stream));
 }
