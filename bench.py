@@ -163,7 +163,7 @@ def sampled_step_task(args):
     from paper_2506_20818_amd import binding as B
     from lp_workloads import make_workload
 
-    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6)
+    products = lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = make_workload(args.workload)
@@ -171,10 +171,10 @@ def sampled_step_task(args):
     f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
     g = lp.lp_build_csr(wl.n_nodes, i32(wl.src), i32(wl.dst), True)
     bf16 = wl.dtype == "bf16"
-    split = (not bf16) and lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
+    split = (not bf16) and products == lp.LP_FP32_PRODUCTS_BF16X6
     tdt = torch.bfloat16 if bf16 else torch.float32
     st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32
-    model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+    model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias], fp32_products=products)
     X = st(wl.X)
     n_pos = min(args.n_pos, wl.n_pos)
     k_neg = wl.k_neg
@@ -326,7 +326,7 @@ def main():
     ap.add_argument("--predictor", default="dot", choices=["dot", "mlp"],
                     help="--task train_step: dot-product scorer (the headline) or the 3-layer MLP edge predictor")
     ap.add_argument("--fp32-products", default="bf16x6", choices=["bf16x6", "native"],
-                    help="how fp32 models form their dense products (see lp_set_fp32_products in include/lp.h)")
+                    help="how fp32 models form their dense products (the fp32_products field of lp_model in include/lp.h)")
     ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
     ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
     ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
@@ -352,7 +352,7 @@ def main():
     from paper_2506_20818_amd import binding as B
     from lp_workloads import make_workload
 
-    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6)
+    products = lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     wl = make_workload(args.workload)
@@ -373,13 +373,14 @@ def main():
     build_s = time.perf_counter() - t0
 
     bf16 = wl.dtype == "bf16"
-    split = (not bf16) and lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
+    split = (not bf16) and products == lp.LP_FP32_PRODUCTS_BF16X6
     tdt = torch.bfloat16 if bf16 else torch.float32
     st = (lambda a: f32(a).to(torch.bfloat16)) if bf16 else f32      # storage type of features and weights
     if gcn:
-        model = lp.Model(None, [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias], layer_type=lp.LP_LAYER_GCN)
+        model = lp.Model(None, [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias], layer_type=lp.LP_LAYER_GCN, fp32_products=products)
     else:
-        model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias])
+        model = lp.Model([st(w) for w in wl.W_self], [st(w) for w in wl.W_neigh], [f32(b) for b in wl.bias], fp32_products=products)
+    models = {"timed": model}
     X = st(wl.X)
     n_pos, k_neg, Bn = wl.n_pos, wl.k_neg, wl.batch_edges
     pos_src = i32(wl.pos_src)
@@ -389,7 +390,7 @@ def main():
         F = wl.dims[-1]
         md = [F, F, F, 1]
         mlp = lp.Mlp([st((rng.standard_normal((md[j], md[j + 1])) / np.sqrt(md[j])).astype(np.float32)) for j in range(3)],
-                     [f32(rng.uniform(-0.1, 0.1, md[j + 1]).astype(np.float32)) for j in range(3)])
+                     [f32(rng.uniform(-0.1, 0.1, md[j + 1]).astype(np.float32)) for j in range(3)], fp32_products=products)
         macts, mgrads = lp.MlpActs(mlp, Bn, dev), lp.MlpGrads(mlp, dev)
     e_src = torch.empty(Bn, dtype=torch.int32, device=dev)
     e_dst = torch.empty(Bn, dtype=torch.int32, device=dev)
@@ -405,7 +406,8 @@ def main():
     dscore = torch.empty(Bn, dtype=torch.float32, device=dev)
     loss = torch.zeros(1, dtype=torch.float32, device=dev)
 
-    def step(i):
+    def step(i, which="timed"):
+        model = models[which]
         lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
         lp.lp_sage_forward(g, model, X, acts, ws_f)
         if mlp is None:
@@ -476,18 +478,16 @@ def main():
 
     # for reference, the same steps with the other way of forming the fp32 products (outside the timed region)
     other_products = None
-    if not bf16:
-        was = lp.lp_get_fp32_products()
-        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE if split else lp.LP_FP32_PRODUCTS_BF16X6)
+    if not bf16 and mlp is None:   # the same weight tensors as a second model with the other value of fp32_products
+        models["other"] = model.with_products(lp.LP_FP32_PRODUCTS_NATIVE if split else lp.LP_FP32_PRODUCTS_BF16X6)
         for i in range(3):
-            step(3000 + i)
+            step(3000 + i, "other")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
-            step(2000 + i)      # the batches of the timed region: the last loss is comparable with "loss"
+            step(2000 + i, "other")      # the batches of the timed region: the last loss is comparable with "loss"
         torch.cuda.synchronize()
         oms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
-        lp.lp_set_fp32_products(was)
         other_products = {"fp32_products": fp32_products_name(False, not split), "ms_per_step_without_events": round(oms, 4),
                           "value": round(Bn / (oms * 1e-3), 1), "loss": round(float(loss.item()), 6)}
 

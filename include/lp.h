@@ -24,8 +24,9 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued on it and, except for lp_build_csr, the call returns
  *    without waiting.
- *  - Apart from the benchmark instrumentation at the end of this file the
- *    library keeps no state between calls.
+ *  - Apart from the benchmark instrumentation at the end of this file (and
+ *    the fixed scratch array of lp_score_loss_noalloc) the library keeps no
+ *    state between calls.
  *  - Return value: LP_OK or a negative LP_ERR_* code.  Arguments are checked on
  *    the host before anything is launched; a call that returns an error other
  *    than LP_ERR_HIP has launched nothing.  No exception crosses this ABI.
@@ -60,6 +61,32 @@ enum {
     LP_F32 = 0, /* fp32 storage */
     LP_BF16 = 1 /* bfloat16 storage (features, weights, activations), fp32 accumulation, fp32 gradients */
 };
+
+/* How the dense products of an fp32 model are formed (Eq. 1's UPDATE and its
+ * gradients; the paper fixes no arithmetic): the `fp32_products` field of
+ * lp_model and lp_mlp, a property of each call.  Storage, accumulation and every
+ * result are fp32 in both modes; models with bf16 storage ignore the field.
+ *   LP_FP32_PRODUCTS_NATIVE (0, what a zero-initialised struct selects): the
+ *     fp32 matrix instructions; IEEE behaviour for every input.
+ *   LP_FP32_PRODUCTS_BF16X6: each fp32 operand value is written as the exact sum
+ *     of three bfloat16 terms and a product is taken as the six largest of the
+ *     nine term products on the bf16 matrix cores, accumulated in fp32.  What is
+ *     left out is below 2^-26 of each product, a quarter of one fp32 rounding;
+ *     measured against fp64 the results are as close as those of the fp32
+ *     matrix instructions, at 6/16 of their issue time.  Contract of this mode:
+ *     every finite fp32 input is split exactly (magnitudes in the last half
+ *     bfloat16 step below the fp32 maximum included); a non-finite input makes
+ *     every result that depends on it non-finite (NaN where the fp32
+ *     instructions might give an infinity); term products below the smallest
+ *     normal fp32 (1.2e-38) are flushed to zero, so products smaller than about
+ *     1e-33 lose the accuracy of their small terms.  Products whose shape the
+ *     bf16-term kernels do not take (an inner dimension that is not a multiple
+ *     of 16, outputs narrower than 65 columns, fused weight gradients below
+ *     192 x 192) use the fp32 matrix instructions in this mode too.
+ * Another value is rejected with LP_ERR_INVALID_ARG by every call that takes the
+ * struct. */
+#define LP_FP32_PRODUCTS_NATIVE 0
+#define LP_FP32_PRODUCTS_BF16X6 1
 
 /* layer types of lp_model */
 enum {
@@ -99,6 +126,8 @@ typedef struct lp_model {
     int32_t dtype;                        /* LP_F32 or LP_BF16: storage of X, W_self, W_neigh, A and H */
     int32_t dims[LP_MAX_LAYERS + 1];      /* F_0 .. F_K */
     int32_t layer_type;                   /* LP_LAYER_SAGE_MEAN or LP_LAYER_GCN */
+    int32_t fp32_products;                /* LP_FP32_PRODUCTS_*: how an LP_F32 model multiplies (ignored with LP_BF16) */
+    int32_t reserved_;                    /* must be 0 */
     const void *W_self[LP_MAX_LAYERS];    /* device [F_{k-1}, F_k] */
     const void *W_neigh[LP_MAX_LAYERS];   /* device [F_{k-1}, F_k] */
     const void *bias[LP_MAX_LAYERS];      /* device [F_k], always fp32 */
@@ -148,7 +177,7 @@ typedef struct lp_mlp {
     int32_t n_layers;                       /* L, 1..LP_MAX_MLP_LAYERS */
     int32_t dtype;                          /* LP_F32 or LP_BF16: storage of W, of the products and of the hidden layers */
     int32_t dims[LP_MAX_MLP_LAYERS + 1];
-    int32_t reserved_;
+    int32_t fp32_products;                  /* LP_FP32_PRODUCTS_*: as in lp_model */
     const void *W[LP_MAX_MLP_LAYERS];       /* device [dims[j], dims[j+1]] */
     const float *bias[LP_MAX_MLP_LAYERS];   /* device [dims[j+1]], fp32 */
 } lp_mlp;
@@ -454,32 +483,6 @@ int lp_backward_edge_grads(const lp_csr *g, const lp_model *m, const void *X, co
                            size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
- * How the dense products of an fp32 model are formed (Eq. 1's UPDATE and its
- * gradients; the paper fixes no arithmetic).  Storage, accumulation and every
- * result stay fp32 in both modes.
- *   LP_FP32_PRODUCTS_BF16X6 (default): each fp32 operand value is written as the
- *     exact sum of three bfloat16 terms and a product is taken as the six largest
- *     of the nine term products on the bf16 matrix cores, accumulated in fp32.
- *     What is left out is below 2^-26 of each product, a quarter of one fp32
- *     rounding; measured against fp64 the results are as close as those of the
- *     fp32 matrix instructions, at 6/16 of their issue time.  Range: non-finite
- *     inputs, and magnitudes above the largest bfloat16 (3.39e38), give NaN where
- *     the fp32 instructions would give an infinity or a finite value; term
- *     products below the smallest normal fp32 (1.2e-38) are flushed to zero, so
- *     products smaller than about 1e-33 lose the accuracy of their small terms.
- *     Products whose shape the bf16-term kernels do not take (an inner dimension
- *     that is not a multiple of 16, outputs narrower than 65 columns, fused weight
- *     gradients below 192 x 192) use the fp32 matrix instructions in this mode too.
- *   LP_FP32_PRODUCTS_NATIVE: fp32 matrix instructions.
- * Process-wide, read at every launch; returns LP_ERR_INVALID_ARG for another
- * value.  bf16 models are not affected.
- */
-#define LP_FP32_PRODUCTS_NATIVE 0
-#define LP_FP32_PRODUCTS_BF16X6 1
-int lp_set_fp32_products(int mode);
-int lp_get_fp32_products(void);
-
-/* ---------------------------------------------------------------------------
  * Instrumentation for benchmarks (not part of the method).  While enabled, each
  * kernel launch made by the calls above is bracketed by two HIP events on the
  * launch stream (lp_timing_enable(1): all classes but LP_KC_OTHER, whose small
@@ -487,7 +490,7 @@ int lp_get_fp32_products(void);
  * every launch; 0: off).  lp_timing_collect waits for the recorded events, writes the
  * summed milliseconds and launch counts per kernel class (arrays of at least
  * LP_KC_COUNT entries) and forgets them.  Off by default.  Process-wide state
- * (with lp_set_fp32_products the only one of the library), guarded by a mutex.
+ * (the only switch the library keeps), guarded by a mutex.
  */
 enum {
     LP_KC_SPMM = 0,     /* CSR mean aggregation, forward and transposed */

@@ -16,6 +16,8 @@ LP_F32 = 0
 LP_BF16 = 1
 LP_LAYER_SAGE_MEAN = 0
 LP_LAYER_GCN = 1
+LP_FP32_PRODUCTS_NATIVE = 0
+LP_FP32_PRODUCTS_BF16X6 = 1
 
 _TORCH_OF = {LP_F32: torch.float32, LP_BF16: torch.bfloat16}
 _LP_OF = {torch.float32: LP_F32, torch.bfloat16: LP_BF16}
@@ -38,7 +40,7 @@ class _CsrStruct(C.Structure):
 
 class _ModelStruct(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("dtype", C.c_int32), ("dims", C.c_int32 * (LP_MAX_LAYERS + 1)),
-                ("layer_type", C.c_int32),
+                ("layer_type", C.c_int32), ("fp32_products", C.c_int32), ("reserved_", C.c_int32),
                 ("W_self", C.c_void_p * LP_MAX_LAYERS), ("W_neigh", C.c_void_p * LP_MAX_LAYERS),
                 ("bias", C.c_void_p * LP_MAX_LAYERS)]
 
@@ -58,7 +60,7 @@ LP_MAX_MLP_LAYERS = 4
 
 class _MlpStruct(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("dtype", C.c_int32), ("dims", C.c_int32 * (LP_MAX_MLP_LAYERS + 1)),
-                ("reserved_", C.c_int32), ("W", C.c_void_p * LP_MAX_MLP_LAYERS), ("bias", C.c_void_p * LP_MAX_MLP_LAYERS)]
+                ("fp32_products", C.c_int32), ("W", C.c_void_p * LP_MAX_MLP_LAYERS), ("bias", C.c_void_p * LP_MAX_MLP_LAYERS)]
 
 
 class _MlpActsStruct(C.Structure):
@@ -137,8 +139,6 @@ EXPORTS = {
     "lp_adam_step": (C.c_int, [C.POINTER(_ModelStruct), C.POINTER(_GradsStruct), C.POINTER(_OptStateStruct), C.c_int64,
                                C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
     "lp_timing_enable": (C.c_int, [C.c_int]),
-    "lp_set_fp32_products": (C.c_int, [C.c_int]),
-    "lp_get_fp32_products": (C.c_int, []),
     "lp_timing_collect": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int32]),
     "lp_backward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                               C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_GradsStruct), C.c_void_p,
@@ -214,8 +214,11 @@ class Model:
     the storage type of the whole model) and bias[k] of shape [F_k] (always float32)."""
 
     def __init__(self, W_self: Optional[List[torch.Tensor]], W_neigh: List[torch.Tensor], bias: List[torch.Tensor],
-                 layer_type: int = LP_LAYER_SAGE_MEAN):
-        """layer_type LP_LAYER_GCN: one weight matrix per layer (given as W_neigh), W_self is None."""
+                 layer_type: int = LP_LAYER_SAGE_MEAN, fp32_products: int = LP_FP32_PRODUCTS_BF16X6):
+        """layer_type LP_LAYER_GCN: one weight matrix per layer (given as W_neigh), W_self is None.
+        fp32_products: how a float32 model forms its dense products (the `fp32_products` field of lp_model; this
+        binding fills in the bfloat16-term mode unless told otherwise, a zeroed C struct means the fp32 matrix
+        instructions); ignored for bfloat16 models."""
         K = len(W_neigh)
         gcn = layer_type == LP_LAYER_GCN
         if W_self is None:
@@ -223,6 +226,7 @@ class Model:
         if not (1 <= K <= LP_MAX_LAYERS and len(W_self) == K and len(bias) == K):
             raise ValueError("bad layer count")
         self.layer_type = layer_type
+        self.fp32_products = int(fp32_products)
         self.W_self, self.W_neigh, self.bias = list(W_self), list(W_neigh), list(bias)
         self.dims = [int(W_neigh[0].shape[0])] + [int(w.shape[1]) for w in W_neigh]
         self.torch_dtype = W_neigh[0].dtype
@@ -230,7 +234,7 @@ class Model:
             raise ValueError("weights must be float32 or bfloat16")
         self.dtype = _LP_OF[self.torch_dtype]
         s = _ModelStruct()
-        s.n_layers, s.dtype, s.layer_type = K, self.dtype, layer_type
+        s.n_layers, s.dtype, s.layer_type, s.fp32_products = K, self.dtype, layer_type, self.fp32_products
         for k in range(K + 1):
             s.dims[k] = self.dims[k]
         for k in range(K):
@@ -244,6 +248,10 @@ class Model:
             s.W_self[k] = W_self[k].data_ptr() if W_self[k] is not None else None
             s.W_neigh[k], s.bias[k] = W_neigh[k].data_ptr(), bias[k].data_ptr()
         self.c = s
+
+    def with_products(self, fp32_products: int) -> "Model":
+        """The same weight tensors as a model that forms its fp32 products the other way."""
+        return Model(self.W_self if self.layer_type != LP_LAYER_GCN else None, self.W_neigh, self.bias, self.layer_type, fp32_products)
 
 
 class Acts:
@@ -522,7 +530,7 @@ class Mlp:
     """Weights of the MLP edge predictor: W[j] of shape [dims[j], dims[j+1]] (float32 or bfloat16), the last one
     [dims[L-1], 1]; bias[j] of shape [dims[j+1]] (float32)."""
 
-    def __init__(self, W: List[torch.Tensor], bias: List[torch.Tensor]):
+    def __init__(self, W: List[torch.Tensor], bias: List[torch.Tensor], fp32_products: int = LP_FP32_PRODUCTS_BF16X6):
         L = len(W)
         if not (1 <= L <= LP_MAX_MLP_LAYERS and len(bias) == L):
             raise ValueError("bad layer count")
@@ -531,7 +539,7 @@ class Mlp:
         self.torch_dtype = W[0].dtype
         self.dtype = _LP_OF[self.torch_dtype]
         s = _MlpStruct()
-        s.n_layers, s.dtype = L, self.dtype
+        s.n_layers, s.dtype, s.fp32_products = L, self.dtype, int(fp32_products)
         for j in range(L + 1):
             s.dims[j] = self.dims[j]
         for j in range(L):
@@ -691,19 +699,6 @@ def backward_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:
 
 def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
     return int(load_library().lp_sage_forward_workspace_bytes(C.byref(m.c), n_nodes))
-
-
-LP_FP32_PRODUCTS_NATIVE = 0
-LP_FP32_PRODUCTS_BF16X6 = 1
-
-
-def lp_set_fp32_products(mode: int) -> None:
-    """How fp32 models multiply matrices: LP_FP32_PRODUCTS_BF16X6 (default) or LP_FP32_PRODUCTS_NATIVE.  Process-wide."""
-    _check(load_library().lp_set_fp32_products(int(mode)), "lp_set_fp32_products")
-
-
-def lp_get_fp32_products() -> int:
-    return int(load_library().lp_get_fp32_products())
 
 
 KERNEL_CLASSES = ["spmm", "gemm_nt", "gemm_tn", "scatter", "score", "sample", "other"]

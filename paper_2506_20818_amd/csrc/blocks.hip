@@ -230,6 +230,7 @@ int check_block_model(const lp_model *m, const lp_blocks *b) {
     if (!m || m->n_layers != b->n_layers) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
+    if (!lp_valid_fp32_products(m->fp32_products) || m->reserved_ != 0) return LP_ERR_INVALID_ARG;
     const bool gcn = m->layer_type == LP_LAYER_GCN;   // a single weight matrix (W_neigh) per layer
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
@@ -491,6 +492,7 @@ extern "C" int lp_sage_forward_blocks(const lp_blocks *b, const lp_model *m, con
         wt += 2 * wbytes;
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = m->fp32_products;
         ge.M = b->cap[k]; ge.m_dev = b->n + k;
         ge.N = Fo; ge.n_split = Fo;
         ge.A[0] = Hprev; ge.A[1] = saved->A[k - 1];   // a frontier is a prefix of the one before: row i is node i in both
@@ -566,6 +568,7 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
         const int32_t *rows_dev = b->n + k;
         WeightGradArgs wg;
         wg.dtype = dt;
+        wg.fp32_products = m->fp32_products;
         wg.Kn = rows; wg.kn_dev = rows_dev;
         if (!gcn) { wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1]; }   // rows 0..n_k-1 of the wider frontier are the same nodes
         wg.At[1] = saved->A[k - 1]; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW_neigh[k - 1];
@@ -576,6 +579,7 @@ int backward_blocks_impl(const lp_blocks *b, const lp_model *m, const void *X_fr
         if (k == 1) break;
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = m->fp32_products;
         ge.M = rows; ge.m_dev = rows_dev;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
         ge.ldb[0] = Fo;

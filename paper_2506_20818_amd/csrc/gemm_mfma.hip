@@ -234,15 +234,26 @@ __device__ __forceinline__ void lp_unrolled(F &&f) {
 
 // fp32 values as sums of three bfloat16 terms (SPLIT variant of the kernel below).  t0 = bf16(x), t1 = bf16(x - t0),
 // t2 = bf16(x - t0 - t1), every rounding to nearest: the remainders are exact in fp32 and the last one fits in eight
-// bits, so t0 + t1 + t2 == x for every finite x whose last term is not subnormal.  A product x*y is then the sum of
+// bits, so t0 + t1 + t2 == x for every finite x whose last term is not subnormal.  (Rounding the few values within
+// half a bfloat16 step of the fp32 maximum would give an infinite t0 and with it NaN terms; t0 is therefore held at
+// the largest finite bfloat16, which leaves an exactly representable remainder.  Non-finite x still yield non-finite
+// terms: infinity - t0 and NaN - t0 propagate through t1.)  A product x*y is then the sum of
 // nine exact bf16 products, of which the three smallest (t1*u2, t2*u1, t2*u2: below 2^-26 of |x*y|) are left out; the
 // other six run on the bf16 matrix cores with fp32 accumulation.  Measured against fp64, the result is as close as
 // the fp32 MFMA's (both are dominated by the fp32 accumulation), at 6/16 of its issue time.
+// Magnitudes of a bfloat16 pair held at the largest finite value 0x7f7f (signs kept).
+__device__ __forceinline__ uint32_t lp_finite_bf16x2(uint32_t p) {
+    typedef unsigned short lp_us2 __attribute__((ext_vector_type(2)));
+    const lp_us2 mag = __builtin_bit_cast(lp_us2, p & 0x7fff7fffu);
+    const lp_us2 cap = __builtin_elementwise_min(mag, lp_us2{0x7f7f, 0x7f7f});
+    return (p & 0x80008000u) | __builtin_bit_cast(uint32_t, cap);
+}
+
 // Four consecutive values of a row -> the 8-byte pieces of the three term planes.
 __device__ __forceinline__ void lp_split3(const v4i &v, uint2 &t0, uint2 &t1, uint2 &t2) {
     const v4f x = __builtin_bit_cast(v4f, v);
     float r[4];
-    t0 = make_uint2(lp_f32x2_to_bf16x2(x[0], x[1]), lp_f32x2_to_bf16x2(x[2], x[3]));
+    t0 = make_uint2(lp_finite_bf16x2(lp_f32x2_to_bf16x2(x[0], x[1])), lp_finite_bf16x2(lp_f32x2_to_bf16x2(x[2], x[3])));
     r[0] = x[0] - __uint_as_float(t0.x << 16);
     r[1] = x[1] - __uint_as_float(t0.x & 0xffff0000u);
     r[2] = x[2] - __uint_as_float(t0.y << 16);
@@ -1716,18 +1727,6 @@ int lp_compute_units() {
     return cus;
 }
 
-// How fp32 matrices are multiplied: LP_FP32_PRODUCTS_BF16X6 (three-term bfloat16 splitting on the bf16 matrix cores)
-// or LP_FP32_PRODUCTS_NATIVE (fp32 MFMA).  Process-wide; read at every launch.
-static std::atomic<int> g_fp32_products{LP_FP32_PRODUCTS_BF16X6};
-
-extern "C" int lp_set_fp32_products(int mode) {
-    if (mode != LP_FP32_PRODUCTS_NATIVE && mode != LP_FP32_PRODUCTS_BF16X6) return LP_ERR_INVALID_ARG;
-    g_fp32_products.store(mode);
-    return LP_OK;
-}
-
-extern "C" int lp_get_fp32_products(void) { return g_fp32_products.load(); }
-
 int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return LP_OK;
     for (int s = 0; s < 2; ++s) {
@@ -1778,7 +1777,7 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64>), pgrid, dim3(256), 0, st, a);
         if (bf16) {
             LP_NT_FAST(lp_bf16_t)
-        } else if (g_fp32_products.load() == LP_FP32_PRODUCTS_BF16X6) {
+        } else if (a.fp32_products == LP_FP32_PRODUCTS_BF16X6) {
             // sixteen values of a row per K step; 256-row tiles once they fill every compute unit
             if (fast_bn == 256 && lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units()) {
                 const int64_t rt = lp_ceil_div(a.M, 256);
@@ -1895,7 +1894,7 @@ int lp_launch_weight_grads(const WeightGradArgs &a, hipStream_t st) {
         if (bf16) {
             if (a.at_index) hipLaunchKernelGGL(weight_grads_bf16_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
             else hipLaunchKernelGGL(weight_grads_bf16_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
-        } else if (g_fp32_products.load() == LP_FP32_PRODUCTS_BF16X6) {
+        } else if (a.fp32_products == LP_FP32_PRODUCTS_BF16X6) {
             if (a.at_index) hipLaunchKernelGGL(weight_grads_split_kernel<true>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
             else hipLaunchKernelGGL(weight_grads_split_kernel<false>, dim3(grid), dim3(WG_THREADS), 0, st, a, p.chunk, p.splits, p.tiles_n, p.tiles);
         } else {

@@ -23,6 +23,7 @@ static inline int lp_after_launch() { return hipGetLastError() == hipSuccess ? L
 static inline int64_t lp_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t lp_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 static inline bool lp_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline bool lp_valid_fp32_products(int32_t v) { return v == LP_FP32_PRODUCTS_NATIVE || v == LP_FP32_PRODUCTS_BF16X6; }
 
 // ---------------------------------------------------------------- instrumentation (lp_timing.hip)
 // Kernel classes of lp_timing_collect, in the order of LP_KC_* in lp.h.
@@ -90,6 +91,7 @@ int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
 // rowscale[m] (optional) and go to C[1] (leading dimension ldc[1]) at column n - n_split, the others to C[0].
 struct GemmNtArgs {
     int32_t dtype = LP_F32;              // storage of A, Bt and C (bias and rowscale are always fp32)
+    int32_t fp32_products = LP_FP32_PRODUCTS_NATIVE;   // LP_F32 only: fp32 matrix instructions or bfloat16 terms
     int32_t M = 0, N = 0;
     int32_t n_split = 0;                 // == N when the output is not split
     const void *A[2] = {nullptr, nullptr};
@@ -133,6 +135,7 @@ int lp_launch_gemm_tn(const GemmTnArgs &a, hipStream_t stream);
 // lp_launch_colsum.  Sums are taken in a fixed order.
 struct WeightGradArgs {
     int32_t dtype = LP_F32;
+    int32_t fp32_products = LP_FP32_PRODUCTS_NATIVE;   // LP_F32 only, as in GemmNtArgs
     int32_t Kn = 0;
     const int32_t *kn_dev = nullptr;
     const int32_t *at_index = nullptr;

@@ -16,6 +16,7 @@ constexpr int kMaxLossBlocks = 2048;
 int check_mlp(const lp_mlp *p) {
     if (!p || p->n_layers < 1 || p->n_layers > LP_MAX_MLP_LAYERS) return LP_ERR_INVALID_ARG;
     if (p->dtype != LP_F32 && p->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (!lp_valid_fp32_products(p->fp32_products)) return LP_ERR_INVALID_ARG;
     const int L = p->n_layers;
     if (p->dims[L] != 1) return LP_ERR_INVALID_ARG;
     for (int j = 0; j < L; ++j) {
@@ -273,6 +274,7 @@ extern "C" int lp_mlp_score_loss(const void *HK, int32_t n_nodes, int64_t B, int
         LP_TRY(lp_launch_transpose(p->W[j - 1], Fi, Fo, WT, dt, st));
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = p->fp32_products;
         ge.M = (int32_t)B; ge.N = Fo; ge.n_split = Fo;
         ge.A[0] = Uprev; ge.lda[0] = Fi; ge.K[0] = Fi;
         ge.Bt[0][0] = WT; ge.ldb[0] = Fi;
@@ -348,6 +350,7 @@ extern "C" int lp_mlp_backward(const lp_mlp *p, const lp_mlp_acts *saved, int64_
         const void *Uin = j > 1 ? saved->U[j - 2] : saved->X;
         WeightGradArgs wg;   // dW_j = U_{j-1}^T dZ and db_j = column sums of dZ in one pass
         wg.dtype = dt;
+        wg.fp32_products = p->fp32_products;
         wg.Kn = (int32_t)B;
         wg.At[1] = Uin; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW[j - 1];
         wg.B = dZ; wg.Nw = Fo; wg.ldb = Fo;
@@ -357,6 +360,7 @@ extern "C" int lp_mlp_backward(const lp_mlp *p, const lp_mlp_acts *saved, int64_
         void *dst = j > 1 ? other : edge_grad;
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = p->fp32_products;
         ge.M = (int32_t)B; ge.N = Fi; ge.n_split = Fi;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
         ge.Bt[0][0] = p->W[j - 1]; ge.ldb[0] = Fo;   // W_j is [Fi, Fo]: row n of it is the n-th row of W_j^T's transpose operand

@@ -57,6 +57,7 @@ int fill_table(const lp_model *m, const lp_grads *g, const lp_opt_state *s, bool
     if (!m || !g || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
+    if (!lp_valid_fp32_products(m->fp32_products) || m->reserved_ != 0) return LP_ERR_INVALID_ARG;
     if (need_state && !s) return LP_ERR_INVALID_ARG;
     t.count = 0;
     n_max = 0;

@@ -10,6 +10,7 @@ int check_model(const lp_model *m) {
     if (!m || m->n_layers < 1 || m->n_layers > LP_MAX_LAYERS) return LP_ERR_INVALID_ARG;
     if (m->dtype != LP_F32 && m->dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
     if (m->layer_type != LP_LAYER_SAGE_MEAN && m->layer_type != LP_LAYER_GCN) return LP_ERR_UNSUPPORTED;
+    if (!lp_valid_fp32_products(m->fp32_products) || m->reserved_ != 0) return LP_ERR_INVALID_ARG;
     const bool has_self = m->layer_type == LP_LAYER_SAGE_MEAN;
     for (int k = 0; k <= m->n_layers; ++k) {
         if (m->dims[k] <= 0) return LP_ERR_INVALID_ARG;
@@ -192,6 +193,7 @@ extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X
         wt += 2 * wbytes;
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = m->fp32_products;
         ge.M = g->n_nodes;
         ge.N = Fo;
         ge.n_split = Fo;
@@ -286,6 +288,7 @@ static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, cons
         const int32_t *row_of = listed ? w.touched : nullptr;
         WeightGradArgs wg;
         wg.dtype = dt;
+        wg.fp32_products = m->fp32_products;
         wg.Kn = rows; wg.kn_dev = rows_dev; wg.at_index = row_of;
         if (!gcn) { wg.At[0] = Hin; wg.Mw[0] = Fi; wg.lda[0] = Fi; wg.C[0] = out->dW_self[k - 1]; }
         wg.At[1] = Ak; wg.Mw[1] = Fi; wg.lda[1] = Fi; wg.C[1] = out->dW_neigh[k - 1];
@@ -296,6 +299,7 @@ static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, cons
         if (k == 1 && !out->dX) break;
         GemmNtArgs ge;
         ge.dtype = dt;
+        ge.fp32_products = m->fp32_products;
         ge.M = rows; ge.m_dev = rows_dev;
         ge.A[0] = dZ; ge.lda[0] = Fo; ge.K[0] = Fo;
         ge.ldb[0] = Fo;

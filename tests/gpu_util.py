@@ -41,8 +41,9 @@ def assert_close(got, ref, tol, what):
     assert e_max <= tol and e_l2 <= tol, "%s: max-norm rel %.3e, 2-norm rel %.3e > %.1e" % (what, e_max, e_l2, tol)
 
 
-def make_model(W_self, W_neigh, bias):
-    return lp.Model([dev_f32(w) for w in W_self], [dev_f32(w) for w in W_neigh], [dev_f32(b) for b in bias])
+def make_model(W_self, W_neigh, bias, products=lp.LP_FP32_PRODUCTS_BF16X6):
+    return lp.Model([dev_f32(w) for w in W_self], [dev_f32(w) for w in W_neigh], [dev_f32(b) for b in bias],
+                    fp32_products=products)
 
 
 class HipStep:

@@ -30,9 +30,9 @@ def test_strerror_covers_all_codes():
     assert len(texts) == 6 and B.lp_strerror(-99) == "unknown status"
 
 
-def _model(dims, dtype=0, null_w=False):
+def _model(dims, dtype=0, null_w=False, products=0):
     m = B._ModelStruct()
-    m.n_layers, m.dtype = len(dims) - 1, dtype
+    m.n_layers, m.dtype, m.fp32_products = len(dims) - 1, dtype, products
     for i, d in enumerate(dims):
         m.dims[i] = d
     for k in range(len(dims) - 1):
@@ -96,6 +96,13 @@ def test_forward_backward_reject_bad_arguments_on_the_host():
     assert fwd(m=_model([128, 254])) == -4            # width not a multiple of 4
     assert fwd(m=_model([128, 2048])) == -4
     assert fwd(m=_model([128, 256], null_w=True)) == -1
+    # the way of forming fp32 products is a field of the model, checked on every call
+    assert fwd(m=_model([128, 256], products=2)) == -1 and fwd(m=_model([128, 256], products=-1)) == -1
+    assert fwd(m=_model([128, 256], dtype=1, products=7)) == -1          # checked for bf16 models too
+    nonzero_reserved = _model([128, 256])
+    nonzero_reserved.reserved_ = 1
+    assert fwd(m=nonzero_reserved) == -1
+    assert lib.lp_sage_forward_workspace_bytes(C.byref(_model([128, 256], products=3)), 1000) == 0
     assert fwd(x=None) == -1
     assert fwd(x=C.c_void_p(0x1004)) == -1            # misaligned features
     assert fwd(ws=None) == -3
@@ -333,13 +340,19 @@ def test_hits_at_k_rejects_bad_arguments_on_the_host():
     assert lib.lp_hits_at_k_workspace_bytes(-1) == 0
 
 
-def test_fp32_product_mode_is_checked_and_remembered():
-    lib = B.load_library()
-    assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_BF16X6       # the default
-    assert lib.lp_set_fp32_products(7) == -1 and lib.lp_set_fp32_products(-1) == -1
-    assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_BF16X6
-    try:
-        assert lib.lp_set_fp32_products(B.LP_FP32_PRODUCTS_NATIVE) == 0
-        assert lib.lp_get_fp32_products() == B.LP_FP32_PRODUCTS_NATIVE
-    finally:
-        assert lib.lp_set_fp32_products(B.LP_FP32_PRODUCTS_BF16X6) == 0
+def test_model_struct_layout_matches_the_header():
+    """The ctypes mirror of lp_model / lp_mlp has the fields of include/lp.h in the header's order (a stale mirror
+    would shift every pointer)."""
+    text = open(os.path.join(ROOT, "include", "lp.h")).read()
+    for cname, mirror in (("lp_model", B._ModelStruct), ("lp_mlp", B._MlpStruct), ("lp_csr", B._CsrStruct),
+                          ("lp_grads", B._GradsStruct), ("lp_acts", B._ActsStruct)):
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (cname, cname), text, re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        names = []
+        for decl in body.split(";"):
+            for part in decl.split(","):
+                m = re.search(r"(\w+)\s*(\[[^\]]*\])?\s*$", part.strip())
+                if m and part.strip():
+                    names.append(m.group(1))
+        assert names == [f[0] for f in mirror._fields_], (cname, names)
+    assert B._ModelStruct.W_self.offset == 56 and B._ModelStruct.fp32_products.offset == 48

@@ -185,8 +185,7 @@ def test_products_from_bfloat16_terms_across_magnitudes(x_scale, w_scale):
     b = [(bb * x_scale * w_scale).astype(np.float32) for bb in b]
     spread = np.exp2(rng.integers(-12, 13, (n, dims[0]))).astype(np.float32)       # exponents differ inside a row
     X = (rng.standard_normal((n, dims[0])) * spread * x_scale).astype(np.float32)
-    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
-    assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
+    model, Xd = make_model(Ws, Wn, b, lp.LP_FP32_PRODUCTS_BF16X6), dev_f32(X)
     acts = lp.lp_sage_forward(g, model, Xd)
     exp = O.sage_forward(ref, Ws, Wn, b, X)
     for k in range(1, len(dims)):
@@ -199,6 +198,69 @@ def test_products_from_bfloat16_terms_across_magnitudes(x_scale, w_scale):
     g_ref = O.backward(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64))
     K = len(dims) - 1
     check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, exp, es, ed, ds.astype(np.float64), hidden_of(acts, K)))
+
+
+def test_two_models_with_different_product_modes_back_to_back():
+    """The way of forming fp32 products belongs to the model handed to each call: two models over the same weight
+    tensors, one per mode, called alternately on one stream without any synchronisation in between, each give what
+    they give when run alone, and the two modes really are different arithmetic."""
+    rng = np.random.default_rng(91)
+    n, dims = 2600, [64, 256, 128]
+    r, c = random_pairs(rng, n, 9000)
+    say("two product modes back to back n=%d dims=%s" % (n, dims))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    m_split = make_model(Ws, Wn, b, lp.LP_FP32_PRODUCTS_BF16X6)
+    m_native = m_split.with_products(lp.LP_FP32_PRODUCTS_NATIVE)
+    assert m_native.W_neigh[0].data_ptr() == m_split.W_neigh[0].data_ptr()
+    Xd = dev_f32(X)
+    alone = {}
+    for name, m in (("split", m_split), ("native", m_native)):
+        alone[name] = host(lp.lp_sage_forward(g, m, Xd).H[-1]).copy()
+    outs = [lp.lp_sage_forward(g, m, Xd).H[-1] for m in (m_split, m_native, m_split, m_native, m_native, m_split)]
+    for t, name in zip(outs, ("split", "native", "split", "native", "native", "split")):
+        assert np.array_equal(host(t), alone[name]), name
+    assert not np.array_equal(alone["split"], alone["native"])
+    exp = O.sage_forward(ref, Ws, Wn, b, X).H[-1]
+    assert_close(alone["split"], exp, TOL_ACT, "H^K, bfloat16 terms")
+    assert_close(alone["native"], exp, TOL_ACT, "H^K, fp32 instructions")
+
+
+def test_products_from_bfloat16_terms_at_the_end_of_the_fp32_range():
+    """Finite inputs up to the largest fp32 value are split exactly (no NaN from a first term that would round to
+    infinity) and give the oracle's result in both modes; an infinite or NaN input makes every output that depends on
+    it non-finite in both modes, and no other output changes by a bit."""
+    rng = np.random.default_rng(92)
+    n, dims = 700, [64, 256]
+    r = rng.integers(4, n, 3000).astype(np.int32)          # nodes 0..3 are nobody's neighbour (directed rows)
+    c = rng.integers(4, n, 3000).astype(np.int32)
+    say("end of the fp32 range n=%d dims=%s" % (n, dims))
+    ref = O.build_csr(n, r, c, False)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), False)
+    Ws, Wn, b = toy_model(rng, dims)
+    Ws[0] = (Ws[0] * 2.0 ** -12).astype(np.float32)        # keeps the sums of the huge rows finite
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    clean = X.copy()
+    fmax = np.finfo(np.float32).max
+    X[0, :] = 0.0
+    X[0, [3, 17, 40]] = [fmax, -fmax, np.float32(3.4e38)]               # all three would round to an infinite bfloat16
+    X[1, [5, 6]] = [np.float32(3.397e38), np.float32(-3.39e38)]         # just above / below the largest finite bfloat16
+    exp = O.sage_forward(ref, Ws, Wn, b, X).H[-1]
+    assert np.all(np.isfinite(exp[:2]))
+    for mode in (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE):
+        model = make_model(Ws, Wn, b, mode)
+        base = host(lp.lp_sage_forward(g, model, dev_f32(clean)).H[-1]).copy()
+        got = host(lp.lp_sage_forward(g, model, dev_f32(X)).H[-1]).copy()
+        for v in (0, 1):
+            assert_close(got[v], exp[v], TOL_ACT, "row %d at the end of the range, mode %d" % (v, mode))
+        assert np.array_equal(got[4:], base[4:])
+        bad = X.copy()
+        bad[2, 7], bad[3, 9] = np.inf, np.nan
+        got = host(lp.lp_sage_forward(g, model, dev_f32(bad)).H[-1]).copy()
+        assert not np.isfinite(got[2]).any() and not np.isfinite(got[3]).any(), "mode %d" % mode
+        assert np.array_equal(got[4:], base[4:]) and np.all(np.isfinite(got[:2]))
 
 
 def test_forward_without_row_order_and_single_node():
@@ -333,7 +395,7 @@ def hidden_of(acts, K, to_host=host):
                                   [192, 200, 232],    # fused weight-gradient tiles that are partly empty
                                   [64, 512, 128], [48, 80, 144]])   # 128-column tiles; K parts of 48 and 80 values
 @pytest.mark.parametrize("sym", [True, False])
-def test_backward_parity(dims, sym):
+def test_backward_parity(dims, sym, products=lp.LP_FP32_PRODUCTS_BF16X6):
     rng = np.random.default_rng(1000 + sum(dims) + sym)
     n = 1300 + dims[-1]
     r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
@@ -345,7 +407,7 @@ def test_backward_parity(dims, sym):
     B, n_pos = 2500, 1000
     es = rng.integers(0, n, B).astype(np.int32)
     ed = rng.integers(0, n, B).astype(np.int32)      # repeated nodes and u == v included
-    model = make_model(Ws, Wn, b)
+    model = make_model(Ws, Wn, b, products)
     Xd = dev_f32(X)
     acts = lp.lp_sage_forward(g, model, Xd)
     s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
@@ -363,13 +425,9 @@ def test_backward_parity(dims, sym):
 
 @pytest.mark.parametrize("dims", [[128, 256, 256, 256], [192, 200, 232], [64, 512, 128], [48, 80, 144]])
 def test_backward_parity_with_fp32_matrix_instructions(dims):
-    """The same bar with LP_FP32_PRODUCTS_NATIVE (the other tests run the default, products from bfloat16 terms)."""
-    lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_NATIVE)
-    try:
-        assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_NATIVE
-        test_backward_parity(dims, True)
-    finally:
-        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
+    """The same bar with LP_FP32_PRODUCTS_NATIVE (the other tests build their models with products from bfloat16
+    terms)."""
+    test_backward_parity(dims, True, lp.LP_FP32_PRODUCTS_NATIVE)
 
 
 @pytest.mark.parametrize("dims", [[16, 32, 8], [128, 256, 64], [64, 520, 8]])
@@ -447,24 +505,20 @@ def run_whole_step(wl, modes=(lp.LP_FP32_PRODUCTS_BF16X6,)):
     check_csr(g, ref)
     K = len(wl.dims) - 1
     errs = {}
-    try:
-        for mode in modes:
-            say("  fp32 products mode %d" % mode)
-            lp.lp_set_fp32_products(mode)
-            got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
-                          wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
-            assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
-            for k in range(1, K + 1):
-                assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
-                assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
-            assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
-            assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
-            assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
-            check_grads(got.grads, exp.grads, K, dx_band(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore,
-                                                         hidden_of(got.acts, K)))
-            errs[mode] = (rel_err(host(got.acts.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
-    finally:
-        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
+    for mode in modes:
+        say("  fp32 products mode %d" % mode)
+        got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias, mode), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
+                      wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+        assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+        for k in range(1, K + 1):
+            assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
+            assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+        assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
+        assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+        assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
+        check_grads(got.grads, exp.grads, K, dx_band(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore,
+                                                     hidden_of(got.acts, K)))
+        errs[mode] = (rel_err(host(got.acts.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
     return errs
 
 

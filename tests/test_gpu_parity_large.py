@@ -78,24 +78,20 @@ def test_whole_step_C4_full_size(c4):
     rows = sample_rows(ref, rng, n_random=3000, n_hubs=40)
     ridx = torch.from_numpy(rows).to(DEV)
     Xd = dev_f32(X)
-    try:
-        for mode in (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE):
-            say("  fp32 products mode %d" % mode)
-            lp.lp_set_fp32_products(mode)
-            got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias), Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
-                          wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step, want_dX=False)
-            assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
-            for k in range(1, K + 1):
-                assert_close(host(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], TOL_ACT, "A^%d rows" % k)
-                assert_close(host(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], TOL_ACT, "H^%d rows" % k)
-            assert bool(torch.isfinite(got.acts.H[-1]).all())
-            assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
-            assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
-            assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
-            check_grads(got.grads, exp.grads, K)
-            del got
-    finally:
-        lp.lp_set_fp32_products(lp.LP_FP32_PRODUCTS_BF16X6)
+    for mode in (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE):
+        say("  fp32 products mode %d" % mode)
+        got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias, mode), Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
+                      wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step, want_dX=False)
+        assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
+        for k in range(1, K + 1):
+            assert_close(host(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], TOL_ACT, "A^%d rows" % k)
+            assert_close(host(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], TOL_ACT, "H^%d rows" % k)
+        assert bool(torch.isfinite(got.acts.H[-1]).all())
+        assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
+        assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
+        assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
+        check_grads(got.grads, exp.grads, K)
+        del got
 
 
 @pytest.mark.parametrize("F", [128, 256])
@@ -250,8 +246,7 @@ def test_hidden_512_persistent_tiles(storage, n):
         assert_close(host(s), s_ref, BF_ACT, "scores")
         bf_check_grads(grads, g_ref, 2, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, 2, hostf), storage="bf16"))
     else:
-        assert lp.lp_get_fp32_products() == lp.LP_FP32_PRODUCTS_BF16X6
-        model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+        model, Xd = make_model(Ws, Wn, b, lp.LP_FP32_PRODUCTS_BF16X6), dev_f32(X)
         acts = lp.lp_sage_forward(g, model, Xd)
         s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
         grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
