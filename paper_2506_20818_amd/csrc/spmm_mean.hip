@@ -159,10 +159,10 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     for (int c = 0; c < C; ++c)
 #pragma unroll
         for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
+    const float scale = row_scale(a, v);   // requested before the gathers, not after them: one memory latency less per row
     accumulate_blocks<T, G, C, W, 4>(a, static_cast<const T *>(a.in), lo, hi, 64, lane, acc);
     fold_groups<G, C, VE>(acc);
     if (sub != 0 || fl >= FV) return;
-    const float scale = row_scale(a, v);
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         const int colv = fl + 64 * c;
