@@ -27,7 +27,9 @@ def build_library(verbose: bool = False) -> str:
     cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include")] + sources() + ["-o", LIB_PATH]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+        # (the host pass of every file remarks that it does not know the packed-fp32 target feature: not an error)
+        text = "\n".join(l for l in (proc.stdout + proc.stderr).splitlines() if "packed-fp32-ops" not in l)
+        raise RuntimeError("hipcc failed:\n" + text)
     if verbose:
         print(" ".join(cmd))
     return LIB_PATH

@@ -297,7 +297,7 @@ BlockBackwardWs carve_block_backward(void *ws, const lp_model *m, const lp_block
     w.bptr = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * ((size_t)b->cap[K] + 1)));
     w.bcol = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * n2));
     w.bw = reinterpret_cast<float *>(take(sizeof(float) * n2));
-    w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(b->cap[0])));
+    w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(b->cap[0], max_dim(m))));
     w.bytes = off;
     return w;
 }

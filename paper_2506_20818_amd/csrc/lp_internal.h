@@ -73,13 +73,13 @@ struct SpmmArgs {
     const void *gate = nullptr;          // optional [n_rows, F]: output is zeroed where gate <= 0
     void *out = nullptr;
     int64_t n_entries = 0;               // entries of colidx (bounds how many rows can be long)
-    int32_t *long_queue = nullptr;       // optional workspace of lp_spmm_queue_bytes(n_rows): rows of at least
-                                         // kSpmmLongRow entries are served by a whole workgroup each
+    int32_t *long_queue = nullptr;       // optional workspace of lp_spmm_queue_bytes(n_rows, F): rows of at least
+                                         // kSpmmLongRow entries are served by whole workgroups
     int32_t long_threshold = 0;          // set by the launcher
     int timing_class = LP_KC_SPMM;       // class the launch is booked under by the instrumentation
 };
 constexpr int32_t kSpmmLongRow = 512;
-size_t lp_spmm_queue_bytes(int32_t n_rows);
+size_t lp_spmm_queue_bytes(int32_t n_rows, int32_t max_width);   // max_width: the widest F the queue will be used with
 int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
 
 // ---------------------------------------------------------------- dense products (gemm_mfma.hip)

@@ -122,7 +122,7 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
     w.bptr = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * ((size_t)n_nodes + 1)));
     w.bcol = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * n2));
     w.bw = take(sizeof(float) * n2);
-    w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(n_nodes)));
+    w.long_queue = reinterpret_cast<int32_t *>(take(lp_spmm_queue_bytes(n_nodes, max_dim(m))));
     const size_t cap = (size_t)touched_cap(n_nodes, B);
     w.touched = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (cap + 1)));
     w.touched_index = reinterpret_cast<int32_t *>(take(sizeof(int32_t) * (size_t)n_nodes));
@@ -150,7 +150,7 @@ int lp_group_batch_by_row(const int32_t *e_src, const int32_t *e_dst, const floa
 
 extern "C" size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes) {
     if (check_model(m) != LP_OK || n_nodes <= 0) return 0;
-    return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m)) + lp_spmm_queue_bytes(n_nodes);
+    return lp_align_up((size_t)lp_elem_bytes(m->dtype) * transposed_weight_elems(m)) + lp_spmm_queue_bytes(n_nodes, max_dim(m));
 }
 
 extern "C" int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws, size_t ws_bytes,

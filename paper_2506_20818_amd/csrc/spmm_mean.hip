@@ -11,10 +11,15 @@
 //
 // Hub rows: a single wavefront keeps only a few KiB in flight, so a row with thousands of neighbours would take
 // longer than the rest of the launch together (power-law graphs have such rows).  When the caller supplies a queue,
-// a wavefront that meets a row of at least kLongRow neighbours appends it to the queue instead, and a second launch
-// gives every queued row to a whole workgroup of sixteen wavefronts: wavefront w takes the 64-neighbour blocks
-// w, w+16, ... and the sixteen partial sums are added in wavefront order through LDS.  Which workgroup serves which
-// queued row depends on scheduling; the value computed for a row does not.
+// a wavefront that meets a row of at least kLongRow neighbours appends it to the queue instead.  The queued rows are
+// then cut into tasks of at most `seg` entries (a multiple of 1024 chosen so that about two thousand tasks result:
+// a row of fifteen thousand entries served by one workgroup would otherwise still be running long after everything
+// else has finished, every workgroup getting the same small share of the memory system).  A task goes to a workgroup
+// of sixteen wavefronts: wavefront w takes the 64-neighbour blocks w, w+16, ... of the task and the sixteen partial
+// sums are added in wavefront order through LDS.  A row that is a single task is finished there; the tasks of a longer
+// row leave fp32 partial rows in scratch memory and a last small kernel adds them in task order and finishes the
+// row.  The plan depends only on the row lengths and on the order in which rows were queued; the latter changes which
+// scratch slot a row uses, never the order of any sum, so results are the same bits on every run.
 // Sums are always accumulated in fp32, whatever the storage type.
 #include "lp_internal.h"
 
@@ -23,6 +28,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kLongThreads = 1024;
 constexpr int kLongWaves = kLongThreads / 64;
+constexpr int kLongHeader = 64;                        // words ahead of the queued rows (count, seg, tasks, slots)
+constexpr int kLongTargetTasks = 2048;                 // aimed-at number of tasks of one launch
+constexpr int kLongSlots = 2 * kLongTargetTasks;       // partial rows that can be live: see plan_long_rows_kernel
 
 // Accumulates the 64-neighbour blocks first, first + stride, ... (< hi) of one CSR row into acc.
 // T: storage type, G: lanes per neighbour row (8..64), C: 16-byte chunks per lane (C > 1 only when G == 64),
@@ -149,8 +157,8 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     const int sub = lane / G, fl = lane % G;
     const int FV = a.F / VE;
     const int32_t lo = a.rowptr[v], hi = a.rowptr[v + 1];
-    if (a.long_queue && hi - lo >= a.long_threshold) {  // a hub: leave it to a whole workgroup of the second launch
-        if (lane == 0) a.long_queue[1 + atomicAdd(a.long_queue, 1)] = v;
+    if (a.long_queue && hi - lo >= a.long_threshold) {  // a hub: leave it to whole workgroups of the later launches
+        if (lane == 0) a.long_queue[kLongHeader + atomicAdd(a.long_queue, 1)] = v;
         return;
     }
 
@@ -171,7 +179,90 @@ __global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
     }
 }
 
-// One workgroup of sixteen wavefronts per queued row; workgroup b serves queue entries b, b + gridDim.x, ...
+// ---- queued rows.  Layout of the queue workspace (int32 words): [0] number of queued rows, [1] seg, [2] number of
+// tasks, [3] number of scratch slots in use; then rows [cap], task_base [cap + 1], slot_base [cap], each padded to a
+// multiple of 64 words, cap = n_rows; then the scratch slots (kLongSlots x F floats).
+
+struct LongQueue {
+    int32_t *head, *rows, *task_base, *slot_base;
+    float *slots;
+};
+__host__ __device__ inline size_t long_words(int32_t cap) { return ((size_t)cap + 1 + 63) / 64 * 64; }
+__host__ __device__ inline LongQueue long_queue_of(int32_t *q, int32_t cap) {
+    LongQueue l;
+    l.head = q;
+    l.rows = q + kLongHeader;
+    l.task_base = l.rows + long_words(cap);
+    l.slot_base = l.task_base + long_words(cap);
+    l.slots = reinterpret_cast<float *>(l.slot_base + long_words(cap));
+    return l;
+}
+
+// One workgroup: seg from the total length of the queued rows, then the running task and slot counts in queue order.
+// Rows of more than seg entries number at most total / seg <= kLongTargetTasks and have at most total / seg + their
+// number <= 2 kLongTargetTasks tasks together: kLongSlots slots always suffice.
+__global__ __launch_bounds__(1024) void plan_long_rows_kernel(const int32_t *__restrict__ rowptr, int32_t *q, int32_t cap) {
+    __shared__ long long red[1024];
+    __shared__ int32_t carry[2];
+    const LongQueue l = long_queue_of(q, cap);
+    const int32_t n = l.head[0];
+    long long total = 0;
+    for (int32_t i = threadIdx.x; i < n; i += 1024) {
+        const int32_t v = l.rows[i];
+        total += rowptr[v + 1] - rowptr[v];
+    }
+    red[threadIdx.x] = total;
+    __syncthreads();
+    for (int d = 512; d >= 1; d >>= 1) {
+        if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+        __syncthreads();
+    }
+    total = red[0];
+    __syncthreads();
+    long long want = (total + kLongTargetTasks - 1) / kLongTargetTasks;
+    const int32_t seg = (int32_t)((want < 1024 ? 1024 : (want + 1023) / 1024 * 1024));
+    if (threadIdx.x == 0) carry[0] = carry[1] = 0;
+    __syncthreads();
+    int32_t *cnt = reinterpret_cast<int32_t *>(red);          // [0..1023] tasks, [1024..2047] slots of this chunk
+    for (int32_t base = 0; base < n; base += 1024) {
+        const int32_t i = base + threadIdx.x;
+        int32_t tasks = 0, slots = 0;
+        if (i < n) {
+            const int32_t v = l.rows[i];
+            tasks = (rowptr[v + 1] - rowptr[v] + seg - 1) / seg;
+            slots = tasks > 1 ? tasks : 0;
+        }
+        cnt[threadIdx.x] = tasks;
+        cnt[1024 + threadIdx.x] = slots;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {                 // inclusive scans of both counts
+            const int32_t a = (int)threadIdx.x >= d ? cnt[threadIdx.x - d] : 0;
+            const int32_t b = (int)threadIdx.x >= d ? cnt[1024 + threadIdx.x - d] : 0;
+            __syncthreads();
+            cnt[threadIdx.x] += a;
+            cnt[1024 + threadIdx.x] += b;
+            __syncthreads();
+        }
+        if (i < n) {
+            l.task_base[i] = carry[0] + cnt[threadIdx.x] - tasks;
+            l.slot_base[i] = carry[1] + cnt[1024 + threadIdx.x] - slots;
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) {
+            carry[0] += cnt[1023];
+            carry[1] += cnt[2047];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        l.task_base[n] = carry[0];
+        l.head[1] = seg;
+        l.head[2] = carry[0];
+        l.head[3] = carry[1];
+    }
+}
+
+// One workgroup of sixteen wavefronts per task; workgroup b serves tasks b, b + gridDim.x, ...
 template <typename T, int G, int C, int W>
 __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
@@ -180,10 +271,20 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane / G, fl = lane % G;
     const int FV = a.F / VE;
-    const int32_t n_queued = a.long_queue[0];
-    for (int32_t i = blockIdx.x; i < n_queued; i += gridDim.x) {  // uniform over the workgroup
-        const int32_t v = a.long_queue[1 + i];
-        const int32_t lo = a.rowptr[v], hi = a.rowptr[v + 1];
+    const LongQueue l = long_queue_of(a.long_queue, a.n_rows);
+    const int32_t n_queued = l.head[0], seg = l.head[1], n_tasks = l.head[2];
+    for (int32_t t = blockIdx.x; t < n_tasks; t += gridDim.x) {  // uniform over the workgroup
+        int32_t lo_i = 0, hi_i = n_queued;                        // last queue entry i with task_base[i] <= t
+        while (hi_i - lo_i > 1) {
+            const int32_t mid = (lo_i + hi_i) >> 1;
+            if (l.task_base[mid] <= t) lo_i = mid; else hi_i = mid;
+        }
+        const int32_t v = l.rows[lo_i];
+        const int32_t part = t - l.task_base[lo_i];
+        const int32_t row_lo = a.rowptr[v], row_hi = a.rowptr[v + 1];
+        const bool whole = row_hi - row_lo <= seg;                // the row is this one task
+        const int32_t lo = row_lo + part * seg;
+        const int32_t hi = min(row_hi, lo + seg);
         float acc[C][VE];
 #pragma unroll
         for (int c = 0; c < C; ++c)
@@ -191,7 +292,8 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
             for (int e = 0; e < VE; ++e) acc[c][e] = 0.f;
         accumulate_blocks<T, G, C, W, U>(a, static_cast<const T *>(a.in), lo + 64 * wave, hi, 64 * kLongWaves, lane, acc);
         fold_groups<G, C, VE>(acc);
-        const float scale = row_scale(a, v);
+        const float scale = whole ? row_scale(a, v) : 1.f;
+        float *slot = whole ? nullptr : l.slots + (size_t)(l.slot_base[lo_i] + part) * a.F;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             if (sub == 0) {
@@ -208,9 +310,41 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
                 for (int w = 1; w < kLongWaves; ++w)
 #pragma unroll
                     for (int e = 0; e < VE; ++e) sum[e] += red[w][fl][e];
-                finish_vector<T>(a, v, FV, colv, scale, sum);
+                if (whole) {
+                    finish_vector<T>(a, v, FV, colv, scale, sum);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) slot[colv * VE + e] = sum[e];
+                }
             }
             __syncthreads();
+        }
+    }
+}
+
+// The rows that were cut into several tasks: one wavefront per queue entry adds the partial rows in task order.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void spmm_long_rows_finish_kernel(SpmmArgs a) {
+    constexpr int VE = LpVec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const LongQueue l = long_queue_of(a.long_queue, a.n_rows);
+    const int32_t n_queued = l.head[0], seg = l.head[1];
+    const int FV = a.F / VE;
+    for (int32_t i = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); i < n_queued; i += gridDim.x * (kThreads / 64)) {
+        const int32_t v = l.rows[i];
+        const int32_t len = a.rowptr[v + 1] - a.rowptr[v];
+        if (len <= seg) continue;
+        const int32_t parts = (len + seg - 1) / seg;
+        const float *slot = l.slots + (size_t)l.slot_base[i] * a.F;
+        const float scale = row_scale(a, v);
+        for (int colv = lane; colv < FV; colv += 64) {
+            float sum[VE];
+#pragma unroll
+            for (int e = 0; e < VE; ++e) sum[e] = 0.f;
+            for (int32_t p = 0; p < parts; ++p)
+#pragma unroll
+                for (int e = 0; e < VE; ++e) sum[e] += slot[(size_t)p * a.F + colv * VE + e];
+            finish_vector<T>(a, v, FV, colv, scale, sum);
         }
     }
 }
@@ -223,14 +357,20 @@ int launch(const SpmmArgs &a, hipStream_t st) {
     else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kThreads), 0, st, a);
     if (a.long_queue) {
-        // no more rows can be queued than fit the entry count; two workgroups per compute unit walk the queue
-        const int64_t most = a.n_entries / a.long_threshold;
+        // no more rows can be queued than fit the entry count, and a row of at least 512 entries is at most two tasks
+        // per 1024 entries; two workgroups per compute unit walk the tasks
+        const int64_t most_rows = a.n_entries / a.long_threshold;
+        const int64_t most_tasks = most_rows + kLongSlots;
         const int64_t slots = 2 * (int64_t)lp_compute_units();
-        const unsigned lgrid = (unsigned)(most < slots ? most : slots);
-        if (lgrid > 0) {
+        const unsigned lgrid = (unsigned)(most_tasks < slots ? most_tasks : slots);
+        if (most_rows > 0) {
+            hipLaunchKernelGGL(plan_long_rows_kernel, dim3(1), dim3(1024), 0, st, a.rowptr, a.long_queue, a.n_rows);
             if (mode == 2) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 2>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
             else if (mode == 1) hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 1>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
             else hipLaunchKernelGGL((spmm_long_rows_kernel<T, G, C, 0>), dim3(lgrid), dim3(kLongThreads), 0, st, a);
+            // rows cut into several tasks are at most kLongTargetTasks; the grid also never needs more wavefronts than rows
+            const int64_t fin_rows = most_rows < 4 * slots ? most_rows : 4 * slots;
+            hipLaunchKernelGGL((spmm_long_rows_finish_kernel<T>), dim3((unsigned)lp_ceil_div(fin_rows, kThreads / 64)), dim3(kThreads), 0, st, a);
         }
     }
     return lp_after_launch();
@@ -250,7 +390,10 @@ int dispatch(const SpmmArgs &a, hipStream_t st) {
 
 }  // namespace
 
-size_t lp_spmm_queue_bytes(int32_t n_rows) { return lp_align_up(sizeof(int32_t) * ((size_t)(n_rows > 0 ? n_rows : 0) + 1)); }
+size_t lp_spmm_queue_bytes(int32_t n_rows, int32_t max_width) {
+    const int32_t cap = n_rows > 0 ? n_rows : 0;
+    return lp_align_up(sizeof(int32_t) * (kLongHeader + 3 * long_words(cap)) + sizeof(float) * (size_t)kLongSlots * (size_t)(max_width > 0 ? max_width : 0));
+}
 
 int lp_launch_spmm(const SpmmArgs &args, hipStream_t st) {
     if (args.n_rows <= 0) return LP_OK;
