@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 import paper_2506_20818_amd as lp
 from lp_workloads import make_workload, to_bf16_grid
 from oracle import lp_oracle as O
-from gpu_util import DEV, assert_close, dev_f32, dev_i32, host
+from gpu_util import DEV, assert_close, dev_f32, dev_i32, host, rel_err
 from test_gpu_parity import assert_dx_close, dx_band, graph_with_hub_and_empty_rows, hidden_of, random_pairs, say, toy_model
 
 TOL_ACT = 2.0 ** -7
@@ -82,6 +82,21 @@ def check_grads(grads, ref, K, dx_band_width=None):
         assert_dx_close(hostf(grads.dX), ref.dX, dx_band_width, TOL_GRAD, cap_on="rescued")
 
 
+def check_grads_against_unrounded_backward(grads, exact, K):
+    """The same gradients against a backward pass that rounds NOTHING (fp64 throughout, from the same bf16 forward
+    activations): a check that does not depend on where the oracle's bf16 mode places its roundings.  Each node-sized
+    matrix kept in bf16 carries a relative rounding error of at most 2^-9 per element, the gradients are linear in each
+    of them, and layer k's weight gradient has at most 3 (K - k) + 1 such matrices upstream (dL/dH^K, then per layer
+    the two products and their gated sum), so its relative 2-norm error is at most (3 (K - k) + 1) 2^-9, plus the
+    fp32 accumulation noise of the kernels (1e-3)."""
+    for k in range(1, K + 1):
+        bound = (3 * (K - k) + 1) * 2.0 ** -9 + 1e-3
+        for name, got, ref in (("dW_self", grads.dW_self[k - 1], exact.dW_self[k - 1]), ("dW_neigh", grads.dW_neigh[k - 1], exact.dW_neigh[k - 1]),
+                               ("dbias", grads.dbias[k - 1], exact.dbias[k - 1])):
+            e_l2 = rel_err(host(got), ref)[1]
+            assert e_l2 <= bound, "%s^%d against the unrounded backward: 2-norm rel %.3e > %.3e" % (name, k, e_l2, bound)
+
+
 @pytest.mark.parametrize("dims", [[8, 16], [24, 40, 8], [64, 64, 64], [128, 512, 512, 512], [72, 136, 24],
                                   [192, 200, 232]])   # the last: fused weight-gradient tiles that are partly empty
 @pytest.mark.parametrize("sym", [True, False])
@@ -110,6 +125,7 @@ def test_backward_parity_bf16(dims, sym):
     assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
     K = len(dims) - 1
     check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K, hostf), storage="bf16"))
+    check_grads_against_unrounded_backward(grads, O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="f32"), K)
 
 
 def whole_step_bf16(name, scale=1.0):
@@ -140,6 +156,7 @@ def whole_step_bf16(name, scale=1.0):
     assert_close(host(s), exp.scores, TOL_ACT, "scores")
     assert abs(float(host(loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
     check_grads(grads, exp.grads, K)
+    check_grads_against_unrounded_backward(grads, O.backward(ref, Ws, Wn, exp.acts, exp.e_src, exp.e_dst, exp.dscore, storage="f32"), K)
 
 
 def test_whole_step_C1_bf16():

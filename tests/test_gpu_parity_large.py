@@ -188,6 +188,9 @@ def whole_step_bf16_sampled_rows(wl, ref, g):
     assert_close(host(got.scores), exp.scores, BF_ACT, "scores")
     assert abs(float(host(got.loss)[0]) - exp.loss) <= BF_ACT * abs(exp.loss)
     bf_check_grads(got.grads, exp.grads, K)
+    if ref.n_nodes < 600000:    # (one more fp64 backward pass: left out at full size)
+        from test_gpu_parity_bf16 import check_grads_against_unrounded_backward
+        check_grads_against_unrounded_backward(got.grads, O.backward(ref, Ws, Wn, exp.acts, exp.e_src, exp.e_dst, exp.dscore, storage="f32"), K)
 
 
 @pytest.mark.timeout(900)
