@@ -203,7 +203,6 @@ __host__ __device__ inline LongQueue long_queue_of(int32_t *q, int32_t cap) {
 // number <= 2 kLongTargetTasks tasks together: kLongSlots slots always suffice.
 __global__ __launch_bounds__(1024) void plan_long_rows_kernel(const int32_t *__restrict__ rowptr, int32_t *q, int32_t cap) {
     __shared__ long long red[1024];
-    __shared__ int32_t carry[2];
     const LongQueue l = long_queue_of(q, cap);
     const int32_t n = l.head[0];
     long long total = 0;
@@ -221,44 +220,44 @@ __global__ __launch_bounds__(1024) void plan_long_rows_kernel(const int32_t *__r
     __syncthreads();
     long long want = (total + kLongTargetTasks - 1) / kLongTargetTasks;
     const int32_t seg = (int32_t)((want < 1024 ? 1024 : (want + 1023) / 1024 * 1024));
-    if (threadIdx.x == 0) carry[0] = carry[1] = 0;
+    // thread t owns the queue entries [t * per, (t + 1) * per): its own totals, one scan over the 1024 threads, then
+    // the running counts of its entries
+    int32_t *cnt = reinterpret_cast<int32_t *>(red);          // [0..1023] tasks, [1024..2047] slots per thread
+    const int32_t per = (n + 1023) / 1024;
+    const int32_t first = (int32_t)threadIdx.x * per;
+    const int32_t last = min(n, first + per);
+    int32_t tasks = 0, slots = 0;
+    for (int32_t i = first; i < last; ++i) {
+        const int32_t v = l.rows[i];
+        const int32_t t = (rowptr[v + 1] - rowptr[v] + seg - 1) / seg;
+        tasks += t;
+        slots += t > 1 ? t : 0;
+    }
+    cnt[threadIdx.x] = tasks;
+    cnt[1024 + threadIdx.x] = slots;
     __syncthreads();
-    int32_t *cnt = reinterpret_cast<int32_t *>(red);          // [0..1023] tasks, [1024..2047] slots of this chunk
-    for (int32_t base = 0; base < n; base += 1024) {
-        const int32_t i = base + threadIdx.x;
-        int32_t tasks = 0, slots = 0;
-        if (i < n) {
-            const int32_t v = l.rows[i];
-            tasks = (rowptr[v + 1] - rowptr[v] + seg - 1) / seg;
-            slots = tasks > 1 ? tasks : 0;
-        }
-        cnt[threadIdx.x] = tasks;
-        cnt[1024 + threadIdx.x] = slots;
+    for (int d = 1; d < 1024; d <<= 1) {                     // inclusive scans of both counts
+        const int32_t a = (int)threadIdx.x >= d ? cnt[threadIdx.x - d] : 0;
+        const int32_t b = (int)threadIdx.x >= d ? cnt[1024 + threadIdx.x - d] : 0;
         __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {                 // inclusive scans of both counts
-            const int32_t a = (int)threadIdx.x >= d ? cnt[threadIdx.x - d] : 0;
-            const int32_t b = (int)threadIdx.x >= d ? cnt[1024 + threadIdx.x - d] : 0;
-            __syncthreads();
-            cnt[threadIdx.x] += a;
-            cnt[1024 + threadIdx.x] += b;
-            __syncthreads();
-        }
-        if (i < n) {
-            l.task_base[i] = carry[0] + cnt[threadIdx.x] - tasks;
-            l.slot_base[i] = carry[1] + cnt[1024 + threadIdx.x] - slots;
-        }
-        __syncthreads();
-        if (threadIdx.x == 1023) {
-            carry[0] += cnt[1023];
-            carry[1] += cnt[2047];
-        }
+        cnt[threadIdx.x] += a;
+        cnt[1024 + threadIdx.x] += b;
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        l.task_base[n] = carry[0];
+    int32_t tb = cnt[threadIdx.x] - tasks, sb = cnt[1024 + threadIdx.x] - slots;
+    for (int32_t i = first; i < last; ++i) {
+        const int32_t v = l.rows[i];
+        const int32_t t = (rowptr[v + 1] - rowptr[v] + seg - 1) / seg;
+        l.task_base[i] = tb;
+        l.slot_base[i] = sb;
+        tb += t;
+        sb += t > 1 ? t : 0;
+    }
+    if (threadIdx.x == 1023) {
+        l.task_base[n] = cnt[1023];
         l.head[1] = seg;
-        l.head[2] = carry[0];
-        l.head[3] = carry[1];
+        l.head[2] = cnt[1023];
+        l.head[3] = cnt[2047];
     }
 }
 
