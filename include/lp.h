@@ -203,6 +203,11 @@ typedef struct lp_opt_state {
 /* Text for a status code (static storage, never NULL). */
 const char *lp_strerror(int status);
 
+/* Version of this header's structs and signatures, bumped with every change to them.  lp_abi_version() returns the
+ * value the library was built with: a caller (or binding) that was written against another one must not go on. */
+#define LP_ABI_VERSION 3
+int lp_abi_version(void);
+
 /* ---------------------------------------------------------------------------
  * lp_build_csr - canonical CSR of the visible edge set (Sec. II-A: the graph
  * is a node set with a set of node pairs; Sec. IV-A: undirected, unweighted,
@@ -267,15 +272,20 @@ int lp_sample_neg(const lp_csr *g, int64_t n_pos, const int32_t *pos_src, int32_
  *   s_e = <H[e_src[e]], H[e_dst[e]]>,  y_e = 1 for e < n_pos_edges else 0,
  *   l_e = -[y ln sigma(s) + (1-y) ln(1-sigma(s))],  loss = (1/B) sum_e l_e,
  *   dscore_e = (sigma(s_e) - y_e) / B.
- * HK: device [n_nodes, F].  e_src, e_dst: device [B], ids in [0, n_nodes)
- * (an edge with an id outside is scored 0, gets dscore 0, adds nothing to the
- * loss sum and still counts in B).  scores: device [B].  loss: device float.  dscore: device [B] or NULL.
+ * HK: device [n_nodes, F].  e_src, e_dst: device [B], ids in [0, n_nodes).
+ * An edge with an id outside that range is never dereferenced: it is scored 0,
+ * gets dscore 0, adds nothing to the loss sum and still counts in B, so a batch
+ * that contains such edges trains on a loss that is too small.  n_invalid:
+ * device int32 or NULL; the caller zeroes it and it receives the number of such
+ * edges, so that a corrupted batch does not go unnoticed (check it whenever the
+ * edge list does not come from lp_sample_neg on the same graph).
+ * scores: device [B].  loss: device float.  dscore: device [B] or NULL.
  * The loss is summed in a fixed order, so repeated calls give the same bits.
  */
 size_t lp_score_loss_workspace_bytes(int64_t B);
 int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
                   const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore,
-                  void *ws, size_t ws_bytes, void *stream);
+                  int32_t *n_invalid, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * lp_score_loss_noalloc - lp_score_loss for callers that cannot allocate or hand
@@ -298,7 +308,7 @@ int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int
 #define LP_SCORE_LOSS_NOALLOC_MAX_EDGES ((int64_t)1 << 28)
 int lp_score_loss_noalloc(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
                           const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore,
-                          void *stream);
+                          int32_t *n_invalid, void *stream);
 
 /* ---------------------------------------------------------------------------
  * lp_backward - gradient of the batch loss with respect to all weights

@@ -88,6 +88,7 @@ class _OptStateStruct(C.Structure):
 
 EXPORTS = {
     "lp_strerror": (C.c_char_p, [C.c_int]),
+    "lp_abi_version": (C.c_int, []),
     "lp_build_csr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_uint32]),
     "lp_build_csr": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
@@ -99,9 +100,9 @@ EXPORTS = {
                                 C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "lp_score_loss_workspace_bytes": (C.c_size_t, [C.c_int64]),
     "lp_score_loss": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
-                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_score_loss_noalloc": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_void_p,
-                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "lp_backward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
     "lp_sparsify_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64]),
     "lp_sparsify": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
@@ -159,9 +160,20 @@ def load_library():
             raise RuntimeError("%s is not built; run `python -m paper_2506_20818_amd.build`" % path)
         lib = C.CDLL(path)
         for name, (res, args) in EXPORTS.items():
-            fn = getattr(lib, name)
+            fn = getattr(lib, name, None)
+            if fn is None:
+                raise RuntimeError("%s does not export %s: it was built from older sources; run "
+                                   "`python -m paper_2506_20818_amd.build`" % (path, name))
             fn.restype = res
             fn.argtypes = args
+        # a library built before the last change of include/lp.h would be called with the wrong struct layouts
+        header = os.path.join(os.path.dirname(_PKG), "include", "lp.h")
+        if os.path.exists(header):
+            import re
+            m = re.search(r"#define\s+LP_ABI_VERSION\s+(\d+)", open(header).read())
+            if m and int(m.group(1)) != int(lib.lp_abi_version()):
+                raise RuntimeError("%s was built for version %d of include/lp.h, the header is at version %s; run "
+                                   "`python -m paper_2506_20818_amd.build`" % (path, lib.lp_abi_version(), m.group(1)))
         _LIB = lib
     return _LIB
 
@@ -338,7 +350,10 @@ def lp_sample_neg(g: Csr, pos_src: torch.Tensor, k_neg: int, n_space: int, seed:
 
 def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_pos_edges: int,
                   scores: Optional[torch.Tensor] = None, loss: Optional[torch.Tensor] = None,
-                  dscore: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+                  dscore: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                  n_invalid: Optional[torch.Tensor] = None):
+    """n_invalid: optional int32 device scalar, zeroed by the caller; receives the number of edges with an id outside
+    the node range (which are scored 0 and left out of the loss sum)."""
     lib = load_library()
     if HK.dtype not in _LP_OF:
         raise ValueError("HK must be float32 or bfloat16")
@@ -356,12 +371,13 @@ def lp_score_loss(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_
     if ws is None:
         ws = _ws(lib.lp_score_loss_workspace_bytes(B), dev)
     _check(lib.lp_score_loss(_ptr(HK), HK.shape[0], HK.shape[1], _LP_OF[HK.dtype], B, n_pos_edges, _ptr(e_src), _ptr(e_dst),
-                             _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(ws), ws.numel(), _stream()), "lp_score_loss")
+                             _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(n_invalid), _ptr(ws), ws.numel(), _stream()), "lp_score_loss")
     return scores, loss, dscore
 
 
 def lp_score_loss_noalloc(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor, n_pos_edges: int,
-                          scores: torch.Tensor, loss: torch.Tensor, dscore: Optional[torch.Tensor] = None):
+                          scores: torch.Tensor, loss: torch.Tensor, dscore: Optional[torch.Tensor] = None,
+                          n_invalid: Optional[torch.Tensor] = None):
     """lp_score_loss without a workspace: the caller passes every output, nothing is allocated here or in the
     library (its scratch is a device array inside the library)."""
     lib = load_library()
@@ -378,7 +394,7 @@ def lp_score_loss_noalloc(HK: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Te
     if int(e_dst.numel()) != B or int(scores.numel()) < B or (dscore is not None and int(dscore.numel()) < B) or loss.numel() < 1:
         raise ValueError("e_dst, scores and dscore must hold one entry per edge of e_src")
     _check(lib.lp_score_loss_noalloc(_ptr(HK), HK.shape[0], HK.shape[1], _LP_OF[HK.dtype], B, n_pos_edges, _ptr(e_src),
-                                     _ptr(e_dst), _ptr(scores), _ptr(loss), _ptr(dscore), _stream()), "lp_score_loss_noalloc")
+                                     _ptr(e_dst), _ptr(scores), _ptr(loss), _ptr(dscore), _ptr(n_invalid), _stream()), "lp_score_loss_noalloc")
     return scores, loss, dscore
 
 

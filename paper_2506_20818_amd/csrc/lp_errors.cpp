@@ -1,4 +1,4 @@
-// lp_strerror: text for the status codes of the C ABI.
+// lp_strerror: text for the status codes of the C ABI; lp_abi_version: the header version the library was built with.
 #include "lp.h"
 
 extern "C" const char *lp_strerror(int status) {
@@ -12,3 +12,5 @@ extern "C" const char *lp_strerror(int status) {
         default: return "unknown status";
     }
 }
+
+extern "C" int lp_abi_version(void) { return LP_ABI_VERSION; }

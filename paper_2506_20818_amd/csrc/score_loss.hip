@@ -48,7 +48,8 @@ template <typename T, int G>
 __global__ __launch_bounds__(kThreads) void score_loss_kernel(const T *__restrict__ H, int32_t n_nodes, int32_t F,
                                                               int64_t B, int64_t n_pos, const int32_t *__restrict__ e_src,
                                                               const int32_t *__restrict__ e_dst, float *__restrict__ scores,
-                                                              float *__restrict__ dscore, float *__restrict__ partial) {
+                                                              float *__restrict__ dscore, float *__restrict__ partial,
+                                                              int32_t *__restrict__ n_invalid) {
     __shared__ float red[kThreads / 64];
     const int sub = threadIdx.x % G;
     const int64_t groups_per_block = kThreads / G;
@@ -81,6 +82,7 @@ __global__ __launch_bounds__(kThreads) void score_loss_kernel(const T *__restric
             scores[e] = s;
             if (dscore) dscore[e] = ok ? (sig - y) * invB : 0.0f;
             if (ok) acc += ell;
+            else if (n_invalid) atomicAdd(n_invalid, 1);   // an integer count: the same on every run
         }
     }
     // block sum in a fixed order
@@ -120,13 +122,13 @@ int group_lanes(int F, int vec) {
 
 template <typename T>
 void launch_score(int G, int nb, hipStream_t st, const void *HK, int32_t n_nodes, int32_t F, int64_t B, int64_t n_pos,
-                  const int32_t *e_src, const int32_t *e_dst, float *scores, float *dscore, float *partial) {
+                  const int32_t *e_src, const int32_t *e_dst, float *scores, float *dscore, float *partial, int32_t *n_invalid) {
     const T *H = static_cast<const T *>(HK);
     switch (G) {
-        case 8: hipLaunchKernelGGL((score_loss_kernel<T, 8>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
-        case 16: hipLaunchKernelGGL((score_loss_kernel<T, 16>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
-        case 32: hipLaunchKernelGGL((score_loss_kernel<T, 32>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial); break;
-        default: hipLaunchKernelGGL((score_loss_kernel<T, 64>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial);
+        case 8: hipLaunchKernelGGL((score_loss_kernel<T, 8>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial, n_invalid); break;
+        case 16: hipLaunchKernelGGL((score_loss_kernel<T, 16>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial, n_invalid); break;
+        case 32: hipLaunchKernelGGL((score_loss_kernel<T, 32>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial, n_invalid); break;
+        default: hipLaunchKernelGGL((score_loss_kernel<T, 64>), dim3(nb), dim3(kThreads), 0, st, H, n_nodes, F, B, n_pos, e_src, e_dst, scores, dscore, partial, n_invalid);
     }
 }
 
@@ -152,13 +154,13 @@ int check_score_args(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, 
 // Both entry points: `partial` holds at least kMaxLossBlocks floats; the first `nb` are overwritten by the scoring
 // kernel (every block writes its sum) and only those are read by the finishing kernel, so nothing needs clearing.
 int run_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
-                   const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, float *partial,
-                   hipStream_t st) {
+                   const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, int32_t *n_invalid,
+                   float *partial, hipStream_t st) {
     const int G = group_lanes(F, lp_vec_elems(dtype));
     const int nb = loss_blocks(B, G);
     LpTimedScope timed(LP_KC_SCORE, st);
-    if (dtype == LP_BF16) launch_score<lp_bf16_t>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
-    else launch_score<float>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial);
+    if (dtype == LP_BF16) launch_score<lp_bf16_t>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial, n_invalid);
+    else launch_score<float>(G, nb, st, HK, n_nodes, F, B, n_pos_edges, e_src, e_dst, scores, dscore, partial, n_invalid);
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, B, loss);
     return lp_after_launch();
 }
@@ -166,21 +168,21 @@ int run_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, in
 }  // namespace
 
 extern "C" int lp_score_loss(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B, int64_t n_pos_edges,
-                             const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore, void *ws,
-                             size_t ws_bytes, void *stream) {
+                             const int32_t *e_src, const int32_t *e_dst, float *scores, float *loss, float *dscore,
+                             int32_t *n_invalid, void *ws, size_t ws_bytes, void *stream) {
     LP_TRY(check_score_args(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss));
     if (!ws || ws_bytes < lp_score_loss_workspace_bytes(B)) return LP_ERR_WORKSPACE;
-    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, static_cast<float *>(ws),
-                          static_cast<hipStream_t>(stream));
+    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, n_invalid,
+                          static_cast<float *>(ws), static_cast<hipStream_t>(stream));
 }
 
 extern "C" int lp_score_loss_noalloc(const void *HK, int32_t n_nodes, int32_t F, int32_t dtype, int64_t B,
                                      int64_t n_pos_edges, const int32_t *e_src, const int32_t *e_dst, float *scores,
-                                     float *loss, float *dscore, void *stream) {
+                                     float *loss, float *dscore, int32_t *n_invalid, void *stream) {
     LP_TRY(check_score_args(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss));
     if (B > LP_SCORE_LOSS_NOALLOC_MAX_EDGES) return LP_ERR_OUT_OF_RANGE;
     float *partial = scratch_of_current_device();   // the device address, never the array's name
     if (!partial) return LP_ERR_HIP;
-    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, partial,
+    return run_score_loss(HK, n_nodes, F, dtype, B, n_pos_edges, e_src, e_dst, scores, loss, dscore, n_invalid, partial,
                           static_cast<hipStream_t>(stream));
 }

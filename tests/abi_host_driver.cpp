@@ -89,7 +89,7 @@ int main(int argc, char **argv) {
         g_fail_symbol = true;
         float *q = reinterpret_cast<float *>(0x1000);
         const int32_t *e = reinterpret_cast<const int32_t *>(0x1000);
-        const int r = lp_score_loss_noalloc(q, 5000, 256, LP_F32, 1000, 400, e, e, q, q, q, nullptr);
+        const int r = lp_score_loss_noalloc(q, 5000, 256, LP_F32, 1000, 400, e, e, q, q, q, nullptr, nullptr);
         std::printf("no-symbol: status %d, %d launches\n", r, g_launches);
         return (r == LP_ERR_HIP && g_launches == 0) ? 0 : 1;
     }
@@ -119,17 +119,17 @@ int main(int argc, char **argv) {
     // ---- lp_score_loss and the variant without a workspace
     const size_t sws = lp_score_loss_workspace_bytes(1000);
     CHECK(sws > 0);
-    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, fp, sws, nullptr) == LP_OK);
-    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, fp, sws - 1, nullptr) == LP_ERR_WORKSPACE);
-    CHECK(lp_score_loss(fp, 5000, 254, LP_F32, 1000, 400, ip, ip, fp, fp, fp, fp, sws, nullptr) == LP_ERR_UNSUPPORTED);
-    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 1001, ip, ip, fp, fp, fp, fp, sws, nullptr) == LP_ERR_INVALID_ARG);
+    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, op, fp, sws, nullptr) == LP_OK);
+    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, op, fp, sws - 1, nullptr) == LP_ERR_WORKSPACE);
+    CHECK(lp_score_loss(fp, 5000, 254, LP_F32, 1000, 400, ip, ip, fp, fp, fp, op, fp, sws, nullptr) == LP_ERR_UNSUPPORTED);
+    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 1001, ip, ip, fp, fp, fp, op, fp, sws, nullptr) == LP_ERR_INVALID_ARG);
     int before = g_launches;
-    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_BF16, 1000, 400, ip, ip, fp, fp, nullptr, nullptr) == LP_OK);
+    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_BF16, 1000, 400, ip, ip, fp, fp, nullptr, nullptr, nullptr) == LP_OK);
     CHECK(g_launches == before + 2);
-    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_F32, LP_SCORE_LOSS_NOALLOC_MAX_EDGES + 1, 0, ip, ip, fp, fp, fp, nullptr) == LP_ERR_OUT_OF_RANGE);
+    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_F32, LP_SCORE_LOSS_NOALLOC_MAX_EDGES + 1, 0, ip, ip, fp, fp, fp, op, nullptr) == LP_ERR_OUT_OF_RANGE);
     g_fail_launch = true;
-    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, nullptr) == LP_ERR_HIP);
-    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, fp, sws, nullptr) == LP_ERR_HIP);
+    CHECK(lp_score_loss_noalloc(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, op, nullptr) == LP_ERR_HIP);
+    CHECK(lp_score_loss(fp, 5000, 256, LP_F32, 1000, 400, ip, ip, fp, fp, fp, op, fp, sws, nullptr) == LP_ERR_HIP);
     g_fail_launch = false;
 
     // ---- lp_sage_forward / lp_backward: the whole host-side orchestration of a three-layer model, both storage

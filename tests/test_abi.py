@@ -25,6 +25,11 @@ def test_library_exports_every_declared_function():
         assert getattr(lib, n) is not None
 
 
+def test_library_and_header_agree_on_the_abi_version():
+    text = open(os.path.join(ROOT, "include", "lp.h")).read()
+    assert int(re.search(r"#define\s+LP_ABI_VERSION\s+(\d+)", text).group(1)) == B.load_library().lp_abi_version()
+
+
 def test_strerror_covers_all_codes():
     texts = {B.lp_strerror(c) for c in (0, -1, -2, -3, -4, -5)}
     assert len(texts) == 6 and B.lp_strerror(-99) == "unknown status"
@@ -135,7 +140,7 @@ def test_sampler_and_loss_reject_bad_arguments_on_the_host():
     assert s(n_pos=1 << 30, k=4) == -2
     assert s(n_pos=0) == 0                             # nothing to do: no launch, no error
     sl = lambda F=64, dt=0, B_=4, npos=2, H=p, ws=p, wsb=1 << 20, loss=p: lib.lp_score_loss(
-        H, 10, F, dt, B_, npos, p, p, p, loss, p, ws, wsb, None)
+        H, 10, F, dt, B_, npos, p, p, p, loss, p, None, ws, wsb, None)
     assert sl(F=6) == -4
     assert sl(dt=3) == -4
     assert sl(npos=5) == -1

@@ -315,6 +315,51 @@ def test_score_loss_zero_embeddings_and_empty_batch():
     assert float(host(loss)[0]) == 0.0
 
 
+def test_edges_with_ids_outside_the_graph_are_counted_and_contribute_nothing():
+    """The documented contract for a corrupted batch: an edge with an end point outside [0, n_nodes) is never
+    dereferenced, is scored 0 with dscore 0, stays out of the loss sum and of every gradient, still counts in B, and is
+    reported through n_invalid."""
+    rng = np.random.default_rng(17)
+    n, dims = 900, [16, 32, 8]
+    r, c = random_pairs(rng, n, 3000)
+    say("edges with ids outside the graph n=%d" % n)
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 1200, 500
+    es, ed = rng.integers(0, n, B).astype(np.int32), rng.integers(0, n, B).astype(np.int32)
+    bad = rng.choice(B, 37, replace=False)
+    es[bad[:12]] = -1
+    ed[bad[12:25]] = n
+    es[bad[25:]] = n + 1000
+    ed[bad[30:]] = -7
+    ok = np.ones(B, bool)
+    ok[bad] = False
+    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+    acts = lp.lp_sage_forward(g, model, Xd)
+    counter = torch.zeros(1, dtype=torch.int32, device=DEV)
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos, n_invalid=counter)
+    assert int(host(counter)[0]) == bad.size
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    y_pos = int(ok[:n_pos].sum())                                   # the valid edges keep their labels
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es[ok], ed[ok], y_pos)
+    n_ok = int(ok.sum())
+    assert np.all(host(s)[~ok] == 0) and np.all(host(ds)[~ok] == 0)
+    assert_close(host(s)[ok], s_ref, TOL_ACT, "scores of the valid edges")
+    assert abs(float(host(loss)[0]) - loss_ref * n_ok / B) <= TOL_ACT * loss_ref
+    assert_close(host(ds)[ok], ds_ref * n_ok / B, TOL_ACT, "dscore of the valid edges")
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es[ok], ed[ok], ds_ref * n_ok / B)
+    K = len(dims) - 1
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es[ok], ed[ok], ds_ref * n_ok / B, hidden_of(acts, K)))
+    # the variant without a workspace counts the same
+    counter.zero_()
+    s2, l2 = torch.empty_like(s), torch.empty_like(loss)
+    lp.lp_score_loss_noalloc(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos, s2, l2, None, n_invalid=counter)
+    assert int(host(counter)[0]) == bad.size and host(l2).tobytes() == host(loss).tobytes()
+
+
 # ------------------------------------------------------------------------------------------------ backward
 DX_BAND_CAP = 1e-3      # the near-tie band of dX may cover at most 0.1 % of its entries
 

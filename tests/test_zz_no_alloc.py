@@ -62,10 +62,10 @@ def test_limits_and_argument_checks():
     l = torch.empty(1, dtype=torch.float32, device=DEV)
     p = lambda t: C.c_void_p(t.data_ptr())
     too_many = (1 << 28) + 1                 # beyond LP_SCORE_LOSS_NOALLOC_MAX_EDGES: rejected before any launch
-    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, too_many, 0, p(e), p(e), p(s), p(l), None, None) == -2
-    assert lib.lp_score_loss_noalloc(None, 4, 8, 0, 4, 0, p(e), p(e), p(s), p(l), None, None) == -1
-    assert lib.lp_score_loss_noalloc(p(H), 4, 6, 0, 4, 0, p(e), p(e), p(s), p(l), None, None) == -4
-    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, 4, 5, p(e), p(e), p(s), p(l), None, None) == -1
-    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, 4, 2, p(e), p(e), p(s), p(l), None, None) == 0
+    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, too_many, 0, p(e), p(e), p(s), p(l), None, None, None) == -2
+    assert lib.lp_score_loss_noalloc(None, 4, 8, 0, 4, 0, p(e), p(e), p(s), p(l), None, None, None) == -1
+    assert lib.lp_score_loss_noalloc(p(H), 4, 6, 0, 4, 0, p(e), p(e), p(s), p(l), None, None, None) == -4
+    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, 4, 5, p(e), p(e), p(s), p(l), None, None, None) == -1
+    assert lib.lp_score_loss_noalloc(p(H), 4, 8, 0, 4, 2, p(e), p(e), p(s), p(l), None, None, None) == 0
     torch.cuda.synchronize()
     assert abs(float(l.item()) - np.log(2.0)) < 1e-6
