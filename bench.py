@@ -7,7 +7,8 @@ by default the largest single-GPU configuration ("C4", the one the aggregation's
 graph with the paper's largest edge count, 2.9 M nodes, ~29 M directed CSR entries (feature matrices of 1.5-3 GB, far
 beyond the 256 MB Infinity Cache), 128 -> 256 -> 256 -> 256 GraphSAGE-mean in fp32, 131 072 positives + 131 072
 negatives per step; --workload selects the other configurations (C1, C2, C3, C5_keep1, C5_keep0.5, C5_keep0.2).
-Prints ONE JSON line.
+Run without --workload, the Collab-scale configuration C2 is measured after it and reported under "also" in the same
+line.  Prints ONE JSON line.
 
 The per-kernel numbers in "roofline" come from HIP events recorded by the library around each launch inside the
 timed region (lp_timing_enable); "cpu_baseline" times the CPU oracle, as it stands, on a stated fraction of the
@@ -307,44 +308,9 @@ def sampled_step_task(args):
     print(json.dumps(out), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default=None, help="default: C4 (train_step), C2 (sampled_step), C3 (sparsify)")
-    ap.add_argument("--cpu-scale", type=float, default=None,
-                    help="fraction of the workload the CPU oracle is timed on (default: per workload, 10-30 s of host work)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--timing-level", type=int, default=1, choices=[1, 2],
-                    help="1: HIP events around the aggregation, GEMM, scatter, score and sampler launches; 2: around every launch")
-    ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
-                    help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "
-                         "sampled_step: the mini-batch mode with sampled neighbourhoods")
-    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
-                    help="--task train_step: GraphSAGE-mean layers (the headline) or GCN layers (self-pairs added to the graph)")
-    ap.add_argument("--predictor", default="dot", choices=["dot", "mlp"],
-                    help="--task train_step: dot-product scorer (the headline) or the 3-layer MLP edge predictor")
-    ap.add_argument("--fp32-products", default="bf16x6", choices=["bf16x6", "native"],
-                    help="how fp32 models form their dense products (the fp32_products field of lp_model in include/lp.h)")
-    ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
-    ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
-    ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
-    ap.add_argument("--copy-calibration-mib", type=int, default=0,
-                    help="also run one plain device copy of this many MiB (a dispatch of known size for counter runs)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.stderr.write("bench.py measures one worker's step on ONE GPU; --gpus %d is not supported "
-                         "(no collectives are part of this build)\n" % args.gpus)
-        sys.exit(2)
-
-    if args.task == "sparsify":
-        return sparsify_task(args)
-    if args.task == "sampled_step":
-        args.workload = args.workload or "C2"
-        return sampled_step_task(args)
-    args.workload = args.workload or "C4"
-
+def run_train_step(args, workload, full=True):
+    """One measurement of the training step on `workload`; returns the JSON object.  full=False (a secondary workload
+    reported beside the headline) leaves out the graph replay, the other way of forming fp32 products and the oracle."""
     import numpy as np
     import torch
 
@@ -355,7 +321,7 @@ def main():
     products = lp.LP_FP32_PRODUCTS_NATIVE if args.fp32_products == "native" else lp.LP_FP32_PRODUCTS_BF16X6
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = make_workload(args.workload)
+    wl = make_workload(workload)
     i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
     f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
 
@@ -419,7 +385,7 @@ def main():
             lp.lp_backward_edge_grads(g, model, X, acts, e_src, e_dst, eg, grads, ws_b)
             loss.copy_(l_)
 
-    if args.copy_calibration_mib > 0:
+    if full and args.copy_calibration_mib > 0:
         a = torch.zeros(args.copy_calibration_mib << 18, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
         torch.cuda.synchronize()
@@ -443,6 +409,8 @@ def main():
     # this figure is informational and `value` comes from the eager steps
     graph_ms = None
     try:
+        if not full:
+            raise RuntimeError("not measured for a secondary workload")
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -460,7 +428,8 @@ def main():
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
     except RuntimeError as exc:   # capture unsupported in this environment: report that, do not fail the benchmark
-        sys.stderr.write("graph replay not measured: %s\n" % exc)
+        if full:
+            sys.stderr.write("graph replay not measured: %s\n" % exc)
 
     # timed region, with the library's per-launch HIP events switched on
     lp.lp_timing_enable(args.timing_level)
@@ -478,7 +447,7 @@ def main():
 
     # for reference, the same steps with the other way of forming the fp32 products (outside the timed region)
     other_products = None
-    if not bf16 and mlp is None:   # the same weight tensors as a second model with the other value of fp32_products
+    if full and not bf16 and mlp is None:   # the same weight tensors as a second model with the other value of fp32_products
         models["other"] = model.with_products(lp.LP_FP32_PRODUCTS_NATIVE if split else lp.LP_FP32_PRODUCTS_BF16X6)
         for i in range(3):
             step(3000 + i, "other")
@@ -535,7 +504,7 @@ def main():
     # each scaled by what a plain copy of known size reads), named in "traffic_source"; null when no summary covers
     # the workload and model variant.
     traffic = {}
-    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % workload)
     if os.path.exists(tpath) and not gcn and not use_mlp and (bf16 or split):
         with open(tpath) as fh:
             traffic = json.load(fh)
@@ -566,13 +535,13 @@ def main():
         t = traffic.get(cls + "_bytes_per_launch")
         lines[cls]["traffic"] = int(t) if t else None
         if t:
-            lines[cls]["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % args.workload)
+            lines[cls]["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % workload)
             if lines[cls]["bound"] == "hbm" and lines[cls]["avg_launch_ms"] > 0:   # counter bytes / time / peak
                 lines[cls]["frac_counters"] = round(t / (lines[cls]["avg_launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     t = traffic.get("sample_bytes_per_launch")
     if t:
         sample_line["traffic"] = int(t)
-        sample_line["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % args.workload)
+        sample_line["traffic_source"] = traffic.get("source", "profiles/traffic_%s.json" % workload)
         if sample_line["avg_launch_ms"] > 0:
             sample_line["counter_gbs"] = round(t / (sample_line["avg_launch_ms"] * 1e-3) / 1e9, 1)
     score_line = lines.pop("score")
@@ -596,7 +565,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: synthetic power-law graph, %d nodes, %d directed CSR entries, %s %s, %s, "
                                "%d positives + %d uniform negatives per step, full-neighbour aggregation"
-                               % (args.workload, n, nnz, "GCN (self-pairs in the graph)" if gcn else "GraphSAGE-mean",
+                               % (workload, n, nnz, "GCN (self-pairs in the graph)" if gcn else "GraphSAGE-mean",
                                   "->".join(map(str, wl.dims)), "3-layer MLP edge predictor" if use_mlp else "dot-product scorer",
                                   n_pos, n_pos * k_neg),
                    "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg,
@@ -614,8 +583,67 @@ def main():
     }
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
         out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
-    if not args.no_cpu_baseline and not gcn and not use_mlp:   # the oracle leg times the headline step only
-        out["cpu_baseline"] = cpu_baseline(args.workload, args.cpu_scale if args.cpu_scale else CPU_SCALE.get(args.workload, 0.1))
+    if full and not args.no_cpu_baseline and not gcn and not use_mlp:   # the oracle leg times the headline step only
+        out["cpu_baseline"] = cpu_baseline(workload, args.cpu_scale if args.cpu_scale else CPU_SCALE.get(workload, 0.1))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None, help="default: C4 (train_step), C2 (sampled_step), C3 (sparsify)")
+    ap.add_argument("--cpu-scale", type=float, default=None,
+                    help="fraction of the workload the CPU oracle is timed on (default: per workload, 10-30 s of host work)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads measured after the headline and reported under \"also\" (same step; no "
+                         "oracle leg).  Default: C2 when --workload is not given, nothing otherwise")
+    ap.add_argument("--timing-level", type=int, default=1, choices=[1, 2],
+                    help="1: HIP events around the aggregation, GEMM, scatter, score and sampler launches; 2: around every launch")
+    ap.add_argument("--task", default="train_step", choices=["train_step", "sparsify", "sampled_step"],
+                    help="train_step: the headline metric; sparsify: the sparsification pass over all partitions; "
+                         "sampled_step: the mini-batch mode with sampled neighbourhoods")
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
+                    help="--task train_step: GraphSAGE-mean layers (the headline) or GCN layers (self-pairs added to the graph)")
+    ap.add_argument("--predictor", default="dot", choices=["dot", "mlp"],
+                    help="--task train_step: dot-product scorer (the headline) or the 3-layer MLP edge predictor")
+    ap.add_argument("--fp32-products", default="bf16x6", choices=["bf16x6", "native"],
+                    help="how fp32 models form their dense products (the fp32_products field of lp_model in include/lp.h)")
+    ap.add_argument("--n-pos", type=int, default=10240, help="positives per batch of --task sampled_step")
+    ap.add_argument("--fanout", default="25,10,5", help="neighbours per hop of --task sampled_step, first hop first")
+    ap.add_argument("--alpha", type=float, default=0.15, help="sparsification level (draws per edge) of --task sparsify")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a dispatch of known size for counter runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py measures one worker's step on ONE GPU; --gpus %d is not supported "
+                         "(no collectives are part of this build)\n" % args.gpus)
+        sys.exit(2)
+
+    if args.task == "sparsify":
+        return sparsify_task(args)
+    if args.task == "sampled_step":
+        args.workload = args.workload or "C2"
+        return sampled_step_task(args)
+    if args.also is None:
+        args.also = "C2" if args.workload is None else ""
+    args.workload = args.workload or "C4"
+
+    out = run_train_step(args, args.workload, True)
+    also = [w for w in args.also.split(",") if w and w != args.workload] if (args.model == "sage" and args.predictor == "dot") else []
+    if also:   # e.g. the Collab-scale workload beside the headline: same step, same code, its own rooflines
+        out["also"] = {}
+        for w in also:
+            import gc
+            import torch
+            gc.collect()
+            torch.cuda.empty_cache()
+            r = run_train_step(args, w, False)
+            out["also"][w] = {k: r[k] for k in ("value", "unit", "ms_per_step", "ms_per_step_without_events", "dtype", "fp32_products",
+                                                "config", "loss", "roofline_spmm", "roofline_gemm_nt", "roofline_gemm_tn",
+                                                "roofline_score", "sampler", "kernel_ms_per_step")}
     print(json.dumps(out), flush=True)
 
 
