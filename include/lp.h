@@ -109,7 +109,9 @@ typedef struct lp_csr {
     const int32_t *t_rowptr;   /* device [n_nodes + 1] */
     const int32_t *t_colidx;   /* device [nnz] */
     const float *inv_deg;      /* device [n_nodes]: 1/|N(v)|, 0 when N(v) is empty */
-    const int32_t *row_order;  /* device [n_nodes] or NULL: rows by decreasing |N(v)| (launch order hint) */
+    const int32_t *row_order;  /* device [n_nodes] or NULL: a permutation of the rows, the order the aggregation visits
+                                  them in (lp_build_csr: rows with |N(v)| >= 64 by decreasing floor(log2 |N(v)|), then
+                                  all others, ids ascending inside a class); any permutation gives the same results */
     const int32_t *t_row_order;/* device [n_nodes] or NULL: same for the transposed CSR */
 } lp_csr;
 

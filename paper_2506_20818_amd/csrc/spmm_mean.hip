@@ -7,7 +7,8 @@
 // (4 floats or 8 bfloat16; fully coalesced: 64 lanes cover 1 KiB); when G < 64 the wavefront reads 64/G neighbours
 // at once and folds the partial sums with xor-shuffles at the end.  Neighbour ids are fetched 64 at a time
 // (coalesced) and handed to the lanes that need them through the LDS crossbar (ds_bpermute), several rows in flight
-// per lane.  Rows are visited in `row_order` (longest first) when given, so that long rows start early.
+// per lane.  Rows are visited in `row_order` when given (lp_build_csr lists rows of 64 and more entries first, by
+// decreasing size class, then all others by ascending id), so that long rows start early.
 //
 // Hub rows: a single wavefront keeps only a few KiB in flight, so a row with thousands of neighbours would take
 // longer than the rest of the launch together (power-law graphs have such rows).  When the caller supplies a queue,
@@ -26,6 +27,9 @@
 namespace {
 
 constexpr int kThreads = 256;
+// One row per workgroup in the row kernel: the wavefronts of a larger workgroup hold their slots until its longest row
+// is done, which cost 1-8 % where neighbouring rows differ much in length (measured with 128 and 256 threads).
+constexpr int kRowThreads = 64;
 constexpr int kLongThreads = 1024;
 constexpr int kLongWaves = kLongThreads / 64;
 constexpr int kLongHeader = 64;                        // words ahead of the queued rows (count, seg, tasks, slots)
@@ -148,10 +152,10 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
 }
 
 template <typename T, int G, int C, int W>
-__global__ __launch_bounds__(kThreads) void spmm_rows_kernel(SpmmArgs a) {
+__global__ __launch_bounds__(kRowThreads) void spmm_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
     const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const int64_t r = (int64_t)blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
     if (r >= a.n_rows || (a.n_rows_dev && r >= *a.n_rows_dev)) return;
     const int32_t v = a.row_order ? a.row_order[r] : (int32_t)r;
     const int sub = lane / G, fl = lane % G;
@@ -350,11 +354,11 @@ __global__ __launch_bounds__(kThreads) void spmm_long_rows_finish_kernel(SpmmArg
 
 template <typename T, int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
-    const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kThreads / 64);
+    const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kRowThreads / 64);
     const int mode = a.entry_rows ? 2 : ((a.w || a.sym_norm) ? 1 : 0);
-    if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2>), dim3(grid), dim3(kThreads), 0, st, a);
-    else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kThreads), 0, st, a);
+    if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2>), dim3(grid), dim3(kRowThreads), 0, st, a);
+    else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kRowThreads), 0, st, a);
+    else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kRowThreads), 0, st, a);
     if (a.long_queue) {
         // no more rows can be queued than fit the entry count, and a row of at least 512 entries is at most two tasks
         // per 1024 entries; two workgroups per compute unit walk the tasks

@@ -37,11 +37,11 @@ def check_csr(g, ref):
         assert np.array_equal(host(getattr(g, name)), getattr(ref, name)), name
     assert np.array_equal(host(g.inv_deg).view(np.uint32), ref.inv_deg.view(np.uint32)), "inv_deg bits"
     for order, rp in ((g.row_order, ref.rowptr), (g.t_row_order, ref.t_rowptr)):
-        o = host(order)
-        assert np.array_equal(np.sort(o), np.arange(ref.n_nodes)), "row order is not a permutation"
-        deg = np.diff(rp)[o].astype(np.int64)
-        cls = np.where(deg > 0, np.floor(np.log2(np.maximum(deg, 1))), -1)
-        assert np.all(np.diff(cls) <= 0), "rows are not listed by decreasing size class"
+        # rows of 64 and more entries by decreasing floor(log2(length)), then all shorter rows; ids ascending in a class
+        deg = np.diff(rp).astype(np.int64)
+        cls = np.where(deg >= 64, np.floor(np.log2(np.maximum(deg, 1))).astype(np.int64), 5)
+        expect = np.lexsort((np.arange(ref.n_nodes), -cls))
+        assert np.array_equal(host(order), expect), "row order"
 
 
 # ------------------------------------------------------------------------------------------------ lp_build_csr
