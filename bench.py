@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark: one worker's link-prediction training step on one MI355X.
 
-A step is one pass of the whole hot path over one minibatch: lp_sample_neg -> lp_sage_forward (full-neighbour,
-all visible nodes) -> lp_score_loss -> lp_backward, with every input already resident in HBM.  The workload is
+A step is one pass of the whole hot path over one minibatch: lp_sample_neg -> lp_sage_forward_edges (full-neighbour
+layers over all visible nodes; the last layer at the end points of the scored edges, the only rows the loss reads) ->
+lp_score_loss -> lp_backward, with every input already resident in HBM.  The workload is
 by default the largest single-GPU configuration ("C4", the one the aggregation's HBM target is judged on): a power-law
 graph with the paper's largest edge count, 2.9 M nodes, ~29 M directed CSR entries (feature matrices of 1.5-3 GB, far
 beyond the 256 MB Infinity Cache), 128 -> 256 -> 256 -> 256 GraphSAGE-mean in fp32, 131 072 positives + 131 072
@@ -55,17 +56,24 @@ def fp32_products_name(bf16, split):
     return "bf16x6 (three bfloat16 terms per value, six term products, fp32 accumulation)" if split else "fp32 matrix instructions"
 
 
+def spmm_bytes_rows(n_t, nnz_t, F, eb=4):
+    """The last layer's forward aggregation: only the n_t rows of the end points of the scored edges (nnz_t entries
+    in all): their list, row pointers, inverse degrees, column ids, gathered rows and output rows."""
+    return n_t * 4 + 2 * n_t * 4 + n_t * 4 + nnz_t * (eb * F + 4) + n_t * eb * F
+
+
 def step_counts(n, nnz, dims, n_t, nnz_t, eb=4, paths=2):
-    """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer's backward products run over the
-    n_t endpoint rows only (every other row of dL/dH^K is exactly zero).  paths: weight matrices per layer (2 for
-    GraphSAGE's self and neighbour paths, 1 for GCN)."""
+    """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer runs over the n_t end points of the
+    scored edges only, forward (no other row of h^(K) is read by the loss) and backward (every other row of dL/dH^K is
+    exactly zero).  paths: weight matrices per layer (2 for GraphSAGE's self and neighbour paths, 1 for GCN)."""
     K = len(dims) - 1
-    sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K + 1))
+    sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K))
+    sp += spmm_bytes_rows(n_t, nnz_t, dims[K - 1], eb)
     sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K))
     if K >= 2:
         sp += spmm_bytes_listed(n, nnz, dims[K - 1], n_t, nnz_t, eb)
     rows = lambda k: n_t if k == K else n
-    nt = sum(2.0 * n * dims[k] * paths * dims[k - 1] for k in range(1, K + 1))            # forward
+    nt = sum(2.0 * rows(k) * dims[k] * paths * dims[k - 1] for k in range(1, K + 1))      # forward
     nt += sum(2.0 * rows(k) * paths * dims[k - 1] * dims[k] for k in range(2, K + 1))     # input gradients
     tn = sum(2.0 * paths * rows(k) * dims[k - 1] * dims[k] for k in range(1, K + 1))      # dW_self, dW_neigh
     return sp, nt, tn
@@ -365,7 +373,7 @@ def run_train_step(args, workload, full=True):
     neg_src, neg_dst = e_src[n_pos:], e_dst[n_pos:]
     acts = lp.Acts(wl.n_nodes, wl.dims, dev, tdt)
     grads = lp.Grads(wl.n_nodes, wl.dims, dev, dtype=tdt)
-    ws_f = torch.empty(B.forward_workspace_bytes(model, wl.n_nodes), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(B.forward_edges_workspace_bytes(model, wl.n_nodes, Bn), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(B.backward_workspace_bytes(model, wl.n_nodes, Bn), dtype=torch.uint8, device=dev)
     ws_l = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
     scores = torch.empty(Bn, dtype=torch.float32, device=dev)
@@ -375,7 +383,7 @@ def run_train_step(args, workload, full=True):
     def step(i, which="timed"):
         model = models[which]
         lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
-        lp.lp_sage_forward(g, model, X, acts, ws_f)
+        lp.lp_sage_forward_edges(g, model, X, e_src, e_dst, acts, ws_f)   # the last layer where the loss reads it
         if mlp is None:
             lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
             lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)

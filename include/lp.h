@@ -207,7 +207,7 @@ const char *lp_strerror(int status);
 
 /* Version of this header's structs and signatures, bumped with every change to them.  lp_abi_version() returns the
  * value the library was built with: a caller (or binding) that was written against another one must not go on. */
-#define LP_ABI_VERSION 3
+#define LP_ABI_VERSION 4
 int lp_abi_version(void);
 
 /* ---------------------------------------------------------------------------
@@ -243,6 +243,28 @@ int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, const int32
 size_t lp_sage_forward_workspace_bytes(const lp_model *m, int32_t n_nodes);
 int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *saved, void *ws,
                     size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * lp_sage_forward_edges - the forward pass of a TRAINING step (Algorithm 1:
+ * the layers of Eq. (1), of which the loss of Eq. (2) reads only the
+ * embeddings of the end points of the scored edges).  Layers 1..K-1 are
+ * evaluated for every visible node as in lp_sage_forward; layer K only for the
+ * nodes that are e_src[i] or e_dst[i] of one of the B scored edges (device
+ * [B] each; an edge with an id outside [0, n_nodes) lists nothing).  Rows of
+ * saved->A[K-1] and saved->H[K-1] that belong to other nodes are unspecified
+ * afterwards: when 4*B < n_nodes they are neither read nor written and keep
+ * whatever they held; a larger batch can touch so much of the graph that
+ * listing does not pay, and every row is evaluated.  lp_score_loss / lp_mlp_score_loss
+ * and lp_backward / lp_backward_edge_grads on the SAME edges read only rows
+ * that were written, and give what they give after lp_sage_forward up to the
+ * order of fp32 sums.  B = 0 evaluates layers 1..K-1 only.  Embeddings of all
+ * nodes (evaluation, inference) need lp_sage_forward.
+ * Errors as lp_sage_forward; B < 0 or B > 0 with a NULL id array is
+ * LP_ERR_INVALID_ARG, B >= 2^31 LP_ERR_OUT_OF_RANGE.
+ */
+size_t lp_sage_forward_edges_workspace_bytes(const lp_model *m, int32_t n_nodes, int64_t B);
+int lp_sage_forward_edges(const lp_csr *g, const lp_model *m, const void *X, int64_t B, const int32_t *e_src,
+                          const int32_t *e_dst, lp_acts *saved, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * lp_sample_neg - per-source uniform negative sampling (Sec. II-B; Algorithm 1,

@@ -94,6 +94,9 @@ EXPORTS = {
                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
                                C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_sage_forward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
+    "lp_sage_forward_edges_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
+    "lp_sage_forward_edges": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.c_int64, C.c_void_p,
+                                        C.c_void_p, C.POINTER(_ActsStruct), C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_sage_forward": (C.c_int, [C.POINTER(_CsrStruct), C.POINTER(_ModelStruct), C.c_void_p, C.POINTER(_ActsStruct),
                                   C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_sample_neg": (C.c_int, [C.POINTER(_CsrStruct), C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
@@ -332,6 +335,28 @@ def lp_sage_forward(g: Csr, m: Model, X: torch.Tensor, acts: Optional[Acts] = No
         ws = _ws(lib.lp_sage_forward_workspace_bytes(C.byref(m.c), g.n_nodes), X.device)
     _check(lib.lp_sage_forward(C.byref(g.c), C.byref(m.c), _ptr(X), C.byref(acts.c), _ptr(ws), ws.numel(), _stream()),
            "lp_sage_forward")
+    return acts
+
+
+def lp_sage_forward_edges(g: Csr, m: Model, X: torch.Tensor, e_src: torch.Tensor, e_dst: torch.Tensor,
+                          acts: Optional[Acts] = None, ws: Optional[torch.Tensor] = None) -> Acts:
+    """The forward pass of a training step: the last layer only for the end points of the scored edges (the other rows
+    of acts.A[-1] and acts.H[-1] keep what they held)."""
+    lib = load_library()
+    _need(X, m.torch_dtype, "X")
+    _need(e_src, torch.int32, "e_src")
+    _need(e_dst, torch.int32, "e_dst")
+    if tuple(X.shape) != (g.n_nodes, m.dims[0]):
+        raise ValueError("X has the wrong shape")
+    Bn = int(e_src.numel())
+    if int(e_dst.numel()) != Bn:
+        raise ValueError("e_src and e_dst differ in length")
+    if acts is None:
+        acts = Acts(g.n_nodes, m.dims, X.device, m.torch_dtype)
+    if ws is None:
+        ws = _ws(lib.lp_sage_forward_edges_workspace_bytes(C.byref(m.c), g.n_nodes, Bn), X.device)
+    _check(lib.lp_sage_forward_edges(C.byref(g.c), C.byref(m.c), _ptr(X), Bn, _ptr(e_src), _ptr(e_dst), C.byref(acts.c),
+                                     _ptr(ws), ws.numel(), _stream()), "lp_sage_forward_edges")
     return acts
 
 
@@ -715,6 +740,10 @@ def backward_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:
 
 def forward_workspace_bytes(m: Model, n_nodes: int) -> int:
     return int(load_library().lp_sage_forward_workspace_bytes(C.byref(m.c), n_nodes))
+
+
+def forward_edges_workspace_bytes(m: Model, n_nodes: int, B: int) -> int:
+    return int(load_library().lp_sage_forward_edges_workspace_bytes(C.byref(m.c), n_nodes, B))
 
 
 KERNEL_CLASSES = ["spmm", "gemm_nt", "gemm_tn", "scatter", "score", "sample", "other"]

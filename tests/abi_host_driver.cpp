@@ -151,6 +151,32 @@ int main(int argc, char **argv) {
         CHECK(lp_sage_forward(&g, &m, fp, &acts, fake<void>(0x100000), fws, nullptr) == LP_OK);
         CHECK(g_launches >= before + 6);   // three aggregations and three products at least
         CHECK(lp_sage_forward(&g, &m, fp, &acts, fake<void>(0x100000), fws - 1, nullptr) == LP_ERR_WORKSPACE);
+        // the training forward: a batch small enough to list the rows of the last layer (more launches than the full
+        // pass: flags, prefix sums, row copies), one too large for that, and an empty one
+        {
+            const int64_t few = g.n_nodes / 4 - 1, many = g.n_nodes;
+            const size_t ews = lp_sage_forward_edges_workspace_bytes(&m, g.n_nodes, few);
+            const size_t mws = lp_sage_forward_edges_workspace_bytes(&m, g.n_nodes, many);
+            CHECK(ews > fws && mws == fws);
+            long b0 = g_launches;
+            CHECK(lp_sage_forward(&g, &m, fp, &acts, fake<void>(0x100000), fws, nullptr) == LP_OK);
+            const long full_launches = g_launches - b0;
+            b0 = g_launches;
+            CHECK(lp_sage_forward_edges(&g, &m, fp, few, ip, ip, &acts, fake<void>(0x100000), ews, nullptr) == LP_OK);
+            CHECK(g_launches - b0 > full_launches);
+            b0 = g_launches;
+            CHECK(lp_sage_forward_edges(&g, &m, fp, many, ip, ip, &acts, fake<void>(0x100000), mws, nullptr) == LP_OK);
+            CHECK(g_launches - b0 == full_launches);
+            b0 = g_launches;
+            CHECK(lp_sage_forward_edges(&g, &m, fp, 0, nullptr, nullptr, &acts, fake<void>(0x100000),
+                                        lp_sage_forward_edges_workspace_bytes(&m, g.n_nodes, 0), nullptr) == LP_OK);
+            CHECK(g_launches - b0 < full_launches);   // the last layer is left out
+            CHECK(lp_sage_forward_edges(&g, &m, fp, few, ip, ip, &acts, fake<void>(0x100000), ews - 1, nullptr) == LP_ERR_WORKSPACE);
+            CHECK(lp_sage_forward_edges(&g, &m, fp, few, nullptr, ip, &acts, fake<void>(0x100000), ews, nullptr) == LP_ERR_INVALID_ARG);
+            g_fail_launch = true;
+            CHECK(lp_sage_forward_edges(&g, &m, fp, few, ip, ip, &acts, fake<void>(0x100000), ews, nullptr) == LP_ERR_HIP);
+            g_fail_launch = false;
+        }
         CHECK(lp_backward(&g, &m, fp, &acts, 2000, ip, ip, fp, &grads, fake<void>(0x100000), bws, nullptr) == LP_OK);
         grads.dX = fake<void>();
         CHECK(lp_backward(&g, &m, fp, &acts, 2000, ip, ip, fp, &grads, fake<void>(0x100000), bws, nullptr) == LP_OK);

@@ -46,10 +46,17 @@ def make_model(W_self, W_neigh, bias, products=lp.LP_FP32_PRODUCTS_BF16X6):
                     fp32_products=products)
 
 
+def nan_filled_acts(n_nodes, model, X):
+    acts = lp.Acts(n_nodes, model.dims, X.device, model.torch_dtype)
+    for t in acts.A + acts.H:
+        t.fill_(float("nan"))
+    return acts
+
+
 class HipStep:
     """One training step through the five C-ABI calls, keeping every intermediate for comparison."""
 
-    def __init__(self, g, model, X, pos_src, pos_dst, k_neg, n_space, seed, step, want_dX=True):
+    def __init__(self, g, model, X, pos_src, pos_dst, k_neg, n_space, seed, step, want_dX=True, forward="all"):
         n_pos = int(pos_src.numel())
         B = n_pos * (1 + k_neg)
         self.e_src = torch.empty(B, dtype=torch.int32, device=DEV)
@@ -59,7 +66,11 @@ class HipStep:
         self.n_failed = torch.zeros(1, dtype=torch.int32, device=DEV)
         lp.lp_sample_neg(g, pos_src, k_neg, n_space, seed, step, neg_dst=self.e_dst[n_pos:], neg_src=self.e_src[n_pos:],
                          n_failed=self.n_failed)
-        self.acts = lp.lp_sage_forward(g, model, X)
+        if forward == "edges":   # the training forward: rows of the last layer that it must not touch hold NaN
+            self.acts = nan_filled_acts(g.n_nodes, model, X)
+            lp.lp_sage_forward_edges(g, model, X, self.e_src, self.e_dst, self.acts)
+        else:
+            self.acts = lp.lp_sage_forward(g, model, X)
         self.scores, self.loss, self.dscore = lp.lp_score_loss(self.acts.H[-1], self.e_src, self.e_dst, n_pos)
         self.grads = lp.lp_backward(g, model, X, self.acts, self.e_src, self.e_dst, self.dscore, want_dX=want_dX)
         torch.cuda.synchronize()

@@ -119,6 +119,23 @@ def test_forward_backward_reject_bad_arguments_on_the_host():
     assert fwd(graph=big) == -2
     zero_layers = _model([128])
     assert fwd(m=zero_layers) == -1
+    # the training forward: the same checks (shared code), plus those on the batch
+    fwe = lambda B_=4, es=p, ed=p, m=good, ws=p, wsb=1 << 40: lib.lp_sage_forward_edges(
+        C.byref(g), C.byref(m), p, B_, es, ed, C.byref(acts), ws, wsb, None)
+    assert fwe(B_=-1) == -1
+    assert fwe(es=None) == -1 and fwe(ed=None) == -1
+    assert fwe(B_=1 << 31) == -2
+    assert fwe(ws=None) == -3 and fwe(wsb=8) == -3
+    assert fwe(m=_model([128, 256], products=2)) == -1
+    n_graph = g.n_nodes
+    few, many = n_graph // 4 - 1, n_graph // 4 + 1
+    w0 = lib.lp_sage_forward_workspace_bytes(C.byref(good), n_graph)
+    w_few = lib.lp_sage_forward_edges_workspace_bytes(C.byref(good), n_graph, few)
+    assert w_few > w0 > 0                                   # the list, its flags and three matrices of listed rows
+    assert lib.lp_sage_forward_edges_workspace_bytes(C.byref(good), n_graph, -1) == 0
+    assert lib.lp_sage_forward_edges_workspace_bytes(C.byref(good), n_graph, 1 << 31) == 0
+    assert lib.lp_sage_forward_edges_workspace_bytes(C.byref(good), n_graph, many) == w0     # too many to list: the plain pass
+    assert fwe(B_=few, wsb=w_few - 1) == -3
     bwd = lambda B_=4, es=p, ws=p, wsb=1 << 40, gr=grads: lib.lp_backward(
         C.byref(g), C.byref(good), p, C.byref(acts), B_, es, p, p, C.byref(gr), ws, wsb, None)
     assert bwd(B_=-1) == -1

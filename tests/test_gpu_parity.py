@@ -531,6 +531,147 @@ def test_backward_empty_batch_gives_zero_gradients():
         assert np.all(host(t) == 0)
 
 
+# ------------------------------------------------------------------------------------------------ training forward
+def oracle_acts_with_the_kernel_gates(acts_ref, hidden_gpu, K, max_abs_z=1e-5, max_share=1e-5):
+    """relu'(z) = [z > 0] is a decision taken in floating point; where the kernel's fp32 pre-activation and the oracle's
+    fp64 one fall on different sides of 0 both answers are correct, and a comparison of what follows has to take the
+    decision in one precision: the kernel's.  Returns the oracle's activations with the sign of Z flipped at exactly
+    those units (nothing else changes), after checking that they are genuine near-ties (|z| <= max_abs_z) and few."""
+    Z = list(acts_ref.Z)
+    flips = 0
+    for k in range(1, K):
+        z = acts_ref.Z[k]
+        differ = (np.asarray(hidden_gpu[k - 1]) > 0) != (z > 0)
+        if differ.any():
+            assert float(np.abs(z[differ]).max()) <= max_abs_z, "gate decisions differ away from 0"
+            Z[k] = np.where(differ, -z, z)
+            Z[k][differ & (z == 0)] = 1e-300          # the oracle's exact 0 (gate closed), the kernel's gate open
+            flips += int(differ.sum())
+    assert flips <= max(1, int(max_share * sum(acts_ref.Z[k].size for k in range(1, K))))
+    return O.Activations(acts_ref.H, acts_ref.A, Z), flips
+
+
+def check_last_layer_listed(acts, a_ref, es, ed, K, tol=TOL_ACT, to_host=host, what=""):
+    """After lp_sage_forward_edges into NaN-filled matrices: the lower layers complete; rows of A^K and H^K of the end
+    points of the scored edges against the oracle; with 4 B < n every other row still NaN (never written), else every
+    row evaluated.  Returns the end points."""
+    n = a_ref.H[K].shape[0]
+    ok = (es >= 0) & (es < n) & (ed >= 0) & (ed < n)
+    ends = np.unique(np.concatenate([es[ok], ed[ok]])).astype(np.int64)
+    rest = np.ones(n, bool)
+    rest[ends] = False
+    for k in range(1, K):
+        assert_close(to_host(acts.A[k - 1]), a_ref.A[k], tol, what + "A^%d" % k)
+        assert_close(to_host(acts.H[k - 1]), a_ref.H[k], tol, what + "H^%d" % k)
+    A, H = to_host(acts.A[K - 1]), to_host(acts.H[K - 1])
+    if 4 * es.size < n:
+        if ends.size:
+            assert_close(A[ends], a_ref.A[K][ends], tol, what + "A^K at the end points")
+            assert_close(H[ends], a_ref.H[K][ends], tol, what + "H^K at the end points")
+        assert np.isnan(A[rest]).all() and np.isnan(H[rest]).all(), "a row of a node that is no end point was written"
+    else:
+        assert_close(A, a_ref.A[K], tol, what + "A^K")
+        assert_close(H, a_ref.H[K], tol, what + "H^K")
+    return ends
+
+
+@pytest.mark.parametrize("dims", [[12, 8], [12, 20, 4], [128, 256, 256, 256], [100, 132, 68], [64, 512, 128]])
+@pytest.mark.parametrize("B,bad_ids", [(1, False), (150, False), (345, False), (6000, False), (345, True)])
+def test_training_forward_evaluates_the_last_layer_at_the_end_points_only(dims, B, bad_ids):
+    """lp_sage_forward_edges, then the loss and the backward pass on the same edges: everything against the oracle's
+    full pass.  B = 345 lists about 600 nodes (more than the rows of one tile of the dense product, the hub row 3 among
+    them); B = 6000 is beyond n / 4, where every node is evaluated.  With bad_ids two edges carry an id outside the graph: they list nothing, and the loss and the
+    gradients are those the library gives after the full forward pass."""
+    rng = np.random.default_rng(4100 + sum(dims) + B + bad_ids)
+    n = 1400 + dims[0]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 700)
+    say("training forward dims=%s B=%d n=%d" % (dims, B, n))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    es[0] = 3                                            # the 700-entry row
+    if bad_ids:
+        es[5], ed[7] = -1, n
+    n_pos = max(1, B // 3)
+    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+    K = len(dims) - 1
+    from gpu_util import nan_filled_acts
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(es), dev_i32(ed), acts)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    ends = check_last_layer_listed(acts, a_ref, es, ed, K)
+    assert ends.size <= 2 * B
+    # what follows reads only rows that were written
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    valid = (es >= 0) & (es < n) & (ed >= 0) & (ed < n)
+    # the same step after the full forward pass: equal up to the order of the sums over hub rows
+    full = lp.lp_sage_forward(g, model, Xd)
+    s2, loss2, ds2 = lp.lp_score_loss(full.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    assert_close(host(s), host(s2), 1e-6, "scores after either forward pass")
+    assert abs(float(host(loss)[0]) - float(host(loss2)[0])) <= 1e-6 * abs(float(host(loss2)[0]))
+    g2 = lp.lp_backward(g, model, Xd, full, dev_i32(es), dev_i32(ed), ds2, want_dX=True)
+    for k in range(K):
+        assert_close(host(grads.dW_self[k]), host(g2.dW_self[k]), 1e-5, "dW_self^%d after either forward pass" % (k + 1))
+        assert_close(host(grads.dW_neigh[k]), host(g2.dW_neigh[k]), 1e-5, "dW_neigh^%d after either forward pass" % (k + 1))
+        assert_close(host(grads.dbias[k]), host(g2.dbias[k]), 1e-5, "dbias^%d after either forward pass" % (k + 1))
+    assert_close(host(grads.dX), host(g2.dX), 1e-5, "dX after either forward pass")
+    if bad_ids:
+        assert not valid.all()
+    else:
+        s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+        assert_close(host(s), s_ref, TOL_ACT, "scores")
+        assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
+        # a batch this small hangs every gradient on a few thousand hidden units, so a single unit whose gate the two
+        # sides decide differently (|z| below 1e-6) moves a weight gradient by more than the bar: the oracle's backward
+        # pass takes the kernel's decision at such units
+        gated, flips = oracle_acts_with_the_kernel_gates(a_ref, hidden_of(acts, K), K)
+        say("  %d hidden unit(s) take the kernel's gate decision in the oracle's backward pass" % flips)
+        g_ref = O.backward(ref, Ws, Wn, gated, es, ed, ds_ref)
+        check_grads(grads, g_ref, K)
+
+
+def test_training_forward_with_an_empty_batch_and_around_the_largest_listed_batch():
+    say("training forward B=0 / B around n/4")
+    rng = np.random.default_rng(4242)
+    n, dims = 900, [16, 32, 8]
+    r, c = random_pairs(rng, n, 3000)
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    model, Xd = make_model(Ws, Wn, b), dev_f32(X)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X)
+    from gpu_util import nan_filled_acts
+    z = dev_i32(np.zeros(0, np.int32))
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, z, z, acts)
+    check_last_layer_listed(acts, a_ref, np.zeros(0, np.int32), np.zeros(0, np.int32), 2)
+    every = np.arange(n, dtype=np.int32)
+    Bmax = (n - 1) // 4                                  # the longest list: 2 Bmax distinct end points
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(every[:Bmax]), dev_i32(every[n - Bmax:]), acts)
+    assert check_last_layer_listed(acts, a_ref, every[:Bmax], every[n - Bmax:], 2).size == 2 * Bmax
+    acts = nan_filled_acts(n, model, Xd)                 # one edge more: every node is evaluated
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(every[:Bmax + 1]), dev_i32(every[n - Bmax - 1:]), acts)
+    check_last_layer_listed(acts, a_ref, every[:Bmax + 1], every[n - Bmax - 1:], 2)
+    assert not np.isnan(host(acts.H[-1])).any()
+    # a GCN model takes the same path (no self term to gather)
+    gl = O.build_csr(n, np.concatenate([r, every]), np.concatenate([c, every]), True)
+    gg = lp.lp_build_csr(n, dev_i32(np.concatenate([r, every])), dev_i32(np.concatenate([c, every])), True)
+    gm = lp.Model(None, [dev_f32(w) for w in Wn], [dev_f32(x) for x in b], layer_type=lp.LP_LAYER_GCN)
+    es, ed = rng.integers(0, n, 200).astype(np.int32), rng.integers(0, n, 200).astype(np.int32)
+    acts = nan_filled_acts(n, gm, Xd)
+    lp.lp_sage_forward_edges(gg, gm, Xd, dev_i32(es), dev_i32(ed), acts)
+    full = lp.lp_sage_forward(gg, gm, Xd)
+    ends = torch.from_numpy(np.unique(np.concatenate([es, ed])).astype(np.int64)).to(DEV)
+    assert_close(host(acts.H[-1][ends]), host(full.H[-1][ends]), 1e-6, "GCN H^K at the end points")
+    assert int(torch.isnan(acts.H[-1]).any(dim=1).sum()) == n - ends.numel()
+
+
 # ------------------------------------------------------------------------------------------------ whole step
 def whole_step(name):
     run_whole_step(make_workload(name))
@@ -552,18 +693,23 @@ def run_whole_step(wl, modes=(lp.LP_FP32_PRODUCTS_BF16X6,)):
     errs = {}
     for mode in modes:
         say("  fp32 products mode %d" % mode)
-        got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias, mode), dev_f32(wl.X), dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
-                      wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step)
+        model, Xd = make_model(wl.W_self, wl.W_neigh, wl.bias, mode), dev_f32(wl.X)
+        # the step as the benchmark runs it: the training forward (last layer at the end points of the batch only)
+        got = HipStep(g, model, Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst), wl.k_neg, wl.n_space, wl.sampler_seed,
+                      wl.sampler_step, forward="edges")
         assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
-        for k in range(1, K + 1):
-            assert_close(host(got.acts.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
-            assert_close(host(got.acts.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+        check_last_layer_listed(got.acts, exp.acts, exp.e_src, exp.e_dst, K)
         assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
         assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
         assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
         check_grads(got.grads, exp.grads, K, dx_band(ref, wl.W_self, wl.W_neigh, exp.acts, exp.e_src, exp.e_dst, exp.dscore,
                                                      hidden_of(got.acts, K)))
-        errs[mode] = (rel_err(host(got.acts.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
+        # the embeddings of every node (evaluation, inference): the full forward pass
+        full = lp.lp_sage_forward(g, model, Xd)
+        for k in range(1, K + 1):
+            assert_close(host(full.A[k - 1]), exp.acts.A[k], TOL_ACT, "A^%d" % k)
+            assert_close(host(full.H[k - 1]), exp.acts.H[k], TOL_ACT, "H^%d" % k)
+        errs[mode] = (rel_err(host(full.H[-1]), exp.acts.H[K])[1], rel_err(host(got.grads.dW_neigh[0]), exp.grads.dW_neigh[0])[1])
     return errs
 
 

@@ -64,6 +64,36 @@ def oracle_step_in_stages(ref, Ws, Wn, bias, X, wl, storage="f32"):
     return O.StepResult(neg, es, ed, acts, s, loss, ds, grads)
 
 
+def check_sampled_rows_of_a_training_step(got, exp, ref, rows, K, tol, to_host):
+    """A step whose forward pass was lp_sage_forward_edges into NaN-filled matrices: layers below K on the sampled
+    rows; layer K on a sample of the end points of the batch (hubs among them).  With 4 B < n every row of a node that
+    is no end point is still NaN; a larger batch has every row evaluated (checked on the sampled rows)."""
+    ridx = torch.from_numpy(rows).to(DEV)
+    for k in range(1, K):
+        assert_close(to_host(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], tol, "A^%d rows" % k)
+        assert_close(to_host(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], tol, "H^%d rows" % k)
+    ends = np.unique(np.concatenate([exp.e_src, exp.e_dst])).astype(np.int64)
+    deg = np.diff(ref.rowptr)
+    pick = np.unique(np.concatenate([np.random.default_rng(7).choice(ends, min(3000, ends.size), replace=False),
+                                     ends[np.argsort(deg[ends])[-40:]]]))
+    pidx = torch.from_numpy(pick).to(DEV)
+    assert_close(to_host(got.acts.A[K - 1][pidx]), exp.acts.A[K][pick], tol, "A^K at end points")
+    assert_close(to_host(got.acts.H[K - 1][pidx]), exp.acts.H[K][pick], tol, "H^K at end points")
+    listed = 4 * exp.e_src.size < ref.n_nodes
+    say("  last layer of the training forward: %s, %d end points of %d nodes" % ("listed rows" if listed else "every row", ends.size, ref.n_nodes))
+    is_end = torch.zeros(ref.n_nodes, dtype=torch.bool, device=DEV)
+    is_end[torch.from_numpy(ends).to(DEV)] = True
+    for t in (got.acts.A[K - 1], got.acts.H[K - 1]):
+        nan_rows = torch.isnan(t).any(dim=1)
+        if listed:
+            assert bool((nan_rows == ~is_end).all()), "rows written by the training forward are not exactly the end points"
+        else:
+            assert not bool(nan_rows.any())
+    if not listed:
+        assert_close(to_host(got.acts.A[K - 1][ridx]), exp.acts.A[K][rows], tol, "A^K rows")
+        assert_close(to_host(got.acts.H[K - 1][ridx]), exp.acts.H[K][rows], tol, "H^K rows")
+
+
 @pytest.mark.timeout(900)
 def test_whole_step_C4_full_size(c4):
     """The configuration the benchmark times, all three layers, at full size and in the launch configuration of the
@@ -81,17 +111,20 @@ def test_whole_step_C4_full_size(c4):
     Xd = dev_f32(X)
     for mode in (lp.LP_FP32_PRODUCTS_BF16X6, lp.LP_FP32_PRODUCTS_NATIVE):
         say("  fp32 products mode %d" % mode)
-        got = HipStep(g, make_model(wl.W_self, wl.W_neigh, wl.bias, mode), Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst),
-                      wl.k_neg, wl.n_space, wl.sampler_seed, wl.sampler_step, want_dX=False)
+        model = make_model(wl.W_self, wl.W_neigh, wl.bias, mode)
+        got = HipStep(g, model, Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst), wl.k_neg, wl.n_space, wl.sampler_seed,
+                      wl.sampler_step, want_dX=False, forward="edges")
         assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
-        for k in range(1, K + 1):
-            assert_close(host(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], TOL_ACT, "A^%d rows" % k)
-            assert_close(host(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], TOL_ACT, "H^%d rows" % k)
-        assert bool(torch.isfinite(got.acts.H[-1]).all())
+        check_sampled_rows_of_a_training_step(got, exp, ref, rows, K, TOL_ACT, host)
         assert_close(host(got.scores), exp.scores, TOL_ACT, "scores")
         assert abs(float(host(got.loss)[0]) - exp.loss) <= TOL_ACT * abs(exp.loss)
         assert_close(host(got.dscore), exp.dscore, TOL_ACT, "dscore")
         check_grads(got.grads, exp.grads, K)
+        say("  the full forward pass, last layer on the sampled rows")
+        lp.lp_sage_forward(g, model, Xd, got.acts)
+        assert_close(host(got.acts.A[K - 1][ridx]), exp.acts.A[K][rows], TOL_ACT, "A^K rows (full pass)")
+        assert_close(host(got.acts.H[K - 1][ridx]), exp.acts.H[K][rows], TOL_ACT, "H^K rows (full pass)")
+        assert bool(torch.isfinite(got.acts.H[-1]).all())
         del got
 
 
@@ -178,17 +211,19 @@ def whole_step_bf16_sampled_rows(wl, ref, g):
     K = len(wl.dims) - 1
     model, Xd = bf16_model(Ws, Wn, wl.bias), dev_bf16(X)
     got = HipStep(g, model, Xd, dev_i32(wl.pos_src), dev_i32(wl.pos_dst), wl.k_neg, wl.n_space, wl.sampler_seed,
-                  wl.sampler_step, want_dX=False)
+                  wl.sampler_step, want_dX=False, forward="edges")
     assert np.array_equal(host(got.e_src), exp.e_src) and np.array_equal(host(got.e_dst), exp.e_dst)
     rows = sample_rows(ref, np.random.default_rng(505), n_random=3000, n_hubs=40)
     ridx = torch.from_numpy(rows).to(DEV)
-    for k in range(1, K + 1):
-        assert_close(hostf(got.acts.A[k - 1][ridx]), exp.acts.A[k][rows], BF_ACT, "A^%d rows" % k)
-        assert_close(hostf(got.acts.H[k - 1][ridx]), exp.acts.H[k][rows], BF_ACT, "H^%d rows" % k)
-    assert bool(torch.isfinite(got.acts.H[-1].float()).all())
+    check_sampled_rows_of_a_training_step(got, exp, ref, rows, K, BF_ACT, hostf)
     assert_close(host(got.scores), exp.scores, BF_ACT, "scores")
     assert abs(float(host(got.loss)[0]) - exp.loss) <= BF_ACT * abs(exp.loss)
     bf_check_grads(got.grads, exp.grads, K)
+    say("  the full forward pass, last layer on the sampled rows")
+    lp.lp_sage_forward(g, model, Xd, got.acts)
+    assert_close(hostf(got.acts.A[K - 1][ridx]), exp.acts.A[K][rows], BF_ACT, "A^K rows (full pass)")
+    assert_close(hostf(got.acts.H[K - 1][ridx]), exp.acts.H[K][rows], BF_ACT, "H^K rows (full pass)")
+    assert bool(torch.isfinite(got.acts.H[-1].float()).all())
     if ref.n_nodes < 600000:    # (one more fp64 backward pass: left out at full size)
         from test_gpu_parity_bf16 import check_grads_against_unrounded_backward
         check_grads_against_unrounded_backward(got.grads, O.backward(ref, Ws, Wn, exp.acts, exp.e_src, exp.e_dst, exp.dscore, storage="f32"), K)
