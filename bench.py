@@ -380,10 +380,13 @@ def run_train_step(args, workload, full=True):
     dscore = torch.empty(Bn, dtype=torch.float32, device=dev)
     loss = torch.zeros(1, dtype=torch.float32, device=dev)
 
-    def step(i, which="timed"):
+    def step(i, which="timed", every_row=False):
         model = models[which]
         lp.lp_sample_neg(g, pos_src, k_neg, wl.n_space, wl.sampler_seed, i, neg_dst=neg_dst, neg_src=neg_src)
-        lp.lp_sage_forward_edges(g, model, X, e_src, e_dst, acts, ws_f)   # the last layer where the loss reads it
+        if every_row:   # for reference only: the last layer for every visible node
+            lp.lp_sage_forward(g, model, X, acts, ws_f)
+        else:           # the training forward: the last layer where the loss reads it
+            lp.lp_sage_forward_edges(g, model, X, e_src, e_dst, acts, ws_f)
         if mlp is None:
             lp.lp_score_loss(acts.H[-1], e_src, e_dst, n_pos, scores, loss, dscore, ws_l)
             lp.lp_backward(g, model, X, acts, e_src, e_dst, dscore, grads, ws_b)
@@ -467,6 +470,20 @@ def run_train_step(args, workload, full=True):
         oms = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
         other_products = {"fp32_products": fp32_products_name(False, not split), "ms_per_step_without_events": round(oms, 4),
                           "value": round(Bn / (oms * 1e-3), 1), "loss": round(float(loss.item()), 6)}
+
+    # for reference, the same steps with the embeddings of EVERY node computed by the last layer (lp_sage_forward), as
+    # an evaluation pass needs them; the training step reads only those of the batch's end points
+    every_row = None
+    if full:
+        for i in range(2):
+            step(3000 + i, every_row=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(2000 + i, every_row=True)
+        torch.cuda.synchronize()
+        ems = (time.perf_counter() - t0) * 1e3 / max(args.steps, 1)
+        every_row = {"ms_per_step_without_events": round(ems, 4), "value": round(Bn / (ems * 1e-3), 1), "loss": round(float(loss.item()), 6)}
 
     # accounting only (outside the timed region): how many nodes are an endpoint of a scored edge in the timed steps,
     # and how many CSR entries point at one of them
@@ -577,7 +594,9 @@ def run_train_step(args, workload, full=True):
                                   "->".join(map(str, wl.dims)), "3-layer MLP edge predictor" if use_mlp else "dot-product scorer",
                                   n_pos, n_pos * k_neg),
                    "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg,
-                   "batch_endpoint_nodes": round(n_t, 1)},
+                   "batch_endpoint_nodes": round(n_t, 1),
+                   "last_layer_rows": ("the end points of the batch (lp_sage_forward_edges lists them: 4 B < N)" if 4 * Bn < n
+                                       else "every node (4 B >= N: lp_sage_forward_edges does not list)")},
         "loss": round(loss_val, 6),
         "csr_build": {"seconds": round(build_s, 5), "input_edges_per_s": round(wl.src.size / build_s, 1)},
         "roofline": lines[dominant],
@@ -588,6 +607,7 @@ def run_train_step(args, workload, full=True):
         "sampler": sample_line,
         "kernel_ms_per_step": {k: round(v[0], 4) for k, v in per_step.items() if k != "other" or args.timing_level > 1},
         "with_other_fp32_products": other_products,
+        "with_last_layer_for_every_node": every_row,
     }
     if args.timing_level <= 1:   # the small launches (fills, transposes, column sums) are not bracketed: by difference
         out["kernel_ms_per_step"]["other_and_gaps"] = round(ms_per_step - sum(v[0] for k, v in per_step.items() if k != "other"), 4)
