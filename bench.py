@@ -62,18 +62,26 @@ def spmm_bytes_rows(n_t, nnz_t, F, eb=4):
     return n_t * 4 + 2 * n_t * 4 + n_t * 4 + nnz_t * (eb * F + 4) + n_t * eb * F
 
 
-def step_counts(n, nnz, dims, n_t, nnz_t, eb=4, paths=2):
-    """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer runs over the n_t end points of the
-    scored edges only, forward (no other row of h^(K) is read by the loss) and backward (every other row of dL/dH^K is
-    exactly zero).  paths: weight matrices per layer (2 for GraphSAGE's self and neighbour paths, 1 for GCN)."""
+def lists_last_layer(n, B):
+    """lp_sage_forward_edges evaluates its last layer only for the end points of the batch when 8 B < 3 N."""
+    return 8 * B < 3 * n
+
+
+def step_counts(n, nnz, dims, n_t, nnz_t, B, eb=4, paths=2):
+    """(spmm algorithmic bytes, NT flops, TN flops) of one step.  The last layer's backward pass runs over the n_t end
+    points of the scored edges only (every other row of dL/dH^K is exactly zero); so does its forward pass when the
+    library lists them (no other row of h^(K) is read by the loss).  paths: weight matrices per layer (2 for
+    GraphSAGE's self and neighbour paths, 1 for GCN)."""
     K = len(dims) - 1
+    listed = lists_last_layer(n, B)
     sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K))
-    sp += spmm_bytes_rows(n_t, nnz_t, dims[K - 1], eb)
+    sp += spmm_bytes_rows(n_t, nnz_t, dims[K - 1], eb) if listed else spmm_bytes(n, nnz, dims[K - 1], False, eb)
     sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K))
     if K >= 2:
         sp += spmm_bytes_listed(n, nnz, dims[K - 1], n_t, nnz_t, eb)
     rows = lambda k: n_t if k == K else n
-    nt = sum(2.0 * rows(k) * dims[k] * paths * dims[k - 1] for k in range(1, K + 1))      # forward
+    frows = lambda k: n_t if (k == K and listed) else n
+    nt = sum(2.0 * frows(k) * dims[k] * paths * dims[k - 1] for k in range(1, K + 1))     # forward
     nt += sum(2.0 * rows(k) * paths * dims[k - 1] * dims[k] for k in range(2, K + 1))     # input gradients
     tn = sum(2.0 * paths * rows(k) * dims[k - 1] * dims[k] for k in range(1, K + 1))      # dW_self, dW_neigh
     return sp, nt, tn
@@ -497,7 +505,7 @@ def run_train_step(args, workload, full=True):
     n_t, nnz_t = n_t_sum / max(args.steps, 1), nnz_t_sum / max(args.steps, 1)
 
     n, nnz = wl.n_nodes, g.nnz
-    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, n_t, nnz_t, 2 if bf16 else 4, 1 if gcn else 2)
+    sp_bytes, nt_flops, tn_flops = step_counts(n, nnz, wl.dims, n_t, nnz_t, Bn, 2 if bf16 else 4, 1 if gcn else 2)
     if use_mlp:   # hidden layers of the predictor on Bn edge rows: forward, input gradients and weight gradients
         F = wl.dims[-1]
         nt_flops += 2 * 2.0 * Bn * F * F + 2 * 2.0 * Bn * F * F
@@ -595,8 +603,8 @@ def run_train_step(args, workload, full=True):
                                   n_pos, n_pos * k_neg),
                    "n_nodes": n, "nnz": nnz, "dims": wl.dims, "n_pos": n_pos, "k_neg": k_neg,
                    "batch_endpoint_nodes": round(n_t, 1),
-                   "last_layer_rows": ("the end points of the batch (lp_sage_forward_edges lists them: 4 B < N)" if 4 * Bn < n
-                                       else "every node (4 B >= N: lp_sage_forward_edges does not list)")},
+                   "last_layer_rows": ("the end points of the batch (lp_sage_forward_edges lists them: 8 B < 3 N)" if lists_last_layer(n, Bn)
+                                       else "every node (8 B >= 3 N: lp_sage_forward_edges does not list)")},
         "loss": round(loss_val, 6),
         "csr_build": {"seconds": round(build_s, 5), "input_edges_per_s": round(wl.src.size / build_s, 1)},
         "roofline": lines[dominant],

@@ -252,7 +252,7 @@ int lp_sage_forward(const lp_csr *g, const lp_model *m, const void *X, lp_acts *
  * nodes that are e_src[i] or e_dst[i] of one of the B scored edges (device
  * [B] each; an edge with an id outside [0, n_nodes) lists nothing).  Rows of
  * saved->A[K-1] and saved->H[K-1] that belong to other nodes are unspecified
- * afterwards: when 4*B < n_nodes they are neither read nor written and keep
+ * afterwards: when 8*B < 3*n_nodes they are neither read nor written and keep
  * whatever they held; a larger batch can touch so much of the graph that
  * listing does not pay, and every row is evaluated.  lp_score_loss / lp_mlp_score_loss
  * and lp_backward / lp_backward_edge_grads on the SAME edges read only rows

@@ -175,11 +175,11 @@ BackwardWs carve_backward(void *ws, const lp_model *m, int32_t n_nodes, int64_t 
 }
 
 
-// Whether the training forward lists the rows of its last layer.  Listing pays when the batch can touch only a small
-// part of the graph: with 2B end points among fewer than 4B nodes the list building and the row copies cost as much
-// as the rows left out save (measured: -10 % of the step at 2B = 0.18 N, -4 % at 0.36 N, +2 % at 0.59 N and 1.1 N),
-// and every node is evaluated.  B < 0: the plain forward pass.
-bool lists_rows(int32_t n_nodes, int64_t B) { return B >= 0 && 4 * B < (int64_t)n_nodes; }
+// Whether the training forward lists the rows of its last layer.  Listing pays when the batch touches a small part of
+// the graph; near 2B = N the list building and the row copies cost what the rows left out save (measured change of the
+// step: -10 % at 2B = 0.18 N, -4 % at 0.73 N, 0 at 0.98 N, +2 % at 1.1 N and 1.2 N), so from 2B = 0.75 N on every
+// node is evaluated.  B < 0: the plain forward pass.
+bool lists_rows(int32_t n_nodes, int64_t B) { return B >= 0 && 8 * B < 3 * (int64_t)n_nodes; }
 
 ForwardWs carve_forward(void *ws, const lp_model *m, int32_t n_nodes, int64_t B) {
     char *p = static_cast<char *>(ws);

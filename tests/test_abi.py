@@ -128,7 +128,7 @@ def test_forward_backward_reject_bad_arguments_on_the_host():
     assert fwe(ws=None) == -3 and fwe(wsb=8) == -3
     assert fwe(m=_model([128, 256], products=2)) == -1
     n_graph = g.n_nodes
-    few, many = n_graph // 4 - 1, n_graph // 4 + 1
+    few, many = n_graph // 4 - 1, n_graph
     w0 = lib.lp_sage_forward_workspace_bytes(C.byref(good), n_graph)
     w_few = lib.lp_sage_forward_edges_workspace_bytes(C.byref(good), n_graph, few)
     assert w_few > w0 > 0                                   # the list, its flags and three matrices of listed rows

@@ -553,7 +553,7 @@ def oracle_acts_with_the_kernel_gates(acts_ref, hidden_gpu, K, max_abs_z=1e-5, m
 
 def check_last_layer_listed(acts, a_ref, es, ed, K, tol=TOL_ACT, to_host=host, what=""):
     """After lp_sage_forward_edges into NaN-filled matrices: the lower layers complete; rows of A^K and H^K of the end
-    points of the scored edges against the oracle; with 4 B < n every other row still NaN (never written), else every
+    points of the scored edges against the oracle; with 8 B < 3 n every other row still NaN (never written), else every
     row evaluated.  Returns the end points."""
     n = a_ref.H[K].shape[0]
     ok = (es >= 0) & (es < n) & (ed >= 0) & (ed < n)
@@ -564,7 +564,7 @@ def check_last_layer_listed(acts, a_ref, es, ed, K, tol=TOL_ACT, to_host=host, w
         assert_close(to_host(acts.A[k - 1]), a_ref.A[k], tol, what + "A^%d" % k)
         assert_close(to_host(acts.H[k - 1]), a_ref.H[k], tol, what + "H^%d" % k)
     A, H = to_host(acts.A[K - 1]), to_host(acts.H[K - 1])
-    if 4 * es.size < n:
+    if 8 * es.size < 3 * n:
         if ends.size:
             assert_close(A[ends], a_ref.A[K][ends], tol, what + "A^K at the end points")
             assert_close(H[ends], a_ref.H[K][ends], tol, what + "H^K at the end points")
@@ -580,7 +580,7 @@ def check_last_layer_listed(acts, a_ref, es, ed, K, tol=TOL_ACT, to_host=host, w
 def test_training_forward_evaluates_the_last_layer_at_the_end_points_only(dims, B, bad_ids):
     """lp_sage_forward_edges, then the loss and the backward pass on the same edges: everything against the oracle's
     full pass.  B = 345 lists about 600 nodes (more than the rows of one tile of the dense product, the hub row 3 among
-    them); B = 6000 is beyond n / 4, where every node is evaluated.  With bad_ids two edges carry an id outside the graph: they list nothing, and the loss and the
+    them); B = 6000 is beyond 3 n / 8, where every node is evaluated.  With bad_ids two edges carry an id outside the graph: they list nothing, and the loss and the
     gradients are those the library gives after the full forward pass."""
     rng = np.random.default_rng(4100 + sum(dims) + B + bad_ids)
     n = 1400 + dims[0]
@@ -635,7 +635,7 @@ def test_training_forward_evaluates_the_last_layer_at_the_end_points_only(dims, 
 
 
 def test_training_forward_with_an_empty_batch_and_around_the_largest_listed_batch():
-    say("training forward B=0 / B around n/4")
+    say("training forward B=0 / B around 3n/8")
     rng = np.random.default_rng(4242)
     n, dims = 900, [16, 32, 8]
     r, c = random_pairs(rng, n, 3000)
@@ -651,7 +651,7 @@ def test_training_forward_with_an_empty_batch_and_around_the_largest_listed_batc
     lp.lp_sage_forward_edges(g, model, Xd, z, z, acts)
     check_last_layer_listed(acts, a_ref, np.zeros(0, np.int32), np.zeros(0, np.int32), 2)
     every = np.arange(n, dtype=np.int32)
-    Bmax = (n - 1) // 4                                  # the longest list: 2 Bmax distinct end points
+    Bmax = (3 * n - 1) // 8                              # the longest list: 2 Bmax distinct end points
     acts = nan_filled_acts(n, model, Xd)
     lp.lp_sage_forward_edges(g, model, Xd, dev_i32(every[:Bmax]), dev_i32(every[n - Bmax:]), acts)
     assert check_last_layer_listed(acts, a_ref, every[:Bmax], every[n - Bmax:], 2).size == 2 * Bmax

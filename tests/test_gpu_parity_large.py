@@ -66,7 +66,7 @@ def oracle_step_in_stages(ref, Ws, Wn, bias, X, wl, storage="f32"):
 
 def check_sampled_rows_of_a_training_step(got, exp, ref, rows, K, tol, to_host):
     """A step whose forward pass was lp_sage_forward_edges into NaN-filled matrices: layers below K on the sampled
-    rows; layer K on a sample of the end points of the batch (hubs among them).  With 4 B < n every row of a node that
+    rows; layer K on a sample of the end points of the batch (hubs among them).  With 8 B < 3 n every row of a node that
     is no end point is still NaN; a larger batch has every row evaluated (checked on the sampled rows)."""
     ridx = torch.from_numpy(rows).to(DEV)
     for k in range(1, K):
@@ -79,7 +79,7 @@ def check_sampled_rows_of_a_training_step(got, exp, ref, rows, K, tol, to_host):
     pidx = torch.from_numpy(pick).to(DEV)
     assert_close(to_host(got.acts.A[K - 1][pidx]), exp.acts.A[K][pick], tol, "A^K at end points")
     assert_close(to_host(got.acts.H[K - 1][pidx]), exp.acts.H[K][pick], tol, "H^K at end points")
-    listed = 4 * exp.e_src.size < ref.n_nodes
+    listed = 8 * exp.e_src.size < 3 * ref.n_nodes
     say("  last layer of the training forward: %s, %d end points of %d nodes" % ("listed rows" if listed else "every row", ends.size, ref.n_nodes))
     is_end = torch.zeros(ref.n_nodes, dtype=torch.bool, device=DEV)
     is_end[torch.from_numpy(ends).to(DEV)] = True
