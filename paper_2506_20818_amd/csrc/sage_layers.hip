@@ -1,7 +1,9 @@
-// lp_sage_forward and lp_backward: the K GraphSAGE-mean layers (Eq. 1 of the paper with the mean aggregator and
-// two linear maps per layer) over every visible node, and the reverse walk through them (Algorithm 1, "Compute
-// the gradient").  Host-side orchestration only; the work is done by the kernels in spmm_mean.hip and
-// gemm_mfma.hip plus the edge-gradient scatter below.
+// lp_sage_forward, lp_sage_forward_edges and lp_backward: the K GraphSAGE-mean layers (Eq. 1 of the paper with the mean
+// aggregator and two linear maps per layer) over every visible node, the same pass with the last layer evaluated only
+// where the loss of a training step reads it (the end points of the scored edges), and the reverse walk through the
+// layers (Algorithm 1, "Compute the gradient").  Host-side orchestration only; the work is done by the kernels in
+// spmm_mean.hip and gemm_mfma.hip plus the small batch kernels below (end-point flags and list, row copies, the
+// edge-gradient grouping).
 #include "lp_internal.h"
 #include "lp_scan.h"
 
