@@ -74,6 +74,53 @@ def test_gcn_step_small_graphs(dims, sym):
     assert np.all(np.sign(step[np.abs(gr) > 1e-6]) == -np.sign(gr[np.abs(gr) > 1e-6]))
 
 
+@pytest.mark.parametrize("dims", [[12, 20, 4], [128, 256, 256, 256]])
+def test_gcn_step_with_the_training_forward(dims):
+    """GCN layers through lp_sage_forward_edges on a batch small enough to be listed (no self term to gather): the
+    last layer is written exactly at the end points and equals the oracle there, and the step's loss and gradients
+    equal those after the full forward pass (whose parity with the oracle the tests above establish) up to the
+    order of sums over hub rows."""
+    from gpu_util import nan_filled_acts
+    rng = np.random.default_rng(260 + sum(dims))
+    n = 1300 + dims[-1]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
+    rl, cl = G.add_self_pairs(n, r, c)
+    say("gcn training forward dims=%s n=%d" % (dims, n))
+    ref = O.build_csr(n, rl, cl, True)
+    g = lp.lp_build_csr(n, dev_i32(rl), dev_i32(cl), True)
+    W, b = toy_weights(rng, dims)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    B, n_pos = 400, 150
+    assert 8 * B < 3 * n
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    es[0] = 3
+    K = len(W)
+    model, Xd = gcn_model(W, b), dev_f32(X)
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(es), dev_i32(ed), acts)
+    a_ref = G.gcn_forward(ref, W, b, X)
+    ends = np.unique(np.concatenate([es, ed])).astype(np.int64)
+    rest = np.ones(n, bool)
+    rest[ends] = False
+    for k in range(1, K):
+        assert_close(host(acts.H[k - 1]), a_ref.H[k], TOL_ACT, "H^%d" % k)
+    HK, AK = host(acts.H[K - 1]), host(acts.A[K - 1])
+    assert_close(HK[ends], a_ref.H[K][ends], TOL_ACT, "H^K at the end points")
+    assert_close(AK[ends], a_ref.A[K][ends], TOL_ACT, "A^K at the end points")
+    assert np.isnan(HK[rest]).all() and np.isnan(AK[rest]).all()
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    full = lp.lp_sage_forward(g, model, Xd)
+    s2, loss2, ds2 = lp.lp_score_loss(full.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    g2 = lp.lp_backward(g, model, Xd, full, dev_i32(es), dev_i32(ed), ds2, want_dX=True)
+    assert_close(host(s), host(s2), 1e-6, "scores after either forward pass")
+    for k in range(K):
+        assert_close(host(grads.dW_neigh[k]), host(g2.dW_neigh[k]), 1e-5, "dW^%d after either forward pass" % (k + 1))
+        assert_close(host(grads.dbias[k]), host(g2.dbias[k]), 1e-5, "dbias^%d after either forward pass" % (k + 1))
+    assert_close(host(grads.dX), host(g2.dX), 1e-5, "dX after either forward pass")
+
+
 def test_gcn_step_collab_scale():
     wl = make_workload("C2")
     rl, cl = G.add_self_pairs(wl.n_nodes, wl.src, wl.dst)

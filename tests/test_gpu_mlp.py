@@ -86,6 +86,25 @@ def test_whole_step_with_mlp_predictor(dims):
     s, loss, ds, macts = lp.lp_mlp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos, p)
     mgrads, eg = lp.lp_mlp_backward(p, macts, ds)
     grads = lp.lp_backward_edge_grads(g, model, Xd, acts, dev_i32(es), dev_i32(ed), eg, want_dX=True)
+    # the same step on the first 400 edges after the training forward (a batch small enough for its last layer to be
+    # listed) and after the full forward pass: the predictor and the edge-gradient backward read only listed rows
+    from gpu_util import nan_filled_acts
+    e4, d4 = dev_i32(es[:400]), dev_i32(ed[:400])
+    listed = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, e4, d4, listed)
+    assert int(torch.isnan(listed.H[-1]).any(dim=1).sum()) == n - np.unique(np.concatenate([es[:400], ed[:400]])).size
+    results = []
+    for a in (listed, acts):
+        s4, loss4, ds4, m4 = lp.lp_mlp_score_loss(a.H[-1], e4, d4, 150, p)
+        mg4, eg4 = lp.lp_mlp_backward(p, m4, ds4)
+        results.append((s4, mg4, lp.lp_backward_edge_grads(g, model, Xd, a, e4, d4, eg4, want_dX=True)))
+    (sa, ma, ga), (sb, mb, gb) = results
+    assert_close(host(sa), host(sb), 1e-6, "MLP scores after either forward pass")
+    for k in range(len(dims) - 1):
+        assert_close(host(ga.dW_self[k]), host(gb.dW_self[k]), 1e-5, "dW_self^%d after either forward pass" % (k + 1))
+        assert_close(host(ga.dW_neigh[k]), host(gb.dW_neigh[k]), 1e-5, "dW_neigh^%d after either forward pass" % (k + 1))
+    for j in range(len(W)):
+        assert_close(host(ma.dW[j]), host(mb.dW[j]), 1e-5, "predictor dW^%d after either forward pass" % (j + 1))
     a_ref = O.sage_forward(ref, Ws, Wn, b, X)
     s_ref, ma_ref = M.mlp_scores(a_ref.H[-1], es, ed, W, cc)
     loss_ref, ds_ref = M.bce_mean(s_ref, n_pos)

@@ -128,6 +128,43 @@ def test_backward_parity_bf16(dims, sym):
     check_grads_against_unrounded_backward(grads, O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="f32"), K)
 
 
+@pytest.mark.parametrize("dims", [[24, 40, 8], [128, 512, 512, 512], [72, 136, 24]])
+def test_training_forward_bf16_lists_the_end_points(dims):
+    """lp_sage_forward_edges with bf16 storage on a batch small enough to be listed: rows of the last layer written
+    exactly at the end points (everything else still NaN), equal to the oracle there; loss and gradients of the step
+    against the oracle's full step."""
+    from gpu_util import nan_filled_acts
+    from test_gpu_parity import check_last_layer_listed
+    rng = np.random.default_rng(2600 + sum(dims))
+    n = 1300 + dims[-1]
+    r, c = graph_with_hub_and_empty_rows(rng, n, 3500, 600)
+    say("bf16 training forward dims=%s n=%d" % (dims, n))
+    ref = O.build_csr(n, r, c, True)
+    g = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), True)
+    Ws, Wn, b = toy_model(rng, dims, scale=0.25)
+    Ws, Wn = grid(Ws), grid(Wn)
+    X = to_bf16_grid(rng.standard_normal((n, dims[0])).astype(np.float32))
+    B, n_pos = 400, 150
+    assert 8 * B < 3 * n
+    es = rng.integers(0, n, B).astype(np.int32)
+    ed = rng.integers(0, n, B).astype(np.int32)
+    es[0] = 3                                            # the 600-entry row
+    model, Xd = bf16_model(Ws, Wn, b), dev_bf16(X)
+    K = len(dims) - 1
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(es), dev_i32(ed), acts)
+    a_ref = O.sage_forward(ref, Ws, Wn, b, X, storage="bf16")
+    ends = check_last_layer_listed(acts, a_ref, es, ed, K, tol=TOL_ACT, to_host=hostf)
+    assert 256 < ends.size <= 2 * B                      # more rows than one tile of the dense product
+    s, loss, ds = lp.lp_score_loss(acts.H[-1], dev_i32(es), dev_i32(ed), n_pos)
+    grads = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    s_ref, loss_ref, ds_ref = O.score_loss(a_ref.H[-1], es, ed, n_pos)
+    g_ref = O.backward(ref, Ws, Wn, a_ref, es, ed, ds_ref, storage="bf16")
+    assert_close(host(s), s_ref, TOL_ACT, "scores")
+    assert abs(float(host(loss)[0]) - loss_ref) <= TOL_ACT * abs(loss_ref)
+    check_grads(grads, g_ref, K, dx_band(ref, Ws, Wn, a_ref, es, ed, ds_ref, hidden_of(acts, K, hostf), storage="bf16"))
+
+
 def whole_step_bf16(name, scale=1.0):
     wl = make_workload(name, scale=scale)
     say("bf16 whole step %s scale=%g N=%d nnz~%d B=%d dims=%s" % (name, scale, wl.n_nodes, 2 * wl.src.size, wl.batch_edges, wl.dims))
