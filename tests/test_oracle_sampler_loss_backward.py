@@ -275,6 +275,38 @@ def test_zero_weight_closed_form_and_untouched_far_node():
     assert np.all(gr.dX[4:] == 0) and np.any(gr.dX[3] != 0)
 
 
+def test_the_step_reads_the_last_layer_only_at_the_end_points_of_the_batch():
+    """Eq. (2) takes h^(K) of the two end points of each scored edge and nothing else, and dL/dh^(K) is zero at every
+    other node: replacing the rows of A^K, Z^K and H^K of all nodes that are no end point by arbitrary finite values
+    changes neither the scores, nor the loss, nor a single bit of any gradient.  (What licenses a training forward
+    pass that evaluates its last layer only at those nodes.)"""
+    rng = np.random.default_rng(26)
+    g, Ws, Wn, b, X, es, ed = _setup(rng, 40, [3, 5, 4, 2], 70, 7)
+    acts = O.sage_forward(g, Ws, Wn, b, X)
+    s, loss, ds = O.score_loss(acts.H[-1], es, ed, 3)
+    gr = O.backward(g, Ws, Wn, acts, es, ed, ds)
+    rest = np.ones(40, bool)
+    rest[np.concatenate([es, ed])] = False
+    assert 20 <= rest.sum() < 40
+    K = 3
+    H, A, Z = list(acts.H), list(acts.A), list(acts.Z)
+    H[K], A[K], Z[K] = H[K].copy(), A[K].copy(), Z[K].copy()
+    for M in (H[K], A[K], Z[K]):
+        M[rest] = rng.standard_normal((int(rest.sum()), M.shape[1])) * 1e6
+    other = O.Activations(H, A, Z)
+    s2, loss2, ds2 = O.score_loss(other.H[-1], es, ed, 3)
+    gr2 = O.backward(g, Ws, Wn, other, es, ed, ds2)
+    assert np.array_equal(s, s2) and loss == loss2 and np.array_equal(ds, ds2)
+    for a, c in zip(gr.dW_self + gr.dW_neigh + gr.dbias + [gr.dX], gr2.dW_self + gr2.dW_neigh + gr2.dbias + [gr2.dX]):
+        assert np.array_equal(a, c)
+    # one layer down the gradient is no longer confined to the end points (it has spread to their neighbours): the
+    # input rows of layer K-1 at the same nodes do enter its weight gradient
+    H[K - 2] = H[K - 2].copy()
+    H[K - 2][rest] += 1.0
+    gr3 = O.backward(g, Ws, Wn, O.Activations(H, A, Z), es, ed, ds2)
+    assert not np.allclose(gr3.dW_self[K - 2], gr.dW_self[K - 2])
+
+
 def test_train_step_assembles_the_batch_in_the_documented_order():
     rng = np.random.default_rng(9)
     g, Ws, Wn, b, X, es, ed = _setup(rng, 30, [3, 4, 2], 40, 6)
