@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kRowThreads) void spmm_rows_kernel(SpmmArgs a) {
 }
 
 // ---- queued rows.  Layout of the queue workspace (int32 words): [0] number of queued rows, [1] seg, [2] number of
-// tasks, [3] number of scratch slots in use; then rows [cap], task_base [cap + 1], slot_base [cap], each padded to a
+// tasks, [3] number of scratch slots in use, [4] tasks handed out so far; then rows [cap], task_base [cap + 1], slot_base [cap], each padded to a
 // multiple of 64 words, cap = n_rows; then the scratch slots (kLongSlots x F floats).
 
 struct LongQueue {
@@ -262,10 +262,11 @@ __global__ __launch_bounds__(1024) void plan_long_rows_kernel(const int32_t *__r
         l.head[1] = seg;
         l.head[2] = cnt[1023];
         l.head[3] = cnt[2047];
+        l.head[4] = 0;          // the task counter of spmm_long_rows_kernel
     }
 }
 
-// One workgroup of sixteen wavefronts per task; workgroup b serves tasks b, b + gridDim.x, ...
+// One workgroup of sixteen wavefronts per task.
 template <typename T, int G, int C, int W>
 __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
@@ -276,7 +277,16 @@ __global__ __launch_bounds__(kLongThreads) void spmm_long_rows_kernel(SpmmArgs a
     const int FV = a.F / VE;
     const LongQueue l = long_queue_of(a.long_queue, a.n_rows);
     const int32_t n_queued = l.head[0], seg = l.head[1], n_tasks = l.head[2];
-    for (int32_t t = blockIdx.x; t < n_tasks; t += gridDim.x) {  // uniform over the workgroup
+    // Tasks differ in length (a row of 512 entries is one task, so is a piece of seg entries), so a workgroup takes
+    // the next task from a counter when it is done with the last one.  Which workgroup serves a task changes
+    // nothing in the result: every task owns its output row or its scratch slot.
+    __shared__ int32_t next_task;
+    for (;;) {
+        if (threadIdx.x == 0) next_task = atomicAdd(&l.head[4], 1);
+        __syncthreads();
+        const int32_t t = next_task;                              // uniform over the workgroup
+        __syncthreads();
+        if (t >= n_tasks) break;
         int32_t lo_i = 0, hi_i = n_queued;                        // last queue entry i with task_base[i] <= t
         while (hi_i - lo_i > 1) {
             const int32_t mid = (lo_i + hi_i) >> 1;
