@@ -76,7 +76,13 @@ def step_counts(n, nnz, dims, n_t, nnz_t, B, eb=4, paths=2):
     listed = lists_last_layer(n, B)
     sp = sum(spmm_bytes(n, nnz, dims[k - 1], False, eb) for k in range(1, K))
     sp += spmm_bytes_rows(n_t, nnz_t, dims[K - 1], eb) if listed else spmm_bytes(n, nnz, dims[K - 1], False, eb)
-    sp += sum(spmm_bytes(n, nnz, dims[k - 1], True, eb) for k in range(2, K))
+    for k in range(2, K):   # adjoint of layer k's aggregation, every row
+        if paths == 2 and eb == 4 and dims[k] <= dims[k - 1]:
+            # fp32 GraphSAGE layers that do not widen: dZ is aggregated before the product (entries weighted by a
+            # per-node scale, 4 more bytes per entry), and the product adds the self path and applies the gate
+            sp += nnz * (eb * dims[k] + 8) + (n + 1) * 4 + n * eb * dims[k]
+        else:
+            sp += spmm_bytes(n, nnz, dims[k - 1], True, eb)
     if K >= 2:
         sp += spmm_bytes_listed(n, nnz, dims[K - 1], n_t, nnz_t, eb)
     rows = lambda k: n_t if k == K else n

@@ -175,7 +175,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 float y = acc[rb][cb][r] + bias;
                 if (g.relu) y = fmaxf(y, 0.f);
                 y *= second ? rs[rb][r] : 1.f;
-                if (n_ok && m < M_) C[m * ldc] = y;
+                if (n_ok && m < M_) {
+                    if (g.gate && !(g.gate[m * g.ldgate + n] > 0.f)) y = 0.f;
+                    C[m * ldc] = y;
+                }
             }
     }
 }
@@ -272,9 +275,12 @@ __device__ __forceinline__ void lp_split3(const v4i &v, uint2 &t0, uint2 &t1, ui
 // bfloat16 terms (an LDS row is plane 0 | plane 1 | plane 2 | 16 bytes of padding = 112 bytes = 28 banks: sixteen
 // consecutive rows start in sixteen different groups of four banks), and a K step is six bf16 MFMAs per accumulator
 // block instead of eight fp32 ones.
-template <typename T, int NB, int MW, int KSB, bool SPLIT = false>
+// GATE (fp32 only): results are zeroed where the gate matrix is not positive; a wavefront requests the gate values of a
+// store pass (one 16-byte vector per store instruction) before it lays the pass out in LDS, so they arrive meanwhile.
+template <typename T, int NB, int MW, int KSB, bool SPLIT = false, bool GATE = false>
 __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) void gemm_nt_fast_kernel(GemmNtArgs g) {
     static_assert(!SPLIT || (sizeof(T) == 4 && KSB == 64), "the split product is defined for fp32 rows, sixteen values per step");
+    static_assert(!GATE || sizeof(T) == 4, "the gated epilogue is written for fp32 storage");
     constexpr int ES = (int)sizeof(T);
     constexpr int TH = 128 * MW;
     constexpr int BMt = 64 * MW;
@@ -612,6 +618,16 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int pass = 0; pass < NB / CBP; ++pass) {
+                v4f gv[GATE ? 32 / RPI : 1];
+                if constexpr (GATE) {
+#pragma unroll
+                    for (int j = 0; j < 32 / RPI; ++j) {
+                        const int64_t m = m0 + rb * 32 + j * RPI + lane / LPR;
+                        const int n = nw0 + pass * EPC + (lane % LPR) * (16 / ES);
+                        gv[j] = v4f{1.f, 1.f, 1.f, 1.f};
+                        if (m < M_ && n < g.N) gv[j] = *reinterpret_cast<const v4f *>(g.gate + m * (int64_t)g.ldgate + n);
+                    }
+                }
 #pragma unroll
                 for (int cbl = 0; cbl < CBP; ++cbl) {
                     const int cb = pass * CBP + cbl;
@@ -636,7 +652,12 @@ __global__ __launch_bounds__(128 * MW) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
                 for (int j = 0; j < 32 / RPI; ++j) {
                     const int row = j * RPI + lane / LPR, chunk = lane % LPR;
-                    const v4i v = *reinterpret_cast<const v4i *>(reg + row * EROW + 16 * chunk);
+                    v4i v = *reinterpret_cast<const v4i *>(reg + row * EROW + 16 * chunk);
+                    if constexpr (GATE) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (!(gv[j][e] > 0.f)) v[e] = 0;
+                    }
                     const int64_t m = m0 + rb * 32 + row;
                     const int n = nw0 + pass * EPC + chunk * (16 / ES);
                     if (m < M_ && n < g.N) *reinterpret_cast<v4i *>(Cb + m * pitchC + (int64_t)(n - nshift) * ES) = v;
@@ -1738,6 +1759,10 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
     }
     if (!a.C[0] || (a.n_split < a.N && !a.C[1])) return LP_ERR_INVALID_ARG;
     if (a.dtype != LP_F32 && a.dtype != LP_BF16) return LP_ERR_UNSUPPORTED;
+    if (a.gate) {   // fp32 storage, one output, gate rows in whole 16-byte vectors
+        if (a.dtype != LP_F32 || a.n_split < a.N) return LP_ERR_UNSUPPORTED;
+        if (!lp_aligned16(a.gate) || (a.ldgate & 3) || a.ldgate < a.N) return LP_ERR_INVALID_ARG;
+    }
     LpTimedScope timed(LP_KC_GEMM_NT, st);
     const bool bf16 = a.dtype == LP_BF16;
     if (bf16 && ((a.N & 3) || (a.n_split & 3) || (a.ldc[0] & 3) || (a.n_split < a.N && (a.ldc[1] & 3)))) return LP_ERR_UNSUPPORTED;
@@ -1771,29 +1796,34 @@ int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t st) {
         const int64_t steps_per_wg = lp_ceil_div(row_tiles, (int64_t)pgrid.x) * lp_ceil_div(a.N, fast_bn) *
                                      ((int64_t)(a.K[0] + a.K[1]) * es / 64);
         if (steps_per_wg >= (int64_t)1 << 31) return LP_ERR_UNSUPPORTED;  // the kernels count K steps in 32 bits
-#define LP_NT_FAST(T)                                                                                             \
-        if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 4, 128>), pgrid, dim3(512), 0, st, a);           \
-        else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 2, 64>), pgrid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64>), pgrid, dim3(256), 0, st, a);
+#define LP_NT_FAST(T, GATED)                                                                                                  \
+        if (big) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 4, 128, false, GATED>), pgrid, dim3(512), 0, st, a);               \
+        else if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 4, 2, 64, false, GATED>), pgrid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((gemm_nt_fast_kernel<T, 2, 2, 64, false, GATED>), pgrid, dim3(256), 0, st, a);
+#define LP_NT_SPLIT(GATED)                                                                                                    \
+        if (fast_bn == 256 && lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units()) {                                         \
+            /* sixteen values of a row per K step; 256-row tiles once they fill every compute unit */                         \
+            const int64_t rt = lp_ceil_div(a.M, 256);                                                                         \
+            const dim3 sgrid((unsigned)(rt < lp_compute_units() ? rt : lp_compute_units()));                                  \
+            hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 4, 64, true, GATED>), sgrid, dim3(512), 0, st, a);              \
+        } else {                                                                                                              \
+            const int64_t rt = lp_ceil_div(a.M, 128);                                                                         \
+            const int64_t sl = (fast_bn == 256 ? 1 : 2) * (int64_t)lp_compute_units();   /* resident workgroups (LDS) */      \
+            const dim3 sgrid((unsigned)(rt < sl ? rt : sl));                                                                  \
+            if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 2, 64, true, GATED>), sgrid, dim3(256), 0, st, a); \
+            else hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 2, 2, 64, true, GATED>), sgrid, dim3(256), 0, st, a);         \
+        }
         if (bf16) {
-            LP_NT_FAST(lp_bf16_t)
+            LP_NT_FAST(lp_bf16_t, false)
         } else if (a.fp32_products == LP_FP32_PRODUCTS_BF16X6) {
-            // sixteen values of a row per K step; 256-row tiles once they fill every compute unit
-            if (fast_bn == 256 && lp_ceil_div(a.M, 256) >= (int64_t)lp_compute_units()) {
-                const int64_t rt = lp_ceil_div(a.M, 256);
-                const dim3 sgrid((unsigned)(rt < lp_compute_units() ? rt : lp_compute_units()));
-                hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 4, 64, true>), sgrid, dim3(512), 0, st, a);
-            } else {
-                const int64_t rt = lp_ceil_div(a.M, 128);
-                const int64_t sl = (fast_bn == 256 ? 1 : 2) * (int64_t)lp_compute_units();   // resident workgroups (LDS)
-                const dim3 sgrid((unsigned)(rt < sl ? rt : sl));
-                if (fast_bn == 256) hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 4, 2, 64, true>), sgrid, dim3(256), 0, st, a);
-                else hipLaunchKernelGGL((gemm_nt_fast_kernel<float, 2, 2, 64, true>), sgrid, dim3(256), 0, st, a);
-            }
+            if (a.gate) { LP_NT_SPLIT(true) } else { LP_NT_SPLIT(false) }
+        } else if (a.gate) {
+            LP_NT_FAST(float, true)
         } else {
-            LP_NT_FAST(float)
+            LP_NT_FAST(float, false)
         }
 #undef LP_NT_FAST
+#undef LP_NT_SPLIT
     } else if (bf16) {
         const int bn = a.N > 128 ? 256 : (a.N > 64 ? 128 : 64);
         if (bn == 256) hipLaunchKernelGGL((gemm_nt_bf16_kernel<4>), grid_for(256), dim3(kThreads), 0, st, a);

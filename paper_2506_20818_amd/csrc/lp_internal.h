@@ -42,7 +42,7 @@ private:
 
 // ---------------------------------------------------------------- sparse aggregation (spmm_mean.hip)
 // out[v, :] = rowscale(v) * sum_{p in row v} w[p] * in[colidx[p], :]  (+ addend[v, :])  (* [gate[v, :] > 0])
-//   w[p] = 1 when w == nullptr
+//   w[p] = 1 when w == nullptr (or col_w[colidx[p]] when col_w is given)
 //   rowscale(v) = inv_deg[v] when inv_deg != nullptr, else 1
 // With `in_index`, `in` and `addend` hold only some rows: node u lives in row in_index[u], and a negative entry
 // stands for an all-zero row.  With `n_rows_dev` the number of output rows is read on the device (at most n_rows).
@@ -56,6 +56,7 @@ struct SpmmArgs {
     const int32_t *row_order = nullptr;  // optional processing order
     const float *inv_deg = nullptr;      // optional per-output-row scale
     const float *w = nullptr;            // optional per-entry weight (parallel to colidx)
+    const float *col_w = nullptr;        // optional per-node weight: entry p weighs col_w[colidx[p]] (instead of w)
     const void *entry_rows = nullptr;    // optional matrix with rows of F values (storage type): entry p is multiplied
     const int32_t *entry_row_index = nullptr;  // element-wise by its row entry_row_index[p] (instead of a scalar weight)
     bool sym_norm = false;               // symmetric normalisation: entry p weighs sqrt(inv_deg[colidx[p]]), row v is
@@ -88,7 +89,8 @@ int lp_launch_spmm(const SpmmArgs &a, hipStream_t stream);
 //   the B operand of K-part s is given transposed: column n of the product reads row n of
 //   Bt[s][0] when n < n_split, else row (n - n_split) of Bt[s][1]; rows have K[s] contiguous floats (ldb[s]).
 // Epilogue: + bias[n] (optional), max(.,0) (optional); columns n >= n_split are multiplied by
-// rowscale[m] (optional) and go to C[1] (leading dimension ldc[1]) at column n - n_split, the others to C[0].
+// rowscale[m] (optional) and go to C[1] (leading dimension ldc[1]) at column n - n_split, the others to C[0];
+// with a gate matrix (fp32 storage, unsplit output) results are zeroed where the gate is not positive.
 struct GemmNtArgs {
     int32_t dtype = LP_F32;              // storage of A, Bt and C (bias and rowscale are always fp32)
     int32_t fp32_products = LP_FP32_PRODUCTS_NATIVE;   // LP_F32 only: fp32 matrix instructions or bfloat16 terms
@@ -106,6 +108,8 @@ struct GemmNtArgs {
     const int32_t *m_dev = nullptr;           // optional device scalar: rows actually present (<= M)
     void *C[2] = {nullptr, nullptr};
     int32_t ldc[2] = {0, 0};
+    const float *gate = nullptr;              // optional [M, N] fp32 (LP_F32, one output only): C[m, n] = 0 where gate[m, n] <= 0
+    int32_t ldgate = 0;
 };
 int lp_launch_gemm_nt(const GemmNtArgs &a, hipStream_t stream);
 

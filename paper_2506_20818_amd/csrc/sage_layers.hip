@@ -429,6 +429,37 @@ static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, cons
         wg.partials = w.tn_partials; wg.colsum_partials = w.colsum_partials;
         LP_TRY(lp_launch_weight_grads(wg, st));
         if (k == 1 && !out->dX) break;
+        // Input gradient G^{k-1} = gate . (dZ W_self^T + M^T(dZ W_neigh^T)), M^T the adjoint of the mean.  The adjoint
+        // commutes with the linear map, so where the layer does not widen the aggregation (F_k <= F_{k-1}) and dZ has a
+        // row per node, dZ is aggregated FIRST (entries weighted by the 1/deg of their source row) and ONE product
+        // [dZ | M^T dZ] [W_self^T ; W_neigh^T] follows, gated in its epilogue: nothing like Q and R below is written and
+        // read back, and the aggregation reads no addend and no gate rows (fp32 storage; the bf16 path keeps the
+        // order whose stored matrices its parity bound is stated for).
+        if (!gcn && !listed && dt == LP_F32 && Fo <= Fi && k > 1) {
+            SpmmArgs sp;
+            sp.dtype = dt;
+            sp.n_rows = N; sp.F = Fo;
+            sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
+            sp.n_entries = g->nnz; sp.long_queue = w.long_queue;
+            sp.col_w = g->inv_deg;
+            sp.in = dZ; sp.out = R;
+            LP_TRY(lp_launch_spmm(sp, st));
+            GemmNtArgs ge;
+            ge.dtype = dt;
+            ge.fp32_products = m->fp32_products;
+            ge.M = N;
+            ge.N = Fi; ge.n_split = Fi;
+            ge.A[0] = dZ; ge.A[1] = R;
+            ge.lda[0] = ge.lda[1] = Fo;
+            ge.K[0] = ge.K[1] = Fo;
+            ge.Bt[0][0] = m->W_self[k - 1]; ge.Bt[1][0] = m->W_neigh[k - 1];
+            ge.ldb[0] = ge.ldb[1] = Fo;
+            ge.C[0] = Q; ge.ldc[0] = Fi;
+            ge.gate = static_cast<const float *>(Hin); ge.ldgate = Fi;
+            LP_TRY(lp_launch_gemm_nt(ge, st));
+            void *t = dZ; dZ = Q; Q = t;
+            continue;
+        }
         GemmNtArgs ge;
         ge.dtype = dt;
         ge.fp32_products = m->fp32_products;

@@ -55,7 +55,7 @@ __device__ __forceinline__ void accumulate_blocks(const SpmmArgs &a, const T *__
         if (W == 1) {
             mine_w = 0.f;
             if (lane < cnt) {
-                if (!a.sym_norm) mine_w = a.w[base + lane];
+                if (!a.sym_norm) mine_w = a.col_w ? a.col_w[mine] : a.w[base + lane];
                 else if (a.sym_col_cnt) mine_w = a.sym_col_cnt[mine] / sqrtf(a.inv_deg[mine]);   // the column has this entry: inv_deg > 0
                 else mine_w = sqrtf(a.inv_deg[mine]);
             }
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void spmm_long_rows_finish_kernel(SpmmArg
 template <typename T, int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
     const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kRowThreads / 64);
-    const int mode = a.entry_rows ? 2 : ((a.w || a.sym_norm) ? 1 : 0);
+    const int mode = a.entry_rows ? 2 : ((a.w || a.col_w || a.sym_norm) ? 1 : 0);
     if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2>), dim3(grid), dim3(kRowThreads), 0, st, a);
     else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kRowThreads), 0, st, a);
     else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kRowThreads), 0, st, a);
