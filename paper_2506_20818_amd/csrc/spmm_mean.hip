@@ -27,9 +27,13 @@
 namespace {
 
 constexpr int kThreads = 256;
-// One row per workgroup in the row kernel: the wavefronts of a larger workgroup hold their slots until its longest row
-// is done, which cost 1-8 % where neighbouring rows differ much in length (measured with 128 and 256 threads).
+// Rows per workgroup of the row kernel.  One (64 threads) where row lengths vary: the wavefronts of a larger workgroup
+// hold their slots until its longest row is done, which cost 1-8 % on graphs whose neighbouring rows differ much in
+// length (measured with 128 and 256 threads).  Four (256 threads) where the caller passes no queue for long rows,
+// i.e. knows its rows to be short (sampled neighbourhoods, at most the fan-out): there the workgroup launches
+// themselves are the cost (+12 % on the sampled step's aggregations with one row per workgroup).
 constexpr int kRowThreads = 64;
+constexpr int kShortRowThreads = 256;
 constexpr int kLongThreads = 1024;
 constexpr int kLongWaves = kLongThreads / 64;
 constexpr int kLongHeader = 64;                        // words ahead of the queued rows (count, seg, tasks, slots)
@@ -151,11 +155,11 @@ __device__ __forceinline__ void finish_vector(const SpmmArgs &a, int32_t v, int 
     LpVec<T>::store_streaming(static_cast<T *>(a.out) + o, y);   // written once, read by a later kernel: leave the caches to the gathered rows
 }
 
-template <typename T, int G, int C, int W>
-__global__ __launch_bounds__(kRowThreads) void spmm_rows_kernel(SpmmArgs a) {
+template <typename T, int G, int C, int W, int RT>
+__global__ __launch_bounds__(RT) void spmm_rows_kernel(SpmmArgs a) {
     constexpr int VE = LpVec<T>::N;
     const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * (kRowThreads / 64) + (threadIdx.x >> 6);
+    const int64_t r = (int64_t)blockIdx.x * (RT / 64) + (threadIdx.x >> 6);
     if (r >= a.n_rows || (a.n_rows_dev && r >= *a.n_rows_dev)) return;
     const int32_t v = a.row_order ? a.row_order[r] : (int32_t)r;
     const int sub = lane / G, fl = lane % G;
@@ -364,11 +368,18 @@ __global__ __launch_bounds__(kThreads) void spmm_long_rows_finish_kernel(SpmmArg
 
 template <typename T, int G, int C>
 int launch(const SpmmArgs &a, hipStream_t st) {
-    const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kRowThreads / 64);
     const int mode = a.entry_rows ? 2 : ((a.w || a.col_w || a.sym_norm) ? 1 : 0);
-    if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2>), dim3(grid), dim3(kRowThreads), 0, st, a);
-    else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1>), dim3(grid), dim3(kRowThreads), 0, st, a);
-    else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0>), dim3(grid), dim3(kRowThreads), 0, st, a);
+    if (a.long_queue) {
+        const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kRowThreads / 64);
+        if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2, kRowThreads>), dim3(grid), dim3(kRowThreads), 0, st, a);
+        else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1, kRowThreads>), dim3(grid), dim3(kRowThreads), 0, st, a);
+        else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0, kRowThreads>), dim3(grid), dim3(kRowThreads), 0, st, a);
+    } else {
+        const unsigned grid = (unsigned)lp_ceil_div(a.n_rows, kShortRowThreads / 64);
+        if (mode == 2) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 2, kShortRowThreads>), dim3(grid), dim3(kShortRowThreads), 0, st, a);
+        else if (mode == 1) hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 1, kShortRowThreads>), dim3(grid), dim3(kShortRowThreads), 0, st, a);
+        else hipLaunchKernelGGL((spmm_rows_kernel<T, G, C, 0, kShortRowThreads>), dim3(grid), dim3(kShortRowThreads), 0, st, a);
+    }
     if (a.long_queue) {
         // no more rows can be queued than fit the entry count, and a row of at least 512 entries is at most two tasks
         // per 1024 entries; two workgroups per compute unit walk the tasks
