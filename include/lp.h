@@ -339,10 +339,13 @@ int lp_score_loss_noalloc(const void *HK, int32_t n_nodes, int32_t F, int32_t dt
  * (Algorithm 1, "Compute the gradient"): scatters dscore through the dot
  * product into dL/dH^K, then walks the layers K..1 through the ReLU, the two
  * linear maps and the adjoint of the mean aggregation (transposed CSR).
- * X and `saved` are the input and result of the lp_sage_forward call for the
- * same graph and model; e_src/e_dst/dscore as in lp_score_loss (an edge with
- * an id outside [0, n_nodes) contributes nothing).  All sums are taken in a
- * fixed order: repeated calls give the same bits.
+ * X and `saved` are the input and result of the lp_sage_forward (or
+ * lp_sage_forward_edges, with the same e_src/e_dst) call for the same graph
+ * and model: of saved->A[K-1] and saved->H[K-1] only the rows of the end
+ * points of the scored edges are read.  e_src/e_dst/dscore as in
+ * lp_score_loss (an edge with an id outside [0, n_nodes) contributes
+ * nothing).  All sums are taken in a fixed order: repeated calls give the
+ * same bits.
  */
 size_t lp_backward_workspace_bytes(const lp_model *m, int32_t n_nodes, int64_t B);
 int lp_backward(const lp_csr *g, const lp_model *m, const void *X, const lp_acts *saved, int64_t B,
