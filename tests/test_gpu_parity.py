@@ -650,6 +650,12 @@ def test_training_forward_with_an_empty_batch_and_around_the_largest_listed_batc
     acts = nan_filled_acts(n, model, Xd)
     lp.lp_sage_forward_edges(g, model, Xd, z, z, acts)
     check_last_layer_listed(acts, a_ref, np.zeros(0, np.int32), np.zeros(0, np.int32), 2)
+    # a batch whose every edge carries an id outside the graph lists nothing: the last layer stays untouched
+    bad = np.full(50, n, np.int32)
+    acts = nan_filled_acts(n, model, Xd)
+    lp.lp_sage_forward_edges(g, model, Xd, dev_i32(bad), dev_i32(-bad), acts)
+    check_last_layer_listed(acts, a_ref, bad, -bad, 2)
+    assert np.isnan(host(acts.H[-1])).all() and np.isnan(host(acts.A[-1])).all()
     every = np.arange(n, dtype=np.int32)
     Bmax = (3 * n - 1) // 8                              # the longest list: 2 Bmax distinct end points
     acts = nan_filled_acts(n, model, Xd)
