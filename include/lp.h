@@ -113,6 +113,9 @@ typedef struct lp_csr {
                                   them in (lp_build_csr: rows with |N(v)| >= 64 by decreasing floor(log2 |N(v)|), then
                                   all others, ids ascending inside a class); any permutation gives the same results */
     const int32_t *t_row_order;/* device [n_nodes] or NULL: same for the transposed CSR */
+    const float *t_entry_scale;/* device [nnz] or NULL: inv_deg[t_colidx[p]] for every entry p of the transposed CSR, i.e.
+                                  the weight 1/|N(v)| with which row v's gradient reaches its neighbour (the adjoint of
+                                  the mean); NULL: the backward pass looks the weights up in inv_deg entry by entry */
 } lp_csr;
 
 /* K-layer model.  Layer k = 1..K maps width dims[k-1] to dims[k]:
@@ -207,7 +210,7 @@ const char *lp_strerror(int status);
 
 /* Version of this header's structs and signatures, bumped with every change to them.  lp_abi_version() returns the
  * value the library was built with: a caller (or binding) that was written against another one must not go on. */
-#define LP_ABI_VERSION 4
+#define LP_ABI_VERSION 5
 int lp_abi_version(void);
 
 /* ---------------------------------------------------------------------------
@@ -220,7 +223,8 @@ int lp_abi_version(void);
  * as an ordinary entry.  With LP_SYMMETRIZE each pair also counts reversed.
  * Outputs (device): rowptr, t_rowptr [n_nodes+1]; colidx, t_colidx with room
  * for n_in entries (2*n_in with LP_SYMMETRIZE); inv_deg [n_nodes]; row_order
- * and t_row_order [n_nodes] (both may be NULL).  *nnz_out (HOST pointer)
+ * and t_row_order [n_nodes] (both may be NULL); t_entry_scale, as many floats
+ * as t_colidx has room for (may be NULL).  *nnz_out (HOST pointer)
  * receives the number of entries.  There is exactly one correct output.
  *
  * This call waits for the stream before it returns (it reads nnz back).
@@ -230,8 +234,8 @@ int lp_abi_version(void);
 size_t lp_build_csr_workspace_bytes(int32_t n_nodes, int64_t n_in, uint32_t flags);
 int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, const int32_t *cols, uint32_t flags,
                  int32_t *rowptr, int32_t *colidx, int32_t *t_rowptr, int32_t *t_colidx, float *inv_deg,
-                 int32_t *row_order, int32_t *t_row_order, int64_t *nnz_out, void *ws, size_t ws_bytes,
-                 void *stream);
+                 int32_t *row_order, int32_t *t_row_order, float *t_entry_scale, int64_t *nnz_out, void *ws,
+                 size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * lp_sage_forward - the K aggregation layers of Eq. (1) for every visible

@@ -35,7 +35,7 @@ class LpError(RuntimeError):
 class _CsrStruct(C.Structure):
     _fields_ = [("n_nodes", C.c_int32), ("reserved_", C.c_int32), ("nnz", C.c_int64),
                 ("rowptr", C.c_void_p), ("colidx", C.c_void_p), ("t_rowptr", C.c_void_p), ("t_colidx", C.c_void_p),
-                ("inv_deg", C.c_void_p), ("row_order", C.c_void_p), ("t_row_order", C.c_void_p)]
+                ("inv_deg", C.c_void_p), ("row_order", C.c_void_p), ("t_row_order", C.c_void_p), ("t_entry_scale", C.c_void_p)]
 
 
 class _ModelStruct(C.Structure):
@@ -91,7 +91,7 @@ EXPORTS = {
     "lp_abi_version": (C.c_int, []),
     "lp_build_csr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_uint32]),
     "lp_build_csr": (C.c_int, [C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
-                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
+                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
                                C.c_void_p, C.c_size_t, C.c_void_p]),
     "lp_sage_forward_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32]),
     "lp_sage_forward_edges_workspace_bytes": (C.c_size_t, [C.POINTER(_ModelStruct), C.c_int32, C.c_int64]),
@@ -210,10 +210,10 @@ def _ws(nbytes: int, device) -> torch.Tensor:
 class Csr:
     """Device CSR of the visible graph, its transpose, inverse degrees and degree-ordered row lists."""
 
-    def __init__(self, n_nodes, nnz, rowptr, colidx, t_rowptr, t_colidx, inv_deg, row_order, t_row_order):
+    def __init__(self, n_nodes, nnz, rowptr, colidx, t_rowptr, t_colidx, inv_deg, row_order, t_row_order, t_entry_scale=None):
         self.n_nodes, self.nnz = int(n_nodes), int(nnz)
         self.rowptr, self.colidx, self.t_rowptr, self.t_colidx = rowptr, colidx, t_rowptr, t_colidx
-        self.inv_deg, self.row_order, self.t_row_order = inv_deg, row_order, t_row_order
+        self.inv_deg, self.row_order, self.t_row_order, self.t_entry_scale = inv_deg, row_order, t_row_order, t_entry_scale
         s = _CsrStruct()
         s.n_nodes, s.nnz = self.n_nodes, self.nnz
         s.rowptr, s.colidx = rowptr.data_ptr(), colidx.data_ptr()
@@ -221,6 +221,7 @@ class Csr:
         s.inv_deg = inv_deg.data_ptr()
         s.row_order = row_order.data_ptr() if row_order is not None else None
         s.t_row_order = t_row_order.data_ptr() if t_row_order is not None else None
+        s.t_entry_scale = t_entry_scale.data_ptr() if t_entry_scale is not None else None
         self.c = s
 
 
@@ -300,7 +301,7 @@ class Grads:
 
 # ----------------------------------------------------------------------------------------------------------
 def lp_build_csr(n_nodes: int, rows: torch.Tensor, cols: torch.Tensor, symmetrize: bool,
-                 with_row_order: bool = True) -> Csr:
+                 with_row_order: bool = True, with_entry_scale: bool = True) -> Csr:
     lib = load_library()
     _need(rows, torch.int32, "rows")
     _need(cols, torch.int32, "cols")
@@ -314,14 +315,16 @@ def lp_build_csr(n_nodes: int, rows: torch.Tensor, cols: torch.Tensor, symmetriz
     inv_deg = torch.empty(n_nodes, dtype=torch.float32, device=dev)
     row_order = i32(n_nodes) if with_row_order else None
     t_row_order = i32(n_nodes) if with_row_order else None
+    t_entry_scale = torch.empty(cap, dtype=torch.float32, device=dev) if with_entry_scale else None
     ws_bytes = lib.lp_build_csr_workspace_bytes(n_nodes, n_in, flags)
     ws = _ws(ws_bytes, dev)
     nnz = C.c_int64(0)
     _check(lib.lp_build_csr(n_nodes, n_in, _ptr(rows), _ptr(cols), flags, _ptr(rowptr), _ptr(colidx), _ptr(t_rowptr),
-                            _ptr(t_colidx), _ptr(inv_deg), _ptr(row_order), _ptr(t_row_order), C.byref(nnz), _ptr(ws),
-                            ws.numel(), _stream()), "lp_build_csr")
+                            _ptr(t_colidx), _ptr(inv_deg), _ptr(row_order), _ptr(t_row_order), _ptr(t_entry_scale), C.byref(nnz),
+                            _ptr(ws), ws.numel(), _stream()), "lp_build_csr")
     n = int(nnz.value)
-    return Csr(n_nodes, n, rowptr, colidx[:n], t_rowptr, t_colidx[:n], inv_deg, row_order, t_row_order)
+    return Csr(n_nodes, n, rowptr, colidx[:n], t_rowptr, t_colidx[:n], inv_deg, row_order, t_row_order,
+               t_entry_scale[:n] if t_entry_scale is not None else None)
 
 
 def lp_sage_forward(g: Csr, m: Model, X: torch.Tensor, acts: Optional[Acts] = None, ws: Optional[torch.Tensor] = None) -> Acts:

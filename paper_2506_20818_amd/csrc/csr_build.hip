@@ -283,10 +283,17 @@ extern "C" size_t lp_build_csr_workspace_bytes(int32_t n_nodes, int64_t n_in, ui
     return carve(nullptr, n_nodes, n_in, flags).bytes;
 }
 
+// scale[p] = inv_deg[col[p]]: the per-node factor of every entry, laid out in entry order
+__global__ void entry_scale_kernel(const int32_t *__restrict__ col, int64_t n, const float *__restrict__ inv_deg,
+                                   float *__restrict__ scale) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) scale[p] = inv_deg[col[p]];
+}
+
 extern "C" int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, const int32_t *cols, uint32_t flags,
                             int32_t *rowptr, int32_t *colidx, int32_t *t_rowptr, int32_t *t_colidx, float *inv_deg,
-                            int32_t *row_order, int32_t *t_row_order, int64_t *nnz_out, void *ws, size_t ws_bytes,
-                            void *stream) {
+                            int32_t *row_order, int32_t *t_row_order, float *t_entry_scale, int64_t *nnz_out, void *ws,
+                            size_t ws_bytes, void *stream) {
     if (n_nodes <= 0 || n_in < 0 || (flags & ~LP_SYMMETRIZE)) return LP_ERR_INVALID_ARG;
     if (!rowptr || !t_rowptr || !inv_deg || !nnz_out) return LP_ERR_INVALID_ARG;
     if (n_in > 0 && (!rows || !cols || !colidx || !t_colidx)) return LP_ERR_INVALID_ARG;
@@ -349,6 +356,11 @@ extern "C" int lp_build_csr(int32_t n_nodes, int64_t n_in, const int32_t *rows, 
                                bits, t_colidx);
         }
         hipLaunchKernelGGL(rowptr_kernel, dim3(g_nodes1), dim3(256), 0, st, tsorted, (int64_t)0, w.scalars, n_nodes, bits, t_rowptr);
+        LP_TRY(lp_after_launch());
+    }
+    if (t_entry_scale && nnz) {
+        hipLaunchKernelGGL(entry_scale_kernel, dim3((unsigned)lp_ceil_div(nnz, 256)), dim3(256), 0, st, t_colidx, nnz, inv_deg,
+                           t_entry_scale);
         LP_TRY(lp_after_launch());
     }
     if (row_order) LP_TRY(order_rows(rowptr, n_nodes, row_order, w, st));

@@ -441,7 +441,8 @@ static int backward_impl(const lp_csr *g, const lp_model *m, const void *X, cons
             sp.n_rows = N; sp.F = Fo;
             sp.rowptr = g->t_rowptr; sp.colidx = g->t_colidx; sp.row_order = g->t_row_order;
             sp.n_entries = g->nnz; sp.long_queue = w.long_queue;
-            sp.col_w = g->inv_deg;
+            if (g->t_entry_scale) sp.w = g->t_entry_scale;   // in entry order: no scattered 4-byte read per entry
+            else sp.col_w = g->inv_deg;
             sp.in = dZ; sp.out = R;
             LP_TRY(lp_launch_spmm(sp, st));
             GemmNtArgs ge;

@@ -230,8 +230,8 @@ int main(int argc, char **argv) {
 
     // ---- calls that read a result back on the host are only checked up to their argument validation
     int64_t nnz = 0;
-    CHECK(lp_build_csr(0, 4, ip, ip, 0, op, op, op, op, fp, op, op, &nnz, fake<void>(), 1 << 20, nullptr) == LP_ERR_INVALID_ARG);
-    CHECK(lp_build_csr(100, 4, ip, ip, 0, op, op, op, op, fp, op, op, &nnz, fake<void>(), 8, nullptr) == LP_ERR_WORKSPACE);
+    CHECK(lp_build_csr(0, 4, ip, ip, 0, op, op, op, op, fp, op, op, fp, &nnz, fake<void>(), 1 << 20, nullptr) == LP_ERR_INVALID_ARG);
+    CHECK(lp_build_csr(100, 4, ip, ip, 0, op, op, op, op, fp, op, op, fp, &nnz, fake<void>(), 8, nullptr) == LP_ERR_WORKSPACE);
     CHECK(lp_hits_at_k(fp, 10, fp, 100, 0, fake<int64_t>(), nullptr, fake<void>(), 1 << 20, nullptr) == LP_ERR_INVALID_ARG);
 
     std::printf("%d launches stubbed, %d checks failed\n", g_launches, g_failed);

@@ -77,7 +77,7 @@ def test_build_csr_rejects_bad_arguments_on_the_host():
     nnz = C.c_int64(0)
     p = C.c_void_p(0x1000)
     args = lambda **kw: [kw.get("n", 10), kw.get("n_in", 4), kw.get("rows", p), p, kw.get("flags", 0), p, p, p, p, p,
-                         None, None, C.byref(nnz), kw.get("ws", p), kw.get("ws_bytes", 1 << 30), None]
+                         None, None, None, C.byref(nnz), kw.get("ws", p), kw.get("ws_bytes", 1 << 30), None]
     assert lib.lp_build_csr(*args(n=0)) == -1
     assert lib.lp_build_csr(*args(n_in=-1)) == -1
     assert lib.lp_build_csr(*args(rows=None)) == -1

@@ -36,6 +36,8 @@ def check_csr(g, ref):
     for name in ("rowptr", "colidx", "t_rowptr", "t_colidx"):
         assert np.array_equal(host(getattr(g, name)), getattr(ref, name)), name
     assert np.array_equal(host(g.inv_deg).view(np.uint32), ref.inv_deg.view(np.uint32)), "inv_deg bits"
+    if g.t_entry_scale is not None:   # the 1/deg of every transposed entry's source row, in entry order
+        assert np.array_equal(host(g.t_entry_scale).view(np.uint32), ref.inv_deg[ref.t_colidx].view(np.uint32)), "t_entry_scale bits"
     for order, rp in ((g.row_order, ref.rowptr), (g.t_row_order, ref.t_rowptr)):
         # rows of 64 and more entries by decreasing floor(log2(length)), then all shorter rows; ids ascending in a class
         deg = np.diff(rp).astype(np.int64)
@@ -466,6 +468,12 @@ def test_backward_parity(dims, sym, products=lp.LP_FP32_PRODUCTS_BF16X6):
     # without dX the weight gradients are the same
     grads2 = lp.lp_backward(g, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=False)
     check_grads(grads2, g_ref, K)
+    # a graph without the per-entry scales of its transpose (the backward pass then looks them up in inv_deg): same bits
+    g3 = lp.lp_build_csr(n, dev_i32(r), dev_i32(c), sym, with_entry_scale=False)
+    grads3 = lp.lp_backward(g3, model, Xd, acts, dev_i32(es), dev_i32(ed), ds, want_dX=True)
+    for k in range(K):
+        assert torch.equal(grads3.dW_self[k], grads.dW_self[k]) and torch.equal(grads3.dW_neigh[k], grads.dW_neigh[k])
+    assert torch.equal(grads3.dX, grads.dX)
 
 
 @pytest.mark.parametrize("dims", [[128, 256, 256, 256], [192, 200, 232], [64, 512, 128], [48, 80, 144]])
