@@ -1324,28 +1324,34 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
         const int64_t klast = Kn_ - 1;
         v4f rv[4];
         int64_t row[4];
-        auto lookup = [&](int64_t k0) {
+        const bool through_list = INDEXED && !is_b;   // wavefront-uniform
+        auto lookup = [&](int64_t k0) {   // rows taken through the list are looked up one step ahead of their fetch
+            if (!through_list) return;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t k = min(k0 + 4 * ng + i, klast);
-                const int64_t listed = INDEXED ? (int64_t)g.at_index[k] : k;   // loaded by the B loaders too: no branch
-                row[i] = is_b ? k : listed;
-            }
+            for (int i = 0; i < 4; ++i) row[i] = (int64_t)g.at_index[min(k0 + 4 * ng + i, klast)];
         };
-        auto fetch = [&](int64_t k0) {
+        auto fetch = [&](int64_t k0) {   // values are used as loaded: see stash_half
+            if (through_list) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const v4f *>(base + row[i] * pitch);   // used as loaded: see stash_half
-            (void)k0;
+                for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const v4f *>(base + row[i] * pitch);
+            } else if (k0 + WS_BK <= kend) {   // a whole step inside the chunk (the same for every thread): consecutive rows, no clamp
+                const float *p = base + (k0 + 4 * ng) * pitch;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const v4f *>(p + i * pitch);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rv[i] = *reinterpret_cast<const v4f *>(base + min(k0 + 4 * ng + i, klast) * pitch);
+            }
         };
         // columns j0, j0 + 1 of the block (four nodes each, fetched for the step that starts at node k0) into a stage;
         // nodes beyond the end of the chunk and columns outside the operand count as zeros (decided here, not at the
         // load, so that nothing waits for the loads before this point); the second half also adds up the block
         auto stash_half = [&](int stage, int j0, int64_t k0) {
             char *dst = lds + stage * STAGE + (is_b ? 256 * WS_ROWB : 0) + c * WS_ROWB + 8 * ng;
-            bool live[4];
+            if (j0 == 0 && !(ok && k0 + WS_BK <= kend)) {   // (a whole step of an operand column that exists needs no masking)
+                bool live[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) live[i] = ok && k0 + 4 * ng + i < kend;
-            if (j0 == 0) {
+                for (int i = 0; i < 4; ++i) live[i] = ok && k0 + 4 * ng + i < kend;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -1511,18 +1517,32 @@ __global__ __launch_bounds__(WG_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
         const int64_t klast = Kn_ - 1;
         v4i rows[8];
         int64_t srow[8];
-        auto lookup = [&](int64_t k0) {
+        auto lookup = [&](int64_t k0) {   // rows taken through the list are looked up one step ahead of their fetch
+            if (!indexed) return;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int64_t k = min(k0 + 8 * q + e, klast);
-                srow[e] = indexed ? (int64_t)g.at_index[k] : k;
-            }
+            for (int e = 0; e < 8; ++e) srow[e] = (int64_t)g.at_index[min(k0 + 8 * q + e, klast)];
         };
         auto fetch = [&](int64_t k0) {
+            if (k0 + TK <= kend) {   // the whole step lies inside the chunk (the same for every thread): nothing to clamp or mask
+                if (indexed) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rows[e] = *reinterpret_cast<const v4i *>(src + srow[e] * pitch);
+                } else {
+                    const lp_bf16_t *p = src + (k0 + 8 * q) * pitch;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rows[e] = *reinterpret_cast<const v4i *>(p + e * pitch);
+                }
+                if (!col_ok) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) rows[e] = v4i{0, 0, 0, 0};
+                }
+                return;
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bool live = col_ok && k0 + 8 * q + e < kend;
-                const v4i v = *reinterpret_cast<const v4i *>(src + srow[e] * pitch);
+                const int64_t row = indexed ? srow[e] : min(k0 + 8 * q + e, klast);
+                const v4i v = *reinterpret_cast<const v4i *>(src + row * pitch);
 #pragma unroll
                 for (int d = 0; d < 4; ++d) rows[e][d] = live ? v[d] : 0;
             }
